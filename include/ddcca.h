@@ -1,0 +1,147 @@
+/*
+ * ddcca.h -- C ABI of the MI355X (gfx950) two-stage DDCCANet feature-extractor hot path.
+ *
+ * The calls follow the paper's statement of the problem: two aligned views of M images
+ * (M x p x q tensors, Section II-A) plus class labels go in; per stage the DDCCA filters
+ * W^1, W^2 come out (Eq. 2-5), every image is convolved with them (Eq. 6), and the
+ * output layer hashes the last stage's maps into per-block code histograms (Eq. 7-9,
+ * Section II-C, Eq. 11-12).
+ *
+ * General rules
+ *   - Every data pointer is a DEVICE pointer owned by the caller (for example the
+ *     data_ptr() of a PyTorch tensor on the context's GPU).  Host pointers are not
+ *     accepted.  The library reads/writes them only inside the call's enqueued work and
+ *     keeps no reference afterwards.
+ *   - All calls enqueue on the context's stream and return without synchronising,
+ *     unless stated otherwise.  Scratch memory is owned by the context, grown on
+ *     demand (hipMalloc) and released by ddcca_destroy.
+ *   - Layouts are dense row-major, innermost index x.  Images: [n][h][w] float.
+ *     A patch / filter element is a = dy*k + dx (Eq. 4-5 read row-major).
+ *     Patches are taken at every pixel with zero padding r=(k-1)/2 (Eq. 1 has M*p*q
+ *     columns) and each patch has its own mean removed.
+ *   - Return value: DDCCA_OK (0) or a negative DDCCA_E* code.  Arguments are validated
+ *     on the host before anything is launched; no C++ exception crosses the boundary.
+ *     ddcca_last_error() gives a text for the last failure on that context.
+ *   - A context is not thread-safe; calls on one context must not overlap.
+ */
+#ifndef DDCCA_H
+#define DDCCA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DDCCA_OK          0
+#define DDCCA_EINVAL    (-1)   /* null pointer, k even or outside 3..9, L outside 1..k*k-1, L2 > 12, block > image, stride < 1, n < 0 */
+#define DDCCA_ESTATE    (-2)   /* call order: accumulate/export/solve without a matching ddcca_corr_begin */
+#define DDCCA_ENOMEM    (-3)   /* scratch allocation failed */
+#define DDCCA_EHIP      (-4)   /* HIP runtime error (no GPU, launch failure, ...) */
+#define DDCCA_EOVERFLOW (-5)   /* a histogram count would not fit uint16 (block area > 65535) */
+#define DDCCA_ELABEL    (-6)   /* a class label outside [0, n_cls) was seen on the device */
+
+#define DDCCA_MIN_K   3
+#define DDCCA_MAX_K   9
+#define DDCCA_MAX_L2 12
+
+typedef struct ddcca_ctx ddcca_ctx;
+
+/* Create a context bound to GPU `device` and to `hip_stream` (a hipStream_t, borrowed;
+ * NULL = the device's default stream).  Touches no GPU state by itself, so it succeeds
+ * on a machine without a GPU; the first call that needs the GPU then fails with
+ * DDCCA_EHIP. */
+int ddcca_create(ddcca_ctx **out, int device, void *hip_stream);
+void ddcca_destroy(ddcca_ctx *ctx);
+const char *ddcca_last_error(const ddcca_ctx *ctx);
+
+/* Synchronise the context's stream and report sticky device-side conditions
+ * (DDCCA_ELABEL) or a pending HIP error. */
+int ddcca_status(ddcca_ctx *ctx);
+
+/* ---- correlation accumulation, streamed over batches (Section III, Eq. 13-15) -------
+ * begin -> accumulate(batch)* -> export / solve.
+ * A batch is n_img samples of G maps each: v1, v2 are [n_img][G][h][w]; map g of view 1
+ * pairs with map g of view 2 (stage 1: G = 1; stage 2: G = L1 and the maps are the
+ * stage-1 outputs).  cls is [n_img] int32 on the device, values in [0, n_cls).
+ * Accumulated: the sums over all patches of x1 x1^T, x2 x2^T, x1 x2^T, and per
+ * (class, g) cell the pixel-wise sums of the member maps, from which the same-class
+ * pair sum C_w and the all-pairs sum C_T follow (Section II-A: C~ = C_w - C_b,
+ * C_b = C_T - C_w).  The result does not depend on how samples are split into
+ * batches. */
+int ddcca_corr_begin(ddcca_ctx *ctx, int k, int n_cls, int G, int h, int w);
+int ddcca_corr_accumulate(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls,
+                          int64_t n_img);
+/* Write the matrices, each divided by the number of patches N = (#maps)*h*w, as
+ * [k*k][k*k] doubles.  Any pointer may be NULL.  May be called once per begin. */
+int ddcca_corr_export(ddcca_ctx *ctx, double *C11, double *C22, double *C12, double *Cw,
+                      double *CT);
+/* Solve Eq. 2-3 on the accumulated matrices (runs the export step itself if it has not
+ * run yet): see ddcca_dcca_solve for the outputs. */
+int ddcca_solve_filters(ddcca_ctx *ctx, int L, double ridge, float *W1, float *W2, double *rho);
+
+/* Eq. 2-3 for given matrices (all [D][D] doubles, D = k*k):
+ *   maximise w1^T C~ w2,  C~ = 2 C_w - C_T,  subject to w_d^T B_d w_d = 1,
+ *   B_d = C_dd + ridge * trace(C_dd)/D * I   (C_dd alone is singular after mean removal).
+ * Returns the L leading pairs in descending rho, pairs mutually B-orthogonal, the sign
+ * of each pair fixed so that the largest-magnitude entry of w1 is positive (lowest
+ * index on ties; w2 flips with it).  W1, W2: [L][k][k] float; rho: [L] double. */
+int ddcca_dcca_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const double *Cw,
+                     const double *CT, int k, int L, double ridge, float *W1, float *W2,
+                     double *rho);
+
+/* ---- the four calls of the path ----------------------------------------------------- */
+
+/* Learn one stage's filters from all samples at once (Section II-A; begin +
+ * accumulate + solve). */
+int ddcca_learn_stage_filters(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls,
+                              int64_t n_img, int G, int h, int w, int n_cls, int k, int L,
+                              double ridge, float *W1, float *W2, double *rho);
+
+/* Eq. 6: out[n][g][y][x] = sum_{dy,dx} W[g][dy][dx] * in_pad[n][y+dy-r][x+dx-r]
+ * (cross-correlation, zero padding).  in: [n][h][w]; W: [L][k][k]; out: [n][L][h][w]. */
+int ddcca_apply_stage(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W,
+                      int k, int L, float *out);
+
+/* Eq. 7-9 + Section II-C: code = sum_l 2^(l-1) [maps[n][l-1][y][x] > 0]; the code map is
+ * cut into block_h x block_w blocks with top-left corners (i*stride_y, j*stride_x), all
+ * blocks fully inside the map; hist[n][i][j][t] counts code t in block (i,j).
+ * maps: [n][L2][h][w] float; hist: [n][nby][nbx][1<<L2] uint16,
+ * nby = (h-block_h)/stride_y + 1, nbx = (w-block_w)/stride_x + 1. */
+int ddcca_hash_histogram(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w,
+                         int block_h, int block_w, int stride_y, int stride_x, uint16_t *hist);
+
+typedef struct ddcca_model {
+    int k, L1, L2;
+    int block_h, block_w, stride_y, stride_x;
+    const float *W[2][2];     /* W[stage][view]: device, [L_stage][k][k] */
+    int64_t batch_images;     /* images per internal batch; 0 = library default */
+} ddcca_model;
+
+/* Both stages and the output layer for m new image pairs with a learned model:
+ * feat[m][view][g][i][j][t], g < L1 (Eq. 11-12: per view the L1 block-histogram sets,
+ * views concatenated per image).  Stage-2 maps are produced batch by batch in context
+ * scratch and never leave the GPU. */
+int ddcca_extract_features(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h,
+                           int w, const ddcca_model *model, uint16_t *feat);
+
+/* ---- per-kernel timing (HIP events on the context's stream) -------------------------- */
+enum {
+    DDCCA_K_GRAM = 0,     /* patch-Gram accumulation */
+    DDCCA_K_CLASS_SUM,    /* per-(class,g) image sums */
+    DDCCA_K_REDUCE,       /* cross-workgroup reduction / export of the matrices */
+    DDCCA_K_SOLVE,        /* DCCA solve */
+    DDCCA_K_CONV,         /* stage convolution */
+    DDCCA_K_HASH_HIST,    /* hashing + block histogram */
+    DDCCA_K_COUNT
+};
+/* While enabled, every kernel launch is bracketed by a pair of events. */
+int ddcca_profile_enable(ddcca_ctx *ctx, int on);
+/* Synchronises the stream; total_ms / launches since the last reset for one kernel id. */
+int ddcca_profile_read(ddcca_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches);
+int ddcca_profile_reset(ddcca_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DDCCA_H */

@@ -1,0 +1,434 @@
+// C ABI of libddcca: argument validation, scratch management and the host-side
+// orchestration of the kernels.  No arithmetic of the method happens on the host.
+#include <stdio.h>
+
+#include <algorithm>
+#include <new>
+
+#include "ddcca_internal.h"
+
+namespace ddcca {
+
+int fail(ddcca_ctx *ctx, int code, const std::string &msg)
+{
+    if (ctx) ctx->err = msg;
+    return code;
+}
+
+int hip_fail(ddcca_ctx *ctx, hipError_t e, const char *what)
+{
+    (void)hipGetLastError();   // clear the sticky (non-fatal) error state
+    return fail(ctx, e == hipErrorOutOfMemory ? DDCCA_ENOMEM : DDCCA_EHIP,
+                std::string(what) + ": " + hipGetErrorString(e));
+}
+
+int device_ready(ddcca_ctx *ctx)
+{
+    DDCCA_HIP(ctx, hipSetDevice(ctx->device));
+    if (ctx->n_cu == 0) {
+        int cu = 0;
+        DDCCA_HIP(ctx, hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, ctx->device));
+        ctx->n_cu = cu > 0 ? cu : 256;
+    }
+    return DDCCA_OK;
+}
+
+int ensure(ddcca_ctx *ctx, Buffer &b, size_t bytes)
+{
+    if (b.bytes >= bytes && b.ptr) return DDCCA_OK;
+    if (b.ptr) {
+        // earlier work on the stream may still use the old allocation
+        DDCCA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        DDCCA_HIP(ctx, hipFree(b.ptr));
+        b.ptr = nullptr;
+        b.bytes = 0;
+    }
+    size_t want = std::max<size_t>(bytes, 256);
+    DDCCA_HIP(ctx, hipMalloc(&b.ptr, want));
+    b.bytes = want;
+    return DDCCA_OK;
+}
+
+ProfScope::ProfScope(ddcca_ctx *c, int kernel_id) : ctx(c), id(kernel_id)
+{
+    if (!ctx->prof) return;
+    ProfSlot &s = ctx->prof_slot[id];
+    if (s.used == s.start.size()) {
+        hipEvent_t a = nullptr, b = nullptr;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+            ctx->prof = false;
+            return;
+        }
+        s.start.push_back(a);
+        s.stop.push_back(b);
+    }
+    (void)hipEventRecord(s.start[s.used], ctx->stream);
+}
+
+ProfScope::~ProfScope()
+{
+    if (!ctx->prof) return;
+    ProfSlot &s = ctx->prof_slot[id];
+    if (s.used >= s.stop.size()) return;
+    (void)hipEventRecord(s.stop[s.used], ctx->stream);
+    s.used += 1;
+    s.launches += 1;
+}
+
+static bool valid_k(int k) { return k >= DDCCA_MIN_K && k <= DDCCA_MAX_K && (k & 1); }
+
+static int check_image_args(ddcca_ctx *ctx, int64_t n, int h, int w, int k)
+{
+    if (n < 0) return fail(ctx, DDCCA_EINVAL, "negative image count");
+    if (h < 1 || w < 1) return fail(ctx, DDCCA_EINVAL, "image height and width must be >= 1");
+    if ((int64_t)h * w > (int64_t)1 << 26) return fail(ctx, DDCCA_EINVAL, "image larger than 2^26 pixels");
+    if (!valid_k(k)) return fail(ctx, DDCCA_EINVAL, "patch side k must be odd and in 3..9");
+    return DDCCA_OK;
+}
+
+static void free_buffer(Buffer &b)
+{
+    if (b.ptr) (void)hipFree(b.ptr);
+    b.ptr = nullptr;
+    b.bytes = 0;
+}
+
+// Finish the accumulation: Gram partials -> stacked Gram, class sums -> class / total
+// images -> their Grams, then the five normalised matrices in ctx->mats.
+static int corr_finish(ddcca_ctx *ctx)
+{
+    const int k = ctx->k, D = k * k;
+    const int tiles = gram_tiles(k);
+    const size_t E = (size_t)tiles * 256;
+    const int64_t P = (int64_t)ctx->h * ctx->w;
+    const int n_cell = ctx->n_cls * ctx->G;
+    int rc;
+    if ((rc = ensure(ctx, ctx->stacked, 3 * E * sizeof(double)))) return rc;
+    if ((rc = ensure(ctx, ctx->mats, 5 * (size_t)D * D * sizeof(double)))) return rc;
+    double *st = (double *)ctx->stacked.ptr;
+    if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, ctx->slots_valid, k, st))) return rc;
+
+    if ((rc = ensure(ctx, ctx->class_img, 2 * (size_t)(n_cell + ctx->G) * P * sizeof(float)))) return rc;
+    float *img = (float *)ctx->class_img.ptr;
+    if ((rc = launch_class_finalize(ctx, (const double *)ctx->class_sum.ptr, ctx->n_cls, ctx->G, P, img))) return rc;
+    const size_t view_stride = (size_t)(n_cell + ctx->G) * P;
+    const int max_slots = max_gram_slots(ctx, k);
+    int valid = 0;
+    if ((rc = launch_patch_gram(ctx, img, img + view_stride, n_cell, ctx->h, ctx->w, k,
+                                (double *)ctx->slots.ptr, max_slots, &valid))) return rc;
+    if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, valid, k, st + E))) return rc;
+    valid = 0;
+    if ((rc = launch_patch_gram(ctx, img + (size_t)n_cell * P, img + view_stride + (size_t)n_cell * P, ctx->G,
+                                ctx->h, ctx->w, k, (double *)ctx->slots.ptr, max_slots, &valid))) return rc;
+    if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, valid, k, st + 2 * E))) return rc;
+    const double N = (double)ctx->n_maps * (double)P;
+    if ((rc = launch_export(ctx, st, st + E, st + 2 * E, k, N, (double *)ctx->mats.ptr))) return rc;
+    ctx->corr_exported = true;
+    ctx->slots_valid = 0;
+    return DDCCA_OK;
+}
+
+}  // namespace ddcca
+
+using namespace ddcca;
+
+extern "C" {
+
+int ddcca_create(ddcca_ctx **out, int device, void *hip_stream)
+{
+    if (!out) return DDCCA_EINVAL;
+    *out = nullptr;
+    if (device < 0) return DDCCA_EINVAL;
+    ddcca_ctx *ctx = new (std::nothrow) ddcca_ctx();
+    if (!ctx) return DDCCA_ENOMEM;
+    ctx->device = device;
+    ctx->stream = (hipStream_t)hip_stream;
+    *out = ctx;
+    return DDCCA_OK;
+}
+
+void ddcca_destroy(ddcca_ctx *ctx)
+{
+    if (!ctx) return;
+    bool touched = ctx->n_cu != 0;
+    if (touched) {
+        (void)hipSetDevice(ctx->device);
+        (void)hipStreamSynchronize(ctx->stream);
+        for (Buffer *b : {&ctx->slots, &ctx->class_sum, &ctx->class_img, &ctx->stacked, &ctx->seg, &ctx->mats,
+                          &ctx->solve_ws, &ctx->flags, &ctx->maps1, &ctx->maps2})
+            free_buffer(*b);
+        for (ProfSlot &s : ctx->prof_slot) {
+            for (hipEvent_t e : s.start) (void)hipEventDestroy(e);
+            for (hipEvent_t e : s.stop) (void)hipEventDestroy(e);
+        }
+    }
+    delete ctx;
+}
+
+const char *ddcca_last_error(const ddcca_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int ddcca_status(ddcca_ctx *ctx)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    int rc;
+    if ((rc = device_ready(ctx))) return rc;
+    DDCCA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->flags.ptr) {
+        int host[4] = {0, 0, 0, 0};
+        DDCCA_HIP(ctx, hipMemcpy(host, ctx->flags.ptr, sizeof(host), hipMemcpyDeviceToHost));
+        if (host[0]) {
+            DDCCA_HIP(ctx, hipMemset(ctx->flags.ptr, 0, sizeof(host)));
+            return fail(ctx, DDCCA_ELABEL, "class label outside [0, n_cls) seen on the device");
+        }
+    }
+    return DDCCA_OK;
+}
+
+int ddcca_corr_begin(ddcca_ctx *ctx, int k, int n_cls, int G, int h, int w)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    int rc;
+    if ((rc = check_image_args(ctx, 0, h, w, k))) return rc;
+    if (n_cls < 1 || n_cls > (1 << 20)) return fail(ctx, DDCCA_EINVAL, "n_cls must be in 1..2^20");
+    if (G < 1 || G > 4096) return fail(ctx, DDCCA_EINVAL, "G (maps per sample) must be in 1..4096");
+    if ((int64_t)n_cls * G > 65535) return fail(ctx, DDCCA_EINVAL, "n_cls * G must not exceed 65535");
+    if ((rc = device_ready(ctx))) return rc;
+    const int64_t P = (int64_t)h * w;
+    const size_t E = (size_t)gram_tiles(k) * 256;
+    const int max_slots = max_gram_slots(ctx, k);
+    if ((rc = ensure(ctx, ctx->slots, (size_t)max_slots * E * sizeof(double)))) return rc;
+    const size_t cs_bytes = 2 * (size_t)n_cls * G * P * sizeof(double);
+    if ((rc = ensure(ctx, ctx->class_sum, cs_bytes))) return rc;
+    DDCCA_HIP(ctx, hipMemsetAsync(ctx->class_sum.ptr, 0, cs_bytes, ctx->stream));
+    if (!ctx->flags.ptr) {
+        if ((rc = ensure(ctx, ctx->flags, 4 * sizeof(int)))) return rc;
+        DDCCA_HIP(ctx, hipMemsetAsync(ctx->flags.ptr, 0, 4 * sizeof(int), ctx->stream));
+    }
+    ctx->k = k; ctx->n_cls = n_cls; ctx->G = G; ctx->h = h; ctx->w = w;
+    ctx->n_maps = 0;
+    ctx->slots_valid = 0;
+    ctx->corr_active = true;
+    ctx->corr_exported = false;
+    return DDCCA_OK;
+}
+
+int ddcca_corr_accumulate(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls, int64_t n_img)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    if (!ctx->corr_active || ctx->corr_exported)
+        return fail(ctx, DDCCA_ESTATE, "ddcca_corr_accumulate needs an open ddcca_corr_begin");
+    if (n_img < 0) return fail(ctx, DDCCA_EINVAL, "negative sample count");
+    if (n_img == 0) return DDCCA_OK;
+    if (!v1 || !v2 || !cls) return fail(ctx, DDCCA_EINVAL, "null data pointer");
+    if (n_img * (int64_t)ctx->G > (int64_t)1 << 40) return fail(ctx, DDCCA_EINVAL, "too many maps");
+    int rc;
+    if ((rc = device_ready(ctx))) return rc;
+    const int64_t n_maps = n_img * ctx->G;
+    const int64_t P = (int64_t)ctx->h * ctx->w;
+    if ((rc = launch_label_check(ctx, cls, n_img, ctx->n_cls, (int *)ctx->flags.ptr))) return rc;
+    if ((rc = launch_class_sum(ctx, v1, v2, cls, n_img, ctx->G, ctx->n_cls, P, (double *)ctx->class_sum.ptr)))
+        return rc;
+    if ((rc = launch_patch_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, (double *)ctx->slots.ptr,
+                                max_gram_slots(ctx, ctx->k), &ctx->slots_valid)))
+        return rc;
+    ctx->n_maps += n_maps;
+    return DDCCA_OK;
+}
+
+int ddcca_corr_export(ddcca_ctx *ctx, double *C11, double *C22, double *C12, double *Cw, double *CT)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    if (!ctx->corr_active) return fail(ctx, DDCCA_ESTATE, "ddcca_corr_export needs ddcca_corr_begin");
+    if (ctx->n_maps == 0) return fail(ctx, DDCCA_ESTATE, "nothing accumulated");
+    int rc;
+    if ((rc = device_ready(ctx))) return rc;
+    if (!ctx->corr_exported && (rc = corr_finish(ctx))) return rc;
+    const size_t bytes = (size_t)ctx->k * ctx->k * ctx->k * ctx->k * sizeof(double);
+    double *dst[5] = {C11, C22, C12, Cw, CT};
+    for (int i = 0; i < 5; ++i)
+        if (dst[i])
+            DDCCA_HIP(ctx, hipMemcpyAsync(dst[i], (const char *)ctx->mats.ptr + i * bytes, bytes,
+                                          hipMemcpyDeviceToDevice, ctx->stream));
+    return DDCCA_OK;
+}
+
+static int check_solve_args(ddcca_ctx *ctx, int k, int L, double ridge, const void *W1, const void *W2,
+                            const void *rho)
+{
+    if (!valid_k(k)) return fail(ctx, DDCCA_EINVAL, "patch side k must be odd and in 3..9");
+    if (L < 1 || L > k * k - 1) return fail(ctx, DDCCA_EINVAL, "L must be in 1..k*k-1");
+    if (!(ridge > 0.0) || !(ridge < 1.0)) return fail(ctx, DDCCA_EINVAL, "ridge must be in (0,1)");
+    if (!W1 || !W2 || !rho) return fail(ctx, DDCCA_EINVAL, "null output pointer");
+    return DDCCA_OK;
+}
+
+int ddcca_solve_filters(ddcca_ctx *ctx, int L, double ridge, float *W1, float *W2, double *rho)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    if (!ctx->corr_active) return fail(ctx, DDCCA_ESTATE, "ddcca_solve_filters needs ddcca_corr_begin");
+    if (ctx->n_maps == 0) return fail(ctx, DDCCA_ESTATE, "nothing accumulated");
+    int rc;
+    if ((rc = check_solve_args(ctx, ctx->k, L, ridge, W1, W2, rho))) return rc;
+    if ((rc = device_ready(ctx))) return rc;
+    if (!ctx->corr_exported && (rc = corr_finish(ctx))) return rc;
+    const size_t DD = (size_t)ctx->k * ctx->k * ctx->k * ctx->k;
+    const double *m = (const double *)ctx->mats.ptr;
+    return launch_solve(ctx, m, m + DD, m + 3 * DD, m + 4 * DD, ctx->k, L, ridge, W1, W2, rho);
+}
+
+int ddcca_dcca_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const double *Cw, const double *CT,
+                     int k, int L, double ridge, float *W1, float *W2, double *rho)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    int rc;
+    if ((rc = check_solve_args(ctx, k, L, ridge, W1, W2, rho))) return rc;
+    if (!C11 || !C22 || !Cw || !CT) return fail(ctx, DDCCA_EINVAL, "null matrix pointer");
+    if ((rc = device_ready(ctx))) return rc;
+    return launch_solve(ctx, C11, C22, Cw, CT, k, L, ridge, W1, W2, rho);
+}
+
+int ddcca_learn_stage_filters(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls, int64_t n_img,
+                              int G, int h, int w, int n_cls, int k, int L, double ridge, float *W1, float *W2,
+                              double *rho)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    int rc;
+    if ((rc = check_image_args(ctx, n_img, h, w, k))) return rc;
+    if ((rc = check_solve_args(ctx, k, L, ridge, W1, W2, rho))) return rc;
+    if (n_img < 1) return fail(ctx, DDCCA_EINVAL, "need at least one sample to learn filters");
+    if (!v1 || !v2 || !cls) return fail(ctx, DDCCA_EINVAL, "null data pointer");
+    if ((rc = ddcca_corr_begin(ctx, k, n_cls, G, h, w))) return rc;
+    if ((rc = ddcca_corr_accumulate(ctx, v1, v2, cls, n_img))) return rc;
+    return ddcca_solve_filters(ctx, L, ridge, W1, W2, rho);
+}
+
+int ddcca_apply_stage(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L,
+                      float *out)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    int rc;
+    if ((rc = check_image_args(ctx, n, h, w, k))) return rc;
+    if (L < 1 || L > 64) return fail(ctx, DDCCA_EINVAL, "L must be in 1..64");
+    if (n == 0) return DDCCA_OK;
+    if (!in || !W || !out) return fail(ctx, DDCCA_EINVAL, "null data pointer");
+    if ((rc = device_ready(ctx))) return rc;
+    return launch_conv(ctx, in, n, h, w, W, k, L, out);
+}
+
+static int check_hist_args(ddcca_ctx *ctx, int64_t n, int L2, int h, int w, int bh, int bw, int sy, int sx)
+{
+    if (n < 0) return fail(ctx, DDCCA_EINVAL, "negative map count");
+    if (h < 1 || w < 1) return fail(ctx, DDCCA_EINVAL, "map height and width must be >= 1");
+    if ((int64_t)h * w > (int64_t)1 << 26) return fail(ctx, DDCCA_EINVAL, "map larger than 2^26 pixels");
+    if (L2 < 1 || L2 > DDCCA_MAX_L2) return fail(ctx, DDCCA_EINVAL, "L2 must be in 1..12");
+    if (bh < 1 || bw < 1 || bh > h || bw > w) return fail(ctx, DDCCA_EINVAL, "block must fit inside the map");
+    if (sy < 1 || sx < 1) return fail(ctx, DDCCA_EINVAL, "stride must be >= 1");
+    if ((int64_t)bh * bw > 65535) return fail(ctx, DDCCA_EOVERFLOW, "block area exceeds the uint16 count range");
+    return DDCCA_OK;
+}
+
+int ddcca_hash_histogram(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int block_h,
+                         int block_w, int stride_y, int stride_x, uint16_t *hist)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    int rc;
+    if ((rc = check_hist_args(ctx, n, L2, h, w, block_h, block_w, stride_y, stride_x))) return rc;
+    if (n == 0) return DDCCA_OK;
+    if (!maps || !hist) return fail(ctx, DDCCA_EINVAL, "null data pointer");
+    if ((rc = device_ready(ctx))) return rc;
+    const int64_t A = (int64_t)((h - block_h) / stride_y + 1) * ((w - block_w) / stride_x + 1);
+    return launch_hash_hist(ctx, maps, n, L2, h, w, block_h, block_w, stride_y, stride_x, hist, 1,
+                            A * ((int64_t)1 << L2));
+}
+
+int ddcca_extract_features(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h, int w,
+                           const ddcca_model *model, uint16_t *feat)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    if (!model) return fail(ctx, DDCCA_EINVAL, "null model");
+    int rc;
+    if ((rc = check_image_args(ctx, m, h, w, model->k))) return rc;
+    if (model->L1 < 1 || model->L1 > 64) return fail(ctx, DDCCA_EINVAL, "L1 must be in 1..64");
+    if ((rc = check_hist_args(ctx, m, model->L2, h, w, model->block_h, model->block_w, model->stride_y,
+                              model->stride_x)))
+        return rc;
+    if (model->batch_images < 0) return fail(ctx, DDCCA_EINVAL, "negative batch size");
+    for (int s = 0; s < 2; ++s)
+        for (int d = 0; d < 2; ++d)
+            if (!model->W[s][d]) return fail(ctx, DDCCA_EINVAL, "null filter pointer in model");
+    if (m == 0) return DDCCA_OK;
+    if (!v1 || !v2 || !feat) return fail(ctx, DDCCA_EINVAL, "null data pointer");
+    if ((rc = device_ready(ctx))) return rc;
+
+    const int L1 = model->L1, L2 = model->L2, k = model->k;
+    const int64_t P = (int64_t)h * w;
+    const int64_t A = (int64_t)((h - model->block_h) / model->stride_y + 1) *
+                      ((w - model->block_w) / model->stride_x + 1);
+    const int64_t bins = (int64_t)1 << L2;
+    // default batch: stage-2 maps of one view for one batch take about 4 GiB
+    int64_t batch = model->batch_images;
+    if (batch == 0) {
+        const double per_image = (double)L1 * L2 * P * sizeof(float);
+        batch = (int64_t)std::max(1.0, 4.0 * 1073741824.0 / per_image);
+    }
+    batch = std::min(batch, m);
+    if ((rc = ensure(ctx, ctx->maps1, (size_t)batch * L1 * P * sizeof(float)))) return rc;
+    if ((rc = ensure(ctx, ctx->maps2, (size_t)batch * L1 * L2 * P * sizeof(float)))) return rc;
+    float *y = (float *)ctx->maps1.ptr, *z = (float *)ctx->maps2.ptr;
+    const float *views[2] = {v1, v2};
+    for (int64_t m0 = 0; m0 < m; m0 += batch) {
+        const int64_t mb = std::min(batch, m - m0);
+        for (int d = 0; d < 2; ++d) {
+            if ((rc = launch_conv(ctx, views[d] + m0 * P, mb, h, w, model->W[0][d], k, L1, y))) return rc;
+            if ((rc = launch_conv(ctx, y, mb * L1, h, w, model->W[1][d], k, L2, z))) return rc;
+            uint16_t *dst = feat + ((m0 * 2 + d) * L1) * A * bins;
+            if ((rc = launch_hash_hist(ctx, z, mb * L1, L2, h, w, model->block_h, model->block_w, model->stride_y,
+                                       model->stride_x, dst, L1, 2 * L1 * A * bins)))
+                return rc;
+        }
+    }
+    return DDCCA_OK;
+}
+
+int ddcca_profile_enable(ddcca_ctx *ctx, int on)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    ctx->prof = on != 0;
+    return DDCCA_OK;
+}
+
+int ddcca_profile_reset(ddcca_ctx *ctx)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    if (ctx->n_cu) DDCCA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    for (ProfSlot &s : ctx->prof_slot) {
+        s.used = 0;
+        s.carried_ms = 0.0;
+        s.launches = 0;
+    }
+    return DDCCA_OK;
+}
+
+int ddcca_profile_read(ddcca_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    if (kernel_id < 0 || kernel_id >= DDCCA_K_COUNT || !total_ms || !launches)
+        return fail(ctx, DDCCA_EINVAL, "bad kernel id or null output");
+    ProfSlot &s = ctx->prof_slot[kernel_id];
+    double ms = s.carried_ms;
+    if (s.used) {
+        int rc;
+        if ((rc = device_ready(ctx))) return rc;
+        DDCCA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        for (size_t i = 0; i < s.used; ++i) {
+            float t = 0.f;
+            DDCCA_HIP(ctx, hipEventElapsedTime(&t, s.start[i], s.stop[i]));
+            ms += t;
+        }
+    }
+    *total_ms = ms;
+    *launches = s.launches;
+    return DDCCA_OK;
+}
+
+}  // extern "C"

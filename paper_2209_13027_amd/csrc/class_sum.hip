@@ -1,0 +1,113 @@
+// Class-conditioned part of the correlation step (Section II-A: within-class and
+// between-class correlation between the two views).  Patch extraction and mean removal
+// are linear in the image, so the per-pixel sum of a cell's patches is the patch of the
+// cell's SUM IMAGE.  These kernels build, per view, the sum image of every
+// (class, g) cell and of every g over all classes; the patch-Gram kernel then runs on
+// those few images and its cross-view block gives C_w and C_T.
+#include "ddcca_internal.h"
+
+namespace ddcca {
+
+__global__ void label_check_kernel(const int32_t *__restrict__ cls, int64_t n_img, int n_cls, int *flag)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_img) {
+        const int c = cls[i];
+        if (c < 0 || c >= n_cls) atomicOr(flag, 1);
+    }
+}
+
+// grid (pixel chunks, n_cls*G).  A workgroup owns 1024 pixels of one cell: it scans the
+// label array 64 labels at a time, and for every member sample (in ascending order, so
+// the sum is reproducible) adds that sample's map g to fp64 accumulators, both views.
+__global__ __launch_bounds__(256) void class_sum_kernel(const float *__restrict__ v1, const float *__restrict__ v2,
+                                                        const int32_t *__restrict__ cls, int64_t n_img, int G,
+                                                        int64_t P, double *__restrict__ sums, int64_t n_cell)
+{
+    const int cell = blockIdx.y;
+    const int c = cell / G, g = cell - c * G;
+    const int lane = threadIdx.x & 63;
+    const int64_t p0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    double a1[4] = {0, 0, 0, 0}, a2[4] = {0, 0, 0, 0};
+    const bool vec = (P & 3) == 0 && ((((uintptr_t)v1) | ((uintptr_t)v2)) & 15) == 0;
+    for (int64_t base = 0; base < n_img; base += 64) {
+        const int64_t idx = base + lane;
+        const int lab = idx < n_img ? cls[idx] : -1;
+        unsigned long long mask = __ballot(lab == c);
+        while (mask) {
+            const int j = __ffsll((long long)mask) - 1;
+            mask &= mask - 1;
+            const int64_t o = ((base + j) * G + g) * P + p0;
+            if (vec && p0 + 3 < P) {
+                const float4 x = *reinterpret_cast<const float4 *>(v1 + o);
+                const float4 y = *reinterpret_cast<const float4 *>(v2 + o);
+                a1[0] += x.x; a1[1] += x.y; a1[2] += x.z; a1[3] += x.w;
+                a2[0] += y.x; a2[1] += y.y; a2[2] += y.z; a2[3] += y.w;
+            } else {
+                for (int e = 0; e < 4; ++e)
+                    if (p0 + e < P) {
+                        a1[e] += v1[o + e];
+                        a2[e] += v2[o + e];
+                    }
+            }
+        }
+    }
+    double *s1 = sums + (int64_t)cell * P, *s2 = sums + (n_cell + cell) * P;
+    for (int e = 0; e < 4; ++e)
+        if (p0 + e < P) {
+            s1[p0 + e] += a1[e];
+            s2[p0 + e] += a2[e];
+        }
+}
+
+// img[view][cell][p] = (float) sums[view][cell][p];  img[view][n_cell + g][p] = (float) sum over classes.
+__global__ void class_finalize_kernel(const double *__restrict__ sums, int n_cls, int G, int64_t P,
+                                      float *__restrict__ img)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= P) return;
+    const int g = blockIdx.y, view = blockIdx.z;
+    const int64_t n_cell = (int64_t)n_cls * G;
+    const double *s = sums + view * n_cell * P;
+    float *o = img + view * (n_cell + G) * P;
+    double tot = 0.0;
+    for (int c = 0; c < n_cls; ++c) {
+        const double v = s[((int64_t)c * G + g) * P + p];
+        o[((int64_t)c * G + g) * P + p] = (float)v;
+        tot += v;
+    }
+    o[(n_cell + g) * P + p] = (float)tot;
+}
+
+int launch_label_check(ddcca_ctx *ctx, const int32_t *cls, int64_t n_img, int n_cls, int *flag)
+{
+    ProfScope prof(ctx, DDCCA_K_CLASS_SUM);
+    hipLaunchKernelGGL(label_check_kernel, dim3((unsigned)((n_img + 255) / 256)), dim3(256), 0, ctx->stream, cls, n_img,
+                       n_cls, flag);
+    DDCCA_HIP(ctx, hipGetLastError());
+    return DDCCA_OK;
+}
+
+int launch_class_sum(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls, int64_t n_img, int G,
+                     int n_cls, int64_t P, double *sums)
+{
+    ProfScope prof(ctx, DDCCA_K_CLASS_SUM);
+    const int64_t n_cell = (int64_t)n_cls * G;
+    const unsigned chunks = (unsigned)((P + 1023) / 1024);
+    if (n_cell > 65535) return fail(ctx, DDCCA_EINVAL, "n_cls * G must not exceed 65535");
+    hipLaunchKernelGGL(class_sum_kernel, dim3(chunks, (unsigned)n_cell), dim3(256), 0, ctx->stream, v1, v2, cls, n_img,
+                       G, P, sums, n_cell);
+    DDCCA_HIP(ctx, hipGetLastError());
+    return DDCCA_OK;
+}
+
+int launch_class_finalize(ddcca_ctx *ctx, const double *sums, int n_cls, int G, int64_t P, float *img)
+{
+    ProfScope prof(ctx, DDCCA_K_CLASS_SUM);
+    hipLaunchKernelGGL(class_finalize_kernel, dim3((unsigned)((P + 255) / 256), G, 2), dim3(256), 0, ctx->stream, sums,
+                       n_cls, G, P, img);
+    DDCCA_HIP(ctx, hipGetLastError());
+    return DDCCA_OK;
+}
+
+}  // namespace ddcca

@@ -1,0 +1,106 @@
+// Internal declarations shared by the HIP translation units of libddcca.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <algorithm>
+#include <string>
+#include <vector>
+
+#include "../../include/ddcca.h"
+
+namespace ddcca {
+
+// A grow-on-demand device buffer owned by the context.
+struct Buffer {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+};
+
+struct ProfSlot {
+    std::vector<hipEvent_t> start, stop;   // pairs recorded since the last reset
+    size_t used = 0;
+    double carried_ms = 0.0;               // time folded in from recycled pairs
+    int64_t launches = 0;
+};
+
+}  // namespace ddcca
+
+struct ddcca_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::string err;
+    int n_cu = 0;                           // compute units of the device (lazy)
+
+    // ---- correlation accumulation state (between corr_begin and export/solve)
+    bool corr_active = false;
+    bool corr_exported = false;
+    int k = 0, n_cls = 0, G = 0, h = 0, w = 0;
+    int64_t n_maps = 0;                     // maps accumulated so far (per view)
+    int slots_valid = 0;                    // Gram partial slots holding data
+    ddcca::Buffer slots;                    // [max_slots][tiles*256] double
+    ddcca::Buffer class_sum;                // [2][n_cls*G][h*w] double
+    ddcca::Buffer class_img;                // [2][n_cls*G + G][h*w] float
+    ddcca::Buffer stacked;                  // 3 x [tiles*256] double (main, class, total)
+    ddcca::Buffer seg;                      // reduction segments
+    ddcca::Buffer mats;                     // 5 x [D][D] double: C11 C22 C12 Cw CT
+    ddcca::Buffer solve_ws;                 // solver scratch (global part)
+    ddcca::Buffer flags;                    // int[4]: [0] label error
+    ddcca::Buffer maps1, maps2;             // extract_features scratch
+
+    // ---- profiling
+    bool prof = false;
+    ddcca::ProfSlot prof_slot[DDCCA_K_COUNT];
+};
+
+namespace ddcca {
+
+int fail(ddcca_ctx *ctx, int code, const std::string &msg);
+int hip_fail(ddcca_ctx *ctx, hipError_t e, const char *what);
+int ensure(ddcca_ctx *ctx, Buffer &b, size_t bytes);     // grow; contents undefined after growth
+int device_ready(ddcca_ctx *ctx);                        // set device, query CU count
+
+#define DDCCA_HIP(ctx, call)                                         \
+    do {                                                             \
+        hipError_t e__ = (call);                                     \
+        if (e__ != hipSuccess) return ddcca::hip_fail(ctx, e__, #call); \
+    } while (0)
+
+// RAII bracket: records an event pair around a launch when profiling is on.
+struct ProfScope {
+    ddcca_ctx *ctx;
+    int id;
+    ProfScope(ddcca_ctx *c, int kernel_id);
+    ~ProfScope();
+};
+
+// ---- geometry of the stacked (two views) patch Gram --------------------------------
+// The stacked patch vector z = [x1; x2] has 2D entries, D = k*k.  Its Gram is computed
+// in 16x16 tiles, upper block-triangle only; tile (bi,bj), bi <= bj, has index
+// tile_index(bi,bj).  Inside a slot, tile t / accumulator register v / lane l sits at
+// (t*4 + v)*64 + l and holds Gram entry (16*bi + 4*(l/16) + v, 16*bj + l%16).
+inline int gram_blocks(int k) { return (2 * k * k + 15) / 16; }
+inline int gram_tiles(int k) { int nb = gram_blocks(k); return nb * (nb + 1) / 2; }
+
+// ---- kernel launchers (each validates nothing; callers have validated) --------------
+int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w,
+                      int k, double *slots, int max_slots, int *slots_valid);
+int max_gram_slots(ddcca_ctx *ctx, int k);
+int launch_gram_reduce(ddcca_ctx *ctx, const double *slots, int n_slots, int k, double *stacked);
+int launch_export(ddcca_ctx *ctx, const double *stacked_main, const double *stacked_cls,
+                  const double *stacked_tot, int k, double n_patches, double *mats);
+int launch_label_check(ddcca_ctx *ctx, const int32_t *cls, int64_t n_img, int n_cls, int *flag);
+int launch_class_sum(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls, int64_t n_img,
+                     int G, int n_cls, int64_t P, double *sums /* [2][n_cls*G][P] */);
+int launch_class_finalize(ddcca_ctx *ctx, const double *sums, int n_cls, int G, int64_t P,
+                          float *img /* [2][n_cls*G + G][P] */);
+int launch_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const double *Cw, const double *CT,
+                 int k, int L, double ridge, float *W1, float *W2, double *rho);
+int launch_conv(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L,
+                float *out);
+// hist for map n goes to hist + (n / group) * group_stride + (n % group) * A * bins
+int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int bh, int bw,
+                     int sy, int sx, uint16_t *hist, int64_t group, int64_t group_stride);
+
+}  // namespace ddcca

@@ -1,0 +1,27 @@
+"""The whole hot path as a sequence of C ABI calls (no arithmetic here).
+
+fit():     learn stage 1 (Eq. 2-5) -> apply stage 1 (Eq. 6) -> learn stage 2 on the maps
+extract(): ddcca_extract_features (both stages + hashing + block histograms, Eq. 6-12)
+"""
+from __future__ import annotations
+
+import torch
+
+from .binding import Context
+
+
+def fit(ctx: Context, v1: torch.Tensor, v2: torch.Tensor, cls: torch.Tensor, n_cls: int, k: int, L1: int, L2: int,
+        ridge: float = 1e-4, keep_maps: bool = False) -> dict:
+    m, h, w = v1.shape
+    W1a, W2a, rho1 = ctx.learn_stage_filters(v1, v2, cls, 1, h, w, n_cls, k, L1, ridge)
+    y1 = ctx.apply_stage(v1, W1a)          # [m, L1, h, w]
+    y2 = ctx.apply_stage(v2, W2a)
+    W1b, W2b, rho2 = ctx.learn_stage_filters(y1, y2, cls, L1, h, w, n_cls, k, L2, ridge)
+    out = {"filters": (W1a, W2a, W1b, W2b), "rho": (rho1, rho2)}
+    if keep_maps:
+        out["maps"] = (y1, y2)
+    return out
+
+
+def extract(ctx: Context, v1, v2, filters, k, L1, L2, block, stride, batch_images=0, out=None):
+    return ctx.extract_features(v1, v2, filters, k, L1, L2, block, stride, batch_images, out)

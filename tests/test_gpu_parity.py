@@ -1,0 +1,269 @@
+"""GPU parity: every call of the C ABI against the CPU oracle, element by element, on the
+same seeded inputs.  Bars: correlation matrices rel. Frobenius error <= 1e-4; filters
+sign-normalised cosine >= 0.9999; hashing / histograms bit-exact on identical fp32 maps;
+end-to-end histogram relative L1 <= 1e-3."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+pytestmark = pytest.mark.gpu
+
+from paper_2209_13027_amd.workloads import WORKLOADS, make_views  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2209_13027_amd.binding import Context
+    c = Context(0)
+    yield c
+    c.close()
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def rel_fro(a, b):
+    return np.linalg.norm(a - b) / np.linalg.norm(b)
+
+
+def rand_views(rng, n, h, w):
+    v1 = rng.standard_normal((n, h, w)).astype(np.float32)
+    v2 = (np.abs(rng.standard_normal((n, h, w))) * 2 + 5).astype(np.float32)
+    return v1, v2
+
+
+# ------------------------------------------------------------------ hashing + histogram
+@pytest.mark.parametrize("n,L2,h,w,block,stride", [
+    (5, 4, 32, 32, 8, 4),            # tiny workload geometry
+    (3, 8, 112, 92, 7, 4),           # small-face geometry (drops one row and one column)
+    (4, 8, 128, 128, 16, 8),         # object / large-scale geometry
+    (2, 8, 256, 256, 32, 16),        # stress geometry
+    (3, 1, 17, 23, 5, 3),            # one bit, ragged everything
+    (2, 12, 40, 36, 9, 5),           # maximum code width
+    (2, 3, 9, 300, (9, 11), (1, 7)),  # single block row, rectangular block, wide map
+    (1, 5, 8, 8, 8, 8),              # one block = whole map
+])
+def test_hash_histogram_bit_exact(ctx, oracle, n, L2, h, w, block, stride):
+    rng = np.random.default_rng(100 + L2 + h)
+    Z = rng.standard_normal((n, L2, h, w)).astype(np.float32)
+    Z[rng.random(Z.shape) < 0.05] = 0.0                     # exact zeros hash to 0
+    Z[0, 0, 0, 0] = -0.0
+    got = ctx.hash_histogram(dev(Z), block, stride).cpu().numpy()
+    want = oracle.block_hist(oracle.hash_maps(Z), block, stride, 1 << L2)
+    assert got.shape == want.shape
+    assert np.array_equal(got.astype(np.int64), want)
+
+
+def test_hash_histogram_smooth_maps(ctx, oracle):
+    # smooth maps: long runs of equal codes (the common case on real maps)
+    rng = np.random.default_rng(7)
+    from scipy import ndimage
+    Z = ndimage.gaussian_filter(rng.standard_normal((6, 8, 128, 128)), (0, 0, 3, 3)).astype(np.float32)
+    got = ctx.hash_histogram(dev(Z), 16, 8).cpu().numpy()
+    want = oracle.block_hist(oracle.hash_maps(Z), 16, 8, 256)
+    assert np.array_equal(got.astype(np.int64), want)
+
+
+def test_hash_histogram_empty(ctx):
+    Z = torch.empty((0, 8, 16, 16), dtype=torch.float32, device="cuda")
+    out = ctx.hash_histogram(Z, 8, 4)
+    assert out.shape == (0, 3, 3, 256)
+
+
+# ------------------------------------------------------------------ convolution
+@pytest.mark.parametrize("n,h,w,k,L", [
+    (3, 32, 32, 5, 4), (2, 112, 92, 7, 8), (2, 128, 128, 5, 8), (1, 256, 256, 9, 8),
+    (3, 19, 70, 3, 5), (2, 5, 7, 9, 3), (1, 1, 1, 3, 2), (2, 33, 130, 7, 11),
+])
+def test_apply_stage(ctx, oracle, n, h, w, k, L):
+    rng = np.random.default_rng(200 + k + h)
+    V, _ = rand_views(rng, n, h, w)
+    F = rng.standard_normal((L, k, k)).astype(np.float32)
+    got = ctx.apply_stage(dev(V), dev(F)).cpu().numpy()
+    want = oracle.conv(V, F)
+    scale = np.abs(F).sum(axis=(1, 2)).max() * np.abs(V).max()
+    assert np.abs(got - want).max() <= 2e-6 * scale
+
+
+def test_apply_stage_empty(ctx):
+    x = torch.empty((0, 8, 8), dtype=torch.float32, device="cuda")
+    W = torch.zeros((4, 5, 5), dtype=torch.float32, device="cuda")
+    assert ctx.apply_stage(x, W).shape == (0, 4, 8, 8)
+
+
+# ------------------------------------------------------------------ correlation matrices
+def gpu_matrices(ctx, V1, V2, cls, n_cls, G, k, cuts=None):
+    n_img = len(cls)
+    h, w = V1.shape[-2:]
+    ctx.corr_begin(k, n_cls, G, h, w)
+    cuts = cuts or [0, n_img]
+    d1, d2, dc = dev(V1), dev(V2), dev(cls.astype(np.int32))
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        ctx.corr_accumulate(d1[a * G:b * G], d2[a * G:b * G], dc[a:b])
+    out = {k_: v.cpu().numpy() for k_, v in ctx.corr_export(k).items()}
+    ctx.status()
+    return out
+
+
+def oracle_matrices(oracle, V1, V2, cls, n_cls, G, k):
+    grp = np.tile(np.arange(G, dtype=np.int32), len(cls))
+    return oracle.stage_matrices(V1, V2, np.repeat(cls, G), grp, n_cls, G, k)
+
+
+@pytest.mark.parametrize("n_img,G,h,w,k,n_cls", [
+    (8, 1, 32, 32, 5, 4),        # tiny geometry
+    (6, 1, 112, 92, 7, 3),       # small-face geometry
+    (4, 2, 40, 52, 9, 2),        # k=9, two groups
+    (5, 3, 21, 30, 3, 2),        # k=3, ragged rows (21) and columns (30 = 4*7+2)
+    (3, 1, 37, 133, 5, 3),       # two column tiles, ragged tail (133 = 4*33+1)
+    (2, 4, 16, 260, 7, 2),       # three column tiles
+    (1, 1, 3, 3, 7, 1),          # image smaller than the patch
+])
+def test_corr_matrices(ctx, oracle, n_img, G, h, w, k, n_cls):
+    rng = np.random.default_rng(300 + k + h)
+    V1, V2 = rand_views(rng, n_img * G, h, w)
+    cls = rng.integers(0, n_cls, size=n_img).astype(np.int32)
+    got = gpu_matrices(ctx, V1, V2, cls, n_cls, G, k)
+    want = oracle_matrices(oracle, V1, V2, cls, n_cls, G, k)
+    for name in ("C11", "C22", "C12", "Cw", "CT"):
+        assert rel_fro(got[name], want[name]) <= 1e-4, name
+        assert rel_fro(got[name], want[name]) <= 2e-6, (name, "looser than expected for fp32 products")
+
+
+def test_corr_batch_split_invariance(ctx):
+    # Eq. 15: any split of the samples into batches gives the same matrices
+    rng = np.random.default_rng(42)
+    V1, V2 = rand_views(rng, 14, 24, 28)
+    cls = rng.integers(0, 3, size=7).astype(np.int32)
+    ref = gpu_matrices(ctx, V1, V2, cls, 3, 2, 5)
+    for cuts in ([0, 1, 7], [0, 3, 4, 7], list(range(8))):
+        got = gpu_matrices(ctx, V1, V2, cls, 3, 2, 5, cuts)
+        for name in ref:
+            assert rel_fro(got[name], ref[name]) <= 1e-6, (name, cuts)
+
+
+def test_corr_reproducible(ctx):
+    rng = np.random.default_rng(43)
+    V1, V2 = rand_views(rng, 40, 32, 32)
+    cls = rng.integers(0, 4, size=40).astype(np.int32)
+    a = gpu_matrices(ctx, V1, V2, cls, 4, 1, 5)
+    b = gpu_matrices(ctx, V1, V2, cls, 4, 1, 5)
+    for name in a:
+        assert np.array_equal(a[name], b[name]), name
+
+
+def test_label_out_of_range_is_reported(ctx):
+    from paper_2209_13027_amd.binding import DdccaError, ELABEL
+    rng = np.random.default_rng(44)
+    V1, V2 = rand_views(rng, 4, 16, 16)
+    ctx.corr_begin(5, 2, 1, 16, 16)
+    ctx.corr_accumulate(dev(V1), dev(V2), dev(np.array([0, 1, 2, 1], dtype=np.int32)))
+    with pytest.raises(DdccaError) as e:
+        ctx.status()
+    assert e.value.code == ELABEL
+    ctx.status()    # flag is cleared after being reported
+
+
+# ------------------------------------------------------------------ DCCA solve
+def filter_cosines(got, want):
+    g = got.reshape(got.shape[0], -1).astype(np.float64)
+    w = want.reshape(want.shape[0], -1)
+    return np.einsum("ga,ga->g", g, w) / (np.linalg.norm(g, axis=1) * np.linalg.norm(w, axis=1))
+
+
+@pytest.mark.parametrize("name,mpc", [("tiny", None), ("small_face", 3), ("stress", 1)])
+def test_dcca_solve_on_oracle_matrices(ctx, oracle, name, mpc):
+    wl = WORKLOADS[name]
+    v1, v2, cls = make_views(wl, max_per_class=mpc)
+    if name == "stress":
+        v1, v2 = v1[:, :64, :64], v2[:, :64, :64]
+    mats = oracle.stage_matrices(v1, v2, cls, np.zeros(len(cls), np.int32), wl.n_classes, 1, wl.k)
+    sol = oracle.dcca_solve(mats["C11"], mats["C22"], mats["Ctilde"], wl.L1)
+    W1, W2, rho = ctx.dcca_solve(dev(mats["C11"]), dev(mats["C22"]), dev(mats["Cw"]), dev(mats["CT"]), wl.k, wl.L1)
+    W1, W2, rho = W1.cpu().numpy(), W2.cpu().numpy(), rho.cpu().numpy()
+    assert np.allclose(rho, sol["rho"], rtol=1e-9)
+    assert filter_cosines(W1, sol["W1"]).min() >= 0.9999      # signed: the sign rule must agree too
+    assert filter_cosines(W2, sol["W2"]).min() >= 0.9999
+    assert np.abs(W1.reshape(wl.L1, -1) - sol["W1"]).max() <= 1e-5 * np.abs(sol["W1"]).max()
+    # constraint of Eq. 3 on the fp32 filters
+    w1 = W1.reshape(wl.L1, -1).astype(np.float64)
+    assert np.abs(w1 @ sol["B1"] @ w1.T - np.eye(wl.L1)).max() <= 1e-4
+
+
+def test_dcca_solve_max_filters(ctx, oracle):
+    rng = np.random.default_rng(9)
+    V1, V2 = rand_views(rng, 6, 20, 20)
+    cls = np.array([0, 1, 2, 0, 1, 2], np.int32)
+    mats = oracle.stage_matrices(V1, V2, cls, np.zeros(6, np.int32), 3, 1, 3)
+    L = 8                                                       # D - 1
+    sol = oracle.dcca_solve(mats["C11"], mats["C22"], mats["Ctilde"], L)
+    W1, W2, rho = ctx.dcca_solve(dev(mats["C11"]), dev(mats["C22"]), dev(mats["Cw"]), dev(mats["CT"]), 3, L)
+    assert np.allclose(rho.cpu().numpy(), sol["rho"], rtol=1e-8, atol=1e-12)
+    ok = sol["gap"] > 1e-3
+    assert np.abs(filter_cosines(W1.cpu().numpy(), sol["W1"]))[ok].min() >= 0.9999
+
+
+# ------------------------------------------------------------------ learn_stage_filters / end to end
+def hist_rel_l1(got, want):
+    return np.abs(got.astype(np.int64) - want).sum() / want.sum()
+
+
+def run_gpu_path(ctx, wl, v1, v2, cls, batch_images=0):
+    from paper_2209_13027_amd import pipeline
+    d1, d2, dc = dev(v1), dev(v2), dev(cls)
+    model = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2, keep_maps=True)
+    feat = pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride, batch_images)
+    ctx.status()
+    return model, feat
+
+
+def check_against_oracle(oracle, wl, v1, v2, cls, model, feat):
+    ref = oracle.two_stage(v1, v2, cls, wl.n_classes, wl.k, wl.L1, wl.L2, wl.block)
+    names = ["stage1.W1", "stage1.W2", "stage2.W1", "stage2.W2"]
+    refs = [ref["stage1"]["W1"], ref["stage1"]["W2"], ref["stage2"]["W1"], ref["stage2"]["W2"]]
+    gaps = [ref["stage1"]["gap"], ref["stage1"]["gap"], ref["stage2"]["gap"], ref["stage2"]["gap"]]
+    for nm, W, R, gap in zip(names, model["filters"], refs, gaps):
+        cos = filter_cosines(W.cpu().numpy(), R)
+        assert cos[gap > 1e-3].min() >= 0.9999, (nm, cos, gap)
+    assert np.allclose(model["rho"][0].cpu().numpy(), ref["stage1"]["rho"], rtol=1e-4)
+    assert np.allclose(model["rho"][1].cpu().numpy(), ref["stage2"]["rho"], rtol=1e-4)
+    got = feat.cpu().numpy()
+    assert got.shape == ref["hist"].shape
+    assert np.all(got.sum(axis=-1) == wl.block ** 2)
+    l1 = hist_rel_l1(got, ref["hist"])
+    assert l1 <= 1e-3, l1
+    return ref, l1
+
+
+def test_end_to_end_tiny(ctx, oracle):
+    wl = WORKLOADS["tiny"]
+    v1, v2, cls = make_views(wl)
+    model, feat = run_gpu_path(ctx, wl, v1, v2, cls, batch_images=16)     # 40 images in 3 ragged batches
+    check_against_oracle(oracle, wl, v1, v2, cls, model, feat)
+
+
+def test_extract_is_bit_exact_given_gpu_maps(ctx, oracle):
+    # the output layer fed with the GPU's own stage-2 maps must reproduce extract_features bit for bit
+    wl = WORKLOADS["tiny"]
+    v1, v2, cls = make_views(wl)
+    model, feat = run_gpu_path(ctx, wl, v1, v2, cls)
+    y = model["maps"]
+    for d in range(2):
+        z = ctx.apply_stage(y[d].reshape(-1, wl.h, wl.w), model["filters"][2 + d])
+        want = oracle.block_hist(oracle.hash_maps(z.cpu().numpy()), wl.block, wl.stride, 1 << wl.L2)
+        got = feat[:, d].cpu().numpy().reshape(want.shape)
+        assert np.array_equal(got.astype(np.int64), want)
+
+
+def test_end_to_end_small_face_slice(ctx, oracle):
+    wl = WORKLOADS["small_face"]
+    v1, v2, cls = make_views(wl, max_per_class=2)                 # 80 images, all 40 classes
+    model, feat = run_gpu_path(ctx, wl, v1, v2, cls)
+    check_against_oracle(oracle, wl, v1, v2, cls, model, feat)
