@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the two-stage DDCCANet hot path on one MI355X.
+
+One "step" = the whole path on one synthetic workload, inputs already in HBM:
+  learn stage-1 filters -> apply stage 1 (both views) -> learn stage-2 filters on the maps
+  -> extract_features (stage-1 conv, stage-2 conv, hashing + block histograms) for all images.
+Prints ONE JSON line: images/s, the roofline of the dominant kernel (patch-Gram, fp32 MFMA),
+per-kernel figures, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_FP32_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
+PEAK_FP32_VALU_TFLOPS = 157.3
+
+
+def algorithmic_work(wl, M):
+    """Algorithmic flops / bytes per step for each kernel (both stages, both views)."""
+    D, P = wl.D, wl.h * wl.w
+    L1, L2, C = wl.L1, wl.L2, wl.n_classes
+    by, bx = wl.blocks
+    A, bins = by * bx, 1 << wl.L2
+    per_patch = 2.0 * (2 * D * D + D)                 # two symmetric blocks + one full block
+    gram_main = per_patch * (M * P + M * L1 * P)
+    gram_class = 2.0 * D * D * P * ((C * 1 + 1) + (C * L1 + L1))   # cross block of class-sum / total images
+    # conv: read 4 B, write 4L B per input pixel; stage 1 runs in fit and again in extract
+    conv_bytes = 2 * (2 * M * P * (4 + 4 * L1)) + 2 * M * L1 * P * (4 + 4 * L2)
+    conv_flops = 2 * (2 * M * P * 2 * D * L1) + 2 * M * L1 * P * 2 * D * L2
+    hist_bytes = 2 * M * L1 * (L2 * P * 4 + A * bins * 2)
+    class_bytes = 2 * 4 * (M * P + M * L1 * P)       # every map of both views read once
+    return {
+        "gram_flops": gram_main + gram_class, "gram_launches_per_step": 6,
+        "conv_bytes": conv_bytes, "conv_flops": conv_flops, "hist_bytes": hist_bytes,
+        "class_sum_bytes": class_bytes,
+    }
+
+
+def run_cpu_baseline(wl, budget_images):
+    """Time the fp64 CPU oracle (whole path) on a bounded class-balanced sample."""
+    from oracle import ddcca_oracle as oracle
+    from paper_2209_13027_amd.workloads import make_views
+    per_class = max(1, budget_images // wl.n_classes)
+    v1, v2, cls = make_views(wl, max_per_class=per_class)
+    t0 = time.perf_counter()
+    oracle.two_stage(v1, v2, cls, wl.n_classes, wl.k, wl.L1, wl.L2, wl.block)
+    dt = time.perf_counter() - t0
+    n = int(v1.shape[0])
+    return {
+        "value": n / dt, "unit": "images/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"{n} of {wl.M} images ({per_class} per class), whole path (learn both stages + extract), "
+                  f"fp64, {dt:.1f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="small_face")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-images", type=int, default=0, help="images in the CPU-oracle sample (0 = default)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2209_13027_amd import pipeline
+    from paper_2209_13027_amd.binding import Context
+    from paper_2209_13027_amd.workloads import WORKLOADS, make_views
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    wl = WORKLOADS[args.workload]
+    v1, v2, cls = make_views(wl)
+    M = int(v1.shape[0])
+    ctx = Context(0)
+    d1, d2, dc = torch.from_numpy(v1).cuda(), torch.from_numpy(v2).cuda(), torch.from_numpy(cls).cuda()
+    by, bx = wl.blocks
+    feat = torch.empty((M, 2, wl.L1, by, bx, 1 << wl.L2), dtype=torch.uint16, device="cuda")
+    batch = wl.extract_batch
+
+    def step():
+        model = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
+        pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride, batch, out=feat)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.status()
+
+    # timed region, per-kernel HIP events recorded by the library on its stream
+    ctx.profile_reset()
+    ctx.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx.profile_enable(False)
+    prof = ctx.profile_read()
+
+    # the same region once more without events, to show their cost
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt_plain = time.perf_counter() - t1
+    ctx.status()
+
+    work = algorithmic_work(wl, M)
+    K = args.steps
+    gram_ms = prof["gram"]["ms"] / max(1, prof["gram"]["launches"])
+    gram_flops_per_launch = work["gram_flops"] * K / max(1, prof["gram"]["launches"])
+    gram_tflops = gram_flops_per_launch / (gram_ms * 1e-3) / 1e12 if gram_ms > 0 else 0.0
+    conv_ms = prof["conv"]["ms"] / K
+    hist_ms = prof["hash_hist"]["ms"] / K
+    kernels = {
+        "gram": {"ms_per_step": prof["gram"]["ms"] / K, "launches_per_step": prof["gram"]["launches"] / K,
+                 "useful_tflops": gram_tflops, "frac_mfma_fp32": gram_tflops / PEAK_MFMA_FP32_TFLOPS},
+        "class_sum": {"ms_per_step": prof["class_sum"]["ms"] / K,
+                      "gbs": work["class_sum_bytes"] / (prof["class_sum"]["ms"] / K * 1e-3) / 1e9
+                      if prof["class_sum"]["ms"] > 0 else 0.0},
+        "reduce": {"ms_per_step": prof["reduce"]["ms"] / K},
+        "solve": {"ms_per_step": prof["solve"]["ms"] / K, "launches_per_step": prof["solve"]["launches"] / K},
+        "conv": {"ms_per_step": conv_ms, "gbs": work["conv_bytes"] / (conv_ms * 1e-3) / 1e9 if conv_ms > 0 else 0.0,
+                 "frac_hbm": work["conv_bytes"] / (conv_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if conv_ms > 0 else 0.0,
+                 "tflops": work["conv_flops"] / (conv_ms * 1e-3) / 1e12 if conv_ms > 0 else 0.0},
+        "hash_hist": {"ms_per_step": hist_ms,
+                      "gbs": work["hist_bytes"] / (hist_ms * 1e-3) / 1e9 if hist_ms > 0 else 0.0,
+                      "frac_hbm": work["hist_bytes"] / (hist_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if hist_ms > 0 else 0.0},
+    }
+    out = {
+        "metric": "images/s for 2-stage DDCCANet extraction (learn both stages + extract features)",
+        "value": M * K / dt, "unit": "images/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": dt / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "images": M, "classes": wl.n_classes, "h": wl.h, "w": wl.w, "k": wl.k,
+                   "L1": wl.L1, "L2": wl.L2, "block": wl.block, "stride": wl.stride, "bins": 1 << wl.L2,
+                   "feature_len": wl.feature_len},
+        "roofline": {"bound": "mfma", "kernel": "patch_gram_kernel", "achieved": gram_tflops,
+                     "peak": PEAK_MFMA_FP32_TFLOPS, "unit": "TFLOP/s", "frac": gram_tflops / PEAK_MFMA_FP32_TFLOPS,
+                     "traffic": None, "avg_launch_ms": gram_ms,
+                     "algorithmic_flop_per_launch": gram_flops_per_launch},
+        "kernels": kernels,
+        "ms_per_step_without_events": dt_plain / K * 1e3,
+    }
+    if not args.no_cpu_baseline:
+        default_images = {"tiny": 40, "small_face": 80, "object": 64, "large_scale": 257, "stress": 16}
+        n_cpu = args.cpu_images or default_images.get(wl.name, 64)
+        out["cpu_baseline"] = run_cpu_baseline(wl, n_cpu)
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
