@@ -114,12 +114,12 @@ static int corr_finish(ddcca_ctx *ctx)
     const size_t view_stride = (size_t)(n_cell + ctx->G) * P;
     const int max_slots = max_gram_slots(ctx, k);
     int valid = 0;
-    if ((rc = launch_patch_gram(ctx, img, img + view_stride, n_cell, ctx->h, ctx->w, k,
+    if ((rc = launch_patch_gram(ctx, img, img + view_stride, n_cell, ctx->h, ctx->w, k, true,
                                 (double *)ctx->slots.ptr, max_slots, &valid))) return rc;
     if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, valid, k, st + E))) return rc;
     valid = 0;
     if ((rc = launch_patch_gram(ctx, img + (size_t)n_cell * P, img + view_stride + (size_t)n_cell * P, ctx->G,
-                                ctx->h, ctx->w, k, (double *)ctx->slots.ptr, max_slots, &valid))) return rc;
+                                ctx->h, ctx->w, k, true, (double *)ctx->slots.ptr, max_slots, &valid))) return rc;
     if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, valid, k, st + 2 * E))) return rc;
     const double N = (double)ctx->n_maps * (double)P;
     if ((rc = launch_export(ctx, st, st + E, st + 2 * E, k, N, (double *)ctx->mats.ptr))) return rc;
@@ -228,7 +228,7 @@ int ddcca_corr_accumulate(ddcca_ctx *ctx, const float *v1, const float *v2, cons
     if ((rc = launch_label_check(ctx, cls, n_img, ctx->n_cls, (int *)ctx->flags.ptr))) return rc;
     if ((rc = launch_class_sum(ctx, v1, v2, cls, n_img, ctx->G, ctx->n_cls, P, (double *)ctx->class_sum.ptr)))
         return rc;
-    if ((rc = launch_patch_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, (double *)ctx->slots.ptr,
+    if ((rc = launch_patch_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, false, (double *)ctx->slots.ptr,
                                 max_gram_slots(ctx, ctx->k), &ctx->slots_valid)))
         return rc;
     ctx->n_maps += n_maps;

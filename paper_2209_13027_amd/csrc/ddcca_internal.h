@@ -84,8 +84,10 @@ inline int gram_blocks(int k) { return (2 * k * k + 15) / 16; }
 inline int gram_tiles(int k) { int nb = gram_blocks(k); return nb * (nb + 1) / 2; }
 
 // ---- kernel launchers (each validates nothing; callers have validated) --------------
+// cross_only: accumulate only the view-1 x view-2 block (the other tiles of the slots are
+// then undefined and must not be read).
 int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w,
-                      int k, double *slots, int max_slots, int *slots_valid);
+                      int k, bool cross_only, double *slots, int max_slots, int *slots_valid);
 int max_gram_slots(ddcca_ctx *ctx, int k);
 int launch_gram_reduce(ddcca_ctx *ctx, const double *slots, int n_slots, int k, double *stacked);
 int launch_export(ddcca_ctx *ctx, const double *stacked_main, const double *stacked_cls,

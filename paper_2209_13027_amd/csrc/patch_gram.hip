@@ -14,7 +14,7 @@ namespace ddcca {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int GRAM_THREADS = 256;          // 4 wavefronts; each owns every 4th patch row of the tile
+constexpr int GRAM_THREADS = 256;          // 4 wavefronts
 constexpr int GRAM_TH = 16;                // patch rows per tile
 constexpr int GRAM_TW_MAX = 128;           // patch columns per tile (multiple of 4)
 
@@ -29,24 +29,153 @@ struct GramParams {
     int slots_valid;                       // slots below this hold earlier partial sums
 };
 
-template <int KS>
+// Compile-time geometry.  TSPLIT wavefronts share one group of patch rows and split the
+// tile list between them (tile t belongs to role t % TSPLIT), which keeps the
+// accumulators of one wavefront within the register budget for large k.
+// CROSS restricts the tile list to the view-1 x view-2 block (all the class-conditioned
+// matrices need).
+template <int KS, int TSPLIT_, bool CROSS_>
 struct GramGeom {
     static constexpr int D = KS * KS;
     static constexpr int R = (KS - 1) / 2;
     static constexpr int NB = (2 * D + 15) / 16;
-    static constexpr int NT = NB * (NB + 1) / 2;
+    static constexpr int NT = NB * (NB + 1) / 2;         // slot layout always covers the full triangle
+    static constexpr int TSPLIT = TSPLIT_;
+    static constexpr bool CROSS = CROSS_;
+    static constexpr int NPG = 4 / TSPLIT_;              // patch-row groups per workgroup
+    static constexpr int B1_END = (D + 15) / 16;         // blocks [0, B1_END) contain view-1 rows
+    static constexpr int B2_BEGIN = D / 16;              // blocks [B2_BEGIN, NB) contain view-2 rows
+    static constexpr bool tile_used(int bi, int bj) { return !CROSS_ || (bi < B1_END && bj >= B2_BEGIN); }
+    static constexpr int used_tiles()
+    {
+        int n = 0;
+        for (int bi = 0; bi < NB; ++bi)
+            for (int bj = bi; bj < NB; ++bj) n += tile_used(bi, bj) ? 1 : 0;
+        return n;
+    }
+    static constexpr int NACC = (used_tiles() + TSPLIT_ - 1) / TSPLIT_;   // accumulator tiles per wavefront
 };
 
-template <int KS>
-__global__ __launch_bounds__(GRAM_THREADS) void patch_gram_kernel(GramParams p)
+template <typename G, int ROLE>
+__device__ __forceinline__ void gram_mfma_step(const float (&z)[G::NB], floatx4 (&acc)[G::NACC])
 {
-    using G = GramGeom<KS>;
+    int u = 0;       // index among used tiles
+#pragma unroll
+    for (int bi = 0; bi < G::NB; ++bi)
+#pragma unroll
+        for (int bj = bi; bj < G::NB; ++bj) {
+            if (G::tile_used(bi, bj)) {
+                if (u % G::TSPLIT == ROLE)
+                    acc[u / G::TSPLIT] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[bi], z[bj], acc[u / G::TSPLIT], 0, 0, 0);
+                ++u;
+            }
+        }
+}
+
+// All k-steps of this wavefront's patch rows of the staged tile.
+template <typename G, int ROLE>
+__device__ __forceinline__ void gram_rows(const float *pix, const float *mean, int pitch, int tw, int rows, int cols,
+                                          int pg, int q, const int (&pix_off)[G::NB], const int (&mean_off)[G::NB],
+                                          floatx4 (&acc)[G::NACC])
+{
+    constexpr int NB = G::NB;
+    const int full = cols >> 2, tail = cols & 3;
+    for (int py = pg; py < rows; py += G::NPG) {
+        const float *prow = pix + py * pitch;
+        const float *mrow = mean + py * tw;
+        float z[NB], zn[NB];
+        if (full > 0) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) z[b] = prow[pix_off[b]] - mrow[mean_off[b]];
+        }
+        for (int kx = 0; kx < full; ++kx) {
+            // operands of the next step are fetched while this step's MFMAs run
+            const int nx = (kx + 1 < full) ? 4 * (kx + 1) : 4 * kx;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) zn[b] = prow[pix_off[b] + nx] - mrow[mean_off[b] + nx];
+            gram_mfma_step<G, ROLE>(z, acc);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) z[b] = zn[b];
+        }
+        if (tail) {                                   // ragged end of the row: patches past the image add 0
+            const bool ok = q < tail;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const float v = prow[pix_off[b] + 4 * full] - mrow[mean_off[b] + 4 * full];
+                z[b] = ok ? v : 0.f;
+            }
+            gram_mfma_step<G, ROLE>(z, acc);
+        }
+    }
+}
+
+// Tile number (position in the full upper block triangle) of the u-th used tile.
+template <typename G>
+struct GramTileTable {
+    int t[G::NT];
+    constexpr GramTileTable() : t()
+    {
+        int u = 0, idx = 0;
+        for (int bi = 0; bi < G::NB; ++bi)
+            for (int bj = bi; bj < G::NB; ++bj, ++idx)
+                if (G::tile_used(bi, bj)) t[u++] = idx;
+        for (; u < G::NT; ++u) t[u] = 0;
+    }
+};
+
+// Add this wavefront's accumulators into the workgroup's fp32 staging buffer (first writer
+// stores, later ones add) and clear them.
+template <typename G>
+__device__ __forceinline__ void gram_stage_acc(floatx4 (&acc)[G::NACC], float *stage, int lane, bool first)
+{
+#pragma unroll
+    for (int a = 0; a < G::NACC; ++a) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float *dst = stage + (a * 4 + v) * 64 + lane;
+            *dst = first ? acc[a][v] : *dst + acc[a][v];
+        }
+        acc[a] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+}
+
+// Workgroup-wide flush: the patch-row groups' fp32 accumulators are summed in LDS (one role
+// at a time) and folded into the workgroup's fp64 slot.  Must be called by all threads.
+template <typename G>
+__device__ __forceinline__ void gram_flush(floatx4 (&acc)[G::NACC], float *stage, double *slot, int pg, int role,
+                                           bool rmw)
+{
+    static constexpr GramTileTable<G> table{};
+    const int lane = threadIdx.x & 63;
+    for (int r = 0; r < G::TSPLIT; ++r) {
+        for (int g = 0; g < G::NPG; ++g) {
+            if (pg == g && role == r) gram_stage_acc<G>(acc, stage, lane, g == 0);
+            __syncthreads();
+        }
+        for (int e = threadIdx.x; e < G::NACC * 256; e += GRAM_THREADS) {
+            const int u = (e >> 8) * G::TSPLIT + r;
+            if (u < G::used_tiles()) {
+                double *dst = slot + (size_t)table.t[u] * 256 + (e & 255);
+                const double add = (double)stage[e];
+                *dst = rmw ? *dst + add : add;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int KS, int TSPLIT, bool CROSS, int WAVES_PER_EU>
+__global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(GramParams p)
+{
+    using G = GramGeom<KS, TSPLIT, CROSS>;
     constexpr int D = G::D, R = G::R, NB = G::NB, NT = G::NT;
     extern __shared__ float lds[];
     float *pix = lds;                                     // [2][GRAM_TH + 2R][pitch]
     float *mean = lds + 2 * p.view_stride;                // [2][GRAM_TH][tw]
+    float *hsum = mean + 2 * GRAM_TH * p.tw;              // [2][GRAM_TH + 2R][tw] horizontal window sums
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int q = lane >> 4, i = lane & 15;
+    const int pg = wave / TSPLIT, role = wave % TSPLIT;
     const int mean_view_stride = GRAM_TH * p.tw;
 
     // per-lane operand offsets for each 16-row block of the stacked vector
@@ -62,9 +191,9 @@ __global__ __launch_bounds__(GRAM_THREADS) void patch_gram_kernel(GramParams p)
         mean_off[b] = view * mean_view_stride + q;
     }
 
-    floatx4 acc[NT];
+    floatx4 acc[G::NACC];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < G::NACC; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     // contiguous range of work items for this workgroup
     const int64_t per = p.n_items / gridDim.x, extra = p.n_items % gridDim.x;
@@ -72,9 +201,8 @@ __global__ __launch_bounds__(GRAM_THREADS) void patch_gram_kernel(GramParams p)
     const int64_t count = per + (blockIdx.x < extra ? 1 : 0);
     const int tiles = p.tiles_x * p.tiles_y;
     const int64_t P = (int64_t)p.h * p.w;
-    const int slot = blockIdx.x * 4 + wave;
-    double *my_slot = p.slots + (size_t)slot * NT * 256;
-    bool rmw = slot < p.slots_valid;
+    double *my_slot = p.slots + (size_t)blockIdx.x * NT * 256;
+    bool rmw = (int)blockIdx.x < p.slots_valid;
     int since_flush = 0;
     constexpr int PH = GRAM_TH + 2 * R;
     const int pw = p.tw + 2 * R;
@@ -99,72 +227,43 @@ __global__ __launch_bounds__(GRAM_THREADS) void patch_gram_kernel(GramParams p)
             pix[p.view_stride + yy * p.pitch + xx] = b;
         }
         __syncthreads();
-        // per-patch means (zero padding counts as zeros)
+        // per-patch means (zero padding counts as zeros), separable: horizontal window sums, then
+        // vertical sums of those
+        for (int e = threadIdx.x; e < 2 * PH * p.tw; e += GRAM_THREADS) {
+            const int view = e / (PH * p.tw);
+            const int r2 = e - view * PH * p.tw;
+            const int yy = r2 / p.tw, px = r2 - yy * p.tw;
+            const float *src = pix + view * p.view_stride + yy * p.pitch + px;
+            float hs = 0.f;
+#pragma unroll
+            for (int dx = 0; dx < KS; ++dx) hs += src[dx];
+            hsum[e] = hs;
+        }
+        __syncthreads();
         for (int e = threadIdx.x; e < 2 * GRAM_TH * p.tw; e += GRAM_THREADS) {
             const int view = e / (GRAM_TH * p.tw);
-            const int r = e - view * GRAM_TH * p.tw;
-            const int py = r / p.tw, px = r - py * p.tw;
-            const float *src = pix + view * p.view_stride + py * p.pitch + px;
-            float s = 0.f;
+            const int r2 = e - view * GRAM_TH * p.tw;
+            const float *src = hsum + view * PH * p.tw + r2;
+            float sum = 0.f;
 #pragma unroll
-            for (int dy = 0; dy < KS; ++dy)
-#pragma unroll
-                for (int dx = 0; dx < KS; ++dx) s += src[dy * p.pitch + dx];
-            mean[view * mean_view_stride + r] = s * (1.0f / D);
+            for (int dy = 0; dy < KS; ++dy) sum += src[dy * p.tw];
+            mean[e] = sum * (1.0f / D);
         }
         __syncthreads();
 
         const int rows = min(GRAM_TH, p.h - ty * GRAM_TH);
         const int cols = min(p.tw, p.w - tx * p.tw);
-        const int full = cols >> 2, tail = cols & 3;
-        for (int py = wave; py < rows; py += 4) {
-            const float *prow = pix + py * p.pitch;
-            const float *mrow = mean + py * p.tw;
-            for (int kx = 0; kx < full; ++kx) {
-                float z[NB];
-#pragma unroll
-                for (int b = 0; b < NB; ++b) z[b] = prow[pix_off[b] + 4 * kx] - mrow[mean_off[b] + 4 * kx];
-                int t2 = 0;
-#pragma unroll
-                for (int bi = 0; bi < NB; ++bi)
-#pragma unroll
-                    for (int bj = bi; bj < NB; ++bj, ++t2)
-                        acc[t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[bi], z[bj], acc[t2], 0, 0, 0);
-            }
-            if (tail) {                                   // ragged end of the row: patches past the image add 0
-                const bool ok = q < tail;
-                float z[NB];
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    const float v = prow[pix_off[b] + 4 * full] - mrow[mean_off[b] + 4 * full];
-                    z[b] = ok ? v : 0.f;
-                }
-                int t2 = 0;
-#pragma unroll
-                for (int bi = 0; bi < NB; ++bi)
-#pragma unroll
-                    for (int bj = bi; bj < NB; ++bj, ++t2)
-                        acc[t2] = __builtin_amdgcn_mfma_f32_16x16x4f32(z[bi], z[bj], acc[t2], 0, 0, 0);
-            }
-        }
+        if (TSPLIT == 1 || role == 0)
+            gram_rows<G, 0>(pix, mean, p.pitch, p.tw, rows, cols, pg, q, pix_off, mean_off, acc);
+        else
+            gram_rows<G, TSPLIT - 1>(pix, mean, p.pitch, p.tw, rows, cols, pg, q, pix_off, mean_off, acc);
+
         if (++since_flush >= p.flush_items || it == count - 1) {
-            // fold the fp32 tile accumulators into this wavefront's fp64 slot
-#pragma unroll
-            for (int t3 = 0; t3 < NT; ++t3)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    double *dst = my_slot + (t3 * 4 + v) * 64 + lane;
-                    const double add = (double)acc[t3][v];
-                    *dst = rmw ? *dst + add : add;
-                }
-#pragma unroll
-            for (int t3 = 0; t3 < NT; ++t3) acc[t3] = floatx4{0.f, 0.f, 0.f, 0.f};
+            __syncthreads();                              // every wavefront is done with the tile
+            gram_flush<G>(acc, lds, my_slot, pg, role, rmw);
             rmw = true;
             since_flush = 0;
         }
-    }
-    if (count == 0 && !rmw) {                             // idle workgroup: its slots must still read as zero
-        for (int e = lane; e < NT * 256; e += 64) my_slot[e] = 0.0;
     }
 }
 
@@ -254,30 +353,38 @@ __global__ __launch_bounds__(256) void gram_export_kernel(const double *__restri
     }
 }
 
-static int gram_occupancy(int k)
+// Launch shape per patch size: wavefronts sharing a patch-row group, wavefronts per SIMD the
+// register budget is set for, workgroups per compute unit.
+struct GramShape { int tsplit, waves_per_eu; };
+static GramShape gram_shape(int k)
 {
-    // workgroups per compute unit the register budget allows (accumulators: tiles*4 per lane)
-    return k <= 5 ? 4 : (k == 7 ? 2 : 1);
+    switch (k) {
+        case 3: return {1, 4};
+        case 5: return {1, 4};
+        case 7: return {1, 2};
+        default: return {2, 2};
+    }
 }
 
-int max_gram_slots(ddcca_ctx *ctx, int k) { return ctx->n_cu * gram_occupancy(k) * 4; }
+// one slot per resident workgroup
+int max_gram_slots(ddcca_ctx *ctx, int k) { return ctx->n_cu * gram_shape(k).waves_per_eu; }
 
-template <int KS>
-static int gram_launch(ddcca_ctx *ctx, GramParams p, int grid, size_t lds)
+template <int KS, int TSPLIT, bool CROSS, int WPE>
+static int gram_launch(ddcca_ctx *ctx, const GramParams &p, int grid, size_t lds)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)patch_gram_kernel<KS>,
+        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)patch_gram_kernel<KS, TSPLIT, CROSS, WPE>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         attr_set = true;
     }
-    hipLaunchKernelGGL(patch_gram_kernel<KS>, dim3(grid), dim3(GRAM_THREADS), lds, ctx->stream, p);
+    hipLaunchKernelGGL((patch_gram_kernel<KS, TSPLIT, CROSS, WPE>), dim3(grid), dim3(GRAM_THREADS), lds, ctx->stream, p);
     DDCCA_HIP(ctx, hipGetLastError());
     return DDCCA_OK;
 }
 
 int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w, int k,
-                      double *slots, int max_slots, int *slots_valid)
+                      bool cross_only, double *slots, int max_slots, int *slots_valid)
 {
     ProfScope prof(ctx, DDCCA_K_GRAM);
     GramParams p;
@@ -296,26 +403,35 @@ int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t 
     while (pitch % 32 != (k + 3) % 32) ++pitch;
     p.pitch = pitch;
     p.view_stride = (GRAM_TH + 2 * r) * pitch + 16;      // +16: shift view 2 by half the banks
-    const size_t lds = (size_t)(2 * p.view_stride + 2 * GRAM_TH * p.tw + 8) * sizeof(float);
+    const GramShape shape = gram_shape(k);
+    const int npg = 4 / shape.tsplit;
+    const size_t tile_floats = (size_t)2 * p.view_stride + 2 * GRAM_TH * p.tw + 2 * (GRAM_TH + 2 * r) * p.tw;
+    const size_t stage_floats = (size_t)((gram_tiles(k) + shape.tsplit - 1) / shape.tsplit) * 256;
+    const size_t lds = std::max(tile_floats, stage_floats) * sizeof(float);
     // about 16k patches between fp64 flushes per wavefront
-    const int patches_per_wave_item = (GRAM_TH / 4) * p.tw;
-    p.flush_items = std::max(1, 16384 / patches_per_wave_item);
+    const int patches_per_group_item = (GRAM_TH / npg) * p.tw;
+    p.flush_items = std::max(1, 16384 / patches_per_group_item);
     p.slots = slots;
     p.slots_valid = *slots_valid;
-    const int max_grid = max_slots / 4;
-    int grid = (int)std::min<int64_t>(max_grid, std::max<int64_t>(p.n_items, 1));
-    // slots that already hold data must all be revisited or kept: a smaller grid leaves
-    // the upper ones untouched (still valid), a larger one initialises new ones
+    const int max_grid = max_slots;
+    const int grid = (int)std::min<int64_t>(max_grid, std::max<int64_t>(p.n_items, 1));
     int rc;
+#define GRAM_CASE(KS, TS, WPE)                                                     \
+    case KS:                                                                       \
+        rc = cross_only ? gram_launch<KS, TS, true, WPE>(ctx, p, grid, lds)        \
+                        : gram_launch<KS, TS, false, WPE>(ctx, p, grid, lds);      \
+        break;
     switch (k) {
-        case 3: rc = gram_launch<3>(ctx, p, grid, lds); break;
-        case 5: rc = gram_launch<5>(ctx, p, grid, lds); break;
-        case 7: rc = gram_launch<7>(ctx, p, grid, lds); break;
-        case 9: rc = gram_launch<9>(ctx, p, grid, lds); break;
+        GRAM_CASE(3, 1, 4)
+        GRAM_CASE(5, 1, 4)
+        GRAM_CASE(7, 1, 2)
+        GRAM_CASE(9, 2, 2)
         default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
     }
+#undef GRAM_CASE
     if (rc) return rc;
-    *slots_valid = std::max(*slots_valid, grid * 4);
+    // slots below the old mark that this grid did not touch keep their data; new ones were initialised
+    *slots_valid = std::max(*slots_valid, grid);
     return DDCCA_OK;
 }
 
