@@ -83,19 +83,26 @@ __device__ __forceinline__ void gram_rows(const float *pix, const float *mean, i
     for (int py = pg; py < rows; py += G::NPG) {
         const float *prow = pix + py * pitch;
         const float *mrow = mean + py * tw;
-        float z[NB], zn[NB];
+        float z[NB];
         if (full > 0) {
 #pragma unroll
             for (int b = 0; b < NB; ++b) z[b] = prow[pix_off[b]] - mrow[mean_off[b]];
         }
         for (int kx = 0; kx < full; ++kx) {
-            // operands of the next step are fetched while this step's MFMAs run
+            // the raw operands of the next step are fetched before this step's MFMAs and
+            // turned into mean-removed values after them, so the LDS latency is covered
             const int nx = (kx + 1 < full) ? 4 * (kx + 1) : 4 * kx;
+            float pn[NB], mn[NB];
 #pragma unroll
-            for (int b = 0; b < NB; ++b) zn[b] = prow[pix_off[b] + nx] - mrow[mean_off[b] + nx];
+            for (int b = 0; b < NB; ++b) {
+                pn[b] = prow[pix_off[b] + nx];
+                mn[b] = mrow[mean_off[b] + nx];
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * NB, 0);     // LDS reads first
             gram_mfma_step<G, ROLE>(z, acc);
+            __builtin_amdgcn_sched_group_barrier(0x008, G::NACC, 0);    // then every MFMA of the step
 #pragma unroll
-            for (int b = 0; b < NB; ++b) z[b] = zn[b];
+            for (int b = 0; b < NB; ++b) z[b] = pn[b] - mn[b];
         }
         if (tail) {                                   // ragged end of the row: patches past the image add 0
             const bool ok = q < tail;
@@ -361,7 +368,7 @@ static GramShape gram_shape(int k)
     switch (k) {
         case 3: return {1, 4};
         case 5: return {1, 4};
-        case 7: return {1, 2};
+        case 7: return {1, 3};
         default: return {2, 2};
     }
 }
@@ -424,7 +431,7 @@ int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t 
     switch (k) {
         GRAM_CASE(3, 1, 4)
         GRAM_CASE(5, 1, 4)
-        GRAM_CASE(7, 1, 2)
+        GRAM_CASE(7, 1, 3)
         GRAM_CASE(9, 2, 2)
         default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
     }
