@@ -1,56 +1,103 @@
 // DCCA solve (Eq. 2-3) in one workgroup, fp64, matrices resident in LDS:
 //   B_d = C_dd + eps_d I (ridge), C~ = 2 C_w - C_T
-//   B_d = L_d L_d^T (Cholesky), T = L_1^{-1} C~ L_2^{-T}
-//   T^T T = V diag(sigma^2) V^T by parallel-ordered cyclic Jacobi rotations
-//   u = T v / sigma,  w_1 = L_1^{-T} u,  w_2 = L_2^{-T} v,  rho = sigma
+//   B_d = L_d L_d^T (Cholesky), L_d^{-1} formed in place, T = L_1^{-1} C~ L_2^{-T}
+//   T = U diag(sigma) V^T: one-sided (Hestenes) Jacobi rotations of column pairs of T in
+//   round-robin order, one 16-lane group per pair, one barrier per round; V is not
+//   accumulated (v = T^T u / sigma for the L leading triplets only)
+//   w_1 = L_1^{-T} u,  w_2 = L_2^{-T} v,  rho = sigma
 // The leading L pairs are written as fp32 filters (Eq. 4-5: row-major k x k).
 #include "ddcca_internal.h"
 
 namespace ddcca {
 
-constexpr int SOLVE_THREADS = 512;
+constexpr int SOLVE_THREADS = 1024;
 constexpr int SOLVE_MAX_SWEEPS = 40;
+constexpr double SOLVE_TOL = 1e-15;      // rotate while |g_p . g_q| > tol * |g_p| |g_q|
+constexpr double SOLVE_QUAD = 1e-8;      // a sweep whose largest cosine was below this is the last one
+
+#ifdef DDCCA_SOLVE_STAMPS
+#define STAMP(i) do { if (threadIdx.x == 0) p.stamps[i] = wall_clock64(); } while (0)
+#else
+#define STAMP(i) do { } while (0)
+#endif
 
 struct SolveParams {
+#ifdef DDCCA_SOLVE_STAMPS
+    long long *stamps;
+#endif
     const double *C11, *C22, *Cw, *CT;
-    int D, L;
+    int L;
     double ridge;
-    double *gL1, *gL2;          // global scratch: the two Cholesky factors
+    double *gI1, *gI2;          // global scratch: the two inverse Cholesky factors
     float *W1, *W2;
     double *rho;
 };
 
-// One right-looking Cholesky column step on `m` (lower triangle), done by `nt` threads
-// with local id `t`; caller places a barrier after each of the two phases.
-__device__ inline void chol_scale(double *m, int D, int j, int t, int nt)
+// Sum over the 16 lanes of a DPP row (lanes 16r .. 16r+15), result in every lane of the row.
+// Rotations by 8, 4, 2, 1 within the row; every lane ends with bit-identical totals.
+__device__ __forceinline__ double row16_sum(double x)
 {
-    const double d = sqrt(m[j * D + j]);
-    for (int i = j + 1 + t; i < D; i += nt) m[i * D + j] /= d;
-}
-__device__ inline void chol_update(double *m, int D, int j, int t, int nt)
-{
-    // after the scale phase m[j][j] still holds the pivot; replace it by its root last
-    const int rem = D - j - 1;
-    for (int e = t; e < rem * rem; e += nt) {
-        const int i = j + 1 + e / rem, c = j + 1 + e % rem;
-        if (c <= i) m[i * D + c] -= m[i * D + j] * m[c * D + j];
+#define DDCCA_ROR(n)                                                                                   \
+    {                                                                                                  \
+        const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x120 + (n), 0xf, 0xf, false); \
+        const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x120 + (n), 0xf, 0xf, false); \
+        x += __hiloint2double(hi, lo);                                                                 \
     }
+    DDCCA_ROR(8) DDCCA_ROR(4) DDCCA_ROR(2) DDCCA_ROR(1)
+#undef DDCCA_ROR
+    return x;
 }
 
+// max over the 16 lanes of a DPP row, result in every lane.
+__device__ __forceinline__ double row16_max(double x)
+{
+#define DDCCA_ROR(n)                                                                                   \
+    {                                                                                                  \
+        const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x120 + (n), 0xf, 0xf, false); \
+        const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x120 + (n), 0xf, 0xf, false); \
+        x = fmax(x, __hiloint2double(hi, lo));                                                         \
+    }
+    DDCCA_ROR(8) DDCCA_ROR(4) DDCCA_ROR(2) DDCCA_ROR(1)
+#undef DDCCA_ROR
+    return x;
+}
+
+__device__ __forceinline__ int row16_min_int(int x)
+{
+#define DDCCA_ROR(n) x = min(x, __builtin_amdgcn_update_dpp(0, x, 0x120 + (n), 0xf, 0xf, false));
+    DDCCA_ROR(8) DDCCA_ROR(4) DDCCA_ROR(2) DDCCA_ROR(1)
+#undef DDCCA_ROR
+    return x;
+}
+
+// 1/sqrt(x) to fp64 accuracy for normal positive x: hardware estimate + two Newton steps.
+__device__ __forceinline__ double fast_rsqrt(double x)
+{
+    double y = __builtin_amdgcn_rsq(x);
+    y = y * (1.5 - 0.5 * x * y * y);
+    y = y * (1.5 - 0.5 * x * y * y);
+    return y;
+}
+
+template <int KS>
 __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p)
 {
     extern __shared__ double sm[];
-    const int D = p.D, L = p.L, DD = D * D;
+    constexpr int D = KS * KS, DD = D * D;
+    constexpr int NR = (D + 15) / 16;            // rows of a column held by one lane of a 16-lane group
+    constexpr int NGRP = SOLVE_THREADS / 16;
+    constexpr int GPASS = (D - 1 + NGRP - 1) / NGRP;   // passes of the groups over up to D-1 filter pairs
+    const int L = p.L;
     double *A = sm, *B = sm + DD, *C = sm + 2 * DD;
-    double *small = sm + 3 * DD;                 // [4*D + 8]
+    double *small = sm + 3 * DD;                 // [2*D + 8] doubles
     double *lam = small;                         // D
-    double *rc = small + D;                      // rotation cosines  (<= D/2+1)
-    double *rs = small + 2 * D;                  // rotation sines
-    double *red = small + 3 * D;                 // reduction scratch (>= 8 + D)
-    int *ip = reinterpret_cast<int *>(small + 4 * D + 8);   // [3*D + 4] ints: pair p, pair q, order
-    int *pair_p = ip, *pair_q = ip + D, *order = ip + 2 * D;
-    const int tid = threadIdx.x, nt = blockDim.x;
+    double *red = small + D;                     // 8
+    int *ip = reinterpret_cast<int *>(small + 2 * D + 8);   // [D + 4] ints
+    int *order = ip, *flag = ip + D;
+    const int tid = threadIdx.x, nt = SOLVE_THREADS;
+    const int grp = tid >> 4, l16 = tid & 15;
 
+    STAMP(0);
     // ---- load, symmetrise, ridge -----------------------------------------------------
     for (int e = tid; e < DD; e += nt) {
         const int i = e / D, j = e - i * D;
@@ -70,148 +117,167 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
     else if (tid < 2 * D) B[(tid - D) * D + (tid - D)] += red[1];
     __syncthreads();
 
-    // ---- Cholesky of both matrices, half of the workgroup each -----------------------
+    STAMP(1);
+    // ---- Cholesky of both matrices (lower factor, in place), half of the workgroup each;
+    //      a half is 32 row-groups of 16 lanes ---------------------------------------------
     {
-        const int half = nt / 2;
+        constexpr int half = SOLVE_THREADS / 2;
         double *m = tid < half ? A : B;
         const int t = tid < half ? tid : tid - half;
+        const int ty = t >> 4, tx = t & 15;
         for (int j = 0; j < D; ++j) {
-            chol_scale(m, D, j, t, half);
+            const double piv = m[j * D + j];
+            const double rd = fast_rsqrt(piv);
+            for (int i = j + 1 + t; i < D; i += half) m[i * D + j] *= rd;
             __syncthreads();
-            chol_update(m, D, j, t, half);
-            if (t == 0) m[j * D + j] = sqrt(m[j * D + j]);
+            if (t == 0) m[j * D + j] = piv * rd;
+            for (int i = j + 1 + ty; i < D; i += 32) {
+                const double lij = m[i * D + j];
+                for (int c = j + 1 + tx; c <= i; c += 16) m[i * D + c] -= lij * m[c * D + j];
+            }
+            __syncthreads();
+        }
+        STAMP(2);
+        // ---- in-place inverse of the lower factor, last column first: with the trailing block
+        //      already inverted, column j of the inverse is -(1/l_jj) * Linv[j+1:, j+1:] * l[j+1:, j]
+        constexpr int RP = (D + 31) / 32;
+        for (int j = D - 1; j >= 0; --j) {
+            const double ajj = 1.0 / m[j * D + j];
+            double tmp[RP];
+#pragma unroll
+            for (int r = 0; r < RP; ++r) {
+                const int i = j + 1 + ty + 32 * r;
+                double s = 0.0;
+                if (i < D)
+                    for (int c = j + 1 + tx; c <= i; c += 16) s += m[i * D + c] * m[c * D + j];
+                tmp[r] = row16_sum(s);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < RP; ++r) {
+                const int i = j + 1 + ty + 32 * r;
+                if (i < D && tx == 0) m[i * D + j] = -ajj * tmp[r];
+            }
+            if (t == 0) m[j * D + j] = ajj;
             __syncthreads();
         }
     }
-    // keep the factors for the final back-substitutions
+    STAMP(3);
+    // ---- T = L1^{-1} C~ L2^{-T}:  X = A*C -> B (B saved to global first), T = X * inv2^T -> C
+    for (int e = tid; e < DD; e += nt) p.gI2[e] = B[e];
+    __syncthreads();
     for (int e = tid; e < DD; e += nt) {
-        p.gL1[e] = A[e];
-        p.gL2[e] = B[e];
+        const int i = e / D, c = e - i * D;
+        double s = 0.0;
+        for (int j = 0; j <= i; ++j) s += A[i * D + j] * C[j * D + c];
+        B[e] = s;
     }
-
-    // ---- T = L1^{-1} C~ L2^{-T}, in place in C ---------------------------------------
-    if (tid < D) {                               // column tid of X = L1^{-1} C~
-        const int c = tid;
-        for (int i = 0; i < D; ++i) {
-            double s = C[i * D + c];
-            for (int j = 0; j < i; ++j) s -= A[i * D + j] * C[j * D + c];
-            C[i * D + c] = s / A[i * D + i];
-        }
-    }
+    for (int e = tid; e < DD; e += nt) p.gI1[e] = A[e];
     __syncthreads();
-    if (tid < D) {                               // row tid of T: L2 t^T = x^T
-        const int r = tid;
-        for (int i = 0; i < D; ++i) {
-            double s = C[r * D + i];
-            for (int j = 0; j < i; ++j) s -= B[i * D + j] * C[r * D + j];
-            C[r * D + i] = s / B[i * D + i];
-        }
-    }
+    for (int e = tid; e < DD; e += nt) A[e] = p.gI2[e];
     __syncthreads();
-
-    // ---- M = T^T T in A, V = I in B ---------------------------------------------------
     for (int e = tid; e < DD; e += nt) {
-        const int a = e / D, b = e - a * D;
-        if (a <= b) {
-            double s = 0.0;
-            for (int r = 0; r < D; ++r) s += C[r * D + a] * C[r * D + b];
-            A[a * D + b] = s;
-            A[b * D + a] = s;
-        }
-        B[e] = (a == b) ? 1.0 : 0.0;
+        const int i = e / D, c = e - i * D;
+        double s = 0.0;
+        for (int j = 0; j <= c; ++j) s += B[i * D + j] * A[c * D + j];
+        C[e] = s;
     }
     __syncthreads();
 
-    // ---- cyclic Jacobi with round-robin (tournament) ordering -------------------------
-    const int np = D + (D & 1);                  // players; index D (if present) is a bye
-    const int n_pairs = np / 2, n_rounds = np - 1;
-    double fro2 = 0.0;
+    // ---- one-sided (Hestenes) Jacobi on T: A holds T^T (one column of T per row) -------------
+    for (int e = tid; e < DD; e += nt) {
+        const int pcol = e / D, i = e - pcol * D;
+        A[e] = C[i * D + pcol];
+    }
+    if (tid == 0) flag[0] = 0;
+    __syncthreads();
+    STAMP(4);
+
+    // A group of 16 lanes owns one column pair per round: it forms the three inner products and
+    // the rotation that makes the two columns orthogonal, and applies it.  Pairs of one round
+    // are disjoint (round-robin tournament), so a round needs a single barrier.
+    constexpr int NP = D + (D & 1);              // players; index D (if present) is a bye
+    constexpr int N_PAIRS = NP / 2, N_ROUNDS = NP - 1;
+    static_assert(N_PAIRS <= NGRP, "one 16-lane group per pair");
     for (int sweep = 0; sweep < SOLVE_MAX_SWEEPS; ++sweep) {
-        // off-diagonal and total squared norms
-        double off = 0.0, all = 0.0;
-        for (int e = tid; e < DD; e += nt) {
-            const int i = e / D, j = e - i * D;
-            const double v = A[e] * A[e];
-            all += v;
-            if (i != j) off += v;
-        }
-        for (int o = 32; o > 0; o >>= 1) {
-            off += __shfl_down(off, o);
-            all += __shfl_down(all, o);
-        }
-        if ((tid & 63) == 0) {
-            red[2 * (tid >> 6)] = off;
-            red[2 * (tid >> 6) + 1] = all;
-        }
-        __syncthreads();
-        off = 0.0;
-        all = 0.0;
-        for (int wv = 0; wv < nt / 64; ++wv) {
-            off += red[2 * wv];
-            all += red[2 * wv + 1];
-        }
-        __syncthreads();
-        if (sweep == 0) fro2 = all;
-        if (off <= 1e-30 * fro2) break;          // off-diagonal norm <= 1e-15 * ||M||_F
-
-        for (int round = 0; round < n_rounds; ++round) {
-            if (tid < n_pairs) {
+        for (int round = 0; round < N_ROUNDS; ++round) {
+            if (grp < N_PAIRS) {
                 int a, b;
-                if (tid == 0) {
-                    a = np - 1;
+                if (grp == 0) {
+                    a = NP - 1;
                     b = round;
                 } else {
-                    a = (round + tid) % (np - 1);
-                    b = (round - tid + (np - 1)) % (np - 1);
+                    a = round + grp;
+                    if (a >= NP - 1) a -= NP - 1;
+                    b = round - grp;
+                    if (b < 0) b += NP - 1;
                 }
-                int pp = min(a, b), qq = max(a, b);
-                double c = 1.0, s = 0.0;
+                const int pp = min(a, b), qq = max(a, b);
                 if (qq < D) {
-                    const double apq = A[pp * D + qq];
-                    if (fabs(apq) > 1e-300) {
-                        const double theta = (A[qq * D + qq] - A[pp * D + pp]) / (2.0 * apq);
-                        const double t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
-                        c = 1.0 / sqrt(t * t + 1.0);
-                        s = t * c;
+                    double *gp = A + pp * D, *gq = A + qq * D;
+                    double x[NR], y[NR];
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) {
+                        const int i = l16 + 16 * r;
+                        const bool in = i < D;
+                        x[r] = in ? gp[i] : 0.0;
+                        y[r] = in ? gq[i] : 0.0;
                     }
-                } else {
-                    pp = qq = 0;                 // bye: identity rotation on a harmless pair
+                    double al = 0.0, be = 0.0, ga = 0.0;
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) {
+                        al += x[r] * x[r];
+                        be += y[r] * y[r];
+                        ga += x[r] * y[r];
+                    }
+                    al = row16_sum(al);
+                    be = row16_sum(be);
+                    ga = row16_sum(ga);
+                    if (ga * ga > (SOLVE_TOL * SOLVE_TOL) * (al * be)) {
+                        // rotation angle theta, |theta| <= pi/4, tan(2 theta) = 2 ga / (be - al):
+                        // cos(2 theta) = |d|/r, c = sqrt((1 + cos 2theta)/2), s = sin(2 theta)/(2c)
+                        const double d = be - al, g2 = 2.0 * ga;
+                        const double rinv = fast_rsqrt(d * d + g2 * g2);
+                        const double h = 0.5 + 0.5 * fabs(d) * rinv;       // c^2, in [0.5, 1]
+                        const double cinv = fast_rsqrt(h);
+                        const double c = h * cinv;
+                        const double sn = (d >= 0.0 ? 0.5 : -0.5) * g2 * rinv * cinv;
+#pragma unroll
+                        for (int r = 0; r < NR; ++r) {
+                            const int i = l16 + 16 * r;
+                            if (i < D) {
+                                gp[i] = c * x[r] - sn * y[r];
+                                gq[i] = sn * x[r] + c * y[r];
+                            }
+                        }
+                        // was any pair of this sweep further from orthogonal than SOLVE_QUAD ?
+                        if (l16 == 0 && ga * ga > (SOLVE_QUAD * SOLVE_QUAD) * (al * be)) flag[0] = 1;
+                    }
                 }
-                pair_p[tid] = pp;
-                pair_q[tid] = qq;
-                rc[tid] = c;
-                rs[tid] = s;
-            }
-            __syncthreads();
-            // columns p,q of M and of V
-            for (int e = tid; e < n_pairs * D * 2; e += nt) {
-                const int pr = e / (2 * D), r2 = e - pr * 2 * D;
-                const int pp = pair_p[pr], qq = pair_q[pr];
-                if (pp == qq) continue;
-                double *m = r2 < D ? A : B;
-                const int i = r2 < D ? r2 : r2 - D;
-                const double c = rc[pr], s = rs[pr];
-                const double x = m[i * D + pp], y = m[i * D + qq];
-                m[i * D + pp] = c * x - s * y;
-                m[i * D + qq] = s * x + c * y;
-            }
-            __syncthreads();
-            // rows p,q of M
-            for (int e = tid; e < n_pairs * D; e += nt) {
-                const int pr = e / D, j = e - pr * D;
-                const int pp = pair_p[pr], qq = pair_q[pr];
-                if (pp == qq) continue;
-                const double c = rc[pr], s = rs[pr];
-                const double x = A[pp * D + j], y = A[qq * D + j];
-                A[pp * D + j] = c * x - s * y;
-                A[qq * D + j] = s * x + c * y;
             }
             __syncthreads();
         }
+        const int coarse = flag[0];
+        __syncthreads();
+        if (tid == 0) flag[0] = 0;
+#ifdef DDCCA_SOLVE_STAMPS
+        if (tid == 0) p.stamps[9] = sweep + 1;
+#endif
+        __syncthreads();
+        // Cyclic Jacobi converges quadratically: once every pair of a sweep was orthogonal to
+        // SOLVE_QUAD (cosine), the rotations of that sweep leave cosines of order SOLVE_QUAD^2.
+        if (!coarse) break;
     }
+    STAMP(5);
 
-    // ---- order the eigenvalues (descending, index breaks ties) ------------------------
-    if (tid < D) lam[tid] = A[tid * D + tid];
+    // ---- squared singular values = squared column norms; order them (descending, index breaks ties)
+    for (int col = grp; col < D; col += NGRP) {
+        const double *gp = A + col * D;
+        double al = 0.0;
+        for (int i = l16; i < D; i += 16) al += gp[i] * gp[i];
+        al = row16_sum(al);
+        if (l16 == 0) lam[col] = al;
+    }
     __syncthreads();
     if (tid < D) {
         const double me = lam[tid];
@@ -224,74 +290,112 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
     }
     __syncthreads();
 
-    // ---- u_g = T v_g / sigma_g into A[g][:], then v_g into C[g][:] ---------------------
+    // ---- u_g = g_j / sigma_j into B[g][:];  v_g = T^T u_g (unscaled) into A[g][:] -------------
     for (int e = tid; e < L * D; e += nt) {
         const int g = e / D, i = e - g * D;
         const int j = order[g];
-        double s = 0.0;
-        for (int c = 0; c < D; ++c) s += C[i * D + c] * B[c * D + j];
-        A[g * D + i] = s;                       // normalised below (||T v|| = sigma)
+        const double l2 = lam[j];
+        B[e] = l2 > 0.0 ? A[j * D + i] * fast_rsqrt(l2) : 0.0;
     }
     __syncthreads();
     for (int e = tid; e < L * D; e += nt) {
-        const int g = e / D, i = e - g * D;
-        C[g * D + i] = B[i * D + order[g]];
+        const int g = e / D, c = e - g * D;
+        double s = 0.0;
+        for (int i = 0; i < D; ++i) s += C[i * D + c] * B[g * D + i];
+        A[e] = s;                                   // scaled to unit length below
     }
     __syncthreads();
-    if (tid < L) {                               // unit length for u (and v, against drift)
-        double nu = 0.0, nv = 0.0;
-        for (int i = 0; i < D; ++i) {
-            nu += A[tid * D + i] * A[tid * D + i];
-            nv += C[tid * D + i] * C[tid * D + i];
-        }
-        nu = nu > 0.0 ? 1.0 / sqrt(nu) : 0.0;
-        nv = nv > 0.0 ? 1.0 / sqrt(nv) : 0.0;
-        for (int i = 0; i < D; ++i) {
-            A[tid * D + i] *= nu;
-            C[tid * D + i] *= nv;
-        }
-    }
+    // ---- w1 = L1^{-T} u: one 16-lane group per pair g; sign from the largest-magnitude entry
+    for (int e = tid; e < DD; e += nt) C[e] = p.gI1[e];
     __syncthreads();
-    // ---- w2 = L2^{-T} v (factor reloaded into B), then w1 = L1^{-T} u -------------------
-    for (int e = tid; e < DD; e += nt) B[e] = p.gL2[e];
-    __syncthreads();
-    if (tid < L) {
-        double *x = C + tid * D;
-        for (int i = D - 1; i >= 0; --i) {
-            double s = x[i];
-            for (int j = i + 1; j < D; ++j) s -= B[j * D + i] * x[j];
-            x[i] = s / B[i * D + i];
-        }
-    }
-    __syncthreads();
-    for (int e = tid; e < DD; e += nt) B[e] = p.gL1[e];
-    __syncthreads();
-    if (tid < L) {
-        double *x = A + tid * D;
-        for (int i = D - 1; i >= 0; --i) {
-            double s = x[i];
-            for (int j = i + 1; j < D; ++j) s -= B[j * D + i] * x[j];
-            x[i] = s / B[i * D + i];
-        }
-        // sign: largest-magnitude entry of w1 positive, lowest index on ties
-        int arg = 0;
-        double best = fabs(x[0]);
-        for (int i = 1; i < D; ++i)
-            if (fabs(x[i]) > best) {
-                best = fabs(x[i]);
-                arg = i;
+    double sign_of[GPASS];
+#pragma unroll
+    for (int pass = 0; pass < GPASS; ++pass) {
+        const int g = grp + pass * NGRP;
+        double sg = 1.0;
+        if (g < L) {
+            const double *u = B + g * D;
+            double w[NR];
+            double best = -1.0;
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                const int i = l16 + 16 * r;
+                double s = 0.0;
+                if (i < D)
+                    for (int j = i; j < D; ++j) s += C[j * D + i] * u[j];
+                w[r] = s;
+                if (i < D) best = fmax(best, fabs(s));
             }
-        const double sg = x[arg] < 0.0 ? -1.0 : 1.0;
-        const double *y = C + tid * D;
-        for (int i = 0; i < D; ++i) {
-            p.W1[tid * D + i] = (float)(sg * x[i]);
-            p.W2[tid * D + i] = (float)(sg * y[i]);
+            const double top = row16_max(best);
+            int arg = 1 << 30;
+#pragma unroll
+            for (int r = NR - 1; r >= 0; --r) {
+                const int i = l16 + 16 * r;
+                if (i < D && fabs(w[r]) == top) arg = i;
+            }
+            arg = row16_min_int(arg);               // lowest index among ties
+            double neg = 0.0;
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+                if (l16 + 16 * r == arg && w[r] < 0.0) neg = 1.0;
+            neg = row16_max(neg);
+            sg = neg > 0.0 ? -1.0 : 1.0;
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                const int i = l16 + 16 * r;
+                if (i < D) p.W1[g * D + i] = (float)(sg * w[r]);
+            }
+            if (l16 == 0) {
+                const double l2 = lam[order[g]];
+                p.rho[g] = l2 > 0.0 ? sqrt(l2) : 0.0;
+            }
         }
-        const double l2 = lam[order[tid]];
-        p.rho[tid] = l2 > 0.0 ? sqrt(l2) : 0.0;
+        sign_of[pass] = sg;
     }
+    __syncthreads();
+    // ---- w2 = L2^{-T} v, v normalised to unit length, same sign --------------------------------
+    for (int e = tid; e < DD; e += nt) C[e] = p.gI2[e];
+    __syncthreads();
+#pragma unroll
+    for (int pass = 0; pass < GPASS; ++pass) {
+        const int g = grp + pass * NGRP;
+        if (g < L) {
+            const double *v = A + g * D;
+            double nv = 0.0;
+            for (int i = l16; i < D; i += 16) nv += v[i] * v[i];
+            nv = row16_sum(nv);
+            const double scale = nv > 0.0 ? sign_of[pass] * fast_rsqrt(nv) : 0.0;
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                const int i = l16 + 16 * r;
+                if (i < D) {
+                    double s = 0.0;
+                    for (int j = i; j < D; ++j) s += C[j * D + i] * v[j];
+                    p.W2[g * D + i] = (float)(scale * s);
+                }
+            }
+        }
+    }
+    STAMP(6);
 }
 
+template <int KS>
+static int solve_launch(ddcca_ctx *ctx, const SolveParams &p)
+{
+    constexpr int D = KS * KS;
+    const size_t lds = (size_t)(3 * D * D + 2 * D + 8) * sizeof(double) + (size_t)(D + 4) * sizeof(int);
+    static bool attr_set = false;
+    if (!attr_set) {
+        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)dcca_solve_kernel<KS>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(dcca_solve_kernel<KS>, dim3(1), dim3(SOLVE_THREADS), lds, ctx->stream, p);
+    DDCCA_HIP(ctx, hipGetLastError());
+    return DDCCA_OK;
+}
+
+#ifndef DDCCA_SOLVE_STAMPS
 int launch_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const double *Cw, const double *CT, int k,
                  int L, double ridge, float *W1, float *W2, double *rho)
 {
@@ -301,20 +405,18 @@ int launch_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const dou
     if ((rc = ensure(ctx, ctx->solve_ws, 2 * (size_t)D * D * sizeof(double)))) return rc;
     SolveParams p;
     p.C11 = C11; p.C22 = C22; p.Cw = Cw; p.CT = CT;
-    p.D = D; p.L = L; p.ridge = ridge;
-    p.gL1 = (double *)ctx->solve_ws.ptr;
-    p.gL2 = p.gL1 + (size_t)D * D;
+    p.L = L; p.ridge = ridge;
+    p.gI1 = (double *)ctx->solve_ws.ptr;
+    p.gI2 = p.gI1 + (size_t)D * D;
     p.W1 = W1; p.W2 = W2; p.rho = rho;
-    const size_t lds = (size_t)(3 * D * D + 4 * D + 8) * sizeof(double) + (size_t)(3 * D + 4) * sizeof(int);
-    static bool attr_set = false;
-    if (!attr_set) {
-        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)dcca_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           160 * 1024));
-        attr_set = true;
+    switch (k) {
+        case 3: return solve_launch<3>(ctx, p);
+        case 5: return solve_launch<5>(ctx, p);
+        case 7: return solve_launch<7>(ctx, p);
+        case 9: return solve_launch<9>(ctx, p);
+        default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
     }
-    hipLaunchKernelGGL(dcca_solve_kernel, dim3(1), dim3(SOLVE_THREADS), lds, ctx->stream, p);
-    DDCCA_HIP(ctx, hipGetLastError());
-    return DDCCA_OK;
 }
+#endif
 
 }  // namespace ddcca
