@@ -122,12 +122,15 @@ def make_views(wl: Workload, max_per_class: int | None = None, n_classes: int | 
             angles = rng.uniform(-wl.max_rot_deg, wl.max_rot_deg, size=n_c)
         shifts = rng.integers(-2, 3, size=(n_c, 2))
         noise = rng.standard_normal((n_c, wl.h, wl.w), dtype=np.float32)
-        for i in range(n_c):
-            img = proto
-            if wl.max_rot_deg > 0:
-                img = ndimage.rotate(img, float(angles[i]), reshape=False, order=1, mode="reflect")
-            img = np.roll(img, (int(shifts[i, 0]), int(shifts[i, 1])), axis=(0, 1))
-            v1[pos + i] = img.astype(np.float32) + np.float32(0.3) * noise[i]
+        if wl.max_rot_deg > 0:
+            base = np.stack([ndimage.rotate(proto, float(a), reshape=False, order=1, mode="reflect") for a in angles])
+        else:
+            base = np.broadcast_to(proto, (n_c, wl.h, wl.w))
+        # circular shift by (dy, dx): out[y, x] = in[(y - dy) % h, (x - dx) % w]
+        rows = (np.arange(wl.h)[None, :] - shifts[:, 0:1]) % wl.h
+        cols = (np.arange(wl.w)[None, :] - shifts[:, 1:2]) % wl.w
+        shifted = base[np.arange(n_c)[:, None, None], rows[:, :, None], cols[:, None, :]]
+        v1[pos:pos + n_c] = shifted.astype(np.float32) + np.float32(0.3) * noise
         labels[pos:pos + n_c] = c
         pos += n_c
     v2 = sobel_magnitude(v1)
@@ -135,12 +138,15 @@ def make_views(wl: Workload, max_per_class: int | None = None, n_classes: int | 
 
 
 def sobel_magnitude(v: np.ndarray) -> np.ndarray:
-    """3x3 Sobel gradient magnitude per image, reflected borders, fp32."""
+    """3x3 Sobel gradient magnitude per image, borders reflected about the edge (d c b a | a b c d),
+    fp32.  gx = [1,2,1]^T (smooth along y) x [-1,0,1] (difference along x); gy likewise transposed."""
     out = np.empty_like(v)
-    step = 512
+    step = 32
     for s in range(0, v.shape[0], step):
-        blk = v[s:s + step].astype(np.float32)
-        gy = ndimage.sobel(blk, axis=1, mode="reflect")
-        gx = ndimage.sobel(blk, axis=2, mode="reflect")
+        p = np.pad(v[s:s + step].astype(np.float32), ((0, 0), (1, 1), (1, 1)), mode="symmetric")
+        sy = p[:, :-2, :] + 2.0 * p[:, 1:-1, :] + p[:, 2:, :]        # smoothed along y, [n, h, w+2]
+        gx = sy[:, :, 2:] - sy[:, :, :-2]
+        sx = p[:, :, :-2] + 2.0 * p[:, :, 1:-1] + p[:, :, 2:]        # smoothed along x, [n, h+2, w]
+        gy = sx[:, 2:, :] - sx[:, :-2, :]
         out[s:s + step] = np.sqrt(gx * gx + gy * gy)
     return out

@@ -267,3 +267,11 @@ def test_end_to_end_small_face_slice(ctx, oracle):
     v1, v2, cls = make_views(wl, max_per_class=2)                 # 80 images, all 40 classes
     model, feat = run_gpu_path(ctx, wl, v1, v2, cls)
     check_against_oracle(oracle, wl, v1, v2, cls, model, feat)
+
+
+def test_end_to_end_small_face_full(ctx, oracle):
+    # the benchmark's default workload at full size (400 images), whole path on both sides
+    wl = WORKLOADS["small_face"]
+    v1, v2, cls = make_views(wl)
+    model, feat = run_gpu_path(ctx, wl, v1, v2, cls)
+    check_against_oracle(oracle, wl, v1, v2, cls, model, feat)

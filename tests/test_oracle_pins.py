@@ -387,3 +387,21 @@ def test_two_stage_shapes_and_invariants(oracle):
     assert np.allclose(ms, 1 - eps1 * (s1["W1"] ** 2).sum(axis=1), rtol=1e-9)
     assert s2["C11"].shape == (wl.D, wl.D) and s2["N"] == M * wl.L1 * wl.h * wl.w
     assert np.all(s1["gap"] > 0) and np.all(s2["gap"] > 0)
+
+
+def test_class_sums_equal_gram_of_class_sum_images(oracle):
+    # linearity of patch extraction and mean removal: the per-pixel sum of a cell's patches is the
+    # patch of the cell's sum image, so Sw is the cross Gram of the n_cls*G sum images
+    rng = np.random.default_rng(16)
+    V1, V2 = rand_views(rng, 12, 7, 6)
+    cls = np.array([0, 0, 1, 1, 2, 2], dtype=np.int32)            # 6 samples x 2 maps
+    cls2, grp2 = np.repeat(cls, 2), np.tile(np.arange(2, dtype=np.int32), 6)
+    Sw, ST = oracle.class_sums(V1, V2, cls2, grp2, 3, 2, 3)
+    S1 = np.stack([V1[(cls2 == c) & (grp2 == g)].sum(0) for c in range(3) for g in range(2)])
+    S2 = np.stack([V2[(cls2 == c) & (grp2 == g)].sum(0) for c in range(3) for g in range(2)])
+    _, _, G12 = oracle.corr_sums(S1, S2, 3)
+    assert np.abs(Sw - G12).max() <= 1e-12 * np.abs(Sw).max()
+    T1 = np.stack([V1[grp2 == g].sum(0) for g in range(2)])
+    T2 = np.stack([V2[grp2 == g].sum(0) for g in range(2)])
+    _, _, GT = oracle.corr_sums(T1, T2, 3)
+    assert np.abs(ST - GT).max() <= 1e-12 * np.abs(ST).max()
