@@ -1,13 +1,20 @@
 // Patch Gram accumulation (Section II-A matrices, Section III Eq. 15 batching):
-//   for every pixel of every map pair, z = [x1; x2] (the two mean-removed k*k patches,
-//   2D entries) and  G += z z^T.
-// The patch matrix of Eq. 1 is never formed: an image tile with its halo is staged in
-// LDS, the per-patch means are computed once per tile, and the MFMA operands are read
-// straight from the tile with a per-lane window offset.  The contraction runs on
-// v_mfma_f32_16x16x4_f32 (K = 4 consecutive patches of a tile row per instruction).
-// For a Gram the A operand of row block bi and the B operand of column block bj have
-// the same register layout (lane l: stacked row 16*b + l%16, patch l/16), so one LDS
+//   for every pixel of every map pair, z = [x1; x2] (the two k*k patches, 2D entries) and
+//   G += z z^T.
+// The patch matrix of Eq. 1 is never formed: an image tile with its halo is staged in LDS and
+// the MFMA operands are read straight from the tile with a per-lane window offset.  The
+// contraction runs on v_mfma_f32_16x16x4_f32 (K = 4 consecutive patches of a tile row per
+// instruction).  For a Gram the A operand of row block bi and the B operand of column block
+// bj have the same register layout (lane l: stacked row 16*b + l%16, patch l/16), so one LDS
 // read per block feeds every tile of that block row and block column.
+//
+// Mean removal: the mean-removed patch is H x with H = I - 11^T/D, so the sum of the
+// mean-removed outer products is H (sum x x^T) H.  The kernel therefore accumulates the Gram
+// of the RAW patches and the export step applies H . H in fp64.  Because H annihilates
+// constants, any constant may be subtracted from all pixels of a tile (padding included)
+// without changing the result; each tile is shifted by an estimate of the local mean pixel
+// value so that a large DC level (non-negative views, 8-bit images) does not eat the fp32
+// mantissa of the accumulators.
 #include "ddcca_internal.h"
 
 namespace ddcca {
@@ -24,6 +31,8 @@ struct GramParams {
     int h, w, tiles_x, tiles_y, tw;        // tw: tile width in patches
     int pitch;                             // LDS row pitch of the pixel tile (floats)
     int view_stride;                       // LDS floats per view's pixel tile
+    int buf_stride;                        // LDS floats per tile buffer (two views); two buffers
+    int dc_off;                            // LDS float offset of the 2x2 DC-estimate cells
     int flush_items;                       // items between fp64 flushes
     double *slots;                         // [n_slots][NT*256]
     int slots_valid;                       // slots below this hold earlier partial sums
@@ -74,41 +83,36 @@ __device__ __forceinline__ void gram_mfma_step(const float (&z)[G::NB], floatx4 
 
 // All k-steps of this wavefront's patch rows of the staged tile.
 template <typename G, int ROLE>
-__device__ __forceinline__ void gram_rows(const float *pix, const float *mean, int pitch, int tw, int rows, int cols,
-                                          int pg, int q, const int (&pix_off)[G::NB], const int (&mean_off)[G::NB],
-                                          floatx4 (&acc)[G::NACC])
+__device__ __forceinline__ void gram_rows(const float *pix, int pitch, int rows, int cols, int pg, int q,
+                                          const int (&pix_off)[G::NB], floatx4 (&acc)[G::NACC])
 {
     constexpr int NB = G::NB;
     const int full = cols >> 2, tail = cols & 3;
     for (int py = pg; py < rows; py += G::NPG) {
         const float *prow = pix + py * pitch;
-        const float *mrow = mean + py * tw;
         float z[NB];
         if (full > 0) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) z[b] = prow[pix_off[b]] - mrow[mean_off[b]];
+            for (int b = 0; b < NB; ++b) z[b] = prow[pix_off[b]];
         }
         for (int kx = 0; kx < full; ++kx) {
-            // the raw operands of the next step are fetched before this step's MFMAs and
-            // turned into mean-removed values after them, so the LDS latency is covered
+            // the operands of the next step are fetched before this step's MFMAs, so the LDS
+            // latency is covered
             const int nx = (kx + 1 < full) ? 4 * (kx + 1) : 4 * kx;
-            float pn[NB], mn[NB];
+            float zn[NB];
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                pn[b] = prow[pix_off[b] + nx];
-                mn[b] = mrow[mean_off[b] + nx];
-            }
-            __builtin_amdgcn_sched_group_barrier(0x100, 2 * NB, 0);     // LDS reads first
+            for (int b = 0; b < NB; ++b) zn[b] = prow[pix_off[b] + nx];
+            __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);         // LDS reads first
             gram_mfma_step<G, ROLE>(z, acc);
             __builtin_amdgcn_sched_group_barrier(0x008, G::NACC, 0);    // then every MFMA of the step
 #pragma unroll
-            for (int b = 0; b < NB; ++b) z[b] = pn[b] - mn[b];
+            for (int b = 0; b < NB; ++b) z[b] = zn[b];
         }
         if (tail) {                                   // ragged end of the row: patches past the image add 0
             const bool ok = q < tail;
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const float v = prow[pix_off[b] + 4 * full] - mrow[mean_off[b] + 4 * full];
+                const float v = prow[pix_off[b] + 4 * full];
                 z[b] = ok ? v : 0.f;
             }
             gram_mfma_step<G, ROLE>(z, acc);
@@ -171,22 +175,102 @@ __device__ __forceinline__ void gram_flush(floatx4 (&acc)[G::NACC], float *stage
     }
 }
 
+// Tile staging.  Thread (wave w, lane l) owns tile elements (row w + 4*jy, column l + 64*jx).
+template <int KS>
+struct GramStage {
+    static constexpr int R = (KS - 1) / 2;
+    static constexpr int PH = GRAM_TH + 2 * R;
+    static constexpr int NJY = (PH + 3) / 4;
+    static constexpr int NJX = (GRAM_TW_MAX + 2 * R + 63) / 64;
+};
+
+// Issue the global loads of one tile (both views) into registers; elements outside the image
+// (zero padding) or outside the tile read as 0.
+template <int KS>
+__device__ __forceinline__ void gram_tile_fetch(const GramParams &p, int64_t item, int tiles, int pw,
+                                                float (&ra)[GramStage<KS>::NJY][GramStage<KS>::NJX],
+                                                float (&rb)[GramStage<KS>::NJY][GramStage<KS>::NJX])
+{
+    using S = GramStage<KS>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t m = item / tiles;
+    const int t = (int)(item - m * tiles);
+    const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
+    const int gy0 = ty * GRAM_TH - S::R + wave, gx0 = tx * p.tw - S::R + lane;
+    const int64_t P = (int64_t)p.h * p.w;
+    const float *s1 = p.v1 + m * P, *s2 = p.v2 + m * P;
+#pragma unroll
+    for (int jy = 0; jy < S::NJY; ++jy) {
+        const int gy = gy0 + 4 * jy;
+        const bool yok = gy >= 0 && gy < p.h && wave + 4 * jy < S::PH;
+#pragma unroll
+        for (int jx = 0; jx < S::NJX; ++jx) {
+            const int gx = gx0 + 64 * jx;
+            float a = 0.f, b = 0.f;
+            if (yok && gx >= 0 && gx < p.w && lane + 64 * jx < pw) {
+                const int64_t o = (int64_t)gy * p.w + gx;
+                a = s1[o];
+                b = s2[o];
+            }
+            ra[jy][jx] = a;
+            rb[jy][jx] = b;
+        }
+    }
+}
+
+// Write a fetched tile into an LDS buffer, shifted by the DC estimates (c1, c2); wavefront 0
+// leaves the mean of its own share of the tile as the DC estimate for the next tile.
+template <int KS>
+__device__ __forceinline__ void gram_tile_store(const GramParams &p, float *buf, int pw, float c1, float c2,
+                                                const float (&ra)[GramStage<KS>::NJY][GramStage<KS>::NJX],
+                                                const float (&rb)[GramStage<KS>::NJY][GramStage<KS>::NJX],
+                                                float *dc_next)
+{
+    using S = GramStage<KS>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int jy = 0; jy < S::NJY; ++jy) {
+        const int yy = wave + 4 * jy;
+#pragma unroll
+        for (int jx = 0; jx < S::NJX; ++jx) {
+            const int xx = lane + 64 * jx;
+            if (yy < S::PH && xx < pw) {
+                buf[yy * p.pitch + xx] = ra[jy][jx] - c1;
+                buf[p.view_stride + yy * p.pitch + xx] = rb[jy][jx] - c2;
+                s1 += ra[jy][jx];
+                s2 += rb[jy][jx];
+            }
+        }
+    }
+    if (wave == 0) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            s1 += __shfl_xor(s1, o);
+            s2 += __shfl_xor(s2, o);
+        }
+        if (lane == 0) {
+            const float inv = 1.0f / (float)(((S::PH + 3) / 4) * pw);
+            dc_next[0] = s1 * inv;
+            dc_next[1] = s2 * inv;
+        }
+    }
+}
+
 template <int KS, int TSPLIT, bool CROSS, int WAVES_PER_EU>
 __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(GramParams p)
 {
     using G = GramGeom<KS, TSPLIT, CROSS>;
+    using S = GramStage<KS>;
     constexpr int D = G::D, R = G::R, NB = G::NB, NT = G::NT;
     extern __shared__ float lds[];
-    float *pix = lds;                                     // [2][GRAM_TH + 2R][pitch]
-    float *mean = lds + 2 * p.view_stride;                // [2][GRAM_TH][tw]
-    float *hsum = mean + 2 * GRAM_TH * p.tw;              // [2][GRAM_TH + 2R][tw] horizontal window sums
+    float *dc = lds + p.dc_off;                            // [2][2] DC estimates, double-buffered
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int q = lane >> 4, i = lane & 15;
     const int pg = wave / TSPLIT, role = wave % TSPLIT;
-    const int mean_view_stride = GRAM_TH * p.tw;
 
     // per-lane operand offsets for each 16-row block of the stacked vector
-    int pix_off[NB], mean_off[NB];
+    int pix_off[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         int row = 16 * b + i;
@@ -195,7 +279,6 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
         const int a = row - view * D;
         const int dy = a / KS, dx = a - dy * KS;
         pix_off[b] = view * p.view_stride + dy * p.pitch + dx + q;
-        mean_off[b] = view * mean_view_stride + q;
     }
 
     floatx4 acc[G::NACC];
@@ -207,69 +290,68 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
     const int64_t first = blockIdx.x * per + min((int64_t)blockIdx.x, extra);
     const int64_t count = per + (blockIdx.x < extra ? 1 : 0);
     const int tiles = p.tiles_x * p.tiles_y;
-    const int64_t P = (int64_t)p.h * p.w;
     double *my_slot = p.slots + (size_t)blockIdx.x * NT * 256;
     bool rmw = (int)blockIdx.x < p.slots_valid;
     int since_flush = 0;
-    constexpr int PH = GRAM_TH + 2 * R;
     const int pw = p.tw + 2 * R;
+
+    float ra[S::NJY][S::NJX], rb[S::NJY][S::NJX];
+    if (count > 0) {
+        // first tile: its own DC estimate, then into buffer 0
+        gram_tile_fetch<KS>(p, first, tiles, pw, ra, rb);
+        float s1 = 0.f, s2 = 0.f;
+        if (wave == 0) {
+#pragma unroll
+            for (int jy = 0; jy < S::NJY; ++jy)
+#pragma unroll
+                for (int jx = 0; jx < S::NJX; ++jx)
+                    if (4 * jy < S::PH && lane + 64 * jx < pw) {
+                        s1 += ra[jy][jx];
+                        s2 += rb[jy][jx];
+                    }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                s1 += __shfl_xor(s1, o);
+                s2 += __shfl_xor(s2, o);
+            }
+            if (lane == 0) {
+                const float inv = 1.0f / (float)(((S::PH + 3) / 4) * pw);
+                dc[2] = s1 * inv;
+                dc[3] = s2 * inv;
+            }
+        }
+        __syncthreads();
+        gram_tile_store<KS>(p, lds, pw, dc[2], dc[3], ra, rb, dc);
+        __syncthreads();
+    }
 
     for (int64_t it = 0; it < count; ++it) {
         const int64_t item = first + it;
+        const int cur = (int)(it & 1);
+        const float *pix = lds + cur * p.buf_stride;
+        const bool more = it + 1 < count;
+        // the next tile travels from HBM to registers while this one is contracted
+        if (more) gram_tile_fetch<KS>(p, item + 1, tiles, pw, ra, rb);
+
         const int64_t m = item / tiles;
         const int t = (int)(item - m * tiles);
         const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
-        const int gy0 = ty * GRAM_TH - R, gx0 = tx * p.tw - R;
-        __syncthreads();                                  // previous item's reads are done
-        for (int e = threadIdx.x; e < PH * pw; e += GRAM_THREADS) {
-            const int yy = e / pw, xx = e - yy * pw;
-            const int gy = gy0 + yy, gx = gx0 + xx;
-            float a = 0.f, b = 0.f;
-            if (gy >= 0 && gy < p.h && gx >= 0 && gx < p.w) {
-                const int64_t o = m * P + (int64_t)gy * p.w + gx;
-                a = p.v1[o];
-                b = p.v2[o];
-            }
-            pix[yy * p.pitch + xx] = a;
-            pix[p.view_stride + yy * p.pitch + xx] = b;
-        }
-        __syncthreads();
-        // per-patch means (zero padding counts as zeros), separable: horizontal window sums, then
-        // vertical sums of those
-        for (int e = threadIdx.x; e < 2 * PH * p.tw; e += GRAM_THREADS) {
-            const int view = e / (PH * p.tw);
-            const int r2 = e - view * PH * p.tw;
-            const int yy = r2 / p.tw, px = r2 - yy * p.tw;
-            const float *src = pix + view * p.view_stride + yy * p.pitch + px;
-            float hs = 0.f;
-#pragma unroll
-            for (int dx = 0; dx < KS; ++dx) hs += src[dx];
-            hsum[e] = hs;
-        }
-        __syncthreads();
-        for (int e = threadIdx.x; e < 2 * GRAM_TH * p.tw; e += GRAM_THREADS) {
-            const int view = e / (GRAM_TH * p.tw);
-            const int r2 = e - view * GRAM_TH * p.tw;
-            const float *src = hsum + view * PH * p.tw + r2;
-            float sum = 0.f;
-#pragma unroll
-            for (int dy = 0; dy < KS; ++dy) sum += src[dy * p.tw];
-            mean[e] = sum * (1.0f / D);
-        }
-        __syncthreads();
-
         const int rows = min(GRAM_TH, p.h - ty * GRAM_TH);
         const int cols = min(p.tw, p.w - tx * p.tw);
-        if (TSPLIT == 1 || role == 0)
-            gram_rows<G, 0>(pix, mean, p.pitch, p.tw, rows, cols, pg, q, pix_off, mean_off, acc);
-        else
-            gram_rows<G, TSPLIT - 1>(pix, mean, p.pitch, p.tw, rows, cols, pg, q, pix_off, mean_off, acc);
+        if (TSPLIT == 1 || role == 0) gram_rows<G, 0>(pix, p.pitch, rows, cols, pg, q, pix_off, acc);
+        else gram_rows<G, TSPLIT - 1>(pix, p.pitch, rows, cols, pg, q, pix_off, acc);
 
-        if (++since_flush >= p.flush_items || it == count - 1) {
+        if (++since_flush >= p.flush_items || !more) {
             __syncthreads();                              // every wavefront is done with the tile
             gram_flush<G>(acc, lds, my_slot, pg, role, rmw);
             rmw = true;
             since_flush = 0;
+        }
+        if (more) {
+            // DC shift of tile it+1 = estimate left by tile it (cells cur), new estimate into the other cells
+            gram_tile_store<KS>(p, lds + (cur ^ 1) * p.buf_stride, pw, dc[2 * cur], dc[2 * cur + 1], ra, rb,
+                                dc + 2 * (cur ^ 1));
+            __syncthreads();
         }
     }
 }
@@ -368,7 +450,7 @@ static GramShape gram_shape(int k)
     switch (k) {
         case 3: return {1, 4};
         case 5: return {1, 4};
-        case 7: return {1, 3};
+        case 7: return {1, 2};
         default: return {2, 2};
     }
 }
@@ -410,11 +492,13 @@ int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t 
     while (pitch % 32 != (k + 3) % 32) ++pitch;
     p.pitch = pitch;
     p.view_stride = (GRAM_TH + 2 * r) * pitch + 16;      // +16: shift view 2 by half the banks
+    p.buf_stride = 2 * p.view_stride;
     const GramShape shape = gram_shape(k);
     const int npg = 4 / shape.tsplit;
-    const size_t tile_floats = (size_t)2 * p.view_stride + 2 * GRAM_TH * p.tw + 2 * (GRAM_TH + 2 * r) * p.tw;
+    const size_t tile_floats = (size_t)2 * p.buf_stride;
     const size_t stage_floats = (size_t)((gram_tiles(k) + shape.tsplit - 1) / shape.tsplit) * 256;
-    const size_t lds = std::max(tile_floats, stage_floats) * sizeof(float);
+    p.dc_off = (int)std::max(tile_floats, stage_floats);
+    const size_t lds = (size_t)(p.dc_off + 4) * sizeof(float);
     // about 16k patches between fp64 flushes per wavefront
     const int patches_per_group_item = (GRAM_TH / npg) * p.tw;
     p.flush_items = std::max(1, 16384 / patches_per_group_item);
@@ -431,7 +515,7 @@ int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t 
     switch (k) {
         GRAM_CASE(3, 1, 4)
         GRAM_CASE(5, 1, 4)
-        GRAM_CASE(7, 1, 3)
+        GRAM_CASE(7, 1, 2)
         GRAM_CASE(9, 2, 2)
         default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
     }
