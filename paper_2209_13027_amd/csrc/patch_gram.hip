@@ -90,32 +90,36 @@ __device__ __forceinline__ void gram_rows(const float *pix, int pitch, int rows,
     const int full = cols >> 2, tail = cols & 3;
     for (int py = pg; py < rows; py += G::NPG) {
         const float *prow = pix + py * pitch;
-        float z[NB];
+        // Two k-steps per iteration with two operand sets: the operands of the next step are
+        // fetched before the MFMAs of the current one, so the LDS latency is covered.
+        float z0[NB], z1[NB];
         if (full > 0) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) z[b] = prow[pix_off[b]];
+            for (int b = 0; b < NB; ++b) z0[b] = prow[pix_off[b]];
         }
-        for (int kx = 0; kx < full; ++kx) {
-            // the operands of the next step are fetched before this step's MFMAs, so the LDS
-            // latency is covered
-            const int nx = (kx + 1 < full) ? 4 * (kx + 1) : 4 * kx;
-            float zn[NB];
+        int kx = 0;
+        for (; kx + 1 < full; kx += 2) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) zn[b] = prow[pix_off[b] + nx];
+            for (int b = 0; b < NB; ++b) z1[b] = prow[pix_off[b] + 4 * (kx + 1)];
             __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);         // LDS reads first
-            gram_mfma_step<G, ROLE>(z, acc);
+            gram_mfma_step<G, ROLE>(z0, acc);
             __builtin_amdgcn_sched_group_barrier(0x008, G::NACC, 0);    // then every MFMA of the step
+            const int nx = (kx + 2 < full) ? 4 * (kx + 2) : 4 * (kx + 1);
 #pragma unroll
-            for (int b = 0; b < NB; ++b) z[b] = zn[b];
+            for (int b = 0; b < NB; ++b) z0[b] = prow[pix_off[b] + nx];
+            __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);
+            gram_mfma_step<G, ROLE>(z1, acc);
+            __builtin_amdgcn_sched_group_barrier(0x008, G::NACC, 0);
         }
+        if (full & 1) gram_mfma_step<G, ROLE>(z0, acc);
         if (tail) {                                   // ragged end of the row: patches past the image add 0
             const bool ok = q < tail;
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const float v = prow[pix_off[b] + 4 * full];
-                z[b] = ok ? v : 0.f;
+                z0[b] = ok ? v : 0.f;
             }
-            gram_mfma_step<G, ROLE>(z, acc);
+            gram_mfma_step<G, ROLE>(z0, acc);
         }
     }
 }
