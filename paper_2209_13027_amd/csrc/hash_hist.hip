@@ -1,87 +1,173 @@
-// Output layer: hashing of the L2 maps of one input into a code map (Eq. 7-9) fused
-// with the per-block code histogram (Section II-C).  Integer work only; HBM-bound.
+// Output layer: hashing of the L2 maps of one input into a code map (Eq. 7-9) fused with the
+// per-block code histogram (Section II-C).  Integer work only; HBM-bound: every map pixel is
+// read (ideally once) and every uint16 count is written once.
+//
+// One workgroup owns RB consecutive block rows of one map and a chunk of block columns.  Its
+// LDS holds their histograms as packed 16-bit counters (two bins per 32-bit word, which is
+// also the memory layout of the output, so the counts leave LDS as a plain vector copy).
+// Every pixel of the rows the block rows cover is hashed once per workgroup (L2 coalesced
+// plane reads, strict "> 0") and added with an LDS atomic to each block that contains it.
+// A count never exceeds the block area (<= 65535, checked on the host), so the two halves
+// of a word cannot overflow into each other.
 #include "ddcca_internal.h"
 
 namespace ddcca {
 
-// General kernel: one workgroup owns one block row (i) of one map and a chunk of block
-// columns.  Its LDS holds the chunk's histograms as 32-bit counters; every pixel of the
-// block row's bh image rows is hashed once by this workgroup and added to each block
-// column of the chunk that contains it.
-template <int L2>
-__global__ __launch_bounds__(256) void hash_hist_rows_kernel(const float *__restrict__ maps, int h, int w, int bh,
-                                                             int bw, int sy, int sx, int nby, int nbx,
-                                                             int cols_per_wg, uint16_t *__restrict__ hist,
-                                                             int64_t group, int64_t group_stride)
-{
-    extern __shared__ unsigned int lds_hist[];
-    constexpr int BINS = 1 << L2;
-    const int64_t n = blockIdx.z;
-    const int i = blockIdx.y;
-    const int j0 = blockIdx.x * cols_per_wg;
-    const int j1 = min(j0 + cols_per_wg, nbx);
-    const int ncol = j1 - j0;
-    for (int e = threadIdx.x; e < ncol * BINS; e += blockDim.x) lds_hist[e] = 0u;
-    __syncthreads();
+constexpr int HIST_THREADS = 256;
+constexpr int HIST_LDS_BYTES = 32 * 1024;   // histogram bytes per workgroup (occupancy 4-5 per CU)
 
-    const int64_t P = (int64_t)h * w;
-    const float *base = maps + n * L2 * P;
-    const int x_lo = j0 * sx;
-    const int x_hi = (j1 - 1) * sx + bw;          // exclusive
-    const int span = x_hi - x_lo;
-    const int y0 = i * sy;
-    for (int e = threadIdx.x; e < bh * span; e += blockDim.x) {
-        const int yy = e / span, x = x_lo + (e - yy * span);
-        const int64_t u = (int64_t)(y0 + yy) * w + x;
-        unsigned int code = 0;
-#pragma unroll
-        for (int l = 0; l < L2; ++l) code |= (base[l * P + u] > 0.0f ? 1u : 0u) << l;
-        // block columns j with j*sx <= x < j*sx + bw
-        int jlo = (x - bw + sx) / sx;             // ceil((x - bw + 1) / sx) for x-bw+1 >= 0
-        if (x - bw + 1 < 0) jlo = 0;
-        int jhi = x / sx;
-        jlo = max(jlo, j0);
-        jhi = min(jhi, j1 - 1);
-        for (int j = jlo; j <= jhi; ++j) atomicAdd(&lds_hist[(j - j0) * BINS + code], 1u);
-    }
-    __syncthreads();
-    const int64_t A = (int64_t)nby * nbx;
-    uint16_t *out = hist + (n / group) * group_stride + (n % group) * A * BINS + ((int64_t)i * nbx + j0) * BINS;
-    for (int e = threadIdx.x; e < ncol * BINS; e += blockDim.x) out[e] = (uint16_t)lds_hist[e];
+struct HistParams {
+    const float *maps;
+    uint16_t *hist;
+    int h, w, bh, bw, sy, sx, nby, nbx;
+    int rb;             // block rows per workgroup
+    int cols;           // block columns per workgroup
+    int row_groups;     // ceil(nby / rb)
+    int col_chunks;     // ceil(nbx / cols)
+    int64_t group, group_stride;
+    int vec4;           // rows may be read as aligned float4
+};
+
+template <int L2>
+__device__ __forceinline__ void hist_add(unsigned int *lds_hist, const HistParams &p, int y, int x, unsigned code,
+                                         int i0, int i1, int j0, int j1, int ncol)
+{
+    constexpr int WORDS = (1 << L2) > 1 ? (1 << L2) / 2 : 1;   // 32-bit words per histogram
+    // block rows i with i*sy <= y < i*sy + bh, block columns j likewise
+    int ilo = y - p.bh + 1 < 0 ? 0 : (y - p.bh + p.sy) / p.sy;
+    int ihi = y / p.sy;
+    int jlo = x - p.bw + 1 < 0 ? 0 : (x - p.bw + p.sx) / p.sx;
+    int jhi = x / p.sx;
+    ilo = max(ilo, i0); ihi = min(ihi, i1 - 1);
+    jlo = max(jlo, j0); jhi = min(jhi, j1 - 1);
+    const unsigned inc = 1u << (16 * (code & 1));
+    const unsigned word = code >> 1;
+    for (int i = ilo; i <= ihi; ++i)
+        for (int j = jlo; j <= jhi; ++j)
+            atomicAdd(&lds_hist[((i - i0) * ncol + (j - j0)) * WORDS + word], inc);
 }
 
 template <int L2>
-static void launch_rows(ddcca_ctx *ctx, const float *maps, int64_t n, int h, int w, int bh, int bw, int sy, int sx,
-                        uint16_t *hist, int64_t group, int64_t group_stride)
+__global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p)
 {
-    const int nby = (h - bh) / sy + 1, nbx = (w - bw) / sx + 1;
+    extern __shared__ unsigned int lds_hist[];
     constexpr int BINS = 1 << L2;
-    int cols = std::max(1, (48 * 1024) / (BINS * 4));
-    cols = std::min(cols, nbx);
-    const int chunks = (nbx + cols - 1) / cols;
-    const size_t lds = (size_t)cols * BINS * sizeof(unsigned int);
-    dim3 grid(chunks, nby, (unsigned)n);      // caller keeps n <= 65535 (grid.z limit)
-    hipLaunchKernelGGL(hash_hist_rows_kernel<L2>, grid, dim3(256), lds, ctx->stream, maps, h, w, bh, bw, sy, sx, nby,
-                       nbx, cols, hist, group, group_stride);
+    constexpr int WORDS = BINS > 1 ? BINS / 2 : 1;
+    const int per_map = p.row_groups * p.col_chunks;
+    const int64_t n = blockIdx.x / per_map;
+    const int r = blockIdx.x - (int)n * per_map;
+    const int rg = r / p.col_chunks, cc = r - rg * p.col_chunks;
+    const int i0 = rg * p.rb, i1 = min(i0 + p.rb, p.nby);
+    const int j0 = cc * p.cols, j1 = min(j0 + p.cols, p.nbx);
+    const int nrow = i1 - i0, ncol = j1 - j0;
+    const int n_words = nrow * ncol * WORDS;
+    for (int e = threadIdx.x; e < n_words; e += HIST_THREADS) lds_hist[e] = 0u;
+    __syncthreads();
+
+    const int64_t P = (int64_t)p.h * p.w;
+    const float *base = p.maps + n * L2 * P;
+    const int y_lo = i0 * p.sy, y_hi = (i1 - 1) * p.sy + p.bh;       // rows [y_lo, y_hi)
+    const int x_lo = j0 * p.sx, x_hi = (j1 - 1) * p.sx + p.bw;       // columns [x_lo, x_hi)
+    if (p.vec4) {
+        // aligned quads of 4 pixels; the quad range covers [x_lo, x_hi) and is clipped per pixel
+        const int q_lo = x_lo >> 2, q_hi = (x_hi + 3) >> 2;
+        const int nq = q_hi - q_lo;
+        const int total = (y_hi - y_lo) * nq;
+        for (int e = threadIdx.x; e < total; e += HIST_THREADS) {
+            const int yy = e / nq, xq = q_lo + (e - yy * nq);
+            const int y = y_lo + yy;
+            const float *src = base + (int64_t)y * p.w + 4 * xq;
+            unsigned c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+#pragma unroll
+            for (int l = 0; l < L2; ++l) {
+                const float4 v = *reinterpret_cast<const float4 *>(src + l * P);
+                c0 |= (v.x > 0.0f ? 1u : 0u) << l;
+                c1 |= (v.y > 0.0f ? 1u : 0u) << l;
+                c2 |= (v.z > 0.0f ? 1u : 0u) << l;
+                c3 |= (v.w > 0.0f ? 1u : 0u) << l;
+            }
+            const int x = 4 * xq;
+            if (x >= x_lo && x < x_hi) hist_add<L2>(lds_hist, p, y, x, c0, i0, i1, j0, j1, ncol);
+            if (x + 1 >= x_lo && x + 1 < x_hi) hist_add<L2>(lds_hist, p, y, x + 1, c1, i0, i1, j0, j1, ncol);
+            if (x + 2 >= x_lo && x + 2 < x_hi) hist_add<L2>(lds_hist, p, y, x + 2, c2, i0, i1, j0, j1, ncol);
+            if (x + 3 >= x_lo && x + 3 < x_hi) hist_add<L2>(lds_hist, p, y, x + 3, c3, i0, i1, j0, j1, ncol);
+        }
+    } else {
+        const int span = x_hi - x_lo;
+        const int total = (y_hi - y_lo) * span;
+        for (int e = threadIdx.x; e < total; e += HIST_THREADS) {
+            const int yy = e / span, x = x_lo + (e - yy * span);
+            const int y = y_lo + yy;
+            const int64_t u = (int64_t)y * p.w + x;
+            unsigned code = 0;
+#pragma unroll
+            for (int l = 0; l < L2; ++l) code |= (base[l * P + u] > 0.0f ? 1u : 0u) << l;
+            hist_add<L2>(lds_hist, p, y, x, code, i0, i1, j0, j1, ncol);
+        }
+    }
+    __syncthreads();
+
+    // copy out: block row i of the chunk is ncol*BINS contiguous uint16 in the output
+    const int64_t A = (int64_t)p.nby * p.nbx;
+    uint16_t *out_map = p.hist + (n / p.group) * p.group_stride + (n % p.group) * A * BINS;
+    if (BINS >= 8 && ((((uintptr_t)out_map) | (uintptr_t)(A * BINS * 2) | (uintptr_t)(p.group_stride * 2)) & 15) == 0) {
+        const int row_vec = ncol * WORDS / 4;                        // uint4 per block row of the chunk
+        for (int e = threadIdx.x; e < nrow * row_vec; e += HIST_THREADS) {
+            const int ir = e / row_vec, v = e - ir * row_vec;
+            const uint4 val = *reinterpret_cast<const uint4 *>(lds_hist + (ir * ncol * WORDS) + 4 * v);
+            uint16_t *dst = out_map + ((int64_t)(i0 + ir) * p.nbx + j0) * BINS;
+            *reinterpret_cast<uint4 *>(dst + 8 * v) = val;
+        }
+    } else {
+        for (int e = threadIdx.x; e < nrow * ncol * BINS; e += HIST_THREADS) {
+            const int ir = e / (ncol * BINS), rest = e - ir * ncol * BINS;
+            const unsigned wv = lds_hist[ir * ncol * WORDS + (rest >> 1)];
+            uint16_t *dst = out_map + ((int64_t)(i0 + ir) * p.nbx + j0) * BINS;
+            dst[rest] = (uint16_t)((BINS > 1 ? (wv >> (16 * (rest & 1))) : wv) & 0xffffu);
+        }
+    }
+}
+
+template <int L2>
+static void hist_launch(ddcca_ctx *ctx, HistParams p, int64_t n)
+{
+    constexpr int BINS = 1 << L2;
+    constexpr int HIST_BYTES = (BINS > 1 ? BINS / 2 : 1) * 4;         // packed histogram of one block
+    const int max_blocks = std::max(1, HIST_LDS_BYTES / HIST_BYTES);
+    p.cols = std::min(p.nbx, max_blocks);
+    p.col_chunks = (p.nbx + p.cols - 1) / p.cols;
+    // several block rows per workgroup cut the re-reading of the rows that overlapping blocks share
+    p.rb = std::max(1, std::min(p.nby, max_blocks / p.cols));
+    p.row_groups = (p.nby + p.rb - 1) / p.rb;
+    const size_t lds = (size_t)p.rb * p.cols * HIST_BYTES;
+    const int64_t per_map = (int64_t)p.row_groups * p.col_chunks;
+    const int64_t maps_per_launch = std::max<int64_t>(p.group, (((int64_t)1 << 30) / per_map) / p.group * p.group);
+    for (int64_t n0 = 0; n0 < n; n0 += maps_per_launch) {
+        const int64_t nb = std::min(maps_per_launch, n - n0);
+        HistParams q = p;
+        q.maps = p.maps + n0 * L2 * (int64_t)p.h * p.w;
+        q.hist = p.hist + (n0 / p.group) * p.group_stride;
+        hipLaunchKernelGGL(hash_hist_kernel<L2>, dim3((unsigned)(nb * per_map)), dim3(HIST_THREADS), lds, ctx->stream,
+                           q);
+    }
 }
 
 int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int bh, int bw, int sy,
                      int sx, uint16_t *hist, int64_t group, int64_t group_stride)
 {
     ProfScope prof(ctx, DDCCA_K_HASH_HIST);
-    // grid.z carries the map index and is limited to 65535; sub-launches start at
-    // multiples of `group` so that the output addressing stays (n / group, n % group)
-    const int64_t step = std::max<int64_t>(group, (65535 / group) * group);
-    for (int64_t n0 = 0; n0 < n; n0 += step) {
-        const int64_t nb = std::min(step, n - n0);
-        const float *m = maps + n0 * L2 * (int64_t)h * w;
-        uint16_t *o = hist + (n0 / group) * group_stride;
-        switch (L2) {
-#define CASE(v) case v: launch_rows<v>(ctx, m, nb, h, w, bh, bw, sy, sx, o, group, group_stride); break;
-            CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12)
+    HistParams p;
+    p.maps = maps; p.hist = hist;
+    p.h = h; p.w = w; p.bh = bh; p.bw = bw; p.sy = sy; p.sx = sx;
+    p.nby = (h - bh) / sy + 1;
+    p.nbx = (w - bw) / sx + 1;
+    p.group = group; p.group_stride = group_stride;
+    p.vec4 = ((w & 3) == 0 && (((uintptr_t)maps) & 15) == 0) ? 1 : 0;
+    switch (L2) {
+#define CASE(v) case v: hist_launch<v>(ctx, p, n); break;
+        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12)
 #undef CASE
-            default: return fail(ctx, DDCCA_EINVAL, "L2 out of range");
-        }
+        default: return fail(ctx, DDCCA_EINVAL, "L2 out of range");
     }
     DDCCA_HIP(ctx, hipGetLastError());
     return DDCCA_OK;
