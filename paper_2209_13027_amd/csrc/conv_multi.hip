@@ -25,36 +25,43 @@ constexpr int CONV_TH = 32;        // tile rows per workgroup
 constexpr int CONV_XB = 32;        // pixels per MFMA column block (16 columns x 2 shifts)
 constexpr int CONV_MAX_NBX = 4;    // column blocks per tile (tile width <= 128)
 
-template <int KS>
+// One workgroup: a 32-row x (32*NBX)-column output tile of one image, all L filters.
+// Wavefront w owns tile rows w, w+4, ...; for one row it runs NBX independent accumulator
+// chains (one per 32-pixel column block), so one window-offset add serves NBX LDS reads and
+// NBX MFMAs.
+template <int KS, int NBX>
 __global__ __launch_bounds__(CONV_THREADS) void conv_mfma_kernel(const float *__restrict__ in, int h, int w,
                                                                  const float *__restrict__ W, int L,
-                                                                 float *__restrict__ out, int tiles_x, int tiles_y,
-                                                                 int nbx, int pitch)
+                                                                 float *__restrict__ out, int tiles_x, int tiles_y)
 {
     constexpr int R = (KS - 1) / 2;
     constexpr int KW = KS + 1;                    // tap columns incl. the shift
     constexpr int TAPS = KS * KW;
     constexpr int KK = (TAPS + 3) / 4;            // MFMA steps
     constexpr int PH = CONV_TH + 2 * R;
-    extern __shared__ float tile[];               // [PH][pitch]
+    constexpr int TW = NBX * CONV_XB;
+    constexpr int PW = TW + 2 * R + 1;            // +1: the odd shift reads one more column
+    constexpr int PITCH = PW | 1;                 // odd pitch: rows start in different banks
+    __shared__ float tile[PH * PITCH];
     const int tiles = tiles_x * tiles_y;
     const int64_t n = blockIdx.x / tiles;
     const int t = blockIdx.x - (int)n * tiles;
     const int tx = t % tiles_x, ty = t / tiles_x;
-    const int tw = nbx * CONV_XB;
-    const int pw = tw + 2 * R + 1;                // +1: the odd shift reads one more column
     const int64_t P = (int64_t)h * w;
-    const float *src = in + n * P;
-    const int gy0 = ty * CONV_TH - R, gx0 = tx * tw - R;
-    for (int e = threadIdx.x; e < PH * pw; e += CONV_THREADS) {
-        const int yy = e / pw, xx = e - yy * pw;
-        const int gy = gy0 + yy, gx = gx0 + xx;
-        float v = 0.f;
-        if (gy >= 0 && gy < h && gx >= 0 && gx < w) v = src[(int64_t)gy * w + gx];
-        tile[yy * pitch + xx] = v;
-    }
-
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    {
+        // stage the input tile with its halo (PW is a compile-time constant: cheap index split)
+        const float *src = in + n * P;
+        const int gy0 = ty * CONV_TH - R, gx0 = tx * TW - R;
+#pragma unroll 4
+        for (int e = threadIdx.x; e < PH * PW; e += CONV_THREADS) {
+            const int yy = e / PW, xx = e - yy * PW;
+            const int gy = gy0 + yy, gx = gx0 + xx;
+            float v = 0.f;
+            if (gy >= 0 && gy < h && gx >= 0 && gx < w) v = src[(int64_t)gy * w + gx];
+            tile[yy * PITCH + xx] = v;
+        }
+    }
     const int q = lane >> 4, c = lane & 15;
     // B-operand window offsets of this lane's tap (4*kk + q) for every step
     int toff[KK];
@@ -62,13 +69,13 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_mfma_kernel(const float *__
     for (int kk = 0; kk < KK; ++kk) {
         const int tap = 4 * kk + q;
         const int dy = tap / KW, dx = tap - dy * KW;
-        toff[kk] = tap < TAPS ? dy * pitch + dx : 0;
+        toff[kk] = tap < TAPS ? dy * PITCH + dx : 0;
     }
     __syncthreads();
 
     const int rows = min(CONV_TH, h - ty * CONV_TH);
-    const int units = rows * nbx;                 // (row, column block) pairs of this tile
     const bool out_al8 = (((uintptr_t)out) & 7) == 0;
+    const int gx_lane = tx * TW + 2 * c;
 
     for (int g0 = 0; g0 < L; g0 += 8) {
         // A operand: row (g,s) = lane%16, tap 4*kk + lane/16
@@ -84,42 +91,41 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_mfma_kernel(const float *__
                 wa[kk] = v;
             }
         }
-        for (int u = wave; u < units; u += 8) {
-            // two independent units per iteration: u and u+4
-            const int u1 = u + 4;
-            const bool has1 = u1 < units;
-            const int r0 = u / nbx, b0 = u - r0 * nbx;
-            const int r1 = has1 ? u1 / nbx : r0, b1 = has1 ? u1 - r1 * nbx : b0;
-            const float *p0 = tile + r0 * pitch + b0 * CONV_XB + 2 * c;
-            const float *p1 = tile + r1 * pitch + b1 * CONV_XB + 2 * c;
-            floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+        // lane (q,c) ends with planes g0+2q (acc[0..1]) and g0+2q+1 (acc[2..3]) at columns x, x+1
+        const int ga = g0 + 2 * q;
+        for (int r = wave; r < rows; r += 4) {
+            const float *prow = tile + r * PITCH + 2 * c;
+            floatx4 acc[NBX];
+#pragma unroll
+            for (int b = 0; b < NBX; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+#ifdef CONV_EXP_NO_MFMA
+#pragma unroll
+            for (int b = 0; b < NBX; ++b) acc[b] = floatx4{prow[b], prow[b + 1], wa[0], wa[1]};
+#else
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                const float x0 = p0[toff[kk]];
-                const float x1 = p1[toff[kk]];
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[kk], x0, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[kk], x1, acc1, 0, 0, 0);
+                const float *pk = prow + toff[kk];
+#pragma unroll
+                for (int b = 0; b < NBX; ++b)
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[kk], pk[b * CONV_XB], acc[b], 0, 0, 0);
             }
-            // lane (q,c) holds filter g0+2q (acc[0..1]) and g0+2q+1 (acc[2..3]) at x, x+1
+#endif
+            const int gy = ty * CONV_TH + r;
+            const int64_t orow = (n * L + ga) * P + (int64_t)gy * w + gx_lane;
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const floatx4 acc = half ? acc1 : acc0;
-                if (half && !has1) break;
-                const int rr = half ? r1 : r0, bb = half ? b1 : b0;
-                const int gy = ty * CONV_TH + rr;
-                const int gx = tx * tw + bb * CONV_XB + 2 * c;
-                if (gx >= w) continue;
+            for (int e = 0; e < 2; ++e) {
+                if (ga + e >= L) continue;
+                float *dst = out + orow + e * P;
+                const bool al = out_al8 && (((orow + e * P) & 1) == 0);
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const int g = g0 + 2 * q + e;
-                    if (g >= L) continue;
-                    const int64_t o = (n * L + g) * P + (int64_t)gy * w + gx;
-                    const float a = acc[2 * e], b = acc[2 * e + 1];
-                    if (gx + 1 < w && out_al8 && (o & 1) == 0) {
-                        *reinterpret_cast<float2 *>(out + o) = make_float2(a, b);
-                    } else {
-                        out[o] = a;
-                        if (gx + 1 < w) out[o + 1] = b;
+                for (int b = 0; b < NBX; ++b) {
+                    const int gx = gx_lane + b * CONV_XB;
+                    const float v0 = acc[b][2 * e], v1 = acc[b][2 * e + 1];
+                    if (gx + 1 < w && al) {
+                        *reinterpret_cast<float2 *>(dst + b * CONV_XB) = make_float2(v0, v1);
+                    } else if (gx < w) {
+                        dst[b * CONV_XB] = v0;
+                        if (gx + 1 < w) dst[b * CONV_XB + 1] = v1;
                     }
                 }
             }
@@ -127,24 +133,33 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_mfma_kernel(const float *__
     }
 }
 
-template <int KS>
-static int conv_launch(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int L, float *out)
+template <int KS, int NBX>
+static void conv_launch_nbx(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int L, float *out)
 {
-    constexpr int R = (KS - 1) / 2;
-    const int xblocks = (w + CONV_XB - 1) / CONV_XB;
-    const int tiles_x = (xblocks + CONV_MAX_NBX - 1) / CONV_MAX_NBX;
-    const int nbx = (xblocks + tiles_x - 1) / tiles_x;          // equal-width tiles
+    const int tiles_x = (w + NBX * CONV_XB - 1) / (NBX * CONV_XB);
     const int tiles_y = (h + CONV_TH - 1) / CONV_TH;
-    int pitch = nbx * CONV_XB + 2 * R + 1;
-    pitch += (pitch & 1) ? 0 : 1;                                // odd pitch: rows start in different banks
-    const size_t lds = (size_t)(CONV_TH + 2 * R) * pitch * sizeof(float);
     const int64_t tiles = (int64_t)tiles_x * tiles_y;
     const int64_t per_launch = std::max<int64_t>(1, ((int64_t)1 << 30) / tiles);   // grid.x stays below 2^31
     for (int64_t n0 = 0; n0 < n; n0 += per_launch) {
         const int64_t nb = std::min(per_launch, n - n0);
-        hipLaunchKernelGGL(conv_mfma_kernel<KS>, dim3((unsigned)(nb * tiles)), dim3(CONV_THREADS), lds, ctx->stream,
-                           in + n0 * (int64_t)h * w, h, w, W, L, out + n0 * L * (int64_t)h * w, tiles_x, tiles_y, nbx,
-                           pitch);
+        hipLaunchKernelGGL((conv_mfma_kernel<KS, NBX>), dim3((unsigned)(nb * tiles)), dim3(CONV_THREADS), 0,
+                           ctx->stream, in + n0 * (int64_t)h * w, h, w, W, L, out + n0 * L * (int64_t)h * w, tiles_x,
+                           tiles_y);
+    }
+}
+
+template <int KS>
+static int conv_launch(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int L, float *out)
+{
+    // equal-width tiles of at most CONV_MAX_NBX column blocks
+    const int xblocks = (w + CONV_XB - 1) / CONV_XB;
+    const int tiles_x = (xblocks + CONV_MAX_NBX - 1) / CONV_MAX_NBX;
+    const int nbx = (xblocks + tiles_x - 1) / tiles_x;
+    switch (nbx) {
+        case 1: conv_launch_nbx<KS, 1>(ctx, in, n, h, w, W, L, out); break;
+        case 2: conv_launch_nbx<KS, 2>(ctx, in, n, h, w, W, L, out); break;
+        case 3: conv_launch_nbx<KS, 3>(ctx, in, n, h, w, W, L, out); break;
+        default: conv_launch_nbx<KS, 4>(ctx, in, n, h, w, W, L, out); break;
     }
     DDCCA_HIP(ctx, hipGetLastError());
     return DDCCA_OK;
