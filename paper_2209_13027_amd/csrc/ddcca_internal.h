@@ -76,11 +76,12 @@ struct ProfScope {
 };
 
 // ---- geometry of the stacked (two views) patch Gram --------------------------------
-// The stacked patch vector z = [x1; x2] has 2D entries, D = k*k.  Its Gram is computed
-// in 16x16 tiles, upper block-triangle only; tile (bi,bj), bi <= bj, has index
-// tile_index(bi,bj).  Inside a slot, tile t / accumulator register v / lane l sits at
-// (t*4 + v)*64 + l and holds Gram entry (16*bi + 4*(l/16) + v, 16*bj + l%16).
-inline int gram_blocks(int k) { return (2 * k * k + 15) / 16; }
+// The stacked vector z = [y1; y2] (patches minus their centre pixel, centre entry dropped)
+// has 2(D-1) entries, D = k*k.  Its Gram is computed in 16x16 tiles, upper block-triangle
+// only; tile (bi,bj), bi <= bj, is number bi*NB - bi(bi-1)/2 + bj - bi.  Inside a slot, tile t /
+// accumulator register v / lane l sits at (t*4 + v)*64 + l and holds Gram entry
+// (16*bi + 4*(l/16) + v, 16*bj + l%16).
+inline int gram_blocks(int k) { return (2 * (k * k - 1)) / 16; }
 inline int gram_tiles(int k) { int nb = gram_blocks(k); return nb * (nb + 1) / 2; }
 
 // ---- kernel launchers (each validates nothing; callers have validated) --------------

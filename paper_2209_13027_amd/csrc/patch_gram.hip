@@ -8,13 +8,15 @@
 // bj have the same register layout (lane l: stacked row 16*b + l%16, patch l/16), so one LDS
 // read per block feeds every tile of that block row and block column.
 //
-// Mean removal: the mean-removed patch is H x with H = I - 11^T/D, so the sum of the
-// mean-removed outer products is H (sum x x^T) H.  The kernel therefore accumulates the Gram
-// of the RAW patches and the export step applies H . H in fp64.  Because H annihilates
-// constants, any constant may be subtracted from all pixels of a tile (padding included)
-// without changing the result; each tile is shifted by an estimate of the local mean pixel
-// value so that a large DC level (non-negative views, 8-bit images) does not eat the fp32
-// mantissa of the accumulators.
+// Mean removal: the mean-removed patch is H x with H = I - 11^T/D, and H annihilates
+// constant vectors, so H x = H (x - c 1) for ANY per-patch constant c.  The kernel uses
+// c = the patch's own centre pixel: y = x - x_centre has a zero at the centre position, so
+// only D-1 entries per view are contracted (2(D-1) = 16, 48, 96, 160 stacked rows for
+// k = 3, 5, 7, 9: whole 16-row blocks, no padding), and the export step rebuilds
+// sum (H x)(H x)^T = H (sum y y^T) H in fp64.  Differences to the centre pixel also carry no
+// DC level, which keeps the fp32 accumulators well scaled; on top of that each tile is
+// shifted by an estimate of its mean pixel value (harmless, and it keeps the staged values
+// themselves small).
 #include "ddcca_internal.h"
 
 namespace ddcca {
@@ -47,13 +49,21 @@ template <int KS, int TSPLIT_, bool CROSS_>
 struct GramGeom {
     static constexpr int D = KS * KS;
     static constexpr int R = (KS - 1) / 2;
-    static constexpr int NB = (2 * D + 15) / 16;
+    static constexpr int DR = D - 1;                     // contracted entries per view (centre dropped)
+    static constexpr int CEN = (D - 1) / 2;              // patch index of the centre pixel
+    static constexpr int NB = (2 * DR) / 16;
+    // centre-pixel operands per k-step: one per view when no 16-row block mixes the views,
+    // else one per block
+    static constexpr bool STRADDLE = (DR % 16) != 0;
+    static constexpr int NCEN = STRADDLE ? NB : 2;
+    static constexpr int cen_index(int b) { return STRADDLE ? b : (b >= NB / 2 ? 1 : 0); }
+    static_assert((2 * DR) % 16 == 0, "2(k^2-1) is a multiple of 16 for odd k");
     static constexpr int NT = NB * (NB + 1) / 2;         // slot layout always covers the full triangle
     static constexpr int TSPLIT = TSPLIT_;
     static constexpr bool CROSS = CROSS_;
     static constexpr int NPG = 4 / TSPLIT_;              // patch-row groups per workgroup
-    static constexpr int B1_END = (D + 15) / 16;         // blocks [0, B1_END) contain view-1 rows
-    static constexpr int B2_BEGIN = D / 16;              // blocks [B2_BEGIN, NB) contain view-2 rows
+    static constexpr int B1_END = (DR + 15) / 16;        // blocks [0, B1_END) contain view-1 rows
+    static constexpr int B2_BEGIN = DR / 16;             // blocks [B2_BEGIN, NB) contain view-2 rows
     static constexpr bool tile_used(int bi, int bj) { return !CROSS_ || (bi < B1_END && bj >= B2_BEGIN); }
     static constexpr int used_tiles()
     {
@@ -84,7 +94,8 @@ __device__ __forceinline__ void gram_mfma_step(const float (&z)[G::NB], floatx4 
 // All k-steps of this wavefront's patch rows of the staged tile.
 template <typename G, int ROLE>
 __device__ __forceinline__ void gram_rows(const float *pix, int pitch, int rows, int cols, int pg, int q,
-                                          const int (&pix_off)[G::NB], floatx4 (&acc)[G::NACC])
+                                          const int (&pix_off)[G::NB], const int (&cen_off)[G::NCEN],
+                                          floatx4 (&acc)[G::NACC])
 {
     constexpr int NB = G::NB;
     const int full = cols >> 2, tail = cols & 3;
@@ -95,28 +106,37 @@ __device__ __forceinline__ void gram_rows(const float *pix, int pitch, int rows,
         float z0[NB], z1[NB];
         if (full > 0) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) z0[b] = prow[pix_off[b]];
+            for (int b = 0; b < NB; ++b) z0[b] = prow[pix_off[b]] - prow[cen_off[G::cen_index(b)]];
         }
         int kx = 0;
         for (; kx + 1 < full; kx += 2) {
+            float pa[NB], pc[G::NCEN];
 #pragma unroll
-            for (int b = 0; b < NB; ++b) z1[b] = prow[pix_off[b] + 4 * (kx + 1)];
-            __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);         // LDS reads first
+            for (int b = 0; b < NB; ++b) pa[b] = prow[pix_off[b] + 4 * (kx + 1)];
+#pragma unroll
+            for (int v = 0; v < G::NCEN; ++v) pc[v] = prow[cen_off[v] + 4 * (kx + 1)];
+            __builtin_amdgcn_sched_group_barrier(0x100, NB + G::NCEN, 0);     // LDS reads first
             gram_mfma_step<G, ROLE>(z0, acc);
             __builtin_amdgcn_sched_group_barrier(0x008, G::NACC, 0);    // then every MFMA of the step
+#pragma unroll
+            for (int b = 0; b < NB; ++b) z1[b] = pa[b] - pc[G::cen_index(b)];
             const int nx = (kx + 2 < full) ? 4 * (kx + 2) : 4 * (kx + 1);
 #pragma unroll
-            for (int b = 0; b < NB; ++b) z0[b] = prow[pix_off[b] + nx];
-            __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);
+            for (int b = 0; b < NB; ++b) pa[b] = prow[pix_off[b] + nx];
+#pragma unroll
+            for (int v = 0; v < G::NCEN; ++v) pc[v] = prow[cen_off[v] + nx];
+            __builtin_amdgcn_sched_group_barrier(0x100, NB + G::NCEN, 0);
             gram_mfma_step<G, ROLE>(z1, acc);
             __builtin_amdgcn_sched_group_barrier(0x008, G::NACC, 0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) z0[b] = pa[b] - pc[G::cen_index(b)];
         }
         if (full & 1) gram_mfma_step<G, ROLE>(z0, acc);
         if (tail) {                                   // ragged end of the row: patches past the image add 0
             const bool ok = q < tail;
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const float v = prow[pix_off[b] + 4 * full];
+                const float v = prow[pix_off[b] + 4 * full] - prow[cen_off[G::cen_index(b)] + 4 * full];
                 z0[b] = ok ? v : 0.f;
             }
             gram_mfma_step<G, ROLE>(z0, acc);
@@ -266,23 +286,29 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
 {
     using G = GramGeom<KS, TSPLIT, CROSS>;
     using S = GramStage<KS>;
-    constexpr int D = G::D, R = G::R, NB = G::NB, NT = G::NT;
+    constexpr int R = G::R, NB = G::NB, NT = G::NT;
     extern __shared__ float lds[];
     float *dc = lds + p.dc_off;                            // [2][2] DC estimates, double-buffered
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int q = lane >> 4, i = lane & 15;
     const int pg = wave / TSPLIT, role = wave % TSPLIT;
 
-    // per-lane operand offsets for each 16-row block of the stacked vector
-    int pix_off[NB];
+    // per-lane operand offsets for each 16-row block of the stacked vector: stacked row
+    // 16*b + i is entry a' of view v (v = row / DR); entries at and after the centre shift by one
+    int pix_off[NB], cen_off[G::NCEN];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        int row = 16 * b + i;
-        if (row >= 2 * D) row = 0;                        // padding rows: any valid address; results unused
-        const int view = row >= D ? 1 : 0;
-        const int a = row - view * D;
+        const int row = 16 * b + i;
+        const int view = row >= G::DR ? 1 : 0;
+        const int ar = row - view * G::DR;
+        const int a = ar >= G::CEN ? ar + 1 : ar;
         const int dy = a / KS, dx = a - dy * KS;
         pix_off[b] = view * p.view_stride + dy * p.pitch + dx + q;
+        if (G::STRADDLE) cen_off[b] = view * p.view_stride + R * p.pitch + R + q;
+    }
+    if (!G::STRADDLE) {
+        cen_off[0] = R * p.pitch + R + q;
+        cen_off[1] = p.view_stride + R * p.pitch + R + q;
     }
 
     floatx4 acc[G::NACC];
@@ -342,8 +368,8 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
         const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
         const int rows = min(GRAM_TH, p.h - ty * GRAM_TH);
         const int cols = min(p.tw, p.w - tx * p.tw);
-        if (TSPLIT == 1 || role == 0) gram_rows<G, 0>(pix, p.pitch, rows, cols, pg, q, pix_off, acc);
-        else gram_rows<G, TSPLIT - 1>(pix, p.pitch, rows, cols, pg, q, pix_off, acc);
+        if (TSPLIT == 1 || role == 0) gram_rows<G, 0>(pix, p.pitch, rows, cols, pg, q, pix_off, cen_off, acc);
+        else gram_rows<G, TSPLIT - 1>(pix, p.pitch, rows, cols, pg, q, pix_off, cen_off, acc);
 
         if (++since_flush >= p.flush_items || !more) {
             __syncthreads();                              // every wavefront is done with the tile
@@ -381,7 +407,7 @@ __global__ void gram_reduce_final_kernel(const double *__restrict__ seg, int S, 
     stacked[e] = sum;
 }
 
-// Entry (r,c) of the stacked 2D x 2D Gram from its tile storage (upper block triangle).
+// Entry (r,c) of the stacked 2(D-1) x 2(D-1) Gram from its tile storage (upper block triangle).
 __device__ inline double stacked_entry(const double *st, int NB, int r, int c)
 {
     int bi = r >> 4, bj = c >> 4;
@@ -392,6 +418,17 @@ __device__ inline double stacked_entry(const double *st, int NB, int r, int c)
     const int tile = bi * NB - bi * (bi - 1) / 2 + (bj - bi);
     const int i = r & 15, j = c & 15;
     return st[(size_t)(tile * 4 + (i & 3)) * 64 + (i >> 2) * 16 + j];
+}
+
+// Entry (a,b) of the D x D block (view va, view vb) of sum y y^T, y = x - x_centre: the centre
+// row and column are zero, the others come from the reduced stacked Gram.
+__device__ inline double patch_block_entry(const double *st, int NB, int D, int va, int a, int vb, int b)
+{
+    const int cen = (D - 1) / 2;
+    if (a == cen || b == cen) return 0.0;
+    const int ra = va * (D - 1) + (a > cen ? a - 1 : a);
+    const int rb = vb * (D - 1) + (b > cen ? b - 1 : b);
+    return stacked_entry(st, NB, ra, rb);
 }
 
 // mats = [C11 | C22 | C12 | Cw | CT], each D*D, divided by the patch count; one workgroup
@@ -413,12 +450,12 @@ __global__ __launch_bounds__(256) void gram_export_kernel(const double *__restri
         double v;
         switch (which) {
             case 0:   // within-view blocks: mirrored entries are equal up to rounding order
-                v = 0.5 * (stacked_entry(st_main, NB, a, b) + stacked_entry(st_main, NB, b, a)); break;
+                v = 0.5 * (patch_block_entry(st_main, NB, D, 0, a, 0, b) + patch_block_entry(st_main, NB, D, 0, b, 0, a)); break;
             case 1:
-                v = 0.5 * (stacked_entry(st_main, NB, D + a, D + b) + stacked_entry(st_main, NB, D + b, D + a)); break;
-            case 2: v = stacked_entry(st_main, NB, a, D + b); break;
-            case 3: v = stacked_entry(st_cls, NB, a, D + b); break;
-            default: v = stacked_entry(st_tot, NB, a, D + b); break;
+                v = 0.5 * (patch_block_entry(st_main, NB, D, 1, a, 1, b) + patch_block_entry(st_main, NB, D, 1, b, 1, a)); break;
+            case 2: v = patch_block_entry(st_main, NB, D, 0, a, 1, b); break;
+            case 3: v = patch_block_entry(st_cls, NB, D, 0, a, 1, b); break;
+            default: v = patch_block_entry(st_tot, NB, D, 0, a, 1, b); break;
         }
         M[e] = v * inv_n;
     }
