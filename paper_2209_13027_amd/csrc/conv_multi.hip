@@ -71,26 +71,31 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_mfma_kernel(const float *__
         const int dy = tap / KW, dx = tap - dy * KW;
         toff[kk] = tap < TAPS ? dy * PITCH + dx : 0;
     }
+    // A operand: row (g,s) = lane%16, tap 4*kk + lane/16; fetched for the first filter group while
+    // the tile loads are still in flight
+    float wa[KK];
+    auto load_weights = [&](int g0) {
+        const int g = g0 + (c >> 1), s = c & 1;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            const int tap = 4 * kk + q;
+            const int dy = tap / KW, dxw = tap - dy * KW - s;
+            float v = 0.f;
+            if (tap < TAPS && dxw >= 0 && dxw < KS && g < L) v = W[(g * KS + dy) * KS + dxw];
+            wa[kk] = v;
+        }
+    };
+    load_weights(0);
     __syncthreads();
 
     const int rows = min(CONV_TH, h - ty * CONV_TH);
-    const bool out_al8 = (((uintptr_t)out) & 7) == 0;
     const int gx_lane = tx * TW + 2 * c;
 
     for (int g0 = 0; g0 < L; g0 += 8) {
-        // A operand: row (g,s) = lane%16, tap 4*kk + lane/16
-        float wa[KK];
-        {
-            const int g = g0 + (c >> 1), s = c & 1;
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                const int tap = 4 * kk + q;
-                const int dy = tap / KW, dxw = tap - dy * KW - s;
-                float v = 0.f;
-                if (tap < TAPS && dxw >= 0 && dxw < KS && g < L) v = W[(g * KS + dy) * KS + dxw];
-                wa[kk] = v;
-            }
-        }
+        if (g0 > 0) load_weights(g0);             // the first group was fetched before the barrier
+        // uniform per workgroup: every store of this pass is an aligned float2 (w even: pairs never straddle the edge)
+        const bool fast = (w & 1) == 0 && (((uintptr_t)out) & 7) == 0 && g0 + 8 <= L;
+        const int nfull = min(NBX, (w - tx * TW) / CONV_XB);   // column blocks of this tile fully inside the image
         // lane (q,c) ends with planes g0+2q (acc[0..1]) and g0+2q+1 (acc[2..3]) at columns x, x+1
         const int ga = g0 + 2 * q;
         for (int r = wave; r < rows; r += 4) {
@@ -111,21 +116,26 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_mfma_kernel(const float *__
             }
 #endif
             const int gy = ty * CONV_TH + r;
-            const int64_t orow = (n * L + ga) * P + (int64_t)gy * w + gx_lane;
+            float *dst = out + (n * L + ga) * P + (int64_t)gy * w + gx_lane;
+            if (fast) {
+                // 8-byte aligned rows, all 8 planes exist: column blocks fully inside the image are
+                // stored unconditionally, the ragged one (if any) per pixel pair
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                if (ga + e >= L) continue;
-                float *dst = out + orow + e * P;
-                const bool al = out_al8 && (((orow + e * P) & 1) == 0);
+                for (int e = 0; e < 2; ++e)
 #pragma unroll
-                for (int b = 0; b < NBX; ++b) {
-                    const int gx = gx_lane + b * CONV_XB;
-                    const float v0 = acc[b][2 * e], v1 = acc[b][2 * e + 1];
-                    if (gx + 1 < w && al) {
-                        *reinterpret_cast<float2 *>(dst + b * CONV_XB) = make_float2(v0, v1);
-                    } else if (gx < w) {
-                        dst[b * CONV_XB] = v0;
-                        if (gx + 1 < w) dst[b * CONV_XB + 1] = v1;
+                    for (int b = 0; b < NBX; ++b)
+                        if (b < nfull || gx_lane + b * CONV_XB < w)
+                            *reinterpret_cast<float2 *>(dst + e * P + b * CONV_XB) =
+                                make_float2(acc[b][2 * e], acc[b][2 * e + 1]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    if (ga + e >= L) continue;
+#pragma unroll
+                    for (int b = 0; b < NBX; ++b) {
+                        const int gx = gx_lane + b * CONV_XB;
+                        if (gx < w) dst[e * P + b * CONV_XB] = acc[b][2 * e];
+                        if (gx + 1 < w) dst[e * P + b * CONV_XB + 1] = acc[b][2 * e + 1];
                     }
                 }
             }
