@@ -26,20 +26,31 @@ struct HistParams {
     int col_chunks;     // ceil(nbx / cols)
     int64_t group, group_stride;
     int vec4;           // rows may be read as aligned float4
+    unsigned magic_sy, magic_sx;   // ceil(2^32 / stride) when h, w < 65536 (exact division by mul-hi), else 0
 };
 
+// x / d for 0 <= x < 65536 with magic = ceil(2^32 / d) (exact), plain division otherwise.
+__device__ __forceinline__ int fast_div(int x, int d, unsigned magic)
+{
+    return magic ? (int)__umulhi((unsigned)x, magic) : x / d;
+}
+
+// Block rows [ilo, ihi] (clipped to the workgroup's [i0, i1)) that contain image row y.
+__device__ __forceinline__ void block_range(int y, int b, int s, unsigned magic, int lo, int hi, int &first, int &last)
+{
+    first = y - b + 1 < 0 ? 0 : fast_div(y - b + s, s, magic);     // ceil((y - b + 1) / s)
+    last = fast_div(y, s, magic);
+    first = max(first, lo);
+    last = min(last, hi - 1);
+}
+
 template <int L2>
-__device__ __forceinline__ void hist_add(unsigned int *lds_hist, const HistParams &p, int y, int x, unsigned code,
-                                         int i0, int i1, int j0, int j1, int ncol)
+__device__ __forceinline__ void hist_add(unsigned int *lds_hist, const HistParams &p, int x, unsigned code, int ilo,
+                                         int ihi, int i0, int j0, int j1, int ncol)
 {
     constexpr int WORDS = (1 << L2) > 1 ? (1 << L2) / 2 : 1;   // 32-bit words per histogram
-    // block rows i with i*sy <= y < i*sy + bh, block columns j likewise
-    int ilo = y - p.bh + 1 < 0 ? 0 : (y - p.bh + p.sy) / p.sy;
-    int ihi = y / p.sy;
-    int jlo = x - p.bw + 1 < 0 ? 0 : (x - p.bw + p.sx) / p.sx;
-    int jhi = x / p.sx;
-    ilo = max(ilo, i0); ihi = min(ihi, i1 - 1);
-    jlo = max(jlo, j0); jhi = min(jhi, j1 - 1);
+    int jlo, jhi;
+    block_range(x, p.bw, p.sx, p.magic_sx, j0, j1, jlo, jhi);
     const unsigned inc = 1u << (16 * (code & 1));
     const unsigned word = code >> 1;
     for (int i = ilo; i <= ihi; ++i)
@@ -68,41 +79,44 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p)
     const float *base = p.maps + n * L2 * P;
     const int y_lo = i0 * p.sy, y_hi = (i1 - 1) * p.sy + p.bh;       // rows [y_lo, y_hi)
     const int x_lo = j0 * p.sx, x_hi = (j1 - 1) * p.sx + p.bw;       // columns [x_lo, x_hi)
+    // threads as 8 rows x 32 columns of work items (no per-item index division)
+    const int tcol = threadIdx.x & 31, trow = threadIdx.x >> 5;
     if (p.vec4) {
         // aligned quads of 4 pixels; the quad range covers [x_lo, x_hi) and is clipped per pixel
         const int q_lo = x_lo >> 2, q_hi = (x_hi + 3) >> 2;
-        const int nq = q_hi - q_lo;
-        const int total = (y_hi - y_lo) * nq;
-        for (int e = threadIdx.x; e < total; e += HIST_THREADS) {
-            const int yy = e / nq, xq = q_lo + (e - yy * nq);
-            const int y = y_lo + yy;
-            const float *src = base + (int64_t)y * p.w + 4 * xq;
-            unsigned c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+        for (int y = y_lo + trow; y < y_hi; y += 8) {
+            int ilo, ihi;
+            block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
+            const float *row = base + (int64_t)y * p.w;
+            for (int xq = q_lo + tcol; xq < q_hi; xq += 32) {
+                const float *src = row + 4 * xq;
+                unsigned c0 = 0, c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
-            for (int l = 0; l < L2; ++l) {
-                const float4 v = *reinterpret_cast<const float4 *>(src + l * P);
-                c0 |= (v.x > 0.0f ? 1u : 0u) << l;
-                c1 |= (v.y > 0.0f ? 1u : 0u) << l;
-                c2 |= (v.z > 0.0f ? 1u : 0u) << l;
-                c3 |= (v.w > 0.0f ? 1u : 0u) << l;
+                for (int l = 0; l < L2; ++l) {
+                    const float4 v = *reinterpret_cast<const float4 *>(src + l * P);
+                    c0 |= (v.x > 0.0f ? 1u : 0u) << l;
+                    c1 |= (v.y > 0.0f ? 1u : 0u) << l;
+                    c2 |= (v.z > 0.0f ? 1u : 0u) << l;
+                    c3 |= (v.w > 0.0f ? 1u : 0u) << l;
+                }
+                const int x = 4 * xq;
+                if (x >= x_lo && x < x_hi) hist_add<L2>(lds_hist, p, x, c0, ilo, ihi, i0, j0, j1, ncol);
+                if (x + 1 >= x_lo && x + 1 < x_hi) hist_add<L2>(lds_hist, p, x + 1, c1, ilo, ihi, i0, j0, j1, ncol);
+                if (x + 2 >= x_lo && x + 2 < x_hi) hist_add<L2>(lds_hist, p, x + 2, c2, ilo, ihi, i0, j0, j1, ncol);
+                if (x + 3 >= x_lo && x + 3 < x_hi) hist_add<L2>(lds_hist, p, x + 3, c3, ilo, ihi, i0, j0, j1, ncol);
             }
-            const int x = 4 * xq;
-            if (x >= x_lo && x < x_hi) hist_add<L2>(lds_hist, p, y, x, c0, i0, i1, j0, j1, ncol);
-            if (x + 1 >= x_lo && x + 1 < x_hi) hist_add<L2>(lds_hist, p, y, x + 1, c1, i0, i1, j0, j1, ncol);
-            if (x + 2 >= x_lo && x + 2 < x_hi) hist_add<L2>(lds_hist, p, y, x + 2, c2, i0, i1, j0, j1, ncol);
-            if (x + 3 >= x_lo && x + 3 < x_hi) hist_add<L2>(lds_hist, p, y, x + 3, c3, i0, i1, j0, j1, ncol);
         }
     } else {
-        const int span = x_hi - x_lo;
-        const int total = (y_hi - y_lo) * span;
-        for (int e = threadIdx.x; e < total; e += HIST_THREADS) {
-            const int yy = e / span, x = x_lo + (e - yy * span);
-            const int y = y_lo + yy;
-            const int64_t u = (int64_t)y * p.w + x;
-            unsigned code = 0;
+        for (int y = y_lo + trow; y < y_hi; y += 8) {
+            int ilo, ihi;
+            block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
+            const float *row = base + (int64_t)y * p.w;
+            for (int x = x_lo + tcol; x < x_hi; x += 32) {
+                unsigned code = 0;
 #pragma unroll
-            for (int l = 0; l < L2; ++l) code |= (base[l * P + u] > 0.0f ? 1u : 0u) << l;
-            hist_add<L2>(lds_hist, p, y, x, code, i0, i1, j0, j1, ncol);
+                for (int l = 0; l < L2; ++l) code |= (row[l * P + x] > 0.0f ? 1u : 0u) << l;
+                hist_add<L2>(lds_hist, p, x, code, ilo, ihi, i0, j0, j1, ncol);
+            }
         }
     }
     __syncthreads();
@@ -163,6 +177,9 @@ int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h
     p.nbx = (w - bw) / sx + 1;
     p.group = group; p.group_stride = group_stride;
     p.vec4 = ((w & 3) == 0 && (((uintptr_t)maps) & 15) == 0) ? 1 : 0;
+    const bool small = h < 65536 && w < 65536;
+    p.magic_sy = small ? (unsigned)((((uint64_t)1 << 32) + sy - 1) / sy) : 0u;
+    p.magic_sx = small ? (unsigned)((((uint64_t)1 << 32) + sx - 1) / sx) : 0u;
     switch (L2) {
 #define CASE(v) case v: hist_launch<v>(ctx, p, n); break;
         CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12)
