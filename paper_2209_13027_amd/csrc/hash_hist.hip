@@ -65,8 +65,14 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p)
     constexpr int BINS = 1 << L2;
     constexpr int WORDS = BINS > 1 ? BINS / 2 : 1;
     const int per_map = p.row_groups * p.col_chunks;
-    const int64_t n = blockIdx.x / per_map;
-    const int r = blockIdx.x - (int)n * per_map;
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber them so
+    // that consecutive work items (neighbouring block-row groups of one map, which share
+    // image rows) run on the same XCD and find the shared rows in its L2.
+    const unsigned nwg = gridDim.x, xcd = blockIdx.x & 7u, pos = blockIdx.x >> 3;
+    const unsigned per = nwg >> 3, rem = nwg & 7u;
+    const unsigned item = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + pos;
+    const int64_t n = item / per_map;
+    const int r = (int)(item - n * per_map);
     const int rg = r / p.col_chunks, cc = r - rg * p.col_chunks;
     const int i0 = rg * p.rb, i1 = min(i0 + p.rb, p.nby);
     const int j0 = cc * p.cols, j1 = min(j0 + p.cols, p.nbx);
