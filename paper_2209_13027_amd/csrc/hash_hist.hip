@@ -14,7 +14,7 @@
 namespace ddcca {
 
 constexpr int HIST_THREADS = 256;
-constexpr int HIST_LDS_BYTES = 32 * 1024;   // histogram bytes per workgroup (occupancy 4-5 per CU)
+constexpr int HIST_LDS_BYTES = 32 * 1024;   // histogram bytes per workgroup (occupancy 4-5 per CU)   // histogram bytes per workgroup (occupancy 4-5 per CU)
 
 struct HistParams {
     const float *maps;
@@ -85,16 +85,20 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p)
     const float *base = p.maps + n * L2 * P;
     const int y_lo = i0 * p.sy, y_hi = (i1 - 1) * p.sy + p.bh;       // rows [y_lo, y_hi)
     const int x_lo = j0 * p.sx, x_hi = (j1 - 1) * p.sx + p.bw;       // columns [x_lo, x_hi)
-    // threads as 8 rows x 32 columns of work items (no per-item index division)
-    const int tcol = threadIdx.x & 31, trow = threadIdx.x >> 5;
+    // threads as TROWS rows x TCOLS columns of work items (no per-item index division); a
+    // wavefront reads whole contiguous row pieces: 32 quads (512 B) suffice for narrow maps,
+    // 64 quads (1 KB) for wide ones
+    const int wide = (x_hi - x_lo) > 128 ? 1 : 0;
+    const int TCOLS = wide ? 64 : 32, TROWS = HIST_THREADS / TCOLS;
+    const int tcol = threadIdx.x & (TCOLS - 1), trow = threadIdx.x / TCOLS;
     if (p.vec4) {
         // aligned quads of 4 pixels; the quad range covers [x_lo, x_hi) and is clipped per pixel
         const int q_lo = x_lo >> 2, q_hi = (x_hi + 3) >> 2;
-        for (int y = y_lo + trow; y < y_hi; y += 8) {
+        for (int y = y_lo + trow; y < y_hi; y += TROWS) {
             int ilo, ihi;
             block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
             const float *row = base + (int64_t)y * p.w;
-            for (int xq = q_lo + tcol; xq < q_hi; xq += 32) {
+            for (int xq = q_lo + tcol; xq < q_hi; xq += TCOLS) {
                 const float *src = row + 4 * xq;
                 unsigned c0 = 0, c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
@@ -113,11 +117,11 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p)
             }
         }
     } else {
-        for (int y = y_lo + trow; y < y_hi; y += 8) {
+        for (int y = y_lo + trow; y < y_hi; y += TROWS) {
             int ilo, ihi;
             block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
             const float *row = base + (int64_t)y * p.w;
-            for (int x = x_lo + tcol; x < x_hi; x += 32) {
+            for (int x = x_lo + tcol; x < x_hi; x += TCOLS) {
                 unsigned code = 0;
 #pragma unroll
                 for (int l = 0; l < L2; ++l) code |= (row[l * P + x] > 0.0f ? 1u : 0u) << l;
