@@ -45,6 +45,25 @@ def algorithmic_work(wl, M):
     }
 
 
+def measured_traffic(workload, kernel_prefix):
+    """HBM bytes per launch (read + write) of the kernels whose name starts with `kernel_prefix`, from the
+    rocprofv3 --pmc passes summarised in profiles/traffic.json (FETCH_SIZE / WRITE_SIZE scaled by a plain
+    copy of known size); None when no profile of this workload is committed."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        data = json.load(f).get(workload)
+    if not data:
+        return None
+    tot_bytes, tot_launches = 0.0, 0
+    for name, v in data.items():
+        if name.startswith(kernel_prefix) and "read_mib_per_launch" in v:
+            tot_bytes += v["launches"] * (v["read_mib_per_launch"] + v["write_mib_per_launch"]) * 1048576.0
+            tot_launches += v["launches"]
+    return tot_bytes / tot_launches if tot_launches else None
+
+
 def run_cpu_baseline(wl, budget_images):
     """Time the fp64 CPU oracle (whole path) on a bounded class-balanced sample."""
     from oracle import ddcca_oracle as oracle
@@ -165,7 +184,7 @@ def main():
                    "feature_len": wl.feature_len},
         "roofline": {"bound": "mfma", "kernel": "patch_gram_kernel", "achieved": gram_tflops,
                      "peak": PEAK_MFMA_FP32_TFLOPS, "unit": "TFLOP/s", "frac": gram_tflops / PEAK_MFMA_FP32_TFLOPS,
-                     "traffic": None, "avg_launch_ms": gram_ms,
+                     "traffic": measured_traffic(wl.name, "patch_gram_kernel"), "avg_launch_ms": gram_ms,
                      "algorithmic_flop_per_launch": gram_flops_per_launch},
         "kernels": kernels,
         "ms_per_step_without_events": dt_plain / K * 1e3,
