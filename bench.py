@@ -39,13 +39,13 @@ def algorithmic_work(wl, M):
     hist_bytes = 2 * M * L1 * (L2 * P * 4 + A * bins * 2)
     class_bytes = 2 * 4 * (M * P + M * L1 * P)       # every map of both views read once
     return {
-        "gram_flops": gram_main + gram_class, "gram_launches_per_step": 6,
+        "gram_flops": gram_main, "gram_cross_flops": gram_class,
         "conv_bytes": conv_bytes, "conv_flops": conv_flops, "hist_bytes": hist_bytes,
         "class_sum_bytes": class_bytes,
     }
 
 
-def measured_traffic(workload, kernel_prefix):
+def measured_traffic(workload, kernel_prefix, must_contain=""):
     """HBM bytes per launch (read + write) of the kernels whose name starts with `kernel_prefix`, from the
     rocprofv3 --pmc passes summarised in profiles/traffic.json (FETCH_SIZE / WRITE_SIZE scaled by a plain
     copy of known size); None when no profile of this workload is committed."""
@@ -58,7 +58,7 @@ def measured_traffic(workload, kernel_prefix):
         return None
     tot_bytes, tot_launches = 0.0, 0
     for name, v in data.items():
-        if name.startswith(kernel_prefix) and "read_mib_per_launch" in v:
+        if name.startswith(kernel_prefix) and must_contain in name and "read_mib_per_launch" in v:
             tot_bytes += v["launches"] * (v["read_mib_per_launch"] + v["write_mib_per_launch"]) * 1048576.0
             tot_launches += v["launches"]
     return tot_bytes / tot_launches if tot_launches else None
@@ -162,6 +162,10 @@ def main():
     kernels = {
         "gram": {"ms_per_step": prof["gram"]["ms"] / K, "launches_per_step": prof["gram"]["launches"] / K,
                  "useful_tflops": gram_tflops, "frac_mfma_fp32": gram_tflops / PEAK_MFMA_FP32_TFLOPS},
+        "gram_cross": {"ms_per_step": prof["gram_cross"]["ms"] / K,
+                       "launches_per_step": prof["gram_cross"]["launches"] / K,
+                       "useful_tflops": work["gram_cross_flops"] * K / (prof["gram_cross"]["ms"] * 1e-3) / 1e12
+                       if prof["gram_cross"]["ms"] > 0 else 0.0},
         "class_sum": {"ms_per_step": prof["class_sum"]["ms"] / K,
                       "gbs": work["class_sum_bytes"] / (prof["class_sum"]["ms"] / K * 1e-3) / 1e9
                       if prof["class_sum"]["ms"] > 0 else 0.0},
@@ -182,9 +186,9 @@ def main():
         "config": {"workload": wl.name, "images": M, "classes": wl.n_classes, "h": wl.h, "w": wl.w, "k": wl.k,
                    "L1": wl.L1, "L2": wl.L2, "block": wl.block, "stride": wl.stride, "bins": 1 << wl.L2,
                    "feature_len": wl.feature_len},
-        "roofline": {"bound": "mfma", "kernel": "patch_gram_kernel", "achieved": gram_tflops,
+        "roofline": {"bound": "mfma", "kernel": "patch_gram_kernel (all-tiles variant: the Gram over the input maps)", "achieved": gram_tflops,
                      "peak": PEAK_MFMA_FP32_TFLOPS, "unit": "TFLOP/s", "frac": gram_tflops / PEAK_MFMA_FP32_TFLOPS,
-                     "traffic": measured_traffic(wl.name, "patch_gram_kernel"), "avg_launch_ms": gram_ms,
+                     "traffic": measured_traffic(wl.name, "patch_gram_kernel", ", false,"), "avg_launch_ms": gram_ms,
                      "algorithmic_flop_per_launch": gram_flops_per_launch},
         "kernels": kernels,
         "ms_per_step_without_events": dt_plain / K * 1e3,

@@ -127,12 +127,13 @@ int ddcca_extract_features(ddcca_ctx *ctx, const float *v1, const float *v2, int
 
 /* ---- per-kernel timing (HIP events on the context's stream) -------------------------- */
 enum {
-    DDCCA_K_GRAM = 0,     /* patch-Gram accumulation */
+    DDCCA_K_GRAM = 0,     /* patch-Gram accumulation over the input maps (all tiles) */
     DDCCA_K_CLASS_SUM,    /* per-(class,g) image sums */
     DDCCA_K_REDUCE,       /* cross-workgroup reduction / export of the matrices */
     DDCCA_K_SOLVE,        /* DCCA solve */
     DDCCA_K_CONV,         /* stage convolution */
     DDCCA_K_HASH_HIST,    /* hashing + block histogram */
+    DDCCA_K_GRAM_CROSS,   /* patch-Gram of the class-sum / total-sum images (cross-view tiles only) */
     DDCCA_K_COUNT
 };
 /* While enabled, every kernel launch is bracketed by a pair of events. */

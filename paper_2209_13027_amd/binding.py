@@ -16,8 +16,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libddcca.so")
 
 OK, EINVAL, ESTATE, ENOMEM, EHIP, EOVERFLOW, ELABEL = 0, -1, -2, -3, -4, -5, -6
-K_GRAM, K_CLASS_SUM, K_REDUCE, K_SOLVE, K_CONV, K_HASH_HIST, K_COUNT = range(7)
-KERNEL_NAMES = ["gram", "class_sum", "reduce", "solve", "conv", "hash_hist"]
+K_GRAM, K_CLASS_SUM, K_REDUCE, K_SOLVE, K_CONV, K_HASH_HIST, K_GRAM_CROSS, K_COUNT = range(8)
+KERNEL_NAMES = ["gram", "class_sum", "reduce", "solve", "conv", "hash_hist", "gram_cross"]
 
 EXPORTS = [
     "ddcca_create", "ddcca_destroy", "ddcca_last_error", "ddcca_status",

@@ -516,7 +516,7 @@ static int gram_launch(ddcca_ctx *ctx, const GramParams &p, int grid, size_t lds
 int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w, int k,
                       bool cross_only, double *slots, int max_slots, int *slots_valid)
 {
-    ProfScope prof(ctx, DDCCA_K_GRAM);
+    ProfScope prof(ctx, cross_only ? DDCCA_K_GRAM_CROSS : DDCCA_K_GRAM);
     GramParams p;
     p.v1 = v1; p.v2 = v2; p.h = h; p.w = w;
     const int w4 = (w + 3) & ~3;
