@@ -14,7 +14,7 @@
 namespace ddcca {
 
 constexpr int HIST_THREADS = 256;
-constexpr int HIST_LDS_BYTES = 32 * 1024;   // histogram bytes per workgroup (occupancy 4-5 per CU)   // histogram bytes per workgroup (occupancy 4-5 per CU)
+constexpr int HIST_LDS_BYTES = 32 * 1024;   // histogram bytes per workgroup (occupancy 4-5 per CU)
 
 struct HistParams {
     const float *maps;
