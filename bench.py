@@ -152,6 +152,26 @@ def main():
     dt_plain = time.perf_counter() - t1
     ctx.status()
 
+    # learning and extraction timed apart, one synchronised repetition at a time (mean and min over K)
+    def timed(fn):
+        ts = []
+        for _ in range(args.steps):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            ts.append(time.perf_counter() - t)
+        return {"ms_mean": sum(ts) / len(ts) * 1e3, "ms_min": min(ts) * 1e3,
+                "images_per_s": M / (sum(ts) / len(ts))}
+    model = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
+    phases = {
+        "learn": timed(lambda: pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)),
+        "extract": timed(lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block,
+                                                  wl.stride, batch, out=feat)),
+        "e2e": timed(step),
+    }
+    ctx.status()
+
     work = algorithmic_work(wl, M)
     K = args.steps
     gram_ms = prof["gram"]["ms"] / max(1, prof["gram"]["launches"])
@@ -191,10 +211,11 @@ def main():
                      "traffic": measured_traffic(wl.name, "patch_gram_kernel", ", false,"), "avg_launch_ms": gram_ms,
                      "algorithmic_flop_per_launch": gram_flops_per_launch},
         "kernels": kernels,
+        "phases": phases,
         "ms_per_step_without_events": dt_plain / K * 1e3,
     }
     if not args.no_cpu_baseline:
-        default_images = {"tiny": 40, "small_face": 80, "object": 64, "large_scale": 257, "stress": 16}
+        default_images = {"tiny": 40, "small_face": 400, "object": 128, "large_scale": 257, "stress": 16}
         n_cpu = args.cpu_images or default_images.get(wl.name, 64)
         out["cpu_baseline"] = run_cpu_baseline(wl, n_cpu)
     ctx.close()
