@@ -10,7 +10,8 @@ Section / equation numbers refer to the paper (Section II: model; Section III: b
 
 Pins (tests/test_oracle_*.py): patch sums, brute-force Gram, batch-split invariance
 (Eq. 15), pair-loop C_w / C_b, eigen residuals and library cross-checks for the solve,
-brute-forced objective (Eq. 2-3), conv/Gram tie, histogram sums and bincount.
+brute-forced objective (Eq. 2-3), conv/Gram tie, histogram sums and bincount,
+information quality (Eq. 10): probabilities sum to one, hand-computed block, monotone.
 Numeric values of filters / features on the paper's own data: parity unpinned (the
 paper prints no intermediate value and its data sets are not available).
 """
@@ -254,6 +255,24 @@ def block_hist(Q, block, stride, bins: int) -> np.ndarray:
     hist = np.empty((n, nby, nbx, bins), dtype=np.int64)
     _lib().orc_block_hist(_p(Q, _i32p), ctypes.c_int64(n), h, w, bh, bw, sy, sx, bins, _p(hist, _i64p))
     return hist
+
+
+def iq_features(hist, block_area: int) -> np.ndarray:
+    """Eq. 10: information quality o = -log p(t) of every code t in every block, natural
+    logarithm.  p(t) is the block's code distribution with one pseudo-count per bin,
+    p(t) = (count(t) + 1) / (block_area + bins), so that codes absent from a block (p = 0 in
+    the raw frequencies, where Eq. 10 is undefined) get the finite value log(block_area +
+    bins) and sum_t p(t) = 1 still holds.  hist: [..., bins] counts; returns float64."""
+    hist = np.asarray(hist)
+    bins = hist.shape[-1]
+    total = float(block_area + bins)
+    out = np.empty(hist.shape, dtype=np.float64)
+    flat_in, flat_out = hist.reshape(-1), out.reshape(-1)
+    step = 1 << 22
+    for a in range(0, flat_in.size, step):
+        c = flat_in[a:a + step].astype(np.float64)
+        flat_out[a:a + step] = -np.log((c + 1.0) / total)
+    return out
 
 
 def default_stride(block: int) -> int:

@@ -2,6 +2,8 @@
 itself -- an independently written brute force, a closed form, an invariant the paper
 fixes, or a library routine (numpy / scipy are used here only, never in the oracle's
 own arithmetic for that step)."""
+import math
+
 import numpy as np
 import pytest
 import scipy.linalg
@@ -405,3 +407,24 @@ def test_class_sums_equal_gram_of_class_sum_images(oracle):
     T2 = np.stack([V2[grp2 == g].sum(0) for g in range(2)])
     _, _, GT = oracle.corr_sums(T1, T2, 3)
     assert np.abs(ST - GT).max() <= 1e-12 * np.abs(ST).max()
+
+
+def test_iq_probabilities_sum_to_one_and_hand_values(oracle):
+    """Eq. 10 with one pseudo-count per bin: exp(-o) is a distribution over the bins of every block;
+    a block of 4 pixels with codes {0, 0, 3, 1} over 4 bins gives p = 3/8, 2/8, 1/8, 2/8."""
+    rng = np.random.default_rng(5)
+    Q = rng.integers(0, 16, size=(3, 20, 24)).astype(np.int32)
+    H = oracle.block_hist(Q, 8, 4, 16)
+    o = oracle.iq_features(H, 64)
+    assert o.shape == H.shape and o.dtype == np.float64
+    np.testing.assert_allclose(np.exp(-o).sum(axis=-1), 1.0, rtol=0, atol=1e-13)
+    # a code seen more often is less informative; an absent code carries log(area + bins)
+    order = np.argsort(H.reshape(-1), kind="stable")
+    assert np.all(np.diff(o.reshape(-1)[order]) <= 1e-15)
+    assert np.allclose(o[H == 0], math.log(64 + 16), rtol=0, atol=1e-14)
+    hand = oracle.iq_features(np.array([2, 1, 0, 1]), 4)
+    np.testing.assert_allclose(hand, [0.98082925301172619, 1.3862943611198906, 2.0794415416798357,
+                                      1.3862943611198906], rtol=0, atol=1e-15)
+    # all pixels of a block share one code: p = (area+1)/(area+bins) for it
+    full = oracle.iq_features(np.array([49, 0, 0, 0, 0, 0, 0, 0]), 49)
+    assert abs(full[0] - math.log(57.0 / 50.0)) < 1e-15 and abs(full[1] - math.log(57.0)) < 1e-14
