@@ -125,6 +125,25 @@ typedef struct ddcca_model {
 int ddcca_extract_features(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h,
                            int w, const ddcca_model *model, uint16_t *feat);
 
+/* ---- information-quality form of the output layer (Eq. 10-12) -------------------------
+ * Eq. 10 turns the code distribution p(t) of every block into o = -log p(t) (natural
+ * logarithm).  p(t) is taken with one pseudo-count per bin,
+ *     p(t) = (count(t) + 1) / (block_h*block_w + 2^L2),
+ * so that a code absent from a block (where Eq. 10 is undefined) gets the finite value
+ * log(block_h*block_w + 2^L2) and the p(t) of a block still sum to one.
+ * feat_type selects the element type of the output: DDCCA_FEAT_IQ_F32 (float) or
+ * DDCCA_FEAT_IQ_F16 (IEEE half, the fp32 value rounded to nearest); DDCCA_FEAT_COUNT_U16
+ * gives the raw counts (the same as the calls above).  Layouts are those of
+ * ddcca_hash_histogram / ddcca_extract_features with the element type replaced.
+ * fp32 values are within one unit in the last place of the exactly rounded result. */
+#define DDCCA_FEAT_COUNT_U16 0
+#define DDCCA_FEAT_IQ_F32    1
+#define DDCCA_FEAT_IQ_F16    2
+int ddcca_hash_iq(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int block_h,
+                  int block_w, int stride_y, int stride_x, int feat_type, void *out);
+int ddcca_extract_iq_features(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h,
+                              int w, const ddcca_model *model, int feat_type, void *feat);
+
 /* ---- per-kernel timing (HIP events on the context's stream) -------------------------- */
 enum {
     DDCCA_K_GRAM = 0,     /* patch-Gram accumulation over the input maps (all tiles) */

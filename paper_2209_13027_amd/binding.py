@@ -23,8 +23,11 @@ EXPORTS = [
     "ddcca_create", "ddcca_destroy", "ddcca_last_error", "ddcca_status",
     "ddcca_corr_begin", "ddcca_corr_accumulate", "ddcca_corr_export", "ddcca_solve_filters",
     "ddcca_dcca_solve", "ddcca_learn_stage_filters", "ddcca_apply_stage", "ddcca_hash_histogram",
-    "ddcca_extract_features", "ddcca_profile_enable", "ddcca_profile_read", "ddcca_profile_reset",
+    "ddcca_extract_features", "ddcca_hash_iq", "ddcca_extract_iq_features",
+    "ddcca_profile_enable", "ddcca_profile_read", "ddcca_profile_reset",
 ]
+FEAT_COUNT_U16, FEAT_IQ_F32, FEAT_IQ_F16 = 0, 1, 2
+FEAT_TYPES = {torch.uint16: FEAT_COUNT_U16, torch.float32: FEAT_IQ_F32, torch.float16: FEAT_IQ_F16}
 
 
 class DdccaError(RuntimeError):
@@ -70,6 +73,8 @@ def lib() -> ctypes.CDLL:
         l.ddcca_apply_stage.argtypes = [vp, vp, i64, i, i, vp, i, i, vp]
         l.ddcca_hash_histogram.argtypes = [vp, vp, i64, i, i, i, i, i, i, i, vp]
         l.ddcca_extract_features.argtypes = [vp, vp, vp, i64, i, i, ctypes.POINTER(_Model), vp]
+        l.ddcca_hash_iq.argtypes = [vp, vp, i64, i, i, i, i, i, i, i, i, vp]
+        l.ddcca_extract_iq_features.argtypes = [vp, vp, vp, i64, i, i, ctypes.POINTER(_Model), i, vp]
         l.ddcca_profile_enable.argtypes = [vp, i]
         l.ddcca_profile_read.argtypes = [vp, i, ctypes.POINTER(d), ctypes.POINTER(i64)]
         l.ddcca_profile_reset.argtypes = [vp]
@@ -195,14 +200,35 @@ class Context:
                                                _ptr(out, torch.uint16, "hist")))
         return out
 
-    def extract_features(self, v1, v2, filters, k, L1, L2, block, stride, batch_images=0, out=None):
+    def hash_iq(self, maps, block, stride, dtype=torch.float32, out=None):
+        """maps: [n, L2, h, w] float32 -> [n, nby, nbx, 2**L2] information quality, float32 or float16."""
+        n, L2, h, w = maps.shape
+        bh, bw = (block, block) if isinstance(block, int) else block
+        sy, sx = (stride, stride) if isinstance(stride, int) else stride
+        if h < bh or w < bw or sy < 1 or sx < 1:
+            nby = nbx = 0
+        else:
+            nby, nbx = (h - bh) // sy + 1, (w - bw) // sx + 1
+        if out is None:
+            out = torch.empty((n, nby, nbx, 1 << L2), dtype=dtype, device=maps.device)
+        self._check(lib().ddcca_hash_iq(self._h, _ptr(maps, torch.float32, "maps"), n, L2, h, w, bh, bw, sy, sx,
+                                        FEAT_TYPES[dtype], _ptr(out, dtype, "out")))
+        return out
+
+    def extract_iq_features(self, v1, v2, filters, k, L1, L2, block, stride, dtype=torch.float32, batch_images=0,
+                            out=None):
+        """As extract_features, with -log p(t) per bin (float32 / float16) instead of the counts."""
+        return self.extract_features(v1, v2, filters, k, L1, L2, block, stride, batch_images, out, dtype)
+
+    def extract_features(self, v1, v2, filters, k, L1, L2, block, stride, batch_images=0, out=None,
+                         dtype=torch.uint16):
         """filters = (W1_stage1, W2_stage1, W1_stage2, W2_stage2) -> [m, 2, L1, nby, nbx, 2**L2] uint16."""
         m, h, w = v1.shape
         bh, bw = (block, block) if isinstance(block, int) else block
         sy, sx = (stride, stride) if isinstance(stride, int) else stride
         nby, nbx = (h - bh) // sy + 1, (w - bw) // sx + 1
         if out is None:
-            out = torch.empty((m, 2, L1, nby, nbx, 1 << L2), dtype=torch.uint16, device=v1.device)
+            out = torch.empty((m, 2, L1, nby, nbx, 1 << L2), dtype=dtype, device=v1.device)
         model = _Model()
         model.k, model.L1, model.L2 = k, L1, L2
         model.block_h, model.block_w, model.stride_y, model.stride_x = bh, bw, sy, sx
@@ -211,8 +237,14 @@ class Context:
             for d in range(2):
                 model.W[s][d] = _ptr(filters[2 * s + d], torch.float32, names[2 * s + d])
         model.batch_images = int(batch_images)
-        self._check(lib().ddcca_extract_features(self._h, _ptr(v1, torch.float32, "v1"), _ptr(v2, torch.float32, "v2"),
-                                                 m, h, w, ctypes.byref(model), _ptr(out, torch.uint16, "feat")))
+        if dtype == torch.uint16:
+            self._check(lib().ddcca_extract_features(self._h, _ptr(v1, torch.float32, "v1"),
+                                                     _ptr(v2, torch.float32, "v2"), m, h, w, ctypes.byref(model),
+                                                     _ptr(out, torch.uint16, "feat")))
+        else:
+            self._check(lib().ddcca_extract_iq_features(self._h, _ptr(v1, torch.float32, "v1"),
+                                                        _ptr(v2, torch.float32, "v2"), m, h, w, ctypes.byref(model),
+                                                        FEAT_TYPES[dtype], _ptr(out, dtype, "feat")))
         return out
 
     # ---- profiling -------------------------------------------------------------------

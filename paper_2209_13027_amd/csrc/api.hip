@@ -155,7 +155,7 @@ void ddcca_destroy(ddcca_ctx *ctx)
         (void)hipSetDevice(ctx->device);
         (void)hipStreamSynchronize(ctx->stream);
         for (Buffer *b : {&ctx->slots, &ctx->class_sum, &ctx->class_img, &ctx->stacked, &ctx->seg, &ctx->mats,
-                          &ctx->solve_ws, &ctx->flags, &ctx->maps1, &ctx->maps2})
+                          &ctx->solve_ws, &ctx->flags, &ctx->maps1, &ctx->maps2, &ctx->iq_lut})
             free_buffer(*b);
         for (ProfSlot &s : ctx->prof_slot) {
             for (hipEvent_t e : s.start) (void)hipEventDestroy(e);
@@ -327,26 +327,49 @@ static int check_hist_args(ddcca_ctx *ctx, int64_t n, int L2, int h, int w, int 
     return DDCCA_OK;
 }
 
-int ddcca_hash_histogram(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int block_h,
-                         int block_w, int stride_y, int stride_x, uint16_t *hist)
+static int check_feat_type(ddcca_ctx *ctx, int feat_type)
+{
+    if (feat_type != DDCCA_FEAT_COUNT_U16 && feat_type != DDCCA_FEAT_IQ_F32 && feat_type != DDCCA_FEAT_IQ_F16)
+        return fail(ctx, DDCCA_EINVAL, "unknown feature type");
+    return DDCCA_OK;
+}
+
+static size_t feat_elem_size(int feat_type) { return feat_type == DDCCA_FEAT_IQ_F32 ? 4 : 2; }
+
+int ddcca_hash_iq(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int block_h, int block_w,
+                  int stride_y, int stride_x, int feat_type, void *out)
 {
     if (!ctx) return DDCCA_EINVAL;
     int rc;
+    if ((rc = check_feat_type(ctx, feat_type))) return rc;
     if ((rc = check_hist_args(ctx, n, L2, h, w, block_h, block_w, stride_y, stride_x))) return rc;
     if (n == 0) return DDCCA_OK;
-    if (!maps || !hist) return fail(ctx, DDCCA_EINVAL, "null data pointer");
+    if (!maps || !out) return fail(ctx, DDCCA_EINVAL, "null data pointer");
     if ((rc = device_ready(ctx))) return rc;
     const int64_t A = (int64_t)((h - block_h) / stride_y + 1) * ((w - block_w) / stride_x + 1);
-    return launch_hash_hist(ctx, maps, n, L2, h, w, block_h, block_w, stride_y, stride_x, hist, 1,
+    return launch_hash_hist(ctx, maps, n, L2, h, w, block_h, block_w, stride_y, stride_x, out, feat_type, 1,
                             A * ((int64_t)1 << L2));
+}
+
+int ddcca_hash_histogram(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int block_h,
+                         int block_w, int stride_y, int stride_x, uint16_t *hist)
+{
+    return ddcca_hash_iq(ctx, maps, n, L2, h, w, block_h, block_w, stride_y, stride_x, DDCCA_FEAT_COUNT_U16, hist);
 }
 
 int ddcca_extract_features(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h, int w,
                            const ddcca_model *model, uint16_t *feat)
 {
+    return ddcca_extract_iq_features(ctx, v1, v2, m, h, w, model, DDCCA_FEAT_COUNT_U16, feat);
+}
+
+int ddcca_extract_iq_features(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h, int w,
+                              const ddcca_model *model, int feat_type, void *feat)
+{
     if (!ctx) return DDCCA_EINVAL;
     if (!model) return fail(ctx, DDCCA_EINVAL, "null model");
     int rc;
+    if ((rc = check_feat_type(ctx, feat_type))) return rc;
     if ((rc = check_image_args(ctx, m, h, w, model->k))) return rc;
     if (model->L1 < 1 || model->L1 > 64) return fail(ctx, DDCCA_EINVAL, "L1 must be in 1..64");
     if ((rc = check_hist_args(ctx, m, model->L2, h, w, model->block_h, model->block_w, model->stride_y,
@@ -381,9 +404,9 @@ int ddcca_extract_features(ddcca_ctx *ctx, const float *v1, const float *v2, int
         for (int d = 0; d < 2; ++d) {
             if ((rc = launch_conv(ctx, views[d] + m0 * P, mb, h, w, model->W[0][d], k, L1, y))) return rc;
             if ((rc = launch_conv(ctx, y, mb * L1, h, w, model->W[1][d], k, L2, z))) return rc;
-            uint16_t *dst = feat + ((m0 * 2 + d) * L1) * A * bins;
+            void *dst = reinterpret_cast<char *>(feat) + ((m0 * 2 + d) * L1) * A * bins * feat_elem_size(feat_type);
             if ((rc = launch_hash_hist(ctx, z, mb * L1, L2, h, w, model->block_h, model->block_w, model->stride_y,
-                                       model->stride_x, dst, L1, 2 * L1 * A * bins)))
+                                       model->stride_x, dst, feat_type, L1, 2 * L1 * A * bins)))
                 return rc;
         }
     }

@@ -48,6 +48,9 @@ struct ddcca_ctx {
     ddcca::Buffer solve_ws;                 // solver scratch (global part)
     ddcca::Buffer flags;                    // int[4]: [0] label error
     ddcca::Buffer maps1, maps2;             // extract_features scratch
+    ddcca::Buffer iq_lut;                   // information-quality table of the output layer
+    int64_t iq_lut_total = 0;               // block area + bins the table was built for (0 = none)
+    int iq_lut_n = 0;
 
     // ---- profiling
     bool prof = false;
@@ -102,8 +105,9 @@ int launch_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const dou
                  int k, int L, double ridge, float *W1, float *W2, double *rho);
 int launch_conv(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L,
                 float *out);
-// hist for map n goes to hist + (n / group) * group_stride + (n % group) * A * bins
+// output for map n goes to element (n / group) * group_stride + (n % group) * A * bins of `out`,
+// whose element type out_type (DDCCA_FEAT_*) selects
 int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int bh, int bw,
-                     int sy, int sx, uint16_t *hist, int64_t group, int64_t group_stride);
+                     int sy, int sx, void *out, int out_type, int64_t group, int64_t group_stride);
 
 }  // namespace ddcca

@@ -9,16 +9,29 @@
 // plane reads, strict "> 0") and added with an LDS atomic to each block that contains it.
 // A count never exceeds the block area (<= 65535, checked on the host), so the two halves
 // of a word cannot overflow into each other.
+//
+// The same kernel also writes the information-quality form of the output (Eq. 10):
+// o = -log p(t), p(t) = (count + 1) / (block area + bins), as fp32 or fp16.  The values for
+// the possible counts come from a table (built in fp64 by a one-workgroup kernel, rounded
+// once to fp32) that every workgroup copies into LDS, so the epilogue is one LDS gather per
+// output element and the kernel stays bound by its HBM writes.
 #include "ddcca_internal.h"
+
+#include <hip/hip_fp16.h>
 
 namespace ddcca {
 
 constexpr int HIST_THREADS = 256;
 constexpr int HIST_LDS_BYTES = 32 * 1024;   // histogram bytes per workgroup (occupancy 4-5 per CU)
 
+constexpr int IQ_LUT_MAX = 2048;            // table entries (counts 0..2047); larger counts are computed directly
+
 struct HistParams {
     const float *maps;
-    uint16_t *hist;
+    void *hist;         // uint16 counts, or fp32 / fp16 information quality
+    const float *lut;   // information-quality table, lut[c] = log(total) - log(c + 1)
+    int lut_n;
+    double log_total;
     int h, w, bh, bw, sy, sx, nby, nbx;
     int rb;             // block rows per workgroup
     int cols;           // block columns per workgroup
@@ -58,12 +71,50 @@ __device__ __forceinline__ void hist_add(unsigned int *lds_hist, const HistParam
             atomicAdd(&lds_hist[((i - i0) * ncol + (j - j0)) * WORDS + word], inc);
 }
 
-template <int L2>
-__global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p)
+template <int OUT> struct HistOut;
+template <> struct HistOut<DDCCA_FEAT_COUNT_U16> { typedef uint16_t type; };
+template <> struct HistOut<DDCCA_FEAT_IQ_F32> { typedef float type; };
+template <> struct HistOut<DDCCA_FEAT_IQ_F16> { typedef __half type; };
+
+__device__ __forceinline__ float iq_value(unsigned c, const float *lut, int lut_n, double log_total)
+{
+    return (int)c < lut_n ? lut[c] : (float)(log_total - log((double)(c + 1u)));
+}
+
+template <int OUT> __device__ __forceinline__ typename HistOut<OUT>::type hist_convert(unsigned c, const float *lut,
+                                                                                      int lut_n, double log_total);
+template <> __device__ __forceinline__ uint16_t hist_convert<DDCCA_FEAT_COUNT_U16>(unsigned c, const float *, int,
+                                                                                   double)
+{
+    return (uint16_t)c;
+}
+template <> __device__ __forceinline__ float hist_convert<DDCCA_FEAT_IQ_F32>(unsigned c, const float *lut, int lut_n,
+                                                                             double log_total)
+{
+    return iq_value(c, lut, lut_n, log_total);
+}
+template <> __device__ __forceinline__ __half hist_convert<DDCCA_FEAT_IQ_F16>(unsigned c, const float *lut, int lut_n,
+                                                                              double log_total)
+{
+    return __float2half_rn(iq_value(c, lut, lut_n, log_total));
+}
+
+__global__ void iq_lut_kernel(double total, int n, float *lut)
+{
+    const double log_total = log(total);
+    for (int c = threadIdx.x; c < n; c += blockDim.x) lut[c] = (float)(log_total - log((double)(c + 1)));
+}
+
+template <int L2, int OUT>
+__global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p, int lds_hist_words)
 {
     extern __shared__ unsigned int lds_hist[];
+    typedef typename HistOut<OUT>::type OutT;
     constexpr int BINS = 1 << L2;
     constexpr int WORDS = BINS > 1 ? BINS / 2 : 1;
+    float *lds_lut = reinterpret_cast<float *>(lds_hist + lds_hist_words);
+    if (OUT != DDCCA_FEAT_COUNT_U16)
+        for (int e = threadIdx.x; e < p.lut_n; e += HIST_THREADS) lds_lut[e] = p.lut[e];
     const int per_map = p.row_groups * p.col_chunks;
     // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber them so
     // that consecutive work items (neighbouring block-row groups of one map, which share
@@ -131,57 +182,84 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p)
     }
     __syncthreads();
 
-    // copy out: block row i of the chunk is ncol*BINS contiguous uint16 in the output
+    // copy out: block row i of the chunk is ncol*BINS contiguous elements in the output
     const int64_t A = (int64_t)p.nby * p.nbx;
-    uint16_t *out_map = p.hist + (n / p.group) * p.group_stride + (n % p.group) * A * BINS;
-    if (BINS >= 8 && ((((uintptr_t)out_map) | (uintptr_t)(A * BINS * 2) | (uintptr_t)(p.group_stride * 2)) & 15) == 0) {
-        const int row_vec = ncol * WORDS / 4;                        // uint4 per block row of the chunk
+    OutT *out_map = reinterpret_cast<OutT *>(p.hist) + (n / p.group) * p.group_stride + (n % p.group) * A * BINS;
+    constexpr int ESZ = (int)sizeof(OutT);
+    constexpr int VW = 8 / ESZ;                                      // packed words per 16-byte store: 4, 2 or 1
+    if (BINS >= 2 * VW && ((((uintptr_t)out_map) | (uintptr_t)(A * BINS * ESZ) | (uintptr_t)(p.group_stride * ESZ)) & 15) == 0) {
+        const int row_vec = ncol * WORDS / VW;                       // 16-byte vectors per block row of the chunk
         for (int e = threadIdx.x; e < nrow * row_vec; e += HIST_THREADS) {
             const int ir = e / row_vec, v = e - ir * row_vec;
-            const uint4 val = *reinterpret_cast<const uint4 *>(lds_hist + (ir * ncol * WORDS) + 4 * v);
-            uint16_t *dst = out_map + ((int64_t)(i0 + ir) * p.nbx + j0) * BINS;
-            *reinterpret_cast<uint4 *>(dst + 8 * v) = val;
+            const unsigned *src = lds_hist + (ir * ncol * WORDS) + VW * v;
+            OutT *dst = out_map + ((int64_t)(i0 + ir) * p.nbx + j0) * BINS + 2 * VW * v;
+            if (OUT == DDCCA_FEAT_COUNT_U16) {
+                *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+            } else {
+                alignas(16) OutT vals[2 * VW];
+#pragma unroll
+                for (int q = 0; q < VW; ++q) {
+                    const unsigned wv = src[q];
+                    vals[2 * q] = hist_convert<OUT>(wv & 0xffffu, lds_lut, p.lut_n, p.log_total);
+                    vals[2 * q + 1] = hist_convert<OUT>(wv >> 16, lds_lut, p.lut_n, p.log_total);
+                }
+                *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(vals);
+            }
         }
     } else {
         for (int e = threadIdx.x; e < nrow * ncol * BINS; e += HIST_THREADS) {
             const int ir = e / (ncol * BINS), rest = e - ir * ncol * BINS;
             const unsigned wv = lds_hist[ir * ncol * WORDS + (rest >> 1)];
-            uint16_t *dst = out_map + ((int64_t)(i0 + ir) * p.nbx + j0) * BINS;
-            dst[rest] = (uint16_t)((BINS > 1 ? (wv >> (16 * (rest & 1))) : wv) & 0xffffu);
+            OutT *dst = out_map + ((int64_t)(i0 + ir) * p.nbx + j0) * BINS;
+            const unsigned c = (BINS > 1 ? (wv >> (16 * (rest & 1))) : wv) & 0xffffu;
+            dst[rest] = hist_convert<OUT>(c, lds_lut, p.lut_n, p.log_total);
         }
     }
 }
 
-template <int L2>
+template <int L2, int OUT>
 static void hist_launch(ddcca_ctx *ctx, HistParams p, int64_t n)
 {
     constexpr int BINS = 1 << L2;
     constexpr int HIST_BYTES = (BINS > 1 ? BINS / 2 : 1) * 4;         // packed histogram of one block
+    constexpr int ESZ = (int)sizeof(typename HistOut<OUT>::type);
     const int max_blocks = std::max(1, HIST_LDS_BYTES / HIST_BYTES);
     p.cols = std::min(p.nbx, max_blocks);
     p.col_chunks = (p.nbx + p.cols - 1) / p.cols;
     // several block rows per workgroup cut the re-reading of the rows that overlapping blocks share
     p.rb = std::max(1, std::min(p.nby, max_blocks / p.cols));
     p.row_groups = (p.nby + p.rb - 1) / p.rb;
-    const size_t lds = (size_t)p.rb * p.cols * HIST_BYTES;
+    const int hist_words = p.rb * p.cols * (HIST_BYTES / 4);
+    const size_t lds = (size_t)hist_words * 4 + (OUT != DDCCA_FEAT_COUNT_U16 ? (size_t)p.lut_n * 4 : 0);
     const int64_t per_map = (int64_t)p.row_groups * p.col_chunks;
     const int64_t maps_per_launch = std::max<int64_t>(p.group, (((int64_t)1 << 30) / per_map) / p.group * p.group);
     for (int64_t n0 = 0; n0 < n; n0 += maps_per_launch) {
         const int64_t nb = std::min(maps_per_launch, n - n0);
         HistParams q = p;
         q.maps = p.maps + n0 * L2 * (int64_t)p.h * p.w;
-        q.hist = p.hist + (n0 / p.group) * p.group_stride;
-        hipLaunchKernelGGL(hash_hist_kernel<L2>, dim3((unsigned)(nb * per_map)), dim3(HIST_THREADS), lds, ctx->stream,
-                           q);
+        q.hist = reinterpret_cast<char *>(p.hist) + (n0 / p.group) * p.group_stride * ESZ;
+        hipLaunchKernelGGL((hash_hist_kernel<L2, OUT>), dim3((unsigned)(nb * per_map)), dim3(HIST_THREADS), lds,
+                           ctx->stream, q, hist_words);
     }
 }
 
-int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int bh, int bw, int sy,
-                     int sx, uint16_t *hist, int64_t group, int64_t group_stride)
+template <int OUT>
+static int hist_dispatch(ddcca_ctx *ctx, const HistParams &p, int64_t n, int L2)
 {
-    ProfScope prof(ctx, DDCCA_K_HASH_HIST);
+    switch (L2) {
+#define CASE(v) case v: hist_launch<v, OUT>(ctx, p, n); break;
+        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12)
+#undef CASE
+        default: return fail(ctx, DDCCA_EINVAL, "L2 out of range");
+    }
+    return DDCCA_OK;
+}
+
+int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int bh, int bw, int sy,
+                     int sx, void *out, int out_type, int64_t group, int64_t group_stride)
+{
     HistParams p;
-    p.maps = maps; p.hist = hist;
+    p.maps = maps; p.hist = out;
     p.h = h; p.w = w; p.bh = bh; p.bw = bw; p.sy = sy; p.sx = sx;
     p.nby = (h - bh) / sy + 1;
     p.nbx = (w - bw) / sx + 1;
@@ -190,12 +268,32 @@ int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h
     const bool small = h < 65536 && w < 65536;
     p.magic_sy = small ? (unsigned)((((uint64_t)1 << 32) + sy - 1) / sy) : 0u;
     p.magic_sx = small ? (unsigned)((((uint64_t)1 << 32) + sx - 1) / sx) : 0u;
-    switch (L2) {
-#define CASE(v) case v: hist_launch<v>(ctx, p, n); break;
-        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12)
-#undef CASE
-        default: return fail(ctx, DDCCA_EINVAL, "L2 out of range");
+    p.lut = nullptr; p.lut_n = 0; p.log_total = 0.0;
+    if (out_type != DDCCA_FEAT_COUNT_U16) {
+        // table of the values for counts 0 .. min(area, IQ_LUT_MAX - 1), rebuilt when the block area or bin count changes
+        const int64_t total = (int64_t)bh * bw + ((int64_t)1 << L2);
+        p.lut_n = (int)std::min<int64_t>((int64_t)bh * bw + 1, IQ_LUT_MAX);
+        p.log_total = std::log((double)total);
+        int rc;
+        if ((rc = ensure(ctx, ctx->iq_lut, IQ_LUT_MAX * sizeof(float)))) return rc;
+        if (ctx->iq_lut_total != total || ctx->iq_lut_n != p.lut_n) {
+            hipLaunchKernelGGL(iq_lut_kernel, dim3(1), dim3(256), 0, ctx->stream, (double)total, p.lut_n,
+                               (float *)ctx->iq_lut.ptr);
+            DDCCA_HIP(ctx, hipGetLastError());
+            ctx->iq_lut_total = total;
+            ctx->iq_lut_n = p.lut_n;
+        }
+        p.lut = (const float *)ctx->iq_lut.ptr;
     }
+    ProfScope prof(ctx, DDCCA_K_HASH_HIST);
+    int rc;
+    switch (out_type) {
+        case DDCCA_FEAT_COUNT_U16: rc = hist_dispatch<DDCCA_FEAT_COUNT_U16>(ctx, p, n, L2); break;
+        case DDCCA_FEAT_IQ_F32: rc = hist_dispatch<DDCCA_FEAT_IQ_F32>(ctx, p, n, L2); break;
+        case DDCCA_FEAT_IQ_F16: rc = hist_dispatch<DDCCA_FEAT_IQ_F16>(ctx, p, n, L2); break;
+        default: return fail(ctx, DDCCA_EINVAL, "unknown feature type");
+    }
+    if (rc) return rc;
     DDCCA_HIP(ctx, hipGetLastError());
     return DDCCA_OK;
 }
