@@ -24,7 +24,7 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 PEAK_FP32_VALU_TFLOPS = 157.3
 
 
-def algorithmic_work(wl, M):
+def algorithmic_work(wl, M, feat_bytes=2):
     """Algorithmic flops / bytes per step for each kernel (both stages, both views)."""
     D, P = wl.D, wl.h * wl.w
     L1, L2, C = wl.L1, wl.L2, wl.n_classes
@@ -36,7 +36,7 @@ def algorithmic_work(wl, M):
     # conv: read 4 B, write 4L B per input pixel; stage 1 runs in fit and again in extract
     conv_bytes = 2 * (2 * M * P * (4 + 4 * L1)) + 2 * M * L1 * P * (4 + 4 * L2)
     conv_flops = 2 * (2 * M * P * 2 * D * L1) + 2 * M * L1 * P * 2 * D * L2
-    hist_bytes = 2 * M * L1 * (L2 * P * 4 + A * bins * 2)
+    hist_bytes = 2 * M * L1 * (L2 * P * 4 + A * bins * feat_bytes)
     class_bytes = 2 * 4 * (M * P + M * L1 * P)       # every map of both views read once
     return {
         "gram_flops": gram_main, "gram_cross_flops": gram_class,
@@ -87,6 +87,9 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="small_face")
+    ap.add_argument("--features", default="counts", choices=["counts", "iq_f32", "iq_f16"],
+                    help="output layer: uint16 block histograms (the headline path) or the information-quality "
+                         "values -log p(t) as fp32 / fp16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=0, help="images in the CPU-oracle sample (0 = default)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -112,12 +115,14 @@ def main():
     ctx = Context(0)
     d1, d2, dc = torch.from_numpy(v1).cuda(), torch.from_numpy(v2).cuda(), torch.from_numpy(cls).cuda()
     by, bx = wl.blocks
-    feat = torch.empty((M, 2, wl.L1, by, bx, 1 << wl.L2), dtype=torch.uint16, device="cuda")
+    feat_dtype = {"counts": torch.uint16, "iq_f32": torch.float32, "iq_f16": torch.float16}[args.features]
+    feat = torch.empty((M, 2, wl.L1, by, bx, 1 << wl.L2), dtype=feat_dtype, device="cuda")
     batch = wl.extract_batch
 
     def step():
         model = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
-        pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride, batch, out=feat)
+        pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride, batch, out=feat,
+                         dtype=feat_dtype)
 
     if args.copy_calibration > 0:
         src = torch.ones(args.copy_calibration * (1 << 18), dtype=torch.float32, device="cuda")
@@ -167,12 +172,12 @@ def main():
     phases = {
         "learn": timed(lambda: pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)),
         "extract": timed(lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block,
-                                                  wl.stride, batch, out=feat)),
+                                                  wl.stride, batch, out=feat, dtype=feat_dtype)),
         "e2e": timed(step),
     }
     ctx.status()
 
-    work = algorithmic_work(wl, M)
+    work = algorithmic_work(wl, M, feat.element_size())
     K = args.steps
     gram_ms = prof["gram"]["ms"] / max(1, prof["gram"]["launches"])
     gram_flops_per_launch = work["gram_flops"] * K / max(1, prof["gram"]["launches"])
@@ -205,7 +210,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "images": M, "classes": wl.n_classes, "h": wl.h, "w": wl.w, "k": wl.k,
                    "L1": wl.L1, "L2": wl.L2, "block": wl.block, "stride": wl.stride, "bins": 1 << wl.L2,
-                   "feature_len": wl.feature_len},
+                   "feature_len": wl.feature_len, "features": args.features},
         "roofline": {"bound": "mfma", "kernel": "patch_gram_kernel (all-tiles variant: the Gram over the input maps)", "achieved": gram_tflops,
                      "peak": PEAK_MFMA_FP32_TFLOPS, "unit": "TFLOP/s", "frac": gram_tflops / PEAK_MFMA_FP32_TFLOPS,
                      "traffic": measured_traffic(wl.name, "patch_gram_kernel", ", false,"), "avg_launch_ms": gram_ms,
