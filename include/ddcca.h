@@ -144,6 +144,19 @@ int ddcca_hash_iq(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, i
 int ddcca_extract_iq_features(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h,
                               int w, const ddcca_model *model, int feat_type, void *feat);
 
+/* ---- fused last stage ------------------------------------------------------------------
+ * Eq. 6 with the L2 filters W followed by the output layer (Eq. 7-12) in one kernel: the L2
+ * maps of every input map are hashed and counted as they are computed and never written.
+ * The result is bit-identical to ddcca_apply_stage followed by ddcca_hash_iq (the
+ * contraction runs in the same order).  in: [n][h][w]; W: [L2][k][k]; out as ddcca_hash_iq. */
+int ddcca_apply_stage_hash(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W,
+                           int k, int L2, int block_h, int block_w, int stride_y, int stride_x,
+                           int feat_type, void *out);
+/* ddcca_extract_iq_features with the second stage and the output layer fused: same output,
+ * bit for bit; only the stage-1 maps of a batch are held in context scratch. */
+int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h,
+                                 int w, const ddcca_model *model, int feat_type, void *feat);
+
 /* ---- per-kernel timing (HIP events on the context's stream) -------------------------- */
 enum {
     DDCCA_K_GRAM = 0,     /* patch-Gram accumulation over the input maps (all tiles) */
@@ -153,6 +166,7 @@ enum {
     DDCCA_K_CONV,         /* stage convolution */
     DDCCA_K_HASH_HIST,    /* hashing + block histogram */
     DDCCA_K_GRAM_CROSS,   /* patch-Gram of the class-sum / total-sum images (cross-view tiles only) */
+    DDCCA_K_CONV_HASH_HIST, /* last stage convolution fused with hashing + block histogram */
     DDCCA_K_COUNT
 };
 /* While enabled, every kernel launch is bracketed by a pair of events. */

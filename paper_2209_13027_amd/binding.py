@@ -16,14 +16,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libddcca.so")
 
 OK, EINVAL, ESTATE, ENOMEM, EHIP, EOVERFLOW, ELABEL = 0, -1, -2, -3, -4, -5, -6
-K_GRAM, K_CLASS_SUM, K_REDUCE, K_SOLVE, K_CONV, K_HASH_HIST, K_GRAM_CROSS, K_COUNT = range(8)
-KERNEL_NAMES = ["gram", "class_sum", "reduce", "solve", "conv", "hash_hist", "gram_cross"]
+K_GRAM, K_CLASS_SUM, K_REDUCE, K_SOLVE, K_CONV, K_HASH_HIST, K_GRAM_CROSS, K_CONV_HASH_HIST, K_COUNT = range(9)
+KERNEL_NAMES = ["gram", "class_sum", "reduce", "solve", "conv", "hash_hist", "gram_cross", "conv_hash_hist"]
 
 EXPORTS = [
     "ddcca_create", "ddcca_destroy", "ddcca_last_error", "ddcca_status",
     "ddcca_corr_begin", "ddcca_corr_accumulate", "ddcca_corr_export", "ddcca_solve_filters",
     "ddcca_dcca_solve", "ddcca_learn_stage_filters", "ddcca_apply_stage", "ddcca_hash_histogram",
     "ddcca_extract_features", "ddcca_hash_iq", "ddcca_extract_iq_features",
+    "ddcca_apply_stage_hash", "ddcca_extract_features_fused",
     "ddcca_profile_enable", "ddcca_profile_read", "ddcca_profile_reset",
 ]
 FEAT_COUNT_U16, FEAT_IQ_F32, FEAT_IQ_F16 = 0, 1, 2
@@ -75,6 +76,8 @@ def lib() -> ctypes.CDLL:
         l.ddcca_extract_features.argtypes = [vp, vp, vp, i64, i, i, ctypes.POINTER(_Model), vp]
         l.ddcca_hash_iq.argtypes = [vp, vp, i64, i, i, i, i, i, i, i, i, vp]
         l.ddcca_extract_iq_features.argtypes = [vp, vp, vp, i64, i, i, ctypes.POINTER(_Model), i, vp]
+        l.ddcca_apply_stage_hash.argtypes = [vp, vp, i64, i, i, vp, i, i, i, i, i, i, i, vp]
+        l.ddcca_extract_features_fused.argtypes = [vp, vp, vp, i64, i, i, ctypes.POINTER(_Model), i, vp]
         l.ddcca_profile_enable.argtypes = [vp, i]
         l.ddcca_profile_read.argtypes = [vp, i, ctypes.POINTER(d), ctypes.POINTER(i64)]
         l.ddcca_profile_reset.argtypes = [vp]
@@ -215,13 +218,31 @@ class Context:
                                         FEAT_TYPES[dtype], _ptr(out, dtype, "out")))
         return out
 
+    def apply_stage_hash(self, x, W, block, stride, dtype=torch.uint16, out=None):
+        """x: [n, h, w]; W: [L2, k, k] -> [n, nby, nbx, 2**L2]: stage convolution fused with hashing and block
+        histograms (counts, or information quality for float dtypes)."""
+        n, h, w = x.shape
+        L2, k = W.shape[0], W.shape[1]
+        bh, bw = (block, block) if isinstance(block, int) else block
+        sy, sx = (stride, stride) if isinstance(stride, int) else stride
+        if h < bh or w < bw or sy < 1 or sx < 1:
+            nby = nbx = 0
+        else:
+            nby, nbx = (h - bh) // sy + 1, (w - bw) // sx + 1
+        if out is None:
+            out = torch.empty((n, nby, nbx, 1 << L2), dtype=dtype, device=x.device)
+        self._check(lib().ddcca_apply_stage_hash(self._h, _ptr(x, torch.float32, "x"), n, h, w,
+                                                 _ptr(W, torch.float32, "W"), k, L2, bh, bw, sy, sx,
+                                                 FEAT_TYPES[dtype], _ptr(out, dtype, "out")))
+        return out
+
     def extract_iq_features(self, v1, v2, filters, k, L1, L2, block, stride, dtype=torch.float32, batch_images=0,
                             out=None):
         """As extract_features, with -log p(t) per bin (float32 / float16) instead of the counts."""
         return self.extract_features(v1, v2, filters, k, L1, L2, block, stride, batch_images, out, dtype)
 
     def extract_features(self, v1, v2, filters, k, L1, L2, block, stride, batch_images=0, out=None,
-                         dtype=torch.uint16):
+                         dtype=torch.uint16, fused=False):
         """filters = (W1_stage1, W2_stage1, W1_stage2, W2_stage2) -> [m, 2, L1, nby, nbx, 2**L2] uint16."""
         m, h, w = v1.shape
         bh, bw = (block, block) if isinstance(block, int) else block
@@ -237,7 +258,12 @@ class Context:
             for d in range(2):
                 model.W[s][d] = _ptr(filters[2 * s + d], torch.float32, names[2 * s + d])
         model.batch_images = int(batch_images)
-        if dtype == torch.uint16:
+        if fused:
+            self._check(lib().ddcca_extract_features_fused(self._h, _ptr(v1, torch.float32, "v1"),
+                                                           _ptr(v2, torch.float32, "v2"), m, h, w,
+                                                           ctypes.byref(model), FEAT_TYPES[dtype],
+                                                           _ptr(out, dtype, "feat")))
+        elif dtype == torch.uint16:
             self._check(lib().ddcca_extract_features(self._h, _ptr(v1, torch.float32, "v1"),
                                                      _ptr(v2, torch.float32, "v2"), m, h, w, ctypes.byref(model),
                                                      _ptr(out, torch.uint16, "feat")))

@@ -363,8 +363,8 @@ int ddcca_extract_features(ddcca_ctx *ctx, const float *v1, const float *v2, int
     return ddcca_extract_iq_features(ctx, v1, v2, m, h, w, model, DDCCA_FEAT_COUNT_U16, feat);
 }
 
-int ddcca_extract_iq_features(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h, int w,
-                              const ddcca_model *model, int feat_type, void *feat)
+static int extract_impl(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h, int w,
+                        const ddcca_model *model, int feat_type, void *feat, bool fused)
 {
     if (!ctx) return DDCCA_EINVAL;
     if (!model) return fail(ctx, DDCCA_EINVAL, "null model");
@@ -388,29 +388,63 @@ int ddcca_extract_iq_features(ddcca_ctx *ctx, const float *v1, const float *v2, 
     const int64_t A = (int64_t)((h - model->block_h) / model->stride_y + 1) *
                       ((w - model->block_w) / model->stride_x + 1);
     const int64_t bins = (int64_t)1 << L2;
-    // default batch: stage-2 maps of one view for one batch take about 4 GiB
+    // default batch: the largest map buffer of one view for one batch (stage-2 maps; stage-1 maps when the
+    // second stage is fused with the output layer) takes about 4 GiB
     int64_t batch = model->batch_images;
     if (batch == 0) {
-        const double per_image = (double)L1 * L2 * P * sizeof(float);
+        const double per_image = (double)L1 * (fused ? 1 : L2) * P * sizeof(float);
         batch = (int64_t)std::max(1.0, 4.0 * 1073741824.0 / per_image);
     }
     batch = std::min(batch, m);
     if ((rc = ensure(ctx, ctx->maps1, (size_t)batch * L1 * P * sizeof(float)))) return rc;
-    if ((rc = ensure(ctx, ctx->maps2, (size_t)batch * L1 * L2 * P * sizeof(float)))) return rc;
+    if (!fused && (rc = ensure(ctx, ctx->maps2, (size_t)batch * L1 * L2 * P * sizeof(float)))) return rc;
     float *y = (float *)ctx->maps1.ptr, *z = (float *)ctx->maps2.ptr;
     const float *views[2] = {v1, v2};
     for (int64_t m0 = 0; m0 < m; m0 += batch) {
         const int64_t mb = std::min(batch, m - m0);
         for (int d = 0; d < 2; ++d) {
             if ((rc = launch_conv(ctx, views[d] + m0 * P, mb, h, w, model->W[0][d], k, L1, y))) return rc;
-            if ((rc = launch_conv(ctx, y, mb * L1, h, w, model->W[1][d], k, L2, z))) return rc;
+            if (!fused && (rc = launch_conv(ctx, y, mb * L1, h, w, model->W[1][d], k, L2, z))) return rc;
             void *dst = reinterpret_cast<char *>(feat) + ((m0 * 2 + d) * L1) * A * bins * feat_elem_size(feat_type);
-            if ((rc = launch_hash_hist(ctx, z, mb * L1, L2, h, w, model->block_h, model->block_w, model->stride_y,
-                                       model->stride_x, dst, feat_type, L1, 2 * L1 * A * bins)))
-                return rc;
+            if (fused)
+                rc = launch_conv_hash_hist(ctx, y, mb * L1, h, w, model->W[1][d], k, L2, model->block_h,
+                                           model->block_w, model->stride_y, model->stride_x, dst, feat_type, L1,
+                                           2 * L1 * A * bins);
+            else
+                rc = launch_hash_hist(ctx, z, mb * L1, L2, h, w, model->block_h, model->block_w, model->stride_y,
+                                      model->stride_x, dst, feat_type, L1, 2 * L1 * A * bins);
+            if (rc) return rc;
         }
     }
     return DDCCA_OK;
+}
+
+int ddcca_extract_iq_features(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h, int w,
+                              const ddcca_model *model, int feat_type, void *feat)
+{
+    return extract_impl(ctx, v1, v2, m, h, w, model, feat_type, feat, false);
+}
+
+int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h, int w,
+                                 const ddcca_model *model, int feat_type, void *feat)
+{
+    return extract_impl(ctx, v1, v2, m, h, w, model, feat_type, feat, true);
+}
+
+int ddcca_apply_stage_hash(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L2,
+                           int block_h, int block_w, int stride_y, int stride_x, int feat_type, void *out)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    int rc;
+    if ((rc = check_feat_type(ctx, feat_type))) return rc;
+    if ((rc = check_image_args(ctx, n, h, w, k))) return rc;
+    if ((rc = check_hist_args(ctx, n, L2, h, w, block_h, block_w, stride_y, stride_x))) return rc;
+    if (n == 0) return DDCCA_OK;
+    if (!in || !W || !out) return fail(ctx, DDCCA_EINVAL, "null data pointer");
+    if ((rc = device_ready(ctx))) return rc;
+    const int64_t A = (int64_t)((h - block_h) / stride_y + 1) * ((w - block_w) / stride_x + 1);
+    return launch_conv_hash_hist(ctx, in, n, h, w, W, k, L2, block_h, block_w, stride_y, stride_x, out, feat_type, 1,
+                                 A * ((int64_t)1 << L2));
 }
 
 int ddcca_profile_enable(ddcca_ctx *ctx, int on)

@@ -110,4 +110,14 @@ int launch_conv(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const 
 int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int bh, int bw,
                      int sy, int sx, void *out, int out_type, int64_t group, int64_t group_stride);
 
+// information-quality table of the output layer (device, owned by the context): lut[c] = log(total) -
+// log(c + 1), total = bh*bw + 2^L2, for c < lut_n; all three outputs are zero for the count output
+int prepare_iq_table(ddcca_ctx *ctx, int out_type, int bh, int bw, int L2, const float **lut, int *lut_n,
+                     double *log_total);
+// stage convolution of n input maps with the L2 filters W fused with hashing + block histograms: the
+// same output as launch_conv followed by launch_hash_hist, without the maps in between
+int launch_conv_hash_hist(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L2,
+                          int bh, int bw, int sy, int sx, void *out, int out_type, int64_t group,
+                          int64_t group_stride);
+
 }  // namespace ddcca

@@ -15,16 +15,12 @@
 // the possible counts come from a table (built in fp64 by a one-workgroup kernel, rounded
 // once to fp32) that every workgroup copies into LDS, so the epilogue is one LDS gather per
 // output element and the kernel stays bound by its HBM writes.
-#include "ddcca_internal.h"
-
-#include <hip/hip_fp16.h>
+#include "hist_common.h"
 
 namespace ddcca {
 
 constexpr int HIST_THREADS = 256;
 constexpr int HIST_LDS_BYTES = 32 * 1024;   // histogram bytes per workgroup (occupancy 4-5 per CU)
-
-constexpr int IQ_LUT_MAX = 2048;            // table entries (counts 0..2047); larger counts are computed directly
 
 struct HistParams {
     const float *maps;
@@ -42,21 +38,6 @@ struct HistParams {
     unsigned magic_sy, magic_sx;   // ceil(2^32 / stride) when h, w < 65536 (exact division by mul-hi), else 0
 };
 
-// x / d for 0 <= x < 65536 with magic = ceil(2^32 / d) (exact), plain division otherwise.
-__device__ __forceinline__ int fast_div(int x, int d, unsigned magic)
-{
-    return magic ? (int)__umulhi((unsigned)x, magic) : x / d;
-}
-
-// Block rows [ilo, ihi] (clipped to the workgroup's [i0, i1)) that contain image row y.
-__device__ __forceinline__ void block_range(int y, int b, int s, unsigned magic, int lo, int hi, int &first, int &last)
-{
-    first = y - b + 1 < 0 ? 0 : fast_div(y - b + s, s, magic);     // ceil((y - b + 1) / s)
-    last = fast_div(y, s, magic);
-    first = max(first, lo);
-    last = min(last, hi - 1);
-}
-
 template <int L2>
 __device__ __forceinline__ void hist_add(unsigned int *lds_hist, const HistParams &p, int x, unsigned code, int ilo,
                                          int ihi, int i0, int j0, int j1, int ncol)
@@ -69,34 +50,6 @@ __device__ __forceinline__ void hist_add(unsigned int *lds_hist, const HistParam
     for (int i = ilo; i <= ihi; ++i)
         for (int j = jlo; j <= jhi; ++j)
             atomicAdd(&lds_hist[((i - i0) * ncol + (j - j0)) * WORDS + word], inc);
-}
-
-template <int OUT> struct HistOut;
-template <> struct HistOut<DDCCA_FEAT_COUNT_U16> { typedef uint16_t type; };
-template <> struct HistOut<DDCCA_FEAT_IQ_F32> { typedef float type; };
-template <> struct HistOut<DDCCA_FEAT_IQ_F16> { typedef __half type; };
-
-__device__ __forceinline__ float iq_value(unsigned c, const float *lut, int lut_n, double log_total)
-{
-    return (int)c < lut_n ? lut[c] : (float)(log_total - log((double)(c + 1u)));
-}
-
-template <int OUT> __device__ __forceinline__ typename HistOut<OUT>::type hist_convert(unsigned c, const float *lut,
-                                                                                      int lut_n, double log_total);
-template <> __device__ __forceinline__ uint16_t hist_convert<DDCCA_FEAT_COUNT_U16>(unsigned c, const float *, int,
-                                                                                   double)
-{
-    return (uint16_t)c;
-}
-template <> __device__ __forceinline__ float hist_convert<DDCCA_FEAT_IQ_F32>(unsigned c, const float *lut, int lut_n,
-                                                                             double log_total)
-{
-    return iq_value(c, lut, lut_n, log_total);
-}
-template <> __device__ __forceinline__ __half hist_convert<DDCCA_FEAT_IQ_F16>(unsigned c, const float *lut, int lut_n,
-                                                                              double log_total)
-{
-    return __float2half_rn(iq_value(c, lut, lut_n, log_total));
 }
 
 __global__ void iq_lut_kernel(double total, int n, float *lut)
@@ -255,6 +208,31 @@ static int hist_dispatch(ddcca_ctx *ctx, const HistParams &p, int64_t n, int L2)
     return DDCCA_OK;
 }
 
+int prepare_iq_table(ddcca_ctx *ctx, int out_type, int bh, int bw, int L2, const float **lut, int *lut_n,
+                     double *log_total)
+{
+    *lut = nullptr;
+    *lut_n = 0;
+    *log_total = 0.0;
+    if (out_type == DDCCA_FEAT_COUNT_U16) return DDCCA_OK;
+    // values for counts 0 .. min(area, IQ_LUT_MAX - 1), rebuilt when the block area or bin count changes
+    const int64_t total = (int64_t)bh * bw + ((int64_t)1 << L2);
+    const int n = (int)std::min<int64_t>((int64_t)bh * bw + 1, IQ_LUT_MAX);
+    int rc;
+    if ((rc = ensure(ctx, ctx->iq_lut, IQ_LUT_MAX * sizeof(float)))) return rc;
+    if (ctx->iq_lut_total != total || ctx->iq_lut_n != n) {
+        hipLaunchKernelGGL(iq_lut_kernel, dim3(1), dim3(256), 0, ctx->stream, (double)total, n,
+                           (float *)ctx->iq_lut.ptr);
+        DDCCA_HIP(ctx, hipGetLastError());
+        ctx->iq_lut_total = total;
+        ctx->iq_lut_n = n;
+    }
+    *lut = (const float *)ctx->iq_lut.ptr;
+    *lut_n = n;
+    *log_total = std::log((double)total);
+    return DDCCA_OK;
+}
+
 int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int bh, int bw, int sy,
                      int sx, void *out, int out_type, int64_t group, int64_t group_stride)
 {
@@ -268,25 +246,9 @@ int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h
     const bool small = h < 65536 && w < 65536;
     p.magic_sy = small ? (unsigned)((((uint64_t)1 << 32) + sy - 1) / sy) : 0u;
     p.magic_sx = small ? (unsigned)((((uint64_t)1 << 32) + sx - 1) / sx) : 0u;
-    p.lut = nullptr; p.lut_n = 0; p.log_total = 0.0;
-    if (out_type != DDCCA_FEAT_COUNT_U16) {
-        // table of the values for counts 0 .. min(area, IQ_LUT_MAX - 1), rebuilt when the block area or bin count changes
-        const int64_t total = (int64_t)bh * bw + ((int64_t)1 << L2);
-        p.lut_n = (int)std::min<int64_t>((int64_t)bh * bw + 1, IQ_LUT_MAX);
-        p.log_total = std::log((double)total);
-        int rc;
-        if ((rc = ensure(ctx, ctx->iq_lut, IQ_LUT_MAX * sizeof(float)))) return rc;
-        if (ctx->iq_lut_total != total || ctx->iq_lut_n != p.lut_n) {
-            hipLaunchKernelGGL(iq_lut_kernel, dim3(1), dim3(256), 0, ctx->stream, (double)total, p.lut_n,
-                               (float *)ctx->iq_lut.ptr);
-            DDCCA_HIP(ctx, hipGetLastError());
-            ctx->iq_lut_total = total;
-            ctx->iq_lut_n = p.lut_n;
-        }
-        p.lut = (const float *)ctx->iq_lut.ptr;
-    }
-    ProfScope prof(ctx, DDCCA_K_HASH_HIST);
     int rc;
+    if ((rc = prepare_iq_table(ctx, out_type, bh, bw, L2, &p.lut, &p.lut_n, &p.log_total))) return rc;
+    ProfScope prof(ctx, DDCCA_K_HASH_HIST);
     switch (out_type) {
         case DDCCA_FEAT_COUNT_U16: rc = hist_dispatch<DDCCA_FEAT_COUNT_U16>(ctx, p, n, L2); break;
         case DDCCA_FEAT_IQ_F32: rc = hist_dispatch<DDCCA_FEAT_IQ_F32>(ctx, p, n, L2); break;

@@ -24,6 +24,7 @@ def fit(ctx: Context, v1: torch.Tensor, v2: torch.Tensor, cls: torch.Tensor, n_c
 
 
 def extract(ctx: Context, v1, v2, filters, k, L1, L2, block, stride, batch_images=0, out=None,
-            dtype=torch.uint16):
-    """dtype uint16: block histograms; float32 / float16: their information quality (Eq. 10)."""
-    return ctx.extract_features(v1, v2, filters, k, L1, L2, block, stride, batch_images, out, dtype)
+            dtype=torch.uint16, fused=False):
+    """dtype uint16: block histograms; float32 / float16: their information quality (Eq. 10).
+    fused: second stage convolution and output layer in one kernel (same result, bit for bit)."""
+    return ctx.extract_features(v1, v2, filters, k, L1, L2, block, stride, batch_images, out, dtype, fused)
