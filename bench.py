@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--features", default="counts", choices=["counts", "iq_f32", "iq_f16"],
                     help="output layer: uint16 block histograms (the headline path) or the information-quality "
                          "values -log p(t) as fp32 / fp16")
+    ap.add_argument("--fused", action="store_true",
+                    help="time the path with the second stage convolution fused into the output layer (the "
+                         "stage-2 maps are never written); the default materialises them")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=0, help="images in the CPU-oracle sample (0 = default)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -122,7 +125,7 @@ def main():
     def step():
         model = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
         pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride, batch, out=feat,
-                         dtype=feat_dtype)
+                         dtype=feat_dtype, fused=args.fused)
 
     if args.copy_calibration > 0:
         src = torch.ones(args.copy_calibration * (1 << 18), dtype=torch.float32, device="cuda")
@@ -172,18 +175,35 @@ def main():
     phases = {
         "learn": timed(lambda: pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)),
         "extract": timed(lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block,
-                                                  wl.stride, batch, out=feat, dtype=feat_dtype)),
+                                                  wl.stride, batch, out=feat, dtype=feat_dtype,
+                                                  fused=args.fused)),
         "e2e": timed(step),
     }
+    if not args.fused:
+        # the same extraction with the second stage fused into the output layer, for comparison
+        ctx.profile_reset()
+        ctx.profile_enable(True)
+        phases["extract_fused"] = timed(lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2,
+                                                                 wl.block, wl.stride, batch, out=feat,
+                                                                 dtype=feat_dtype, fused=True))
+        ctx.profile_enable(False)
+        pf = ctx.profile_read()["conv_hash_hist"]
+        phases["extract_fused"]["conv_hash_hist_ms"] = pf["ms"] / args.steps
+        phases["extract_fused"]["e2e_images_per_s"] = M / ((phases["learn"]["ms_mean"]
+                                                            + phases["extract_fused"]["ms_mean"]) * 1e-3)
     ctx.status()
 
     work = algorithmic_work(wl, M, feat.element_size())
+    L1v, P = wl.L1, wl.h * wl.w
     K = args.steps
     gram_ms = prof["gram"]["ms"] / max(1, prof["gram"]["launches"])
     gram_flops_per_launch = work["gram_flops"] * K / max(1, prof["gram"]["launches"])
     gram_tflops = gram_flops_per_launch / (gram_ms * 1e-3) / 1e12 if gram_ms > 0 else 0.0
     conv_ms = prof["conv"]["ms"] / K
     hist_ms = prof["hash_hist"]["ms"] / K
+    fused_ms = prof["conv_hash_hist"]["ms"] / K
+    fused_flops = 2 * M * L1v * P * 2 * wl.D * wl.L2
+    fused_bytes = 2 * M * L1v * (P * 4 + by * bx * (1 << wl.L2) * feat.element_size())
     kernels = {
         "gram": {"ms_per_step": prof["gram"]["ms"] / K, "launches_per_step": prof["gram"]["launches"] / K,
                  "useful_tflops": gram_tflops, "frac_mfma_fp32": gram_tflops / PEAK_MFMA_FP32_TFLOPS},
@@ -203,6 +223,16 @@ def main():
                       "gbs": work["hist_bytes"] / (hist_ms * 1e-3) / 1e9 if hist_ms > 0 else 0.0,
                       "frac_hbm": work["hist_bytes"] / (hist_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if hist_ms > 0 else 0.0},
     }
+    if fused_ms > 0:
+        # stage-2 conv bytes and flops move from "conv" into the fused kernel
+        s1_bytes = 2 * (2 * M * P * (4 + 4 * L1v))
+        kernels["conv"]["gbs"] = s1_bytes / (conv_ms * 1e-3) / 1e9 if conv_ms > 0 else 0.0
+        kernels["conv"]["frac_hbm"] = kernels["conv"]["gbs"] / PEAK_HBM_GBS
+        kernels["conv"]["tflops"] = 2 * (2 * M * P * 2 * wl.D * L1v) / (conv_ms * 1e-3) / 1e12 if conv_ms > 0 else 0.0
+        del kernels["hash_hist"]
+        kernels["conv_hash_hist"] = {"ms_per_step": fused_ms, "tflops": fused_flops / (fused_ms * 1e-3) / 1e12,
+                                     "frac_mfma_fp32": fused_flops / (fused_ms * 1e-3) / 1e12 / PEAK_MFMA_FP32_TFLOPS,
+                                     "gbs": fused_bytes / (fused_ms * 1e-3) / 1e9}
     out = {
         "metric": "images/s for 2-stage DDCCANet extraction (learn both stages + extract features)",
         "value": M * K / dt, "unit": "images/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
@@ -210,7 +240,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "images": M, "classes": wl.n_classes, "h": wl.h, "w": wl.w, "k": wl.k,
                    "L1": wl.L1, "L2": wl.L2, "block": wl.block, "stride": wl.stride, "bins": 1 << wl.L2,
-                   "feature_len": wl.feature_len, "features": args.features},
+                   "feature_len": wl.feature_len, "features": args.features,
+                   "fused_last_stage": bool(args.fused)},
         "roofline": {"bound": "mfma", "kernel": "patch_gram_kernel (all-tiles variant: the Gram over the input maps)", "achieved": gram_tflops,
                      "peak": PEAK_MFMA_FP32_TFLOPS, "unit": "TFLOP/s", "frac": gram_tflops / PEAK_MFMA_FP32_TFLOPS,
                      "traffic": measured_traffic(wl.name, "patch_gram_kernel", ", false,"), "avg_launch_ms": gram_ms,

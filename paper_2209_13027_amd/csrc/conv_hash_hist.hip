@@ -9,23 +9,34 @@
 // so every map value, and with it every code and count, is bit-identical to running the
 // convolution and the hash+histogram kernels one after the other.
 //
-// One workgroup owns RB block rows x a chunk of block columns of one input map (their packed
-// 16-bit histograms stay in LDS, as in the unfused kernel) and walks the pixel rectangle those
-// blocks cover in 32-row x (32*NBX)-column tiles: stage tile + halo in LDS, one wavefront per
-// tile row runs NBX accumulator chains, takes the signs, ORs the partial codes of the four
-// 16-lane groups together (each holds two filters) and adds the 32 pixels of a column block
-// to the histograms of the blocks that contain them.
+// Main kernel ("ring"): one workgroup of 8 wavefronts sweeps one input map (or a chunk of its
+// block columns) top to bottom in tiles of TH rows x (32*NBX) columns.  Only the block rows
+// that overlap the current tile are live, so their packed 16-bit histograms sit in a ring of
+// a few block rows in LDS; a block row is written out (and its slot cleared) as soon as the
+// sweep has passed its last pixel row.  Every map value is therefore computed exactly once.
+// Tiles are double-buffered: the next tile travels HBM -> registers while the current one is
+// contracted, and is written to the other LDS buffer afterwards (one barrier per tile, one
+// more when block rows are flushed).  A wavefront owns whole tile rows: NBX accumulator
+// chains, signs, OR of the partial codes of the four 16-lane groups (each holds two filters),
+// then the 32 pixels of a column block are added to the histograms of the blocks that
+// contain them.
+// Fallback kernel ("group"), for block geometries whose live block rows do not fit in LDS
+// (very dense overlap, 4096 bins): a workgroup owns RB block rows x a chunk of block columns
+// and recomputes the map rows that neighbouring groups share.
 #include "hist_common.h"
 
 namespace ddcca {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int FUSED_THREADS = 256;
-constexpr int FUSED_TH = 32;              // tile rows
 constexpr int FUSED_XB = 32;              // pixels per MFMA column block (16 columns x 2 shifts)
 constexpr int FUSED_MAX_NBX = 4;
 constexpr int FUSED_LDS_BYTES = 80 * 1024;   // per workgroup: two workgroups share a compute unit's 160 KB
+constexpr int RING_THREADS = 512;
+constexpr int RING_WAVES = RING_THREADS / 64;
+constexpr int RING_TH_MAX = 32;           // largest tile height of the ring kernel
+constexpr int GROUP_THREADS = 256;
+constexpr int GROUP_TH = 32;              // tile rows of the group kernel
 
 struct FusedParams {
     const float *in;      // [n][h][w]
@@ -37,29 +48,283 @@ struct FusedParams {
     int out_type;
     int L2;
     int h, w, bh, bw, sy, sx, nby, nbx;
-    int rb, cols, row_groups, col_chunks;
+    int cols, col_chunks; // block columns per workgroup, chunks per map
+    int rb, row_groups;   // group kernel: block rows per workgroup, groups per map
+    int th, ring;         // ring kernel: tile rows, block rows held in LDS
     int64_t group, group_stride;
-    unsigned magic_sy, magic_sx;
+    unsigned magic_sy, magic_sx, magic_ring;
     int hist_words;       // LDS words of the histograms (padded to 4)
     int lut_words;        // LDS words reserved for the table (padded to 4)
+    int tile_floats;      // LDS floats of one tile buffer
 };
 
 template <int KS, int NBX>
-__host__ __device__ constexpr int fused_tile_floats()
+struct FusedGeom {
+    static constexpr int R = (KS - 1) / 2;
+    static constexpr int KW = KS + 1;              // tap columns incl. the shift
+    static constexpr int TAPS = KS * KW;
+    static constexpr int KK = (TAPS + 3) / 4;      // MFMA steps
+    static constexpr int TW = NBX * FUSED_XB;
+    static constexpr int PW = TW + 2 * R + 1;      // +1: the odd shift reads one more column
+    static constexpr int PITCH = PW | 1;           // odd pitch: rows start in different banks
+    static constexpr int tile_floats(int th) { return (th + 2 * R) * PITCH; }
+};
+
+// Per-lane constants of the implicit GEMM: B-operand window offsets and the A operand (filters).
+template <int KS, int NBX, int NG>
+__device__ __forceinline__ void fused_operands(const float *W, int L2, int q, int c, int (&toff)[FusedGeom<KS, NBX>::KK],
+                                               float (&wa)[NG][FusedGeom<KS, NBX>::KK])
 {
-    return (FUSED_TH + KS - 1) * ((NBX * FUSED_XB + KS) | 1);
+    typedef FusedGeom<KS, NBX> G;
+#pragma unroll
+    for (int kk = 0; kk < G::KK; ++kk) {
+        const int tap = 4 * kk + q;
+        const int dy = tap / G::KW, dx = tap - dy * G::KW;
+        toff[kk] = tap < G::TAPS ? dy * G::PITCH + dx : 0;
+    }
+    // A operand: row (g,s) = lane%16, tap 4*kk + lane/16, for every group of 8 filters
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {
+        const int g = 8 * gi + (c >> 1), s = c & 1;
+#pragma unroll
+        for (int kk = 0; kk < G::KK; ++kk) {
+            const int tap = 4 * kk + q;
+            const int dy = tap / G::KW, dxw = tap - dy * G::KW - s;
+            float v = 0.f;
+            if (tap < G::TAPS && dxw >= 0 && dxw < KS && g < L2) v = W[(g * KS + dy) * KS + dxw];
+            wa[gi][kk] = v;
+        }
+    }
 }
 
+// One tile row: the L2 map values of 32*NBX pixels on the matrix unit, then their hash codes.
+// Returns per column block the codes of the pixel pair (x0 + 2c, x0 + 2c + 1) in the low / high
+// half of pc[b], identical in all four 16-lane groups.
 template <int KS, int NBX, int NG>
-__global__ __launch_bounds__(FUSED_THREADS) void conv_hash_hist_kernel(FusedParams p)
+__device__ __forceinline__ void fused_row_codes(const float *prow, const int (&toff)[FusedGeom<KS, NBX>::KK],
+                                                const float (&wa)[NG][FusedGeom<KS, NBX>::KK], int q,
+                                                unsigned (&pc)[NBX])
 {
-    constexpr int R = (KS - 1) / 2;
-    constexpr int KW = KS + 1;                    // tap columns incl. the shift
-    constexpr int TAPS = KS * KW;
-    constexpr int KK = (TAPS + 3) / 4;            // MFMA steps
-    constexpr int TW = NBX * FUSED_XB;
-    constexpr int PW = TW + 2 * R + 1;            // +1: the odd shift reads one more column
-    constexpr int PITCH = PW | 1;
+    typedef FusedGeom<KS, NBX> G;
+#pragma unroll
+    for (int b = 0; b < NBX; ++b) pc[b] = 0u;
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {
+        floatx4 acc[NBX];
+#pragma unroll
+        for (int b = 0; b < NBX; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < G::KK; ++kk) {
+            const float *pk = prow + toff[kk];
+#pragma unroll
+            for (int b = 0; b < NBX; ++b)
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[gi][kk], pk[b * FUSED_XB], acc[b], 0, 0, 0);
+        }
+        // lane (q,c): acc[0], acc[1] = filter 8gi+2q at pixels x, x+1; acc[2], acc[3] = filter 8gi+2q+1
+        const int sh = 8 * gi + 2 * q;
+#pragma unroll
+        for (int b = 0; b < NBX; ++b)
+            pc[b] |= ((acc[b][0] > 0.0f ? 1u : 0u) << sh) | ((acc[b][2] > 0.0f ? 1u : 0u) << (sh + 1)) |
+                     ((acc[b][1] > 0.0f ? 1u : 0u) << (sh + 16)) | ((acc[b][3] > 0.0f ? 1u : 0u) << (sh + 17));
+    }
+#pragma unroll
+    for (int b = 0; b < NBX; ++b) {
+        unsigned v = pc[b];
+        v |= (unsigned)__shfl_xor((int)v, 16);
+        v |= (unsigned)__shfl_xor((int)v, 32);
+        pc[b] = v;
+    }
+}
+
+// Convert `n_words` packed histogram words at `sp` (LDS) to the output element type at `dst`
+// (both contiguous).  All threads of the workgroup take part; with `clear` every word is set
+// to zero by the thread that read it.
+__device__ __forceinline__ void fused_write_out(unsigned *sp, char *dst, int n_words, int bins, int out_type,
+                                                const float *lds_lut, int lut_n, double log_total, bool aligned,
+                                                bool clear, int tid, int n_threads)
+{
+    const int esz = out_type == DDCCA_FEAT_IQ_F32 ? 4 : 2;
+    const int vw = 8 / esz;                                          // packed words per 16-byte store
+    if (aligned && bins >= 2 * vw) {
+        for (int e = tid; e < n_words / vw; e += n_threads) {
+            unsigned *s = sp + vw * e;
+            uint4 val;
+            if (out_type == DDCCA_FEAT_COUNT_U16) {
+                val = *reinterpret_cast<const uint4 *>(s);
+                if (clear) *reinterpret_cast<uint4 *>(s) = make_uint4(0u, 0u, 0u, 0u);
+            } else if (out_type == DDCCA_FEAT_IQ_F32) {
+                const uint2 wv = *reinterpret_cast<const uint2 *>(s);
+                if (clear) *reinterpret_cast<uint2 *>(s) = make_uint2(0u, 0u);
+                val.x = __float_as_uint(iq_value(wv.x & 0xffffu, lds_lut, lut_n, log_total));
+                val.y = __float_as_uint(iq_value(wv.x >> 16, lds_lut, lut_n, log_total));
+                val.z = __float_as_uint(iq_value(wv.y & 0xffffu, lds_lut, lut_n, log_total));
+                val.w = __float_as_uint(iq_value(wv.y >> 16, lds_lut, lut_n, log_total));
+            } else {
+                const uint4 wv = *reinterpret_cast<const uint4 *>(s);
+                if (clear) *reinterpret_cast<uint4 *>(s) = make_uint4(0u, 0u, 0u, 0u);
+                const unsigned in[4] = {wv.x, wv.y, wv.z, wv.w};
+                unsigned o[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const __half lo = __float2half_rn(iq_value(in[t] & 0xffffu, lds_lut, lut_n, log_total));
+                    const __half hi = __float2half_rn(iq_value(in[t] >> 16, lds_lut, lut_n, log_total));
+                    o[t] = (unsigned)__half_as_ushort(lo) | ((unsigned)__half_as_ushort(hi) << 16);
+                }
+                val = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+            *reinterpret_cast<uint4 *>(dst + (size_t)e * 16) = val;
+        }
+    } else {
+        // one thread per word: its one (bins == 1) or two elements
+        const int per_word = bins > 1 ? 2 : 1;
+        for (int e = tid; e < n_words; e += n_threads) {
+            const unsigned wv = sp[e];
+            if (clear) sp[e] = 0u;
+            for (int t = 0; t < per_word; ++t) {
+                const unsigned cnt = (wv >> (16 * t)) & 0xffffu;
+                char *d = dst + ((size_t)e * per_word + t) * esz;
+                if (out_type == DDCCA_FEAT_COUNT_U16)
+                    *reinterpret_cast<uint16_t *>(d) = (uint16_t)cnt;
+                else if (out_type == DDCCA_FEAT_IQ_F32)
+                    *reinterpret_cast<float *>(d) = iq_value(cnt, lds_lut, lut_n, log_total);
+                else
+                    *reinterpret_cast<__half *>(d) = __float2half_rn(iq_value(cnt, lds_lut, lut_n, log_total));
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------ ring kernel
+template <int KS, int NBX, int NG>
+__global__ __launch_bounds__(RING_THREADS) void conv_hash_hist_ring_kernel(FusedParams p)
+{
+    typedef FusedGeom<KS, NBX> G;
+    constexpr int R = G::R, KK = G::KK, TW = G::TW, PW = G::PW, PITCH = G::PITCH;
+    constexpr int NPRE = ((RING_TH_MAX + 2 * R) * PW + RING_THREADS - 1) / RING_THREADS;
+    extern __shared__ unsigned int lds[];
+    unsigned int *lds_hist = lds;
+    float *lds_lut = reinterpret_cast<float *>(lds + p.hist_words);
+    float *tile0 = lds_lut + p.lut_words;
+
+    const int bins = 1 << p.L2;
+    const int words = bins > 1 ? bins / 2 : 1;    // 32-bit words per packed histogram
+    const int64_t n = blockIdx.x / p.col_chunks;
+    const int cc = (int)(blockIdx.x - n * p.col_chunks);
+    const int j0 = cc * p.cols, j1 = min(j0 + p.cols, p.nbx);
+    const int ncol = j1 - j0;
+    const int row_words = ncol * words;           // one block row of the chunk
+    for (int e = threadIdx.x; e < p.ring * row_words; e += RING_THREADS) lds_hist[e] = 0u;
+    if (p.out_type != DDCCA_FEAT_COUNT_U16)
+        for (int e = threadIdx.x; e < p.lut_n; e += RING_THREADS) lds_lut[e] = p.lut[e];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int q = lane >> 4, c = lane & 15;
+    int toff[KK];
+    float wa[NG][KK];
+    fused_operands<KS, NBX, NG>(p.W, p.L2, q, c, toff, wa);
+
+    const int64_t P = (int64_t)p.h * p.w;
+    const float *src = p.in + n * P;
+    const int y_hi = (p.nby - 1) * p.sy + p.bh;                      // pixel rows [0, y_hi)
+    const int x_lo = j0 * p.sx, x_hi = (j1 - 1) * p.sx + p.bw;       // pixel columns [x_lo, x_hi)
+    const int my_s = q & 1, my_ioff = q >> 1;                        // this lane's pixel of a pair / block-row parity
+    const int tiles_x = (x_hi - x_lo + TW - 1) / TW;
+    const int tiles_y = (y_hi + p.th - 1) / p.th;
+    const int n_tiles = tiles_x * tiles_y;
+
+    const int64_t A = (int64_t)p.nby * p.nbx;
+    const int esz = p.out_type == DDCCA_FEAT_IQ_F32 ? 4 : 2;
+    char *out_map = reinterpret_cast<char *>(p.out) + ((n / p.group) * p.group_stride + (n % p.group) * A * bins) * esz;
+    // a block row of the chunk starts on a 16-byte boundary in the output
+    const bool aligned = ((((uintptr_t)out_map) | (uintptr_t)((int64_t)p.nbx * bins * esz) | (uintptr_t)((int64_t)j0 * bins * esz)) & 15) == 0;
+
+    float pre[NPRE];
+    auto fetch = [&](int t) {
+        const int tyi = t / tiles_x, txi = t - tyi * tiles_x;
+        const int ty0 = tyi * p.th, rows = min(p.th, y_hi - ty0);
+        const int gy0 = ty0 - R, gx0 = x_lo + txi * TW - R;
+        const int n_el = (rows + 2 * R) * PW;
+#pragma unroll
+        for (int u = 0; u < NPRE; ++u) {
+            const int e = threadIdx.x + u * RING_THREADS;
+            const int yy = e / PW, xx = e - yy * PW;
+            const int gy = gy0 + yy, gx = gx0 + xx;
+            float v = 0.f;
+            if (e < n_el && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w) v = src[(int64_t)gy * p.w + gx];
+            pre[u] = v;
+        }
+    };
+    auto stash = [&](float *tile, int t) {
+        const int tyi = t / tiles_x;
+        const int rows = min(p.th, y_hi - tyi * p.th);
+        const int n_el = (rows + 2 * R) * PW;
+#pragma unroll
+        for (int u = 0; u < NPRE; ++u) {
+            const int e = threadIdx.x + u * RING_THREADS;
+            const int yy = e / PW, xx = e - yy * PW;
+            if (e < n_el) tile[yy * PITCH + xx] = pre[u];
+        }
+    };
+
+    fetch(0);
+    stash(tile0, 0);
+    int next_flush = 0;                           // first block row not yet written out
+    for (int t = 0; t < n_tiles; ++t) {
+        __syncthreads();                          // tile t is in LDS; cleared slots are visible
+        const float *tile = tile0 + (t & 1) * p.tile_floats;
+        if (t + 1 < n_tiles) fetch(t + 1);
+        const int tyi = t / tiles_x, txi = t - tyi * tiles_x;
+        const int ty0 = tyi * p.th, rows = min(p.th, y_hi - ty0);
+        const int tx0 = x_lo + txi * TW;
+        for (int r = wave; r < rows; r += RING_WAVES) {
+            unsigned pc[NBX];
+            fused_row_codes<KS, NBX, NG>(tile + r * PITCH + 2 * c, toff, wa, q, pc);
+            const int y = ty0 + r;
+            int ilo, ihi;
+            block_range(y, p.bh, p.sy, p.magic_sy, 0, p.nby, ilo, ihi);
+#pragma unroll
+            for (int b = 0; b < NBX; ++b) {
+                // 64 lanes, 32 pixels: lane (q,c) takes pixel x0 + 2c + (q&1) and the block rows ilo + (q>>1), +2, ...
+                const unsigned code = (pc[b] >> (16 * my_s)) & 0xffffu;
+                const int x = tx0 + b * FUSED_XB + 2 * c + my_s;
+                if (x < x_hi) {
+                    int jlo, jhi;
+                    block_range(x, p.bw, p.sx, p.magic_sx, j0, j1, jlo, jhi);
+                    const unsigned inc = 1u << (16 * (code & 1));
+                    const unsigned word = code >> 1;
+                    for (int i = ilo + my_ioff; i <= ihi; i += 2) {
+                        const int slot = p.magic_ring ? i - p.ring * (int)__umulhi((unsigned)i, p.magic_ring) : i % p.ring;
+                        for (int j = jlo; j <= jhi; ++j)
+                            atomicAdd(&lds_hist[slot * row_words + (j - j0) * words + word], inc);
+                    }
+                }
+            }
+        }
+        if (t + 1 < n_tiles) stash(tile0 + ((t + 1) & 1) * p.tile_floats, t + 1);
+        if (txi == tiles_x - 1) {
+            // block rows whose last pixel row lies inside the rows swept so far are complete
+            const int done = ty0 + rows - p.bh;
+            const int i_end = done < 0 ? 0 : min(p.nby, fast_div(done, p.sy, p.magic_sy) + 1);
+            if (i_end > next_flush) {
+                __syncthreads();                  // every count of these block rows has been added
+                for (int i = next_flush; i < i_end; ++i) {
+                    const int slot = i % p.ring;
+                    fused_write_out(lds_hist + slot * row_words, out_map + ((int64_t)i * p.nbx + j0) * bins * esz,
+                                    row_words, bins, p.out_type, lds_lut, p.lut_n, p.log_total, aligned, true,
+                                    threadIdx.x, RING_THREADS);
+                }
+                next_flush = i_end;
+            }
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------- group kernel
+template <int KS, int NBX, int NG>
+__global__ __launch_bounds__(GROUP_THREADS) void conv_hash_hist_group_kernel(FusedParams p)
+{
+    typedef FusedGeom<KS, NBX> G;
+    constexpr int R = G::R, KK = G::KK, TW = G::TW, PW = G::PW, PITCH = G::PITCH;
     extern __shared__ unsigned int lds[];
     unsigned int *lds_hist = lds;
     float *lds_lut = reinterpret_cast<float *>(lds + p.hist_words);
@@ -74,51 +339,32 @@ __global__ __launch_bounds__(FUSED_THREADS) void conv_hash_hist_kernel(FusedPara
     const int i0 = rg * p.rb, i1 = min(i0 + p.rb, p.nby);
     const int j0 = cc * p.cols, j1 = min(j0 + p.cols, p.nbx);
     const int nrow = i1 - i0, ncol = j1 - j0;
-    const int n_words = nrow * ncol * words;
-    for (int e = threadIdx.x; e < n_words; e += FUSED_THREADS) lds_hist[e] = 0u;
+    const int row_words = ncol * words;
+    for (int e = threadIdx.x; e < nrow * row_words; e += GROUP_THREADS) lds_hist[e] = 0u;
     if (p.out_type != DDCCA_FEAT_COUNT_U16)
-        for (int e = threadIdx.x; e < p.lut_n; e += FUSED_THREADS) lds_lut[e] = p.lut[e];
+        for (int e = threadIdx.x; e < p.lut_n; e += GROUP_THREADS) lds_lut[e] = p.lut[e];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int q = lane >> 4, c = lane & 15;
-    // B-operand window offsets of this lane's tap (4*kk + q) for every step
     int toff[KK];
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-        const int tap = 4 * kk + q;
-        const int dy = tap / KW, dx = tap - dy * KW;
-        toff[kk] = tap < TAPS ? dy * PITCH + dx : 0;
-    }
-    // A operand: row (g,s) = lane%16, tap 4*kk + lane/16, for every group of 8 filters
     float wa[NG][KK];
-#pragma unroll
-    for (int gi = 0; gi < NG; ++gi) {
-        const int g = 8 * gi + (c >> 1), s = c & 1;
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            const int tap = 4 * kk + q;
-            const int dy = tap / KW, dxw = tap - dy * KW - s;
-            float v = 0.f;
-            if (tap < TAPS && dxw >= 0 && dxw < KS && g < p.L2) v = p.W[(g * KS + dy) * KS + dxw];
-            wa[gi][kk] = v;
-        }
-    }
+    fused_operands<KS, NBX, NG>(p.W, p.L2, q, c, toff, wa);
 
     const int64_t P = (int64_t)p.h * p.w;
     const float *src = p.in + n * P;
     const int y_lo = i0 * p.sy, y_hi = (i1 - 1) * p.sy + p.bh;       // pixel rows [y_lo, y_hi)
     const int x_lo = j0 * p.sx, x_hi = (j1 - 1) * p.sx + p.bw;       // pixel columns [x_lo, x_hi)
-    const int my_s = q & 1, my_ioff = q >> 1;                        // this lane's pixel of a pair / block-row parity
+    const int my_s = q & 1, my_ioff = q >> 1;
 
-    for (int ty0 = y_lo; ty0 < y_hi; ty0 += FUSED_TH) {
-        const int rows = min(FUSED_TH, y_hi - ty0);
+    for (int ty0 = y_lo; ty0 < y_hi; ty0 += GROUP_TH) {
+        const int rows = min(GROUP_TH, y_hi - ty0);
         for (int tx0 = x_lo; tx0 < x_hi; tx0 += TW) {
             __syncthreads();                      // the previous tile has been consumed (first pass: LDS initialised)
             {
                 const int gy0 = ty0 - R, gx0 = tx0 - R;
                 const int n_el = (rows + 2 * R) * PW;
 #pragma unroll 4
-                for (int e = threadIdx.x; e < n_el; e += FUSED_THREADS) {
+                for (int e = threadIdx.x; e < n_el; e += GROUP_THREADS) {
                     const int yy = e / PW, xx = e - yy * PW;
                     const int gy = gy0 + yy, gx = gx0 + xx;
                     float v = 0.f;
@@ -127,40 +373,15 @@ __global__ __launch_bounds__(FUSED_THREADS) void conv_hash_hist_kernel(FusedPara
                 }
             }
             __syncthreads();
-            for (int r = wave; r < rows; r += 4) {
-                const float *prow = tile + r * PITCH + 2 * c;
+            for (int r = wave; r < rows; r += GROUP_THREADS / 64) {
                 unsigned pc[NBX];
-#pragma unroll
-                for (int b = 0; b < NBX; ++b) pc[b] = 0u;
-#pragma unroll
-                for (int gi = 0; gi < NG; ++gi) {
-                    floatx4 acc[NBX];
-#pragma unroll
-                    for (int b = 0; b < NBX; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int kk = 0; kk < KK; ++kk) {
-                        const float *pk = prow + toff[kk];
-#pragma unroll
-                        for (int b = 0; b < NBX; ++b)
-                            acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[gi][kk], pk[b * FUSED_XB], acc[b], 0, 0, 0);
-                    }
-                    // lane (q,c): acc[0], acc[1] = filter 8gi+2q at pixels x, x+1; acc[2], acc[3] = filter 8gi+2q+1
-                    const int sh = 8 * gi + 2 * q;
-#pragma unroll
-                    for (int b = 0; b < NBX; ++b)
-                        pc[b] |= ((acc[b][0] > 0.0f ? 1u : 0u) << sh) | ((acc[b][2] > 0.0f ? 1u : 0u) << (sh + 1)) |
-                                 ((acc[b][1] > 0.0f ? 1u : 0u) << (sh + 16)) | ((acc[b][3] > 0.0f ? 1u : 0u) << (sh + 17));
-                }
+                fused_row_codes<KS, NBX, NG>(tile + r * PITCH + 2 * c, toff, wa, q, pc);
                 const int y = ty0 + r;
                 int ilo, ihi;
                 block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
 #pragma unroll
                 for (int b = 0; b < NBX; ++b) {
-                    unsigned v = pc[b];
-                    v |= (unsigned)__shfl_xor((int)v, 16);
-                    v |= (unsigned)__shfl_xor((int)v, 32);
-                    // 64 lanes, 32 pixels: lane (q,c) takes pixel x0 + 2c + (q&1) and the block rows ilo + (q>>1), +2, ...
-                    const unsigned code = (v >> (16 * my_s)) & 0xffffu;
+                    const unsigned code = (pc[b] >> (16 * my_s)) & 0xffffu;
                     const int x = tx0 + b * FUSED_XB + 2 * c + my_s;
                     if (x < x_hi) {
                         int jlo, jhi;
@@ -169,7 +390,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void conv_hash_hist_kernel(FusedPara
                         const unsigned word = code >> 1;
                         for (int i = ilo + my_ioff; i <= ihi; i += 2)
                             for (int j = jlo; j <= jhi; ++j)
-                                atomicAdd(&lds_hist[((i - i0) * ncol + (j - j0)) * words + word], inc);
+                                atomicAdd(&lds_hist[(i - i0) * row_words + (j - j0) * words + word], inc);
                     }
                 }
             }
@@ -177,68 +398,39 @@ __global__ __launch_bounds__(FUSED_THREADS) void conv_hash_hist_kernel(FusedPara
     }
     __syncthreads();
 
-    // copy out: block row i of the chunk is ncol*bins contiguous elements in the output
     const int64_t A = (int64_t)p.nby * p.nbx;
     const int esz = p.out_type == DDCCA_FEAT_IQ_F32 ? 4 : 2;
-    const int64_t map_off = (n / p.group) * p.group_stride + (n % p.group) * A * bins;
-    char *out_map = reinterpret_cast<char *>(p.out) + map_off * esz;
-    const int vw = 8 / esz;                                          // packed words per 16-byte store
-    if (bins >= 2 * vw && ((((uintptr_t)out_map) | (uintptr_t)(A * bins * esz) | (uintptr_t)(p.group_stride * esz)) & 15) == 0) {
-        const int row_vec = ncol * words / vw;
-        for (int e = threadIdx.x; e < nrow * row_vec; e += FUSED_THREADS) {
-            const int ir = e / row_vec, v = e - ir * row_vec;
-            const unsigned *sp = lds_hist + (ir * ncol * words) + vw * v;
-            char *dst = out_map + (((int64_t)(i0 + ir) * p.nbx + j0) * bins + 2 * vw * v) * esz;
-            uint4 val;
-            if (p.out_type == DDCCA_FEAT_COUNT_U16) {
-                val = *reinterpret_cast<const uint4 *>(sp);
-            } else if (p.out_type == DDCCA_FEAT_IQ_F32) {
-                const unsigned w0 = sp[0], w1 = sp[1];
-                val.x = __float_as_uint(iq_value(w0 & 0xffffu, lds_lut, p.lut_n, p.log_total));
-                val.y = __float_as_uint(iq_value(w0 >> 16, lds_lut, p.lut_n, p.log_total));
-                val.z = __float_as_uint(iq_value(w1 & 0xffffu, lds_lut, p.lut_n, p.log_total));
-                val.w = __float_as_uint(iq_value(w1 >> 16, lds_lut, p.lut_n, p.log_total));
-            } else {
-                unsigned o[4];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const unsigned wv = sp[t];
-                    const __half lo = __float2half_rn(iq_value(wv & 0xffffu, lds_lut, p.lut_n, p.log_total));
-                    const __half hi = __float2half_rn(iq_value(wv >> 16, lds_lut, p.lut_n, p.log_total));
-                    o[t] = (unsigned)__half_as_ushort(lo) | ((unsigned)__half_as_ushort(hi) << 16);
-                }
-                val = make_uint4(o[0], o[1], o[2], o[3]);
-            }
-            *reinterpret_cast<uint4 *>(dst) = val;
-        }
-    } else {
-        for (int e = threadIdx.x; e < nrow * ncol * bins; e += FUSED_THREADS) {
-            const int ir = e / (ncol * bins), rest = e - ir * ncol * bins;
-            const unsigned wv = lds_hist[ir * ncol * words + (rest >> 1)];
-            const unsigned cnt = (bins > 1 ? (wv >> (16 * (rest & 1))) : wv) & 0xffffu;
-            char *dst = out_map + (((int64_t)(i0 + ir) * p.nbx + j0) * bins + rest) * esz;
-            if (p.out_type == DDCCA_FEAT_COUNT_U16)
-                *reinterpret_cast<uint16_t *>(dst) = (uint16_t)cnt;
-            else if (p.out_type == DDCCA_FEAT_IQ_F32)
-                *reinterpret_cast<float *>(dst) = iq_value(cnt, lds_lut, p.lut_n, p.log_total);
-            else
-                *reinterpret_cast<__half *>(dst) = __float2half_rn(iq_value(cnt, lds_lut, p.lut_n, p.log_total));
-        }
+    char *out_map = reinterpret_cast<char *>(p.out) + ((n / p.group) * p.group_stride + (n % p.group) * A * bins) * esz;
+    const bool aligned = ((((uintptr_t)out_map) | (uintptr_t)((int64_t)p.nbx * bins * esz) | (uintptr_t)((int64_t)j0 * bins * esz)) & 15) == 0;
+    for (int ir = 0; ir < nrow; ++ir)
+        fused_write_out(lds_hist + ir * row_words, out_map + ((int64_t)(i0 + ir) * p.nbx + j0) * bins * esz, row_words,
+                        bins, p.out_type, lds_lut, p.lut_n, p.log_total, aligned, false, threadIdx.x, GROUP_THREADS);
+}
+
+// ------------------------------------------------------------------------------------ host
+template <typename Kernel>
+static int fused_set_lds(ddcca_ctx *ctx, Kernel kernel, bool *done)
+{
+    if (!*done) {
+        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           FUSED_LDS_BYTES));
+        *done = true;
     }
+    return DDCCA_OK;
 }
 
 template <int KS, int NBX, int NG>
-static int fused_launch(ddcca_ctx *ctx, FusedParams p, int64_t n)
+static int fused_launch(ddcca_ctx *ctx, FusedParams p, int64_t n, bool ring)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)conv_hash_hist_kernel<KS, NBX, NG>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, FUSED_LDS_BYTES));
-        attr_set = true;
-    }
-    const size_t lds = ((size_t)p.hist_words + p.lut_words + fused_tile_floats<KS, NBX>()) * 4;
+    static bool ring_attr = false, group_attr = false;
+    int rc;
+    if ((rc = ring ? fused_set_lds(ctx, conv_hash_hist_ring_kernel<KS, NBX, NG>, &ring_attr)
+                   : fused_set_lds(ctx, conv_hash_hist_group_kernel<KS, NBX, NG>, &group_attr)))
+        return rc;
+    p.tile_floats = FusedGeom<KS, NBX>::tile_floats(ring ? p.th : GROUP_TH);
+    const size_t lds = ((size_t)p.hist_words + p.lut_words + (size_t)p.tile_floats * (ring ? 2 : 1)) * 4;
     if (lds > (size_t)FUSED_LDS_BYTES) return fail(ctx, DDCCA_EINVAL, "internal: fused kernel LDS budget exceeded");
-    const int64_t per_map = (int64_t)p.row_groups * p.col_chunks;
+    const int64_t per_map = (int64_t)p.col_chunks * (ring ? 1 : p.row_groups);
     const int64_t esz = p.out_type == DDCCA_FEAT_IQ_F32 ? 4 : 2;
     const int64_t maps_per_launch = std::max<int64_t>(p.group, (((int64_t)1 << 30) / per_map) / p.group * p.group);
     for (int64_t n0 = 0; n0 < n; n0 += maps_per_launch) {
@@ -246,47 +438,96 @@ static int fused_launch(ddcca_ctx *ctx, FusedParams p, int64_t n)
         FusedParams q = p;
         q.in = p.in + n0 * (int64_t)p.h * p.w;
         q.out = reinterpret_cast<char *>(p.out) + (n0 / p.group) * p.group_stride * esz;
-        hipLaunchKernelGGL((conv_hash_hist_kernel<KS, NBX, NG>), dim3((unsigned)(nb * per_map)), dim3(FUSED_THREADS),
-                           lds, ctx->stream, q);
+        if (ring)
+            hipLaunchKernelGGL((conv_hash_hist_ring_kernel<KS, NBX, NG>), dim3((unsigned)(nb * per_map)),
+                               dim3(RING_THREADS), lds, ctx->stream, q);
+        else
+            hipLaunchKernelGGL((conv_hash_hist_group_kernel<KS, NBX, NG>), dim3((unsigned)(nb * per_map)),
+                               dim3(GROUP_THREADS), lds, ctx->stream, q);
     }
     DDCCA_HIP(ctx, hipGetLastError());
     return DDCCA_OK;
 }
 
 template <int KS, int NG>
-static int fused_pick_nbx(ddcca_ctx *ctx, FusedParams &p, int64_t n)
+static int fused_dispatch_nbx(ddcca_ctx *ctx, const FusedParams &p, int64_t n, int nbx_tile, bool ring)
 {
-    // Geometry.  Histogram budget: what the largest tile leaves of the workgroup's LDS.  Block columns and
-    // block rows are spread evenly over the chunks / groups so that the workgroups of a map do equal work.
+    switch (nbx_tile) {
+        case 1: return fused_launch<KS, 1, NG>(ctx, p, n, ring);
+        case 2: return fused_launch<KS, 2, NG>(ctx, p, n, ring);
+        case 3: return fused_launch<KS, 3, NG>(ctx, p, n, ring);
+        default: return fused_launch<KS, 4, NG>(ctx, p, n, ring);
+    }
+}
+
+// equal-width tiles of at most FUSED_MAX_NBX column blocks across a pixel rectangle of this width
+static int fused_tile_blocks(int width)
+{
+    const int xblocks = (width + FUSED_XB - 1) / FUSED_XB;
+    const int tiles_x = (xblocks + FUSED_MAX_NBX - 1) / FUSED_MAX_NBX;
+    return (xblocks + tiles_x - 1) / tiles_x;
+}
+
+// Largest number of block rows that overlap one tile of th pixel rows.
+static int fused_live_rows(int th, int bh, int sy, int nby)
+{
+    const int y_hi = (nby - 1) * sy + bh;
+    int live = 1;
+    for (int ty0 = 0; ty0 < y_hi; ty0 += th) {
+        const int y_last = std::min(ty0 + th, y_hi) - 1;
+        const int first = ty0 - bh + 1 <= 0 ? 0 : (ty0 - bh + sy) / sy;    // ceil((ty0 - bh + 1) / sy)
+        const int last = std::min(nby - 1, y_last / sy);
+        live = std::max(live, last - first + 1);
+    }
+    return live;
+}
+
+template <int KS, int NG>
+static int fused_plan(ddcca_ctx *ctx, FusedParams &p, int64_t n)
+{
     const int bins = 1 << p.L2;
-    const int hist_bytes = (bins > 1 ? bins / 2 : 1) * 4;
+    const int hist_bytes = (bins > 1 ? bins / 2 : 1) * 4;             // packed histogram of one block
     p.lut_words = p.out_type != DDCCA_FEAT_COUNT_U16 ? (p.lut_n + 3) / 4 * 4 : 0;
-    const int budget = FUSED_LDS_BYTES - fused_tile_floats<KS, FUSED_MAX_NBX>() * 4 - p.lut_words * 4 - 16;
+    const int fixed = p.lut_words * 4 + 16;
+    constexpr int PITCH_MAX = ((FUSED_MAX_NBX * FUSED_XB + KS) | 1);
+    // Ring kernel: the fewest column chunks, then the tallest tile, whose live block rows and two tile
+    // buffers fit in the workgroup's LDS.
+    for (int chunks = 1; chunks <= p.nbx; ++chunks) {
+        const int cols = (p.nbx + chunks - 1) / chunks;
+        if ((p.nbx + cols - 1) / cols != chunks) continue;            // same chunk count as a smaller one
+        const int nbt = fused_tile_blocks((cols - 1) * p.sx + p.bw);
+        const int pitch = (nbt * FUSED_XB + KS) | 1;
+        for (int th = RING_TH_MAX; th >= 8; th /= 2) {
+            const int ring = fused_live_rows(th, p.bh, p.sy, p.nby);
+            const int64_t need = (int64_t)ring * cols * hist_bytes + fixed + 2 * (int64_t)(th + KS - 1) * pitch * 4;
+            if (need > FUSED_LDS_BYTES) continue;
+            p.cols = cols; p.col_chunks = chunks; p.th = th; p.ring = ring;
+            p.rb = 0; p.row_groups = 0;
+            p.hist_words = (ring * cols * (hist_bytes / 4) + 3) / 4 * 4;
+            p.magic_ring = p.nby < 65536 ? (unsigned)((((uint64_t)1 << 32) + ring - 1) / ring) : 0u;
+            return fused_dispatch_nbx<KS, NG>(ctx, p, n, nbt, true);
+        }
+    }
+    // Group kernel.  Histogram budget: what the largest tile leaves of the workgroup's LDS; block columns and
+    // block rows are spread evenly over the chunks / groups.
+    const int budget = FUSED_LDS_BYTES - (GROUP_TH + KS - 1) * PITCH_MAX * 4 - fixed;
     const int max_blocks = std::max(1, budget / hist_bytes);
     p.col_chunks = (p.nbx + max_blocks - 1) / max_blocks;
     p.cols = (p.nbx + p.col_chunks - 1) / p.col_chunks;
+    p.col_chunks = (p.nbx + p.cols - 1) / p.cols;
     const int rb_max = std::max(1, max_blocks / p.cols);
     p.row_groups = (p.nby + rb_max - 1) / rb_max;
     p.rb = (p.nby + p.row_groups - 1) / p.row_groups;
     p.row_groups = (p.nby + p.rb - 1) / p.rb;
+    p.th = GROUP_TH; p.ring = 0; p.magic_ring = 0;
     p.hist_words = (p.rb * p.cols * (hist_bytes / 4) + 3) / 4 * 4;
-    // equal-width tiles of at most FUSED_MAX_NBX column blocks across the widest pixel rectangle
-    const int width = (p.cols - 1) * p.sx + p.bw;
-    const int xblocks = (width + FUSED_XB - 1) / FUSED_XB;
-    const int tiles_x = (xblocks + FUSED_MAX_NBX - 1) / FUSED_MAX_NBX;
-    const int nbx_tile = (xblocks + tiles_x - 1) / tiles_x;
-    switch (nbx_tile) {
-        case 1: return fused_launch<KS, 1, NG>(ctx, p, n);
-        case 2: return fused_launch<KS, 2, NG>(ctx, p, n);
-        case 3: return fused_launch<KS, 3, NG>(ctx, p, n);
-        default: return fused_launch<KS, 4, NG>(ctx, p, n);
-    }
+    return fused_dispatch_nbx<KS, NG>(ctx, p, n, fused_tile_blocks((p.cols - 1) * p.sx + p.bw), false);
 }
 
 template <int KS>
 static int fused_pick_groups(ddcca_ctx *ctx, FusedParams &p, int64_t n)
 {
-    return p.L2 <= 8 ? fused_pick_nbx<KS, 1>(ctx, p, n) : fused_pick_nbx<KS, 2>(ctx, p, n);
+    return p.L2 <= 8 ? fused_plan<KS, 1>(ctx, p, n) : fused_plan<KS, 2>(ctx, p, n);
 }
 
 int launch_conv_hash_hist(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L2,

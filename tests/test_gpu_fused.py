@@ -41,6 +41,8 @@ GEOMETRIES = [
     (2, 9, 300, 3, 3, (9, 11), (1, 7)),  # single block row, rectangular block, three tile columns
     (1, 8, 8, 9, 5, 8, 8),               # filter larger than the map, one block
     (2, 33, 130, 7, 11, (6, 10), (2, 3)),  # dense block overlap (stride < block/2), 11 filters
+    (2, 24, 24, 3, 12, 9, 1),            # stride 1 with 4096 bins: live block rows exceed LDS (row-group kernel)
+    (2, 150, 40, 5, 8, 16, 8),           # tall narrow map: many tile rows, several block-row flushes
 ]
 
 
