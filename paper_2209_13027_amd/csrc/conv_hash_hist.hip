@@ -32,7 +32,16 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int FUSED_XB = 32;              // pixels per MFMA column block (16 columns x 2 shifts)
 constexpr int FUSED_MAX_NBX = 4;
 constexpr int FUSED_LDS_BYTES = 80 * 1024;   // per workgroup: two workgroups share a compute unit's 160 KB
+#ifndef FUSED_EXP_RING_THREADS
 constexpr int RING_THREADS = 512;
+#else
+constexpr int RING_THREADS = FUSED_EXP_RING_THREADS;
+#endif
+#ifndef FUSED_EXP_RING_MINWG
+constexpr int RING_MIN_WG = 4;            // wavefronts per SIMD the register budget must allow (two workgroups per compute unit)
+#else
+constexpr int RING_MIN_WG = FUSED_EXP_RING_MINWG;
+#endif
 constexpr int RING_WAVES = RING_THREADS / 64;
 constexpr int RING_TH_MAX = 32;           // largest tile height of the ring kernel
 constexpr int GROUP_THREADS = 256;
@@ -60,6 +69,7 @@ struct FusedParams {
 
 template <int KS, int NBX>
 struct FusedGeom {
+    static constexpr int KSZ = KS;
     static constexpr int R = (KS - 1) / 2;
     static constexpr int KW = KS + 1;              // tap columns incl. the shift
     static constexpr int TAPS = KS * KW;
@@ -70,12 +80,27 @@ struct FusedGeom {
     static constexpr int tile_floats(int th) { return (th + 2 * R) * PITCH; }
 };
 
+// Tile of the ring kernel: rows start at an image column that is a multiple of 4 (16-byte loads and
+// LDS stores), which costs up to 3 columns of slack.
+template <int KS, int NBX>
+struct RingGeom {
+    static constexpr int KSZ = KS;
+    static constexpr int R = (KS - 1) / 2;
+    static constexpr int KW = KS + 1;
+    static constexpr int TAPS = KS * KW;
+    static constexpr int KK = (TAPS + 3) / 4;
+    static constexpr int TW = NBX * FUSED_XB;
+    static constexpr int PITCH = (TW + 2 * R + 1 + 3 + 3) / 4 * 4;
+    static constexpr int V4 = PITCH / 4;           // 16-byte vectors per tile row
+    static constexpr int tile_floats(int th) { return (th + 2 * R) * PITCH; }
+};
+
 // Per-lane constants of the implicit GEMM: B-operand window offsets and the A operand (filters).
-template <int KS, int NBX, int NG>
-__device__ __forceinline__ void fused_operands(const float *W, int L2, int q, int c, int (&toff)[FusedGeom<KS, NBX>::KK],
-                                               float (&wa)[NG][FusedGeom<KS, NBX>::KK])
+template <class G, int NG>
+__device__ __forceinline__ void fused_operands(const float *W, int L2, int q, int c, int (&toff)[G::KK],
+                                               float (&wa)[NG][G::KK])
 {
-    typedef FusedGeom<KS, NBX> G;
+    constexpr int KS = G::KSZ;
 #pragma unroll
     for (int kk = 0; kk < G::KK; ++kk) {
         const int tap = 4 * kk + q;
@@ -97,43 +122,62 @@ __device__ __forceinline__ void fused_operands(const float *W, int L2, int q, in
     }
 }
 
-// One tile row: the L2 map values of 32*NBX pixels on the matrix unit, then their hash codes.
-// Returns per column block the codes of the pixel pair (x0 + 2c, x0 + 2c + 1) in the low / high
-// half of pc[b], identical in all four 16-lane groups.
-template <int KS, int NBX, int NG>
-__device__ __forceinline__ void fused_row_codes(const float *prow, const int (&toff)[FusedGeom<KS, NBX>::KK],
-                                                const float (&wa)[NG][FusedGeom<KS, NBX>::KK], int q,
-                                                unsigned (&pc)[NBX])
+// RU tile rows (RSTRIDE floats apart in LDS): the L2 map values of 32*NBX pixels per row on the matrix
+// unit, then their hash codes.  Returns per row and column block the codes of the pixel pair
+// (x0 + 2c, x0 + 2c + 1) in the low / high half of pc[u][b], identical in all four 16-lane groups.
+template <class G, int NBX, int NG, int RU, int RSTRIDE>
+__device__ __forceinline__ void fused_row_codes(const float *prow, const int (&toff)[G::KK],
+                                                const float (&wa)[NG][G::KK], int q, unsigned (&pc)[RU][NBX])
 {
-    typedef FusedGeom<KS, NBX> G;
 #pragma unroll
-    for (int b = 0; b < NBX; ++b) pc[b] = 0u;
+    for (int u = 0; u < RU; ++u)
+#pragma unroll
+        for (int b = 0; b < NBX; ++b) pc[u][b] = 0u;
+    // lane (q,c): acc[0], acc[1] = filter 8gi+2q at pixels x, x+1; acc[2], acc[3] = filter 8gi+2q+1
+    const unsigned m0 = 1u << (2 * q), m1 = m0 << 1, m16 = m0 << 16, m17 = m0 << 17;
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
-        floatx4 acc[NBX];
+        floatx4 acc[RU][NBX];
 #pragma unroll
-        for (int b = 0; b < NBX; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int u = 0; u < RU; ++u)
+#pragma unroll
+            for (int b = 0; b < NBX; ++b) acc[u][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+#ifdef FUSED_EXP_NO_MFMA
+#pragma unroll
+        for (int u = 0; u < RU; ++u)
+#pragma unroll
+            for (int b = 0; b < NBX; ++b)
+                acc[u][b] = floatx4{prow[u * RSTRIDE + b], prow[b + 1] + wa[gi][0], wa[gi][1] + prow[toff[1]], wa[gi][2]};
+#else
 #pragma unroll
         for (int kk = 0; kk < G::KK; ++kk) {
             const float *pk = prow + toff[kk];
 #pragma unroll
-            for (int b = 0; b < NBX; ++b)
-                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[gi][kk], pk[b * FUSED_XB], acc[b], 0, 0, 0);
+            for (int u = 0; u < RU; ++u)
+#pragma unroll
+                for (int b = 0; b < NBX; ++b)
+                    acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[gi][kk], pk[u * RSTRIDE + b * FUSED_XB], acc[u][b],
+                                                                     0, 0, 0);
         }
-        // lane (q,c): acc[0], acc[1] = filter 8gi+2q at pixels x, x+1; acc[2], acc[3] = filter 8gi+2q+1
-        const int sh = 8 * gi + 2 * q;
+#endif
 #pragma unroll
-        for (int b = 0; b < NBX; ++b)
-            pc[b] |= ((acc[b][0] > 0.0f ? 1u : 0u) << sh) | ((acc[b][2] > 0.0f ? 1u : 0u) << (sh + 1)) |
-                     ((acc[b][1] > 0.0f ? 1u : 0u) << (sh + 16)) | ((acc[b][3] > 0.0f ? 1u : 0u) << (sh + 17));
+        for (int u = 0; u < RU; ++u)
+#pragma unroll
+            for (int b = 0; b < NBX; ++b) {
+                const unsigned bits = (acc[u][b][0] > 0.0f ? m0 : 0u) | (acc[u][b][2] > 0.0f ? m1 : 0u) |
+                                      (acc[u][b][1] > 0.0f ? m16 : 0u) | (acc[u][b][3] > 0.0f ? m17 : 0u);
+                pc[u][b] |= bits << (8 * gi);
+            }
     }
 #pragma unroll
-    for (int b = 0; b < NBX; ++b) {
-        unsigned v = pc[b];
-        v |= (unsigned)__shfl_xor((int)v, 16);
-        v |= (unsigned)__shfl_xor((int)v, 32);
-        pc[b] = v;
-    }
+    for (int u = 0; u < RU; ++u)
+#pragma unroll
+        for (int b = 0; b < NBX; ++b) {
+            unsigned v = pc[u][b];
+            v |= (unsigned)__shfl_xor((int)v, 16);
+            v |= (unsigned)__shfl_xor((int)v, 32);
+            pc[u][b] = v;
+        }
 }
 
 // Convert `n_words` packed histogram words at `sp` (LDS) to the output element type at `dst`
@@ -195,12 +239,12 @@ __device__ __forceinline__ void fused_write_out(unsigned *sp, char *dst, int n_w
 }
 
 // ------------------------------------------------------------------------------ ring kernel
-template <int KS, int NBX, int NG>
-__global__ __launch_bounds__(RING_THREADS) void conv_hash_hist_ring_kernel(FusedParams p)
+template <int KS, int NBX, int NG, int RU>
+__global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring_kernel(FusedParams p)
 {
-    typedef FusedGeom<KS, NBX> G;
-    constexpr int R = G::R, KK = G::KK, TW = G::TW, PW = G::PW, PITCH = G::PITCH;
-    constexpr int NPRE = ((RING_TH_MAX + 2 * R) * PW + RING_THREADS - 1) / RING_THREADS;
+    typedef RingGeom<KS, NBX> G;
+    constexpr int R = G::R, KK = G::KK, TW = G::TW, PITCH = G::PITCH, V4 = G::V4;
+    constexpr int NPRE = ((RING_TH_MAX + 2 * R) * V4 + RING_THREADS - 1) / RING_THREADS;
     extern __shared__ unsigned int lds[];
     unsigned int *lds_hist = lds;
     float *lds_lut = reinterpret_cast<float *>(lds + p.hist_words);
@@ -217,14 +261,16 @@ __global__ __launch_bounds__(RING_THREADS) void conv_hash_hist_ring_kernel(Fused
     if (p.out_type != DDCCA_FEAT_COUNT_U16)
         for (int e = threadIdx.x; e < p.lut_n; e += RING_THREADS) lds_lut[e] = p.lut[e];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: row indices stay on the scalar unit
     const int q = lane >> 4, c = lane & 15;
     int toff[KK];
     float wa[NG][KK];
-    fused_operands<KS, NBX, NG>(p.W, p.L2, q, c, toff, wa);
+    fused_operands<G, NG>(p.W, p.L2, q, c, toff, wa);
 
     const int64_t P = (int64_t)p.h * p.w;
     const float *src = p.in + n * P;
+    const bool vec4 = (p.w & 3) == 0 && (((uintptr_t)src) & 15) == 0;
     const int y_hi = (p.nby - 1) * p.sy + p.bh;                      // pixel rows [0, y_hi)
     const int x_lo = j0 * p.sx, x_hi = (j1 - 1) * p.sx + p.bw;       // pixel columns [x_lo, x_hi)
     const int my_s = q & 1, my_ioff = q >> 1;                        // this lane's pixel of a pair / block-row parity
@@ -238,69 +284,106 @@ __global__ __launch_bounds__(RING_THREADS) void conv_hash_hist_ring_kernel(Fused
     // a block row of the chunk starts on a 16-byte boundary in the output
     const bool aligned = ((((uintptr_t)out_map) | (uintptr_t)((int64_t)p.nbx * bins * esz) | (uintptr_t)((int64_t)j0 * bins * esz)) & 15) == 0;
 
-    float pre[NPRE];
+    // tile t: rows [ty0 - R, ty0 + rows + R), columns [gxa, gxa + PITCH), gxa = the multiple of 4 at or
+    // below the first halo column
+    float4 pre[NPRE];
     auto fetch = [&](int t) {
         const int tyi = t / tiles_x, txi = t - tyi * tiles_x;
         const int ty0 = tyi * p.th, rows = min(p.th, y_hi - ty0);
-        const int gy0 = ty0 - R, gx0 = x_lo + txi * TW - R;
-        const int n_el = (rows + 2 * R) * PW;
+        const int gy0 = ty0 - R, gxa = (x_lo + txi * TW - R) & ~3;
+        const int n_el = (rows + 2 * R) * V4;
 #pragma unroll
         for (int u = 0; u < NPRE; ++u) {
             const int e = threadIdx.x + u * RING_THREADS;
-            const int yy = e / PW, xx = e - yy * PW;
-            const int gy = gy0 + yy, gx = gx0 + xx;
-            float v = 0.f;
-            if (e < n_el && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w) v = src[(int64_t)gy * p.w + gx];
+            const int yy = e / V4, xv = e - yy * V4;
+            const int gy = gy0 + yy, gx = gxa + 4 * xv;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (e < n_el && gy >= 0 && gy < p.h) {
+                const float *row = src + (int64_t)gy * p.w;
+                if (vec4 && gx >= 0 && gx + 3 < p.w) {
+                    v = *reinterpret_cast<const float4 *>(row + gx);
+                } else {
+                    if (gx >= 0 && gx < p.w) v.x = row[gx];
+                    if (gx + 1 >= 0 && gx + 1 < p.w) v.y = row[gx + 1];
+                    if (gx + 2 >= 0 && gx + 2 < p.w) v.z = row[gx + 2];
+                    if (gx + 3 >= 0 && gx + 3 < p.w) v.w = row[gx + 3];
+                }
+            }
             pre[u] = v;
         }
     };
     auto stash = [&](float *tile, int t) {
         const int tyi = t / tiles_x;
         const int rows = min(p.th, y_hi - tyi * p.th);
-        const int n_el = (rows + 2 * R) * PW;
+        const int n_el = (rows + 2 * R) * V4;
 #pragma unroll
         for (int u = 0; u < NPRE; ++u) {
             const int e = threadIdx.x + u * RING_THREADS;
-            const int yy = e / PW, xx = e - yy * PW;
-            if (e < n_el) tile[yy * PITCH + xx] = pre[u];
+            if (e < n_el) *reinterpret_cast<float4 *>(tile + 4 * e) = pre[u];   // row yy, vector xv: 4 * (yy * V4 + xv)
         }
     };
 
     fetch(0);
     stash(tile0, 0);
     int next_flush = 0;                           // first block row not yet written out
+    int cur_txi = -1;
+    int jo[NBX], nj[NBX];                         // this lane's pixel column per block: first block column (word offset), count
+    const int my_sh = 16 * my_s;
     for (int t = 0; t < n_tiles; ++t) {
         __syncthreads();                          // tile t is in LDS; cleared slots are visible
         const float *tile = tile0 + (t & 1) * p.tile_floats;
+#ifndef FUSED_EXP_NO_STAGE
         if (t + 1 < n_tiles) fetch(t + 1);
+#endif
         const int tyi = t / tiles_x, txi = t - tyi * tiles_x;
         const int ty0 = tyi * p.th, rows = min(p.th, y_hi - ty0);
         const int tx0 = x_lo + txi * TW;
-        for (int r = wave; r < rows; r += RING_WAVES) {
-            unsigned pc[NBX];
-            fused_row_codes<KS, NBX, NG>(tile + r * PITCH + 2 * c, toff, wa, q, pc);
-            const int y = ty0 + r;
-            int ilo, ihi;
-            block_range(y, p.bh, p.sy, p.magic_sy, 0, p.nby, ilo, ihi);
+        const int shx = (tx0 - R) & 3;            // first halo column inside the aligned tile row
+        if (txi != cur_txi) {
+            cur_txi = txi;
 #pragma unroll
             for (int b = 0; b < NBX; ++b) {
-                // 64 lanes, 32 pixels: lane (q,c) takes pixel x0 + 2c + (q&1) and the block rows ilo + (q>>1), +2, ...
-                const unsigned code = (pc[b] >> (16 * my_s)) & 0xffffu;
                 const int x = tx0 + b * FUSED_XB + 2 * c + my_s;
-                if (x < x_hi) {
-                    int jlo, jhi;
-                    block_range(x, p.bw, p.sx, p.magic_sx, j0, j1, jlo, jhi);
-                    const unsigned inc = 1u << (16 * (code & 1));
-                    const unsigned word = code >> 1;
-                    for (int i = ilo + my_ioff; i <= ihi; i += 2) {
-                        const int slot = p.magic_ring ? i - p.ring * (int)__umulhi((unsigned)i, p.magic_ring) : i % p.ring;
-                        for (int j = jlo; j <= jhi; ++j)
-                            atomicAdd(&lds_hist[slot * row_words + (j - j0) * words + word], inc);
+                int jlo = 0, jhi = -1;
+                if (x < x_hi) block_range(x, p.bw, p.sx, p.magic_sx, j0, j1, jlo, jhi);
+                jo[b] = (jlo - j0) * words;
+                nj[b] = jhi - jlo + 1;
+            }
+        }
+        for (int r0 = wave; r0 < rows; r0 += RU * RING_WAVES) {
+            unsigned pc[RU][NBX];
+            fused_row_codes<G, NBX, NG, RU, RING_WAVES * PITCH>(tile + r0 * PITCH + shx + 2 * c, toff, wa, q, pc);
+#pragma unroll
+            for (int u = 0; u < RU; ++u) {
+                const int r = r0 + u * RING_WAVES;
+                if (r >= rows) break;
+                int ilo, ihi;
+                block_range(ty0 + r, p.bh, p.sy, p.magic_sy, 0, p.nby, ilo, ihi);
+                // 64 lanes, 32 pixels: lane (q,c) takes pixel x0 + 2c + (q&1) and the block rows ilo + (q>>1), +2, ...
+                for (int ib = ilo; ib <= ihi; ib += 2) {
+                    const int ic = min(ib + 1, ihi);
+                    const int so_a = (p.magic_ring ? ib - p.ring * (int)__umulhi((unsigned)ib, p.magic_ring) : ib % p.ring) * row_words;
+                    const int so_c = (p.magic_ring ? ic - p.ring * (int)__umulhi((unsigned)ic, p.magic_ring) : ic % p.ring) * row_words;
+                    const int so = my_ioff ? so_c : so_a;
+#ifndef FUSED_EXP_NO_ATOMICS
+                    if (ib + my_ioff <= ihi) {
+#pragma unroll
+                        for (int b = 0; b < NBX; ++b) {
+                            const unsigned code = (pc[u][b] >> my_sh) & 0xffffu;
+                            const unsigned inc = 1u << (16 * (code & 1));
+                            unsigned int *dst = lds_hist + so + jo[b] + (code >> 1);
+                            for (int jj = 0; jj < nj[b]; ++jj) atomicAdd(dst + jj * words, inc);
+                        }
                     }
+#else
+                    if (pc[u][0] == 0x12345u + (unsigned)so) lds_hist[0] = pc[u][NBX - 1];
+#endif
                 }
             }
         }
+#ifndef FUSED_EXP_NO_STAGE
         if (t + 1 < n_tiles) stash(tile0 + ((t + 1) & 1) * p.tile_floats, t + 1);
+#endif
         if (txi == tiles_x - 1) {
             // block rows whose last pixel row lies inside the rows swept so far are complete
             const int done = ty0 + rows - p.bh;
@@ -348,7 +431,7 @@ __global__ __launch_bounds__(GROUP_THREADS) void conv_hash_hist_group_kernel(Fus
     const int q = lane >> 4, c = lane & 15;
     int toff[KK];
     float wa[NG][KK];
-    fused_operands<KS, NBX, NG>(p.W, p.L2, q, c, toff, wa);
+    fused_operands<G, NG>(p.W, p.L2, q, c, toff, wa);
 
     const int64_t P = (int64_t)p.h * p.w;
     const float *src = p.in + n * P;
@@ -374,14 +457,14 @@ __global__ __launch_bounds__(GROUP_THREADS) void conv_hash_hist_group_kernel(Fus
             }
             __syncthreads();
             for (int r = wave; r < rows; r += GROUP_THREADS / 64) {
-                unsigned pc[NBX];
-                fused_row_codes<KS, NBX, NG>(tile + r * PITCH + 2 * c, toff, wa, q, pc);
+                unsigned pc[1][NBX];
+                fused_row_codes<G, NBX, NG, 1, 0>(tile + r * PITCH + 2 * c, toff, wa, q, pc);
                 const int y = ty0 + r;
                 int ilo, ihi;
                 block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
 #pragma unroll
                 for (int b = 0; b < NBX; ++b) {
-                    const unsigned code = (pc[b] >> (16 * my_s)) & 0xffffu;
+                    const unsigned code = (pc[0][b] >> (16 * my_s)) & 0xffffu;
                     const int x = tx0 + b * FUSED_XB + 2 * c + my_s;
                     if (x < x_hi) {
                         int jlo, jhi;
@@ -419,15 +502,22 @@ static int fused_set_lds(ddcca_ctx *ctx, Kernel kernel, bool *done)
     return DDCCA_OK;
 }
 
+// Rows a wavefront of the ring kernel contracts together: two when the registers allow it (one filter
+// group, k <= 7) and the tile has at least 16 rows.
+template <int KS, int NG> constexpr int ring_rows_together() { return NG == 1 && KS <= 7 ? 2 : 1; }
+
 template <int KS, int NBX, int NG>
 static int fused_launch(ddcca_ctx *ctx, FusedParams p, int64_t n, bool ring)
 {
-    static bool ring_attr = false, group_attr = false;
+    static bool ring2_attr = false, ring1_attr = false, group_attr = false;
+    constexpr int RU2 = ring_rows_together<KS, NG>();
+    const bool two = ring && RU2 == 2 && p.th >= 2 * RING_WAVES;
     int rc;
-    if ((rc = ring ? fused_set_lds(ctx, conv_hash_hist_ring_kernel<KS, NBX, NG>, &ring_attr)
-                   : fused_set_lds(ctx, conv_hash_hist_group_kernel<KS, NBX, NG>, &group_attr)))
+    if ((rc = !ring ? fused_set_lds(ctx, conv_hash_hist_group_kernel<KS, NBX, NG>, &group_attr)
+              : two ? fused_set_lds(ctx, conv_hash_hist_ring_kernel<KS, NBX, NG, RU2>, &ring2_attr)
+                    : fused_set_lds(ctx, conv_hash_hist_ring_kernel<KS, NBX, NG, 1>, &ring1_attr)))
         return rc;
-    p.tile_floats = FusedGeom<KS, NBX>::tile_floats(ring ? p.th : GROUP_TH);
+    p.tile_floats = ring ? RingGeom<KS, NBX>::tile_floats(p.th) : FusedGeom<KS, NBX>::tile_floats(GROUP_TH);
     const size_t lds = ((size_t)p.hist_words + p.lut_words + (size_t)p.tile_floats * (ring ? 2 : 1)) * 4;
     if (lds > (size_t)FUSED_LDS_BYTES) return fail(ctx, DDCCA_EINVAL, "internal: fused kernel LDS budget exceeded");
     const int64_t per_map = (int64_t)p.col_chunks * (ring ? 1 : p.row_groups);
@@ -438,8 +528,11 @@ static int fused_launch(ddcca_ctx *ctx, FusedParams p, int64_t n, bool ring)
         FusedParams q = p;
         q.in = p.in + n0 * (int64_t)p.h * p.w;
         q.out = reinterpret_cast<char *>(p.out) + (n0 / p.group) * p.group_stride * esz;
-        if (ring)
-            hipLaunchKernelGGL((conv_hash_hist_ring_kernel<KS, NBX, NG>), dim3((unsigned)(nb * per_map)),
+        if (two)
+            hipLaunchKernelGGL((conv_hash_hist_ring_kernel<KS, NBX, NG, RU2>),
+                               dim3((unsigned)(nb * per_map)), dim3(RING_THREADS), lds, ctx->stream, q);
+        else if (ring)
+            hipLaunchKernelGGL((conv_hash_hist_ring_kernel<KS, NBX, NG, 1>), dim3((unsigned)(nb * per_map)),
                                dim3(RING_THREADS), lds, ctx->stream, q);
         else
             hipLaunchKernelGGL((conv_hash_hist_group_kernel<KS, NBX, NG>), dim3((unsigned)(nb * per_map)),
@@ -496,7 +589,7 @@ static int fused_plan(ddcca_ctx *ctx, FusedParams &p, int64_t n)
         const int cols = (p.nbx + chunks - 1) / chunks;
         if ((p.nbx + cols - 1) / cols != chunks) continue;            // same chunk count as a smaller one
         const int nbt = fused_tile_blocks((cols - 1) * p.sx + p.bw);
-        const int pitch = (nbt * FUSED_XB + KS) | 1;
+        const int pitch = (nbt * FUSED_XB + KS + 6) / 4 * 4;          // RingGeom<KS, nbt>::PITCH
         for (int th = RING_TH_MAX; th >= 8; th /= 2) {
             const int ring = fused_live_rows(th, p.bh, p.sy, p.nby);
             const int64_t need = (int64_t)ring * cols * hist_bytes + fixed + 2 * (int64_t)(th + KS - 1) * pitch * 4;
