@@ -328,6 +328,7 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
     int next_flush = 0;                           // first block row not yet written out
     int cur_txi = -1;
     int jo[NBX], nj[NBX];                         // this lane's pixel column per block: first block column (word offset), count
+    unsigned brk = 0u;                            // bit b: the lane to the left (c - 1) has another block-column set, or c == 0
     const int my_sh = 16 * my_s;
     for (int t = 0; t < n_tiles; ++t) {
         __syncthreads();                          // tile t is in LDS; cleared slots are visible
@@ -349,6 +350,13 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
                 jo[b] = (jlo - j0) * words;
                 nj[b] = jhi - jlo + 1;
             }
+            brk = 0u;
+#pragma unroll
+            for (int b = 0; b < NBX; ++b) {
+                const int pj = __builtin_amdgcn_update_dpp(-1, jo[b], 0x111, 0xf, 0xf, false);   // row_shr:1
+                const int pn = __builtin_amdgcn_update_dpp(-1, nj[b], 0x111, 0xf, 0xf, false);
+                if (c == 0 || pj != jo[b] || pn != nj[b]) brk |= 1u << b;
+            }
         }
         for (int r0 = wave; r0 < rows; r0 += RU * RING_WAVES) {
             unsigned pc[RU][NBX];
@@ -360,6 +368,21 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
                 int ilo, ihi;
                 block_range(ty0 + r, p.bh, p.sy, p.magic_sy, 0, p.nby, ilo, ihi);
                 // 64 lanes, 32 pixels: lane (q,c) takes pixel x0 + 2c + (q&1) and the block rows ilo + (q>>1), +2, ...
+                // Neighbouring pixels mostly share their code, and equal codes going to the same word would
+                // serialise in LDS: a run of lanes (within a 16-lane group) with equal code and equal block
+                // columns is added once, by its first lane, with the run length.
+                unsigned word[NBX], inc[NBX];
+#pragma unroll
+                for (int b = 0; b < NBX; ++b) {
+                    const unsigned code = (pc[u][b] >> my_sh) & 0xffffu;
+                    const unsigned prev = (unsigned)__builtin_amdgcn_update_dpp(-1, (int)code, 0x111, 0xf, 0xf, false);
+                    const bool head = ((brk >> b) & 1u) != 0u || prev != code;
+                    const unsigned long long heads = __ballot(head);
+                    const unsigned grp = (unsigned)(heads >> (lane & 48)) & 0xffffu;     // this 16-lane group's heads
+                    const unsigned len = (unsigned)__ffs((int)((grp | 0x10000u) >> (c + 1)));   // lanes up to the next head
+                    word[b] = code >> 1;
+                    inc[b] = head ? len << (16 * (code & 1)) : 0u;
+                }
                 for (int ib = ilo; ib <= ihi; ib += 2) {
                     const int ic = min(ib + 1, ihi);
                     const int so_a = (p.magic_ring ? ib - p.ring * (int)__umulhi((unsigned)ib, p.magic_ring) : ib % p.ring) * row_words;
@@ -369,14 +392,13 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
                     if (ib + my_ioff <= ihi) {
 #pragma unroll
                         for (int b = 0; b < NBX; ++b) {
-                            const unsigned code = (pc[u][b] >> my_sh) & 0xffffu;
-                            const unsigned inc = 1u << (16 * (code & 1));
-                            unsigned int *dst = lds_hist + so + jo[b] + (code >> 1);
-                            for (int jj = 0; jj < nj[b]; ++jj) atomicAdd(dst + jj * words, inc);
+                            if (inc[b] == 0u) continue;
+                            unsigned int *dst = lds_hist + so + jo[b] + word[b];
+                            for (int jj = 0; jj < nj[b]; ++jj) atomicAdd(dst + jj * words, inc[b]);
                         }
                     }
 #else
-                    if (pc[u][0] == 0x12345u + (unsigned)so) lds_hist[0] = pc[u][NBX - 1];
+                    if (inc[0] == 0x12345u + (unsigned)so) lds_hist[0] = word[NBX - 1];
 #endif
                 }
             }
