@@ -31,7 +31,11 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int FUSED_XB = 32;              // pixels per MFMA column block (16 columns x 2 shifts)
 constexpr int FUSED_MAX_NBX = 4;
+#ifndef FUSED_EXP_LDS_BYTES
 constexpr int FUSED_LDS_BYTES = 80 * 1024;   // per workgroup: two workgroups share a compute unit's 160 KB
+#else
+constexpr int FUSED_LDS_BYTES = FUSED_EXP_LDS_BYTES;
+#endif
 #ifndef FUSED_EXP_RING_THREADS
 constexpr int RING_THREADS = 512;
 #else
@@ -107,10 +111,12 @@ __device__ __forceinline__ void fused_operands(const float *W, int L2, int q, in
         const int dy = tap / G::KW, dx = tap - dy * G::KW;
         toff[kk] = tap < G::TAPS ? dy * G::PITCH + dx : 0;
     }
-    // A operand: row (g,s) = lane%16, tap 4*kk + lane/16, for every group of 8 filters
+    // A operand: row = lane%16 = 8*s + g (x-shift s, filter g of the group), tap 4*kk + lane/16, for every
+    // group of 8 filters.  (The stand-alone convolution orders its rows (g,s); every output element is the
+    // same dot product in the same order of taps either way.)
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
-        const int g = 8 * gi + (c >> 1), s = c & 1;
+        const int g = 8 * gi + (c & 7), s = c >> 3;
 #pragma unroll
         for (int kk = 0; kk < G::KK; ++kk) {
             const int tap = 4 * kk + q;
@@ -123,25 +129,21 @@ __device__ __forceinline__ void fused_operands(const float *W, int L2, int q, in
 }
 
 // RU tile rows (RSTRIDE floats apart in LDS): the L2 map values of 32*NBX pixels per row on the matrix
-// unit, then their hash codes.  Returns per row and column block the codes of the pixel pair
-// (x0 + 2c, x0 + 2c + 1) in the low / high half of pc[u][b], identical in all four 16-lane groups.
+// unit, then their hash codes.  Lane (q,c) receives, per row and column block, the code of pixel
+// x0 + 2c + (q >> 1) (lanes q and q^1 hold the same value).
 template <class G, int NBX, int NG, int RU, int RSTRIDE>
 __device__ __forceinline__ void fused_row_codes(const float *prow, const int (&toff)[G::KK],
-                                                const float (&wa)[NG][G::KK], int q, unsigned (&pc)[RU][NBX])
+                                                const float (&wa)[NG][G::KK], int q, unsigned (&code)[RU][NBX])
 {
 #pragma unroll
     for (int u = 0; u < RU; ++u)
 #pragma unroll
-        for (int b = 0; b < NBX; ++b) pc[u][b] = 0u;
-    // lane (q,c): acc[0], acc[1] = filter 8gi+2q at pixels x, x+1; acc[2], acc[3] = filter 8gi+2q+1
-    const unsigned m0 = 1u << (2 * q), m1 = m0 << 1, m16 = m0 << 16, m17 = m0 << 17;
+        for (int b = 0; b < NBX; ++b) code[u][b] = 0u;
+    // output rows 4q..4q+3 of a lane: x-shift q>>1, filters 8gi + 4(q&1) + 0..3
+    const unsigned m0 = 1u << (4 * (q & 1)), m1 = m0 << 1, m2 = m0 << 2, m3 = m0 << 3;
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
         floatx4 acc[RU][NBX];
-#pragma unroll
-        for (int u = 0; u < RU; ++u)
-#pragma unroll
-            for (int b = 0; b < NBX; ++b) acc[u][b] = floatx4{0.f, 0.f, 0.f, 0.f};
 #ifdef FUSED_EXP_NO_MFMA
 #pragma unroll
         for (int u = 0; u < RU; ++u)
@@ -156,28 +158,23 @@ __device__ __forceinline__ void fused_row_codes(const float *prow, const int (&t
             for (int u = 0; u < RU; ++u)
 #pragma unroll
                 for (int b = 0; b < NBX; ++b)
-                    acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[gi][kk], pk[u * RSTRIDE + b * FUSED_XB], acc[u][b],
-                                                                     0, 0, 0);
+                    acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[gi][kk], pk[u * RSTRIDE + b * FUSED_XB],
+                                                                     kk == 0 ? floatx4{0.f, 0.f, 0.f, 0.f} : acc[u][b], 0, 0, 0);
         }
 #endif
 #pragma unroll
         for (int u = 0; u < RU; ++u)
 #pragma unroll
             for (int b = 0; b < NBX; ++b) {
-                const unsigned bits = (acc[u][b][0] > 0.0f ? m0 : 0u) | (acc[u][b][2] > 0.0f ? m1 : 0u) |
-                                      (acc[u][b][1] > 0.0f ? m16 : 0u) | (acc[u][b][3] > 0.0f ? m17 : 0u);
-                pc[u][b] |= bits << (8 * gi);
+                const unsigned bits = (acc[u][b][0] > 0.0f ? m0 : 0u) | (acc[u][b][1] > 0.0f ? m1 : 0u) |
+                                      (acc[u][b][2] > 0.0f ? m2 : 0u) | (acc[u][b][3] > 0.0f ? m3 : 0u);
+                code[u][b] |= bits << (8 * gi);
             }
     }
 #pragma unroll
     for (int u = 0; u < RU; ++u)
 #pragma unroll
-        for (int b = 0; b < NBX; ++b) {
-            unsigned v = pc[u][b];
-            v |= (unsigned)__shfl_xor((int)v, 16);
-            v |= (unsigned)__shfl_xor((int)v, 32);
-            pc[u][b] = v;
-        }
+        for (int b = 0; b < NBX; ++b) code[u][b] |= (unsigned)__shfl_xor((int)code[u][b], 16);
 }
 
 // Convert `n_words` packed histogram words at `sp` (LDS) to the output element type at `dst`
@@ -244,7 +241,6 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
 {
     typedef RingGeom<KS, NBX> G;
     constexpr int R = G::R, KK = G::KK, TW = G::TW, PITCH = G::PITCH, V4 = G::V4;
-    constexpr int NPRE = ((RING_TH_MAX + 2 * R) * V4 + RING_THREADS - 1) / RING_THREADS;
     extern __shared__ unsigned int lds[];
     unsigned int *lds_hist = lds;
     float *lds_lut = reinterpret_cast<float *>(lds + p.hist_words);
@@ -273,7 +269,7 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
     const bool vec4 = (p.w & 3) == 0 && (((uintptr_t)src) & 15) == 0;
     const int y_hi = (p.nby - 1) * p.sy + p.bh;                      // pixel rows [0, y_hi)
     const int x_lo = j0 * p.sx, x_hi = (j1 - 1) * p.sx + p.bw;       // pixel columns [x_lo, x_hi)
-    const int my_s = q & 1, my_ioff = q >> 1;                        // this lane's pixel of a pair / block-row parity
+    const int my_s = q >> 1, my_ioff = q & 1;                        // this lane's pixel of a pair / block-row parity
     const int tiles_x = (x_hi - x_lo + TW - 1) / TW;
     const int tiles_y = (y_hi + p.th - 1) / p.th;
     const int n_tiles = tiles_x * tiles_y;
@@ -285,28 +281,32 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
     const bool aligned = ((((uintptr_t)out_map) | (uintptr_t)((int64_t)p.nbx * bins * esz) | (uintptr_t)((int64_t)j0 * bins * esz)) & 15) == 0;
 
     // tile t: rows [ty0 - R, ty0 + rows + R), columns [gxa, gxa + PITCH), gxa = the multiple of 4 at or
-    // below the first halo column
+    // below the first halo column.  A thread always moves the same 16-byte column of RPP rows per pass.
+    constexpr int RPP = RING_THREADS / V4;        // tile rows per pass of the workgroup
+    constexpr int NPRE = (RING_TH_MAX + 2 * R + RPP - 1) / RPP;
+    const int st_xv = threadIdx.x % V4, st_yy = threadIdx.x / V4;    // st_yy >= RPP: no part in staging
     float4 pre[NPRE];
     auto fetch = [&](int t) {
         const int tyi = t / tiles_x, txi = t - tyi * tiles_x;
         const int ty0 = tyi * p.th, rows = min(p.th, y_hi - ty0);
-        const int gy0 = ty0 - R, gxa = (x_lo + txi * TW - R) & ~3;
-        const int n_el = (rows + 2 * R) * V4;
+        const int gy0 = ty0 - R + st_yy;
+        const int gx = ((x_lo + txi * TW - R) & ~3) + 4 * st_xv;
+        const int n_rows = st_yy < RPP ? rows + 2 * R - st_yy : 0;   // tile rows at and below this thread's first
+        const bool whole = vec4 && gx >= 0 && gx + 3 < p.w;
+        const float *col = src + gx;
 #pragma unroll
         for (int u = 0; u < NPRE; ++u) {
-            const int e = threadIdx.x + u * RING_THREADS;
-            const int yy = e / V4, xv = e - yy * V4;
-            const int gy = gy0 + yy, gx = gxa + 4 * xv;
+            const int gy = gy0 + u * RPP;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (e < n_el && gy >= 0 && gy < p.h) {
-                const float *row = src + (int64_t)gy * p.w;
-                if (vec4 && gx >= 0 && gx + 3 < p.w) {
-                    v = *reinterpret_cast<const float4 *>(row + gx);
+            if (u * RPP < n_rows && gy >= 0 && gy < p.h) {
+                const float *row = col + (int64_t)gy * p.w;
+                if (whole) {
+                    v = *reinterpret_cast<const float4 *>(row);
                 } else {
-                    if (gx >= 0 && gx < p.w) v.x = row[gx];
-                    if (gx + 1 >= 0 && gx + 1 < p.w) v.y = row[gx + 1];
-                    if (gx + 2 >= 0 && gx + 2 < p.w) v.z = row[gx + 2];
-                    if (gx + 3 >= 0 && gx + 3 < p.w) v.w = row[gx + 3];
+                    if (gx >= 0 && gx < p.w) v.x = row[0];
+                    if (gx + 1 >= 0 && gx + 1 < p.w) v.y = row[1];
+                    if (gx + 2 >= 0 && gx + 2 < p.w) v.z = row[2];
+                    if (gx + 3 >= 0 && gx + 3 < p.w) v.w = row[3];
                 }
             }
             pre[u] = v;
@@ -315,12 +315,11 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
     auto stash = [&](float *tile, int t) {
         const int tyi = t / tiles_x;
         const int rows = min(p.th, y_hi - tyi * p.th);
-        const int n_el = (rows + 2 * R) * V4;
+        const int n_rows = st_yy < RPP ? rows + 2 * R - st_yy : 0;
+        float *dst = tile + st_yy * PITCH + 4 * st_xv;
 #pragma unroll
-        for (int u = 0; u < NPRE; ++u) {
-            const int e = threadIdx.x + u * RING_THREADS;
-            if (e < n_el) *reinterpret_cast<float4 *>(tile + 4 * e) = pre[u];   // row yy, vector xv: 4 * (yy * V4 + xv)
-        }
+        for (int u = 0; u < NPRE; ++u)
+            if (u * RPP < n_rows) *reinterpret_cast<float4 *>(dst + u * RPP * PITCH) = pre[u];
     };
 
     fetch(0);
@@ -329,7 +328,6 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
     int cur_txi = -1;
     int jo[NBX], nj[NBX];                         // this lane's pixel column per block: first block column (word offset), count
     unsigned brk = 0u;                            // bit b: the lane to the left (c - 1) has another block-column set, or c == 0
-    const int my_sh = 16 * my_s;
     for (int t = 0; t < n_tiles; ++t) {
         __syncthreads();                          // tile t is in LDS; cleared slots are visible
         const float *tile = tile0 + (t & 1) * p.tile_floats;
@@ -359,8 +357,8 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
             }
         }
         for (int r0 = wave; r0 < rows; r0 += RU * RING_WAVES) {
-            unsigned pc[RU][NBX];
-            fused_row_codes<G, NBX, NG, RU, RING_WAVES * PITCH>(tile + r0 * PITCH + shx + 2 * c, toff, wa, q, pc);
+            unsigned codes[RU][NBX];
+            fused_row_codes<G, NBX, NG, RU, RING_WAVES * PITCH>(tile + r0 * PITCH + shx + 2 * c, toff, wa, q, codes);
 #pragma unroll
             for (int u = 0; u < RU; ++u) {
                 const int r = r0 + u * RING_WAVES;
@@ -374,7 +372,7 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
                 unsigned word[NBX], inc[NBX];
 #pragma unroll
                 for (int b = 0; b < NBX; ++b) {
-                    const unsigned code = (pc[u][b] >> my_sh) & 0xffffu;
+                    const unsigned code = codes[u][b];
                     const unsigned prev = (unsigned)__builtin_amdgcn_update_dpp(-1, (int)code, 0x111, 0xf, 0xf, false);
                     const bool head = ((brk >> b) & 1u) != 0u || prev != code;
                     const unsigned long long heads = __ballot(head);
@@ -459,7 +457,7 @@ __global__ __launch_bounds__(GROUP_THREADS) void conv_hash_hist_group_kernel(Fus
     const float *src = p.in + n * P;
     const int y_lo = i0 * p.sy, y_hi = (i1 - 1) * p.sy + p.bh;       // pixel rows [y_lo, y_hi)
     const int x_lo = j0 * p.sx, x_hi = (j1 - 1) * p.sx + p.bw;       // pixel columns [x_lo, x_hi)
-    const int my_s = q & 1, my_ioff = q >> 1;
+    const int my_s = q >> 1, my_ioff = q & 1;
 
     for (int ty0 = y_lo; ty0 < y_hi; ty0 += GROUP_TH) {
         const int rows = min(GROUP_TH, y_hi - ty0);
@@ -479,14 +477,14 @@ __global__ __launch_bounds__(GROUP_THREADS) void conv_hash_hist_group_kernel(Fus
             }
             __syncthreads();
             for (int r = wave; r < rows; r += GROUP_THREADS / 64) {
-                unsigned pc[1][NBX];
-                fused_row_codes<G, NBX, NG, 1, 0>(tile + r * PITCH + 2 * c, toff, wa, q, pc);
+                unsigned codes[1][NBX];
+                fused_row_codes<G, NBX, NG, 1, 0>(tile + r * PITCH + 2 * c, toff, wa, q, codes);
                 const int y = ty0 + r;
                 int ilo, ihi;
                 block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
 #pragma unroll
                 for (int b = 0; b < NBX; ++b) {
-                    const unsigned code = (pc[0][b] >> (16 * my_s)) & 0xffffu;
+                    const unsigned code = codes[0][b];
                     const int x = tx0 + b * FUSED_XB + 2 * c + my_s;
                     if (x < x_hi) {
                         int jlo, jhi;
