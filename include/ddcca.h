@@ -157,6 +157,20 @@ int ddcca_apply_stage_hash(ddcca_ctx *ctx, const float *in, int64_t n, int h, in
 int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h,
                                  int w, const ddcca_model *model, int feat_type, void *feat);
 
+/* ---- options ---------------------------------------------------------------------------
+ * DDCCA_OPT_CONV_ARITH selects the arithmetic of the stage convolution (Eq. 6), in
+ * ddcca_apply_stage, ddcca_extract_*features* and the fused last stage alike:
+ *   DDCCA_CONV_FP32   (default) fp32 products and sums on the fp32 matrix instructions;
+ *   DDCCA_CONV_BF16X3 every fp32 operand split exactly into three bf16 pieces and the six
+ *                     significant piece products summed in fp32 on the bf16 matrix pipeline:
+ *                     the accuracy of an fp32 dot product (the dropped products are below
+ *                     2^-24 relative), another rounding order, several times the rate.
+ * Returns DDCCA_EINVAL for an unknown option or value. */
+#define DDCCA_OPT_CONV_ARITH 1
+#define DDCCA_CONV_FP32      0
+#define DDCCA_CONV_BF16X3    1
+int ddcca_set_option(ddcca_ctx *ctx, int option, int value);
+
 /* ---- per-kernel timing (HIP events on the context's stream) -------------------------- */
 enum {
     DDCCA_K_GRAM = 0,     /* patch-Gram accumulation over the input maps (all tiles) */

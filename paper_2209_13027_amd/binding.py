@@ -24,10 +24,12 @@ EXPORTS = [
     "ddcca_corr_begin", "ddcca_corr_accumulate", "ddcca_corr_export", "ddcca_solve_filters",
     "ddcca_dcca_solve", "ddcca_learn_stage_filters", "ddcca_apply_stage", "ddcca_hash_histogram",
     "ddcca_extract_features", "ddcca_hash_iq", "ddcca_extract_iq_features",
-    "ddcca_apply_stage_hash", "ddcca_extract_features_fused",
+    "ddcca_apply_stage_hash", "ddcca_extract_features_fused", "ddcca_set_option",
     "ddcca_profile_enable", "ddcca_profile_read", "ddcca_profile_reset",
 ]
 FEAT_COUNT_U16, FEAT_IQ_F32, FEAT_IQ_F16 = 0, 1, 2
+OPT_CONV_ARITH = 1
+CONV_FP32, CONV_BF16X3 = 0, 1
 FEAT_TYPES = {torch.uint16: FEAT_COUNT_U16, torch.float32: FEAT_IQ_F32, torch.float16: FEAT_IQ_F16}
 
 
@@ -78,6 +80,7 @@ def lib() -> ctypes.CDLL:
         l.ddcca_extract_iq_features.argtypes = [vp, vp, vp, i64, i, i, ctypes.POINTER(_Model), i, vp]
         l.ddcca_apply_stage_hash.argtypes = [vp, vp, i64, i, i, vp, i, i, i, i, i, i, i, vp]
         l.ddcca_extract_features_fused.argtypes = [vp, vp, vp, i64, i, i, ctypes.POINTER(_Model), i, vp]
+        l.ddcca_set_option.argtypes = [vp, i, i]
         l.ddcca_profile_enable.argtypes = [vp, i]
         l.ddcca_profile_read.argtypes = [vp, i, ctypes.POINTER(d), ctypes.POINTER(i64)]
         l.ddcca_profile_reset.argtypes = [vp]
@@ -272,6 +275,9 @@ class Context:
                                                         _ptr(v2, torch.float32, "v2"), m, h, w, ctypes.byref(model),
                                                         FEAT_TYPES[dtype], _ptr(out, dtype, "feat")))
         return out
+
+    def set_option(self, option: int, value: int):
+        self._check(lib().ddcca_set_option(self._h, option, value))
 
     # ---- profiling -------------------------------------------------------------------
     def profile_enable(self, on: bool):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libddcca.so")
 SOURCES = ["api.hip", "patch_gram.hip", "class_sum.hip", "dcca_solve.hip", "conv_multi.hip", "hash_hist.hip",
-           "conv_hash_hist.hip"]
+           "conv_hash_hist.hip", "conv_split.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall",
     # hipcc must not form packed fp32 instructions on this target
@@ -34,7 +34,7 @@ def build_library(extra_flags=(), verbose: bool = False) -> str:
     build_dir = os.path.join(HERE, "_build")
     os.makedirs(build_dir, exist_ok=True)
     objs = [os.path.join(build_dir, s.replace(".hip", ".o")) for s in SOURCES]
-    with concurrent.futures.ThreadPoolExecutor(max_workers=min(7, os.cpu_count() or 1)) as ex:
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         futs = [ex.submit(_compile, s, o, list(extra_flags)) for s, o in zip(SOURCES, objs)]
         for f in futs:
             f.result()

@@ -302,6 +302,25 @@ int ddcca_learn_stage_filters(ddcca_ctx *ctx, const float *v1, const float *v2, 
     return ddcca_solve_filters(ctx, L, ridge, W1, W2, rho);
 }
 
+static int run_conv(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L, float *out)
+{
+    return ctx->conv_arith == DDCCA_CONV_BF16X3 ? launch_conv_split(ctx, in, n, h, w, W, k, L, out)
+                                                : launch_conv(ctx, in, n, h, w, W, k, L, out);
+}
+
+int ddcca_set_option(ddcca_ctx *ctx, int option, int value)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    switch (option) {
+        case DDCCA_OPT_CONV_ARITH:
+            if (value != DDCCA_CONV_FP32 && value != DDCCA_CONV_BF16X3)
+                return fail(ctx, DDCCA_EINVAL, "unknown convolution arithmetic");
+            ctx->conv_arith = value;
+            return DDCCA_OK;
+        default: return fail(ctx, DDCCA_EINVAL, "unknown option");
+    }
+}
+
 int ddcca_apply_stage(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L,
                       float *out)
 {
@@ -312,7 +331,7 @@ int ddcca_apply_stage(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, 
     if (n == 0) return DDCCA_OK;
     if (!in || !W || !out) return fail(ctx, DDCCA_EINVAL, "null data pointer");
     if ((rc = device_ready(ctx))) return rc;
-    return launch_conv(ctx, in, n, h, w, W, k, L, out);
+    return run_conv(ctx, in, n, h, w, W, k, L, out);
 }
 
 static int check_hist_args(ddcca_ctx *ctx, int64_t n, int L2, int h, int w, int bh, int bw, int sy, int sx)
@@ -403,8 +422,8 @@ static int extract_impl(ddcca_ctx *ctx, const float *v1, const float *v2, int64_
     for (int64_t m0 = 0; m0 < m; m0 += batch) {
         const int64_t mb = std::min(batch, m - m0);
         for (int d = 0; d < 2; ++d) {
-            if ((rc = launch_conv(ctx, views[d] + m0 * P, mb, h, w, model->W[0][d], k, L1, y))) return rc;
-            if (!fused && (rc = launch_conv(ctx, y, mb * L1, h, w, model->W[1][d], k, L2, z))) return rc;
+            if ((rc = run_conv(ctx, views[d] + m0 * P, mb, h, w, model->W[0][d], k, L1, y))) return rc;
+            if (!fused && (rc = run_conv(ctx, y, mb * L1, h, w, model->W[1][d], k, L2, z))) return rc;
             void *dst = reinterpret_cast<char *>(feat) + ((m0 * 2 + d) * L1) * A * bins * feat_elem_size(feat_type);
             if (fused)
                 rc = launch_conv_hash_hist(ctx, y, mb * L1, h, w, model->W[1][d], k, L2, model->block_h,

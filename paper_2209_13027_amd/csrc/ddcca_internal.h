@@ -52,6 +52,8 @@ struct ddcca_ctx {
     int64_t iq_lut_total = 0;               // block area + bins the table was built for (0 = none)
     int iq_lut_n = 0;
 
+    int conv_arith = DDCCA_CONV_FP32;       // DDCCA_OPT_CONV_ARITH
+
     // ---- profiling
     bool prof = false;
     ddcca::ProfSlot prof_slot[DDCCA_K_COUNT];
@@ -105,6 +107,9 @@ int launch_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const dou
                  int k, int L, double ridge, float *W1, float *W2, double *rho);
 int launch_conv(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L,
                 float *out);
+// the same with three-piece bf16 operands (DDCCA_CONV_BF16X3)
+int launch_conv_split(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L,
+                      float *out);
 // output for map n goes to element (n / group) * group_stride + (n % group) * A * bins of `out`,
 // whose element type out_type (DDCCA_FEAT_*) selects
 int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int bh, int bw,
