@@ -93,6 +93,9 @@ def main():
     ap.add_argument("--fused", action="store_true",
                     help="time the path with the second stage convolution fused into the output layer (the "
                          "stage-2 maps are never written); the default materialises them")
+    ap.add_argument("--conv", default="fp32", choices=["fp32", "bf16x3"],
+                    help="arithmetic of the stage convolution: fp32 matrix instructions (the headline path) or "
+                         "three-piece bf16 operands on the bf16 matrix pipeline (same accuracy)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=0, help="images in the CPU-oracle sample (0 = default)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -116,6 +119,9 @@ def main():
     v1, v2, cls = make_views(wl)
     M = int(v1.shape[0])
     ctx = Context(0)
+    if args.conv == "bf16x3":
+        from paper_2209_13027_amd.binding import OPT_CONV_ARITH, CONV_BF16X3
+        ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
     d1, d2, dc = torch.from_numpy(v1).cuda(), torch.from_numpy(v2).cuda(), torch.from_numpy(cls).cuda()
     by, bx = wl.blocks
     feat_dtype = {"counts": torch.uint16, "iq_f32": torch.float32, "iq_f16": torch.float16}[args.features]
@@ -243,7 +249,7 @@ def main():
         "config": {"workload": wl.name, "images": M, "classes": wl.n_classes, "h": wl.h, "w": wl.w, "k": wl.k,
                    "L1": wl.L1, "L2": wl.L2, "block": wl.block, "stride": wl.stride, "bins": 1 << wl.L2,
                    "feature_len": wl.feature_len, "features": args.features,
-                   "fused_last_stage": bool(args.fused)},
+                   "fused_last_stage": bool(args.fused), "conv_arithmetic": args.conv},
         "roofline": {"bound": "mfma", "kernel": "patch_gram_kernel (all-tiles variant: the Gram over the input maps)", "achieved": gram_tflops,
                      "peak": PEAK_MFMA_FP32_TFLOPS, "unit": "TFLOP/s", "frac": gram_tflops / PEAK_MFMA_FP32_TFLOPS,
                      "traffic": measured_traffic(wl.name, "patch_gram_kernel", ", false,"), "avg_launch_ms": gram_ms,

@@ -158,8 +158,10 @@ int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v
                                  int w, const ddcca_model *model, int feat_type, void *feat);
 
 /* ---- options ---------------------------------------------------------------------------
- * DDCCA_OPT_CONV_ARITH selects the arithmetic of the stage convolution (Eq. 6), in
- * ddcca_apply_stage, ddcca_extract_*features* and the fused last stage alike:
+ * DDCCA_OPT_CONV_ARITH selects the arithmetic of the stage convolution (Eq. 6) in
+ * ddcca_apply_stage and in both stages of ddcca_extract_features / ddcca_extract_iq_features
+ * (the fused last stage always uses the fp32 instructions: it is bound by its vector
+ * work, not by the matrix unit):
  *   DDCCA_CONV_FP32   (default) fp32 products and sums on the fp32 matrix instructions;
  *   DDCCA_CONV_BF16X3 every fp32 operand split exactly into three bf16 pieces and the six
  *                     significant piece products summed in fp32 on the bf16 matrix pipeline:

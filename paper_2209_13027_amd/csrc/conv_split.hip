@@ -63,7 +63,7 @@ __global__ __launch_bounds__(CSPLIT_THREADS) void conv_split_kernel(const float 
             }
         }
     }
-    int toff[STEPS];
+    int toff[STEPS][4];
     split_offsets<G>(q, toff);
     SplitOperand wa[STEPS][3];
     split_weights<G, KS, true>(W, L, 0, q, c, wa);
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(CSPLIT_THREADS) void conv_split_kernel(const float 
         const int ga = g0 + 2 * q;
         for (int r = wave; r < rows; r += 4) {
             floatx4 acc[1][NBX];
-            split_rows<G, NBX, 1, 0>(lane_base + r * G::PWORDS, toff, wa, acc);
+            split_rows<G, NBX, 1>(lane_base + r * G::PWORDS, 0, G::PLANE, toff, wa, acc);
             const int gy = ty * CSPLIT_TH + r;
             float *dst = out + (n * L + ga) * P + (int64_t)gy * w + gx_lane;
             if (fast) {

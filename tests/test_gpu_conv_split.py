@@ -69,3 +69,23 @@ def test_unknown_option_is_rejected(ctx):
         ctx.set_option(OPT_CONV_ARITH, 7)
     with pytest.raises(DdccaError):
         ctx.set_option(99, 0)
+
+
+def test_end_to_end_tiny_bf16x3(ctx, oracle):
+    """Whole path with the three-piece convolution in both stages: the end-to-end histogram bar."""
+    from paper_2209_13027_amd.workloads import WORKLOADS, make_views
+    from paper_2209_13027_amd import pipeline
+    wl = WORKLOADS["tiny"]
+    v1, v2, cls = make_views(wl)
+    d1, d2, dc = dev(v1), dev(v2), dev(cls)
+    model = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
+    feat = pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride, 16)
+    ref = oracle.two_stage(v1, v2, cls, wl.n_classes, wl.k, wl.L1, wl.L2, wl.block, wl.stride)
+    got = feat.cpu().numpy().astype(np.int64)
+    assert np.abs(got - ref["hist"]).sum() / ref["hist"].sum() <= 1e-3
+    for s in (0, 1):
+        for d in (0, 1):
+            W = model["filters"][2 * s + d].cpu().numpy().reshape(-1, wl.k * wl.k)
+            F = ref["stage%d" % (s + 1)]["F%d" % (d + 1)].reshape(-1, wl.k * wl.k)
+            cos = np.sum(W * F, axis=1) / (np.linalg.norm(W, axis=1) * np.linalg.norm(F, axis=1))
+            assert cos.min() >= 0.9999
