@@ -199,6 +199,20 @@ def main():
         phases["extract_fused"]["conv_hash_hist_ms"] = pf["ms"] / args.steps
         phases["extract_fused"]["e2e_images_per_s"] = M / ((phases["learn"]["ms_mean"]
                                                             + phases["extract_fused"]["ms_mean"]) * 1e-3)
+    conv_split = None
+    if args.conv == "fp32" and not args.fused:
+        # the same extraction with the three-piece bf16 convolution (same accuracy), for comparison
+        from paper_2209_13027_amd.binding import OPT_CONV_ARITH, CONV_BF16X3, CONV_FP32
+        ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
+        run = lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride,
+                                       batch, out=feat, dtype=feat_dtype)
+        run()
+        ctx.profile_reset()
+        ctx.profile_enable(True)
+        phases["extract_conv_bf16x3"] = timed(run)
+        ctx.profile_enable(False)
+        conv_split = ctx.profile_read()["conv"]["ms"] / args.steps
+        ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
     ctx.status()
 
     work = algorithmic_work(wl, M, feat.element_size())
@@ -231,6 +245,11 @@ def main():
                       "gbs": work["hist_bytes"] / (hist_ms * 1e-3) / 1e9 if hist_ms > 0 else 0.0,
                       "frac_hbm": work["hist_bytes"] / (hist_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if hist_ms > 0 else 0.0},
     }
+    if conv_split:
+        # extraction only: stage 1 once per view plus stage 2
+        xbytes = 2 * M * P * (4 + 4 * L1v) + 2 * M * L1v * P * (4 + 4 * wl.L2)
+        kernels["conv_bf16x3_extract"] = {"ms_per_extract": conv_split, "gbs": xbytes / (conv_split * 1e-3) / 1e9,
+                                          "frac_hbm": xbytes / (conv_split * 1e-3) / 1e9 / PEAK_HBM_GBS}
     if fused_ms > 0:
         # stage-2 conv bytes and flops move from "conv" into the fused kernel
         s1_bytes = 2 * (2 * M * P * (4 + 4 * L1v))
