@@ -167,10 +167,16 @@ int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v
  *                     significant piece products summed in fp32 on the bf16 matrix pipeline:
  *                     the accuracy of an fp32 dot product (the dropped products are below
  *                     2^-24 relative), another rounding order, several times the rate.
+ * DDCCA_OPT_GRAM_ARITH selects the arithmetic of the patch-Gram accumulation (Section II-A
+ * matrices) in the same way: DDCCA_GRAM_FP32 (default) or DDCCA_GRAM_BF16X3.  Accumulation
+ * across tiles stays fp64 and the result does not depend on the batch split in either.
  * Returns DDCCA_EINVAL for an unknown option or value. */
 #define DDCCA_OPT_CONV_ARITH 1
 #define DDCCA_CONV_FP32      0
 #define DDCCA_CONV_BF16X3    1
+#define DDCCA_OPT_GRAM_ARITH 2
+#define DDCCA_GRAM_FP32      0
+#define DDCCA_GRAM_BF16X3    1
 int ddcca_set_option(ddcca_ctx *ctx, int option, int value);
 
 /* ---- per-kernel timing (HIP events on the context's stream) -------------------------- */

@@ -317,6 +317,12 @@ int ddcca_set_option(ddcca_ctx *ctx, int option, int value)
                 return fail(ctx, DDCCA_EINVAL, "unknown convolution arithmetic");
             ctx->conv_arith = value;
             return DDCCA_OK;
+        case DDCCA_OPT_GRAM_ARITH:
+            if (value != DDCCA_GRAM_FP32 && value != DDCCA_GRAM_BF16X3)
+                return fail(ctx, DDCCA_EINVAL, "unknown Gram arithmetic");
+            if (ctx->corr_active) return fail(ctx, DDCCA_ESTATE, "cannot change the Gram arithmetic during an accumulation");
+            ctx->gram_arith = value;
+            return DDCCA_OK;
         default: return fail(ctx, DDCCA_EINVAL, "unknown option");
     }
 }

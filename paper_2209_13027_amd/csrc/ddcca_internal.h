@@ -53,6 +53,7 @@ struct ddcca_ctx {
     int iq_lut_n = 0;
 
     int conv_arith = DDCCA_CONV_FP32;       // DDCCA_OPT_CONV_ARITH
+    int gram_arith = DDCCA_GRAM_FP32;       // DDCCA_OPT_GRAM_ARITH
 
     // ---- profiling
     bool prof = false;

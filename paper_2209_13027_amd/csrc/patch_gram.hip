@@ -17,11 +17,16 @@
 // DC level, which keeps the fp32 accumulators well scaled; on top of that each tile is
 // shifted by an estimate of its mean pixel value (harmless, and it keeps the staged values
 // themselves small).
-#include "ddcca_internal.h"
+//
+// Optional arithmetic (DDCCA_GRAM_BF16X3): the contraction on the bf16 matrix pipeline with every operand
+// y split exactly into three bf16 pieces and the six significant piece products summed in fp32 (see
+// conv_split.h).  K = 32 consecutive patches per instruction; the pieces of a block's operand (8 patches
+// per lane) are made in registers right after the centre subtraction, so tiles, slots, flushes and the
+// export are those of the fp32 kernel.  The bf16 matrix instructions run beside the vector ALU, which the
+// fp32 ones do not, so the splitting work hides behind the matrix work of the other resident wavefront.
+#include "conv_split.h"
 
 namespace ddcca {
-
-typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int GRAM_THREADS = 256;          // 4 wavefronts
 constexpr int GRAM_TH = 16;                // patch rows per tile
@@ -140,6 +145,87 @@ __device__ __forceinline__ void gram_rows(const float *pix, int pitch, int rows,
                 z0[b] = ok ? v : 0.f;
             }
             gram_mfma_step<G, ROLE>(z0, acc);
+        }
+    }
+}
+
+// ---- three-piece bf16 operands --------------------------------------------------------------------------
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ unsigned bf16_pair(float a, float b)
+{
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(floatx2{a, b}, bf16x2));
+}
+
+// The three pieces of the pair (a, b), each as bf16(a) | bf16(b) << 16.
+__device__ __forceinline__ void split3_pair(float a, float b, unsigned &h, unsigned &m, unsigned &l)
+{
+    h = bf16_pair(a, b);
+    const float ra = a - __uint_as_float(h << 16), rb = b - __uint_as_float(h & 0xffff0000u);
+    m = bf16_pair(ra, rb);
+    l = bf16_pair(ra - __uint_as_float(m << 16), rb - __uint_as_float(m & 0xffff0000u));
+}
+
+// One K = 32 step: six piece products per tile, product by product across the tiles (consecutive
+// instructions write different accumulators), small terms first.
+template <typename G, int ROLE>
+__device__ __forceinline__ void gram_mfma_step_split(const SplitOperand (&zh)[G::NB], const SplitOperand (&zm)[G::NB],
+                                                     const SplitOperand (&zl)[G::NB], floatx4 (&acc)[G::NACC])
+{
+#pragma unroll
+    for (int pr = 0; pr < 6; ++pr) {
+        int u = 0;
+#pragma unroll
+        for (int bi = 0; bi < G::NB; ++bi)
+#pragma unroll
+            for (int bj = bi; bj < G::NB; ++bj) {
+                if (G::tile_used(bi, bj)) {
+                    if (u % G::TSPLIT == ROLE) {
+                        const bf16x8 a = pr == 1 ? zl[bi].v : (pr == 2 || pr == 4) ? zm[bi].v : zh[bi].v;
+                        const bf16x8 b = pr == 0 ? zl[bj].v : (pr == 2 || pr == 3) ? zm[bj].v : zh[bj].v;
+                        acc[u / G::TSPLIT] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[u / G::TSPLIT], 0, 0, 0);
+                    }
+                    ++u;
+                }
+            }
+    }
+}
+
+// All K = 32 steps of this wavefront's patch rows of the staged tile.  pix_off / cen_off point at the first
+// of the lane's 8 consecutive patches (8 * (lane / 16)).
+template <typename G, int ROLE>
+__device__ __forceinline__ void gram_rows_split(const float *pix, int pitch, int rows, int cols, int pg, int q,
+                                                const int (&pix_off)[G::NB], const int (&cen_off)[G::NCEN],
+                                                floatx4 (&acc)[G::NACC])
+{
+    constexpr int NB = G::NB;
+    const int steps = (cols + 31) >> 5;
+    for (int py = pg; py < rows; py += G::NPG) {
+        const float *prow = pix + py * pitch;
+        for (int ks = 0; ks < steps; ++ks) {
+            const int x0 = 32 * ks;
+            const bool partial = x0 + 32 > cols;          // ragged end of the row: patches past the tile add 0
+            const int valid = cols - x0 - 8 * q;          // this lane's patches j < valid exist
+            float cen[G::NCEN][8];
+#pragma unroll
+            for (int v = 0; v < G::NCEN; ++v)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) cen[v][j] = prow[cen_off[v] + x0 + j];
+            SplitOperand zh[NB], zm[NB], zl[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                float y[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) y[j] = prow[pix_off[b] + x0 + j] - cen[G::cen_index(b)][j];
+                if (partial) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) y[j] = j < valid ? y[j] : 0.f;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) split3_pair(y[2 * i], y[2 * i + 1], zh[b].w[i], zm[b].w[i], zl[b].w[i]);
+            }
+            gram_mfma_step_split<G, ROLE>(zh, zm, zl, acc);
         }
     }
 }
@@ -281,7 +367,7 @@ __device__ __forceinline__ void gram_tile_store(const GramParams &p, float *buf,
     }
 }
 
-template <int KS, int TSPLIT, bool CROSS, int WAVES_PER_EU>
+template <int KS, int TSPLIT, bool CROSS, int WAVES_PER_EU, bool SPLIT>
 __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(GramParams p)
 {
     using G = GramGeom<KS, TSPLIT, CROSS>;
@@ -296,6 +382,7 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
     // per-lane operand offsets for each 16-row block of the stacked vector: stacked row
     // 16*b + i is entry a' of view v (v = row / DR); entries at and after the centre shift by one
     int pix_off[NB], cen_off[G::NCEN];
+    const int lane_patch = SPLIT ? 8 * q : q;             // first patch of the lane within a k-step
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const int row = 16 * b + i;
@@ -303,12 +390,12 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
         const int ar = row - view * G::DR;
         const int a = ar >= G::CEN ? ar + 1 : ar;
         const int dy = a / KS, dx = a - dy * KS;
-        pix_off[b] = view * p.view_stride + dy * p.pitch + dx + q;
-        if (G::STRADDLE) cen_off[b] = view * p.view_stride + R * p.pitch + R + q;
+        pix_off[b] = view * p.view_stride + dy * p.pitch + dx + lane_patch;
+        if (G::STRADDLE) cen_off[b] = view * p.view_stride + R * p.pitch + R + lane_patch;
     }
     if (!G::STRADDLE) {
-        cen_off[0] = R * p.pitch + R + q;
-        cen_off[1] = p.view_stride + R * p.pitch + R + q;
+        cen_off[0] = R * p.pitch + R + lane_patch;
+        cen_off[1] = p.view_stride + R * p.pitch + R + lane_patch;
     }
 
     floatx4 acc[G::NACC];
@@ -368,8 +455,13 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
         const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
         const int rows = min(GRAM_TH, p.h - ty * GRAM_TH);
         const int cols = min(p.tw, p.w - tx * p.tw);
-        if (TSPLIT == 1 || role == 0) gram_rows<G, 0>(pix, p.pitch, rows, cols, pg, q, pix_off, cen_off, acc);
-        else gram_rows<G, TSPLIT - 1>(pix, p.pitch, rows, cols, pg, q, pix_off, cen_off, acc);
+        if constexpr (SPLIT) {
+            if (TSPLIT == 1 || role == 0) gram_rows_split<G, 0>(pix, p.pitch, rows, cols, pg, q, pix_off, cen_off, acc);
+            else gram_rows_split<G, TSPLIT - 1>(pix, p.pitch, rows, cols, pg, q, pix_off, cen_off, acc);
+        } else {
+            if (TSPLIT == 1 || role == 0) gram_rows<G, 0>(pix, p.pitch, rows, cols, pg, q, pix_off, cen_off, acc);
+            else gram_rows<G, TSPLIT - 1>(pix, p.pitch, rows, cols, pg, q, pix_off, cen_off, acc);
+        }
 
         if (++since_flush >= p.flush_items || !more) {
             __syncthreads();                              // every wavefront is done with the tile
@@ -499,16 +591,17 @@ static GramShape gram_shape(int k)
 // one slot per resident workgroup
 int max_gram_slots(ddcca_ctx *ctx, int k) { return ctx->n_cu * gram_shape(k).waves_per_eu; }
 
-template <int KS, int TSPLIT, bool CROSS, int WPE>
+template <int KS, int TSPLIT, bool CROSS, int WPE, bool SPLIT>
 static int gram_launch(ddcca_ctx *ctx, const GramParams &p, int grid, size_t lds)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)patch_gram_kernel<KS, TSPLIT, CROSS, WPE>,
+        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)patch_gram_kernel<KS, TSPLIT, CROSS, WPE, SPLIT>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         attr_set = true;
     }
-    hipLaunchKernelGGL((patch_gram_kernel<KS, TSPLIT, CROSS, WPE>), dim3(grid), dim3(GRAM_THREADS), lds, ctx->stream, p);
+    hipLaunchKernelGGL((patch_gram_kernel<KS, TSPLIT, CROSS, WPE, SPLIT>), dim3(grid), dim3(GRAM_THREADS), lds,
+                       ctx->stream, p);
     DDCCA_HIP(ctx, hipGetLastError());
     return DDCCA_OK;
 }
@@ -529,7 +622,9 @@ int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t 
     const int r = (k - 1) / 2;
     // row pitch: >= tile width + halo, and congruent to k+3 mod 32 so that the window
     // rows a lane group touches fall into distinct LDS banks
-    int pitch = p.tw + 2 * r;
+    const bool split = ctx->gram_arith == DDCCA_GRAM_BF16X3;
+    // (three-piece operands read whole groups of 32 patches: the pitch covers the rounded-up width)
+    int pitch = (split ? (p.tw + 31) / 32 * 32 : p.tw) + 2 * r;
     while (pitch % 32 != (k + 3) % 32) ++pitch;
     p.pitch = pitch;
     p.view_stride = (GRAM_TH + 2 * r) * pitch + 16;      // +16: shift view 2 by half the banks
@@ -548,10 +643,12 @@ int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t 
     const int max_grid = max_slots;
     const int grid = (int)std::min<int64_t>(max_grid, std::max<int64_t>(p.n_items, 1));
     int rc;
-#define GRAM_CASE(KS, TS, WPE)                                                     \
-    case KS:                                                                       \
-        rc = cross_only ? gram_launch<KS, TS, true, WPE>(ctx, p, grid, lds)        \
-                        : gram_launch<KS, TS, false, WPE>(ctx, p, grid, lds);      \
+#define GRAM_CASE(KS, TS, WPE)                                                                   \
+    case KS:                                                                                     \
+        rc = split ? (cross_only ? gram_launch<KS, TS, true, WPE, true>(ctx, p, grid, lds)       \
+                                 : gram_launch<KS, TS, false, WPE, true>(ctx, p, grid, lds))     \
+                   : (cross_only ? gram_launch<KS, TS, true, WPE, false>(ctx, p, grid, lds)      \
+                                 : gram_launch<KS, TS, false, WPE, false>(ctx, p, grid, lds));   \
         break;
     switch (k) {
         GRAM_CASE(3, 1, 4)

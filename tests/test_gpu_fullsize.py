@@ -1,4 +1,4 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
+"""GPU parity at the full sizes of the five benchmark workloads, in the launch configuration bench.py times
 (pipeline.fit + pipeline.extract on the whole workload).  The CPU oracle cannot redo a full run in
 seconds, so each stage of the full-size GPU result is checked on outputs the oracle can compute one
 by one, and by properties that hold at any size:
