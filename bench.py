@@ -96,6 +96,9 @@ def main():
     ap.add_argument("--conv", default="fp32", choices=["fp32", "bf16x3"],
                     help="arithmetic of the stage convolution: fp32 matrix instructions (the headline path) or "
                          "three-piece bf16 operands on the bf16 matrix pipeline (same accuracy)")
+    ap.add_argument("--gram", default="fp32", choices=["fp32", "bf16x3"],
+                    help="arithmetic of the patch-Gram accumulation: fp32 matrix instructions (the headline path) "
+                         "or three-piece bf16 operands on the bf16 matrix pipeline (same accuracy)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=0, help="images in the CPU-oracle sample (0 = default)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -119,6 +122,9 @@ def main():
     v1, v2, cls = make_views(wl)
     M = int(v1.shape[0])
     ctx = Context(0)
+    if args.gram == "bf16x3":
+        from paper_2209_13027_amd.binding import OPT_GRAM_ARITH, GRAM_BF16X3
+        ctx.set_option(OPT_GRAM_ARITH, GRAM_BF16X3)
     if args.conv == "bf16x3":
         from paper_2209_13027_amd.binding import OPT_CONV_ARITH, CONV_BF16X3
         ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
@@ -213,6 +219,32 @@ def main():
         ctx.profile_enable(False)
         conv_split = ctx.profile_read()["conv"]["ms"] / args.steps
         ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
+    fast = None
+    if args.conv == "fp32" and args.gram == "fp32" and not args.fused:
+        # The whole step once more with every widened option on: three-piece bf16 operands in the Gram and the
+        # convolution (same accuracy bars, see the parity tests) and the fused last stage.  Not part of `value`.
+        from paper_2209_13027_amd.binding import (OPT_CONV_ARITH, CONV_BF16X3, CONV_FP32, OPT_GRAM_ARITH,
+                                                  GRAM_BF16X3, GRAM_FP32)
+        ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
+        ctx.set_option(OPT_GRAM_ARITH, GRAM_BF16X3)
+
+        def fast_step():
+            mdl = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
+            pipeline.extract(ctx, d1, d2, mdl["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride, batch, out=feat,
+                             dtype=feat_dtype, fused=True)
+        fast_step()
+        ctx.profile_reset()
+        ctx.profile_enable(True)
+        fast = timed(fast_step)
+        ctx.profile_enable(False)
+        pf = ctx.profile_read()
+        fast["gram_ms"] = pf["gram"]["ms"] / args.steps
+        fast["gram_useful_tflops"] = (algorithmic_work(wl, M)["gram_flops"] / (fast["gram_ms"] * 1e-3) / 1e12
+                                      if fast["gram_ms"] > 0 else 0.0)
+        fast["conv_hash_hist_ms"] = pf["conv_hash_hist"]["ms"] / args.steps
+        fast["options"] = "gram bf16x3, conv bf16x3, fused last stage"
+        ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
+        ctx.set_option(OPT_GRAM_ARITH, GRAM_FP32)
     ctx.status()
 
     work = algorithmic_work(wl, M, feat.element_size())
@@ -268,13 +300,15 @@ def main():
         "config": {"workload": wl.name, "images": M, "classes": wl.n_classes, "h": wl.h, "w": wl.w, "k": wl.k,
                    "L1": wl.L1, "L2": wl.L2, "block": wl.block, "stride": wl.stride, "bins": 1 << wl.L2,
                    "feature_len": wl.feature_len, "features": args.features,
-                   "fused_last_stage": bool(args.fused), "conv_arithmetic": args.conv},
+                   "fused_last_stage": bool(args.fused), "conv_arithmetic": args.conv,
+                   "gram_arithmetic": args.gram},
         "roofline": {"bound": "mfma", "kernel": "patch_gram_kernel (all-tiles variant: the Gram over the input maps)", "achieved": gram_tflops,
                      "peak": PEAK_MFMA_FP32_TFLOPS, "unit": "TFLOP/s", "frac": gram_tflops / PEAK_MFMA_FP32_TFLOPS,
                      "traffic": measured_traffic(wl.name, "patch_gram_kernel", ", false,"), "avg_launch_ms": gram_ms,
                      "algorithmic_flop_per_launch": gram_flops_per_launch},
         "kernels": kernels,
         "phases": phases,
+        "widened_path": fast,
         "ms_per_step_without_events": dt_plain / K * 1e3,
     }
     if not args.no_cpu_baseline:

@@ -320,7 +320,8 @@ int ddcca_set_option(ddcca_ctx *ctx, int option, int value)
         case DDCCA_OPT_GRAM_ARITH:
             if (value != DDCCA_GRAM_FP32 && value != DDCCA_GRAM_BF16X3)
                 return fail(ctx, DDCCA_EINVAL, "unknown Gram arithmetic");
-            if (ctx->corr_active) return fail(ctx, DDCCA_ESTATE, "cannot change the Gram arithmetic during an accumulation");
+            if (ctx->corr_active && !ctx->corr_exported)
+                return fail(ctx, DDCCA_ESTATE, "cannot change the Gram arithmetic during an accumulation");
             ctx->gram_arith = value;
             return DDCCA_OK;
         default: return fail(ctx, DDCCA_EINVAL, "unknown option");
