@@ -114,6 +114,55 @@ def test_validation_before_any_launch(binding):
     lib.ddcca_destroy(h)
 
 
+def test_validation_of_the_widened_calls(binding):
+    """Information-quality output, fused last stage and the arithmetic options: host-side validation."""
+    lib = binding.lib()
+    h = make_ctx(binding)
+    one = ctypes.c_void_p(256)
+    E = binding.EINVAL
+    # hash_iq: feature type, then the checks of hash_histogram
+    assert lib.ddcca_hash_iq(h, one, 2, 8, 16, 16, 8, 8, 4, 4, 7, one) == E
+    assert b"feature type" in lib.ddcca_last_error(h)
+    assert lib.ddcca_hash_iq(h, one, 2, 13, 16, 16, 8, 8, 4, 4, binding.FEAT_IQ_F32, one) == E
+    assert lib.ddcca_hash_iq(h, one, 2, 8, 16, 16, 8, 8, 4, 4, binding.FEAT_IQ_F16, None) == E
+    assert lib.ddcca_hash_iq(h, one, 0, 8, 16, 16, 8, 8, 4, 4, binding.FEAT_IQ_F16, one) == binding.OK
+    # apply_stage_hash: the checks of apply_stage and of hash_histogram
+    args = (8, 4, 4)
+    assert lib.ddcca_apply_stage_hash(h, one, 2, 16, 16, one, 4, 4, 8, *args, 0, one) == E      # even k
+    assert lib.ddcca_apply_stage_hash(h, one, 2, 16, 16, one, 5, 13, 8, *args, 0, one) == E     # L2 > 12
+    assert lib.ddcca_apply_stage_hash(h, one, 2, 16, 16, one, 5, 4, 32, *args, 0, one) == E     # block > map
+    assert lib.ddcca_apply_stage_hash(h, one, 2, 16, 16, None, 5, 4, 8, *args, 0, one) == E     # null filters
+    assert lib.ddcca_apply_stage_hash(h, one, 2, 16, 16, one, 5, 4, 8, *args, 3, one) == E      # feature type
+    assert lib.ddcca_apply_stage_hash(h, one, 0, 16, 16, one, 5, 4, 8, *args, 0, one) == binding.OK
+    # extract_features_fused / extract_iq_features
+    m = binding._Model()
+    m.k, m.L1, m.L2, m.block_h, m.block_w, m.stride_y, m.stride_x = 5, 4, 4, 8, 8, 4, 4
+    assert lib.ddcca_extract_features_fused(h, one, one, 2, 16, 16, ctypes.byref(m), 0, one) == E   # null filters
+    for s in range(2):
+        for d in range(2):
+            m.W[s][d] = 256
+    assert lib.ddcca_extract_features_fused(h, one, one, 2, 16, 16, ctypes.byref(m), 9, one) == E
+    assert lib.ddcca_extract_iq_features(h, one, one, 2, 16, 16, ctypes.byref(m), 9, one) == E
+    assert lib.ddcca_extract_features_fused(h, one, one, 0, 16, 16, ctypes.byref(m), 0, one) == binding.OK
+    # options: known values are accepted without a GPU, anything else is rejected
+    assert lib.ddcca_set_option(h, binding.OPT_CONV_ARITH, binding.CONV_BF16X3) == binding.OK
+    assert lib.ddcca_set_option(h, binding.OPT_GRAM_ARITH, binding.GRAM_BF16X3) == binding.OK
+    assert lib.ddcca_set_option(h, binding.OPT_GRAM_ARITH, binding.GRAM_FP32) == binding.OK
+    assert lib.ddcca_set_option(h, binding.OPT_CONV_ARITH, 2) == E
+    assert lib.ddcca_set_option(h, binding.OPT_GRAM_ARITH, -1) == E
+    assert lib.ddcca_set_option(h, 99, 0) == E
+    assert lib.ddcca_set_option(None, binding.OPT_CONV_ARITH, 0) == E
+    lib.ddcca_destroy(h)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr
+
+
 def test_compute_without_gpu_fails_loudly(binding):
     import torch
     if torch.cuda.is_available():
