@@ -31,21 +31,9 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int FUSED_XB = 32;              // pixels per MFMA column block (16 columns x 2 shifts)
 constexpr int FUSED_MAX_NBX = 4;
-#ifndef FUSED_EXP_LDS_BYTES
 constexpr int FUSED_LDS_BYTES = 80 * 1024;   // per workgroup: two workgroups share a compute unit's 160 KB
-#else
-constexpr int FUSED_LDS_BYTES = FUSED_EXP_LDS_BYTES;
-#endif
-#ifndef FUSED_EXP_RING_THREADS
 constexpr int RING_THREADS = 512;
-#else
-constexpr int RING_THREADS = FUSED_EXP_RING_THREADS;
-#endif
-#ifndef FUSED_EXP_RING_MINWG
 constexpr int RING_MIN_WG = 4;            // wavefronts per SIMD the register budget must allow (two workgroups per compute unit)
-#else
-constexpr int RING_MIN_WG = FUSED_EXP_RING_MINWG;
-#endif
 constexpr int RING_WAVES = RING_THREADS / 64;
 constexpr int RING_TH_MAX = 32;           // largest tile height of the ring kernel
 constexpr int GROUP_THREADS = 256;
@@ -144,13 +132,6 @@ __device__ __forceinline__ void fused_row_codes(const float *prow, const int (&t
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
         floatx4 acc[RU][NBX];
-#ifdef FUSED_EXP_NO_MFMA
-#pragma unroll
-        for (int u = 0; u < RU; ++u)
-#pragma unroll
-            for (int b = 0; b < NBX; ++b)
-                acc[u][b] = floatx4{prow[u * RSTRIDE + b], prow[b + 1] + wa[gi][0], wa[gi][1] + prow[toff[1]], wa[gi][2]};
-#else
 #pragma unroll
         for (int kk = 0; kk < G::KK; ++kk) {
             const float *pk = prow + toff[kk];
@@ -161,7 +142,6 @@ __device__ __forceinline__ void fused_row_codes(const float *prow, const int (&t
                     acc[u][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[gi][kk], pk[u * RSTRIDE + b * FUSED_XB],
                                                                      kk == 0 ? floatx4{0.f, 0.f, 0.f, 0.f} : acc[u][b], 0, 0, 0);
         }
-#endif
 #pragma unroll
         for (int u = 0; u < RU; ++u)
 #pragma unroll
@@ -331,9 +311,7 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
     for (int t = 0; t < n_tiles; ++t) {
         __syncthreads();                          // tile t is in LDS; cleared slots are visible
         const float *tile = tile0 + (t & 1) * p.tile_floats;
-#ifndef FUSED_EXP_NO_STAGE
         if (t + 1 < n_tiles) fetch(t + 1);
-#endif
         const int tyi = t / tiles_x, txi = t - tyi * tiles_x;
         const int ty0 = tyi * p.th, rows = min(p.th, y_hi - ty0);
         const int tx0 = x_lo + txi * TW;
@@ -386,7 +364,6 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
                     const int so_a = (p.magic_ring ? ib - p.ring * (int)__umulhi((unsigned)ib, p.magic_ring) : ib % p.ring) * row_words;
                     const int so_c = (p.magic_ring ? ic - p.ring * (int)__umulhi((unsigned)ic, p.magic_ring) : ic % p.ring) * row_words;
                     const int so = my_ioff ? so_c : so_a;
-#ifndef FUSED_EXP_NO_ATOMICS
                     if (ib + my_ioff <= ihi) {
 #pragma unroll
                         for (int b = 0; b < NBX; ++b) {
@@ -395,15 +372,10 @@ __global__ __launch_bounds__(RING_THREADS, RING_MIN_WG) void conv_hash_hist_ring
                             for (int jj = 0; jj < nj[b]; ++jj) atomicAdd(dst + jj * words, inc[b]);
                         }
                     }
-#else
-                    if (inc[0] == 0x12345u + (unsigned)so) lds_hist[0] = word[NBX - 1];
-#endif
                 }
             }
         }
-#ifndef FUSED_EXP_NO_STAGE
         if (t + 1 < n_tiles) stash(tile0 + ((t + 1) & 1) * p.tile_floats, t + 1);
-#endif
         if (txi == tiles_x - 1) {
             // block rows whose last pixel row lies inside the rows swept so far are complete
             const int done = ty0 + rows - p.bh;

@@ -103,10 +103,6 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_mfma_kernel(const float *__
             floatx4 acc[NBX];
 #pragma unroll
             for (int b = 0; b < NBX; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
-#ifdef CONV_EXP_NO_MFMA
-#pragma unroll
-            for (int b = 0; b < NBX; ++b) acc[b] = floatx4{prow[b], prow[b + 1], wa[0], wa[1]};
-#else
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
                 const float *pk = prow + toff[kk];
@@ -114,7 +110,6 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_mfma_kernel(const float *__
                 for (int b = 0; b < NBX; ++b)
                     acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[kk], pk[b * CONV_XB], acc[b], 0, 0, 0);
             }
-#endif
             const int gy = ty * CONV_TH + r;
             float *dst = out + (n * L + ga) * P + (int64_t)gy * w + gx_lane;
             if (fast) {
