@@ -43,6 +43,11 @@ GEOMETRIES = [
     (2, 33, 130, 7, 11, (6, 10), (2, 3)),  # dense block overlap (stride < block/2), 11 filters
     (2, 24, 24, 3, 12, 9, 1),            # stride 1 with 4096 bins: live block rows exceed LDS (row-group kernel)
     (2, 150, 40, 5, 8, 16, 8),           # tall narrow map: many tile rows, several block-row flushes
+    (3, 1, 40, 3, 2, (1, 8), (1, 4)),    # one pixel row
+    (2, 37, 41, 5, 6, 9, 4),             # odd width and height: unaligned rows, scalar tile staging
+    (1, 300, 500, 7, 8, 64, 32),         # large map, large blocks: four tile columns, long block rows
+    (2, 64, 64, 9, 8, 8, 8),             # stride = block (no overlap): each pixel in exactly one block
+    (2, 48, 80, 5, 7, 6, 9),             # stride > block: pixels between blocks belong to none
 ]
 
 
@@ -99,6 +104,19 @@ def test_extract_fused_equals_unfused(ctx, name, images, batch):
         b = pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride, batch,
                              dtype=dtype, fused=True)
         assert a.shape == b.shape and torch.equal(a, b)
+
+
+def test_extract_fused_odd_group_and_ragged_batches(ctx):
+    # L1 = 3 maps per image, 5 images in batches of 2: group layout and ragged last batch of the fused launch
+    rng = np.random.default_rng(31)
+    v1 = rng.standard_normal((5, 30, 44)).astype(np.float32)
+    v2 = rng.standard_normal((5, 30, 44)).astype(np.float32)
+    filters = [dev(rng.standard_normal((L, 5, 5)).astype(np.float32)) for L in (3, 3, 6, 6)]
+    a = ctx.extract_features(dev(v1), dev(v2), filters, 5, 3, 6, 10, 5, batch_images=2)
+    b = ctx.extract_features(dev(v1), dev(v2), filters, 5, 3, 6, 10, 5, batch_images=2, fused=True)
+    c = ctx.extract_features(dev(v1), dev(v2), filters, 5, 3, 6, 10, 5, batch_images=0, fused=True)
+    assert a.shape == (5, 2, 3, 5, 7, 64)
+    assert torch.equal(a, b) and torch.equal(a, c)
 
 
 def test_end_to_end_tiny_fused(ctx, oracle):
