@@ -170,7 +170,9 @@ int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v
  * DDCCA_OPT_GRAM_ARITH selects the arithmetic of the patch-Gram accumulation (Section II-A
  * matrices) in the same way: DDCCA_GRAM_FP32 (default) or DDCCA_GRAM_BF16X3.  Accumulation
  * across tiles stays fp64 and the result does not depend on the batch split in either.
- * Returns DDCCA_EINVAL for an unknown option or value. */
+ * Returns DDCCA_EINVAL for an unknown option or value, DDCCA_ESTATE when the Gram
+ * arithmetic is changed between ddcca_corr_begin and the export / solve of that
+ * accumulation. */
 #define DDCCA_OPT_CONV_ARITH 1
 #define DDCCA_CONV_FP32      0
 #define DDCCA_CONV_BF16X3    1
