@@ -2,7 +2,7 @@
 //   B_d = C_dd + eps_d I (ridge), C~ = 2 C_w - C_T
 //   B_d = L_d L_d^T (Cholesky), L_d^{-1} formed in place, T = L_1^{-1} C~ L_2^{-T}
 //   T = U diag(sigma) V^T: one-sided (Hestenes) Jacobi rotations of column pairs of T in
-//   round-robin order, one 16-lane group per pair, one barrier per round; V is not
+//   round-robin order, one 8-lane group per pair, one barrier per round; V is not
 //   accumulated (v = T^T u / sigma for the L leading triplets only)
 //   w_1 = L_1^{-T} u,  w_2 = L_2^{-T} v,  rho = sigma
 // The leading L pairs are written as fp32 filters (Eq. 4-5: row-major k x k).
@@ -68,6 +68,32 @@ __device__ __forceinline__ int row16_min_int(int x)
     DDCCA_ROR(8) DDCCA_ROR(4) DDCCA_ROR(2) DDCCA_ROR(1)
 #undef DDCCA_ROR
     return x;
+}
+
+
+// One lane-exchange step of a double: both halves through the data-parallel primitive `ctrl`.
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x)
+{
+    const int lo = __builtin_amdgcn_mov_dpp(__double2loint(x), CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(x), CTRL, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+
+// Sums of a, b, c over the 8 lanes of a group (lanes 8r .. 8r+7), results in every lane of the group and
+// bit-identical there.  Exchanges: lane^1, lane^2 (quad permutations), 7-lane (mirror of the half row).  The
+// three sums advance in lockstep so that their dependent chains overlap.
+__device__ __forceinline__ void group8_sum3(double &a, double &b, double &c)
+{
+#define DDCCA_STEP(ctrl)                                                                     \
+    {                                                                                        \
+        const double ta = dpp_f64<ctrl>(a), tb = dpp_f64<ctrl>(b), tc = dpp_f64<ctrl>(c);    \
+        a += ta;                                                                             \
+        b += tb;                                                                             \
+        c += tc;                                                                             \
+    }
+    DDCCA_STEP(0xb1) DDCCA_STEP(0x4e) DDCCA_STEP(0x141)
+#undef DDCCA_STEP
 }
 
 // 1/sqrt(x) to fp64 accuracy for normal positive x: hardware estimate + two Newton steps.
@@ -193,46 +219,47 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
     __syncthreads();
     STAMP(4);
 
-    // A group of 16 lanes owns one column pair per round: it forms the three inner products and
+    // A group of 8 lanes owns one column pair per round: it forms the three inner products and
     // the rotation that makes the two columns orthogonal, and applies it.  Pairs of one round
-    // are disjoint (round-robin tournament), so a round needs a single barrier.
+    // are disjoint (round-robin tournament), so a round needs a single barrier.  Eight lanes per
+    // pair put all pairs of a round into at most one wavefront per SIMD up to k = 7.
     constexpr int NP = D + (D & 1);              // players; index D (if present) is a bye
     constexpr int N_PAIRS = NP / 2, N_ROUNDS = NP - 1;
-    static_assert(N_PAIRS <= NGRP, "one 16-lane group per pair");
+    constexpr int JR = (D + 7) / 8;              // rows of a column held by one lane of the group
+    static_assert(N_PAIRS <= SOLVE_THREADS / 8, "one 8-lane group per pair");
+    const int jg = tid >> 3, l8 = tid & 7;
     for (int sweep = 0; sweep < SOLVE_MAX_SWEEPS; ++sweep) {
         for (int round = 0; round < N_ROUNDS; ++round) {
-            if (grp < N_PAIRS) {
+            if (jg < N_PAIRS) {
                 int a, b;
-                if (grp == 0) {
+                if (jg == 0) {
                     a = NP - 1;
                     b = round;
                 } else {
-                    a = round + grp;
+                    a = round + jg;
                     if (a >= NP - 1) a -= NP - 1;
-                    b = round - grp;
+                    b = round - jg;
                     if (b < 0) b += NP - 1;
                 }
                 const int pp = min(a, b), qq = max(a, b);
                 if (qq < D) {
                     double *gp = A + pp * D, *gq = A + qq * D;
-                    double x[NR], y[NR];
+                    double x[JR], y[JR];
 #pragma unroll
-                    for (int r = 0; r < NR; ++r) {
-                        const int i = l16 + 16 * r;
+                    for (int r = 0; r < JR; ++r) {
+                        const int i = l8 + 8 * r;
                         const bool in = i < D;
                         x[r] = in ? gp[i] : 0.0;
                         y[r] = in ? gq[i] : 0.0;
                     }
                     double al = 0.0, be = 0.0, ga = 0.0;
 #pragma unroll
-                    for (int r = 0; r < NR; ++r) {
+                    for (int r = 0; r < JR; ++r) {
                         al += x[r] * x[r];
                         be += y[r] * y[r];
                         ga += x[r] * y[r];
                     }
-                    al = row16_sum(al);
-                    be = row16_sum(be);
-                    ga = row16_sum(ga);
+                    group8_sum3(al, be, ga);
                     if (ga * ga > (SOLVE_TOL * SOLVE_TOL) * (al * be)) {
                         // rotation angle theta, |theta| <= pi/4, tan(2 theta) = 2 ga / (be - al):
                         // cos(2 theta) = |d|/r, c = sqrt((1 + cos 2theta)/2), s = sin(2 theta)/(2c)
@@ -243,15 +270,15 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
                         const double c = h * cinv;
                         const double sn = (d >= 0.0 ? 0.5 : -0.5) * g2 * rinv * cinv;
 #pragma unroll
-                        for (int r = 0; r < NR; ++r) {
-                            const int i = l16 + 16 * r;
+                        for (int r = 0; r < JR; ++r) {
+                            const int i = l8 + 8 * r;
                             if (i < D) {
                                 gp[i] = c * x[r] - sn * y[r];
                                 gq[i] = sn * x[r] + c * y[r];
                             }
                         }
                         // was any pair of this sweep further from orthogonal than SOLVE_QUAD ?
-                        if (l16 == 0 && ga * ga > (SOLVE_QUAD * SOLVE_QUAD) * (al * be)) flag[0] = 1;
+                        if (l8 == 0 && ga * ga > (SOLVE_QUAD * SOLVE_QUAD) * (al * be)) flag[0] = 1;
                     }
                 }
             }
