@@ -33,11 +33,12 @@ def algorithmic_work(wl, M, feat_bytes=2):
     per_patch = 2.0 * (2 * D * D + D)                 # two symmetric blocks + one full block
     gram_main = per_patch * (M * P + M * L1 * P)
     gram_class = 2.0 * D * D * P * ((C * 1 + 1) + (C * L1 + L1))   # cross block of class-sum / total images
-    # conv: read 4 B, write 4L B per input pixel; stage 1 runs in fit and again in extract
-    conv_bytes = 2 * (2 * M * P * (4 + 4 * L1)) + 2 * M * L1 * P * (4 + 4 * L2)
-    conv_flops = 2 * (2 * M * P * 2 * D * L1) + 2 * M * L1 * P * 2 * D * L2
+    # conv: read 4 B, write 4L B per input pixel; stage 1 runs in fit (the samples and the C + 1 sum images of
+    # the second learning stage) and again in extract
+    conv_bytes = 2 * ((2 * M + C + 1) * P * (4 + 4 * L1)) + 2 * M * L1 * P * (4 + 4 * L2)
+    conv_flops = 2 * ((2 * M + C + 1) * P * 2 * D * L1) + 2 * M * L1 * P * 2 * D * L2
     hist_bytes = 2 * M * L1 * (L2 * P * 4 + A * bins * feat_bytes)
-    class_bytes = 2 * 4 * (M * P + M * L1 * P)       # every map of both views read once
+    class_bytes = 2 * 4 * (M * P + M * P)            # the inputs of both views, read once per learning stage
     return {
         "gram_flops": gram_main, "gram_cross_flops": gram_class,
         "conv_bytes": conv_bytes, "conv_flops": conv_flops, "hist_bytes": hist_bytes,

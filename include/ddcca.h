@@ -181,6 +181,28 @@ int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v
 #define DDCCA_GRAM_BF16X3    1
 int ddcca_set_option(ddcca_ctx *ctx, int option, int value);
 
+/* Learn the filters of the stage that follows a given stage (Section II-B: the second stage
+ * is learned on the maps of the first; Section II-A for the matrices) without holding those
+ * maps: the result of ddcca_apply_stage(v_d, Wp_d) for both views followed by
+ * ddcca_learn_stage_filters on the maps with G = G_in * L_prev.
+ *   v1, v2 : DEVICE, [n_img][G_in][h][w] float, the INPUTS of the previous stage
+ *   Wp1, Wp2 : DEVICE, [L_prev][k_prev][k_prev] float, the previous stage's filters per view
+ *   batch_images : samples whose maps exist at a time (0 = as many as fit 1 GiB per view);
+ *                  the result does not depend on it beyond the rounding order of the fp64
+ *                  accumulation across batches
+ * Every batch is convolved into a scratch buffer of the context and accumulated at once.
+ * The class-conditioned sum images (the C_w and C_T terms) are formed as the previous-stage
+ * convolution of the inputs' sum images -- the convolution of Eq. 6 is linear -- so they
+ * differ from the sums of the fp32 maps by fp32 rounding only (relative 1e-7 per pixel).
+ * The convolution arithmetic follows DDCCA_OPT_CONV_ARITH.  Other arguments, outputs and
+ * errors as in ddcca_learn_stage_filters; additionally DDCCA_EINVAL when L_prev is outside
+ * 1..k_prev*k_prev-1, G_in * L_prev exceeds 4096 or batch_images is negative. */
+int ddcca_learn_next_stage_filters(ddcca_ctx *ctx, const float *v1, const float *v2,
+                                   const int32_t *cls, int64_t n_img, int G_in, int h, int w,
+                                   int n_cls, const float *Wp1, const float *Wp2, int k_prev,
+                                   int L_prev, int k, int L, double ridge, int64_t batch_images,
+                                   float *W1, float *W2, double *rho);
+
 /* ---- per-kernel timing (HIP events on the context's stream) -------------------------- */
 enum {
     DDCCA_K_GRAM = 0,     /* patch-Gram accumulation over the input maps (all tiles) */

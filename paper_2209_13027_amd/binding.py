@@ -25,6 +25,7 @@ EXPORTS = [
     "ddcca_dcca_solve", "ddcca_learn_stage_filters", "ddcca_apply_stage", "ddcca_hash_histogram",
     "ddcca_extract_features", "ddcca_hash_iq", "ddcca_extract_iq_features",
     "ddcca_apply_stage_hash", "ddcca_extract_features_fused", "ddcca_set_option",
+    "ddcca_learn_next_stage_filters",
     "ddcca_profile_enable", "ddcca_profile_read", "ddcca_profile_reset",
 ]
 FEAT_COUNT_U16, FEAT_IQ_F32, FEAT_IQ_F16 = 0, 1, 2
@@ -82,6 +83,8 @@ def lib() -> ctypes.CDLL:
         l.ddcca_apply_stage_hash.argtypes = [vp, vp, i64, i, i, vp, i, i, i, i, i, i, i, vp]
         l.ddcca_extract_features_fused.argtypes = [vp, vp, vp, i64, i, i, ctypes.POINTER(_Model), i, vp]
         l.ddcca_set_option.argtypes = [vp, i, i]
+        l.ddcca_learn_next_stage_filters.argtypes = [vp, vp, vp, vp, i64, i, i, i, i, vp, vp, i, i, i, i, d, i64,
+                                                     vp, vp, vp]
         l.ddcca_profile_enable.argtypes = [vp, i]
         l.ddcca_profile_read.argtypes = [vp, i, ctypes.POINTER(d), ctypes.POINTER(i64)]
         l.ddcca_profile_reset.argtypes = [vp]
@@ -177,6 +180,23 @@ class Context:
         self._check(lib().ddcca_learn_stage_filters(
             self._h, _ptr(v1, torch.float32, "v1"), _ptr(v2, torch.float32, "v2"), _ptr(cls, torch.int32, "cls"),
             n_img, G, h, w, n_cls, k, L, ridge, _ptr(W1, torch.float32, "W1"), _ptr(W2, torch.float32, "W2"),
+            _ptr(rho, torch.float64, "rho")))
+        return W1, W2, rho
+
+    def learn_next_stage_filters(self, v1, v2, cls, G_in, h, w, n_cls, Wp1, Wp2, k, L, ridge=1e-4, batch_images=0):
+        """Filters of the stage after the one with filters Wp1 / Wp2 ([L_prev, k_prev, k_prev]), learned from that
+        stage's INPUTS v1, v2 ([n_img * G_in, h, w]) without holding its maps."""
+        n_img = int(cls.shape[0])
+        if v1.numel() != n_img * G_in * h * w or v2.numel() != n_img * G_in * h * w:
+            raise ValueError("view tensors do not match n_img * G_in * h * w")
+        L_prev, k_prev, _ = Wp1.shape
+        if tuple(Wp2.shape) != tuple(Wp1.shape):
+            raise ValueError("the two views' filter banks differ in shape")
+        W1, W2, rho = self._filter_outputs(k, L)
+        self._check(lib().ddcca_learn_next_stage_filters(
+            self._h, _ptr(v1, torch.float32, "v1"), _ptr(v2, torch.float32, "v2"), _ptr(cls, torch.int32, "cls"),
+            n_img, G_in, h, w, n_cls, _ptr(Wp1, torch.float32, "Wp1"), _ptr(Wp2, torch.float32, "Wp2"), k_prev,
+            L_prev, k, L, ridge, batch_images, _ptr(W1, torch.float32, "W1"), _ptr(W2, torch.float32, "W2"),
             _ptr(rho, torch.float64, "rho")))
         return W1, W2, rho
 

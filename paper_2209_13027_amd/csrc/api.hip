@@ -110,7 +110,9 @@ static int corr_finish(ddcca_ctx *ctx)
 
     if ((rc = ensure(ctx, ctx->class_img, 2 * (size_t)(n_cell + ctx->G) * P * sizeof(float)))) return rc;
     float *img = (float *)ctx->class_img.ptr;
-    if ((rc = launch_class_finalize(ctx, (const double *)ctx->class_sum.ptr, ctx->n_cls, ctx->G, P, img))) return rc;
+    if (!ctx->class_img_ready &&
+        (rc = launch_class_finalize(ctx, (const double *)ctx->class_sum.ptr, ctx->n_cls, ctx->G, P, img)))
+        return rc;
     const size_t view_stride = (size_t)(n_cell + ctx->G) * P;
     const int max_slots = max_gram_slots(ctx, k);
     int valid = 0;
@@ -209,6 +211,7 @@ int ddcca_corr_begin(ddcca_ctx *ctx, int k, int n_cls, int G, int h, int w)
     ctx->slots_valid = 0;
     ctx->corr_active = true;
     ctx->corr_exported = false;
+    ctx->class_img_ready = false;
     return DDCCA_OK;
 }
 
@@ -306,6 +309,59 @@ static int run_conv(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, co
 {
     return ctx->conv_arith == DDCCA_CONV_BF16X3 ? launch_conv_split(ctx, in, n, h, w, W, k, L, out)
                                                 : launch_conv(ctx, in, n, h, w, W, k, L, out);
+}
+
+int ddcca_learn_next_stage_filters(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls, int64_t n_img,
+                                   int G_in, int h, int w, int n_cls, const float *Wp1, const float *Wp2, int k_prev,
+                                   int L_prev, int k, int L, double ridge, int64_t batch_images, float *W1, float *W2,
+                                   double *rho)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    int rc;
+    if ((rc = check_image_args(ctx, n_img, h, w, k))) return rc;
+    if ((rc = check_image_args(ctx, n_img, h, w, k_prev))) return rc;
+    if ((rc = check_solve_args(ctx, k, L, ridge, W1, W2, rho))) return rc;
+    if (n_img < 1) return fail(ctx, DDCCA_EINVAL, "need at least one sample to learn filters");
+    if (!v1 || !v2 || !cls || !Wp1 || !Wp2) return fail(ctx, DDCCA_EINVAL, "null data pointer");
+    if (G_in < 1 || L_prev < 1 || L_prev > k_prev * k_prev - 1)
+        return fail(ctx, DDCCA_EINVAL, "G_in must be positive and L_prev in 1..k_prev*k_prev-1");
+    if ((int64_t)G_in * L_prev > 4096) return fail(ctx, DDCCA_EINVAL, "G_in * L_prev must not exceed 4096");
+    if (batch_images < 0) return fail(ctx, DDCCA_EINVAL, "negative batch size");
+    const int G = G_in * L_prev;
+    if ((rc = ddcca_corr_begin(ctx, k, n_cls, G, h, w))) return rc;
+    const int64_t P = (int64_t)h * w;
+    const int64_t cells_in = (int64_t)n_cls * G_in, n_cell = (int64_t)n_cls * G;
+    // class-conditioned sum images of the next stage = previous-stage convolution of the inputs' sum images
+    if ((rc = launch_label_check(ctx, cls, n_img, n_cls, (int *)ctx->flags.ptr))) return rc;
+    if ((rc = launch_class_sum(ctx, v1, v2, cls, n_img, G_in, n_cls, P, (double *)ctx->class_sum.ptr))) return rc;
+    if ((rc = ensure(ctx, ctx->prev_img, 2 * (size_t)(cells_in + G_in) * P * sizeof(float)))) return rc;
+    float *pimg = (float *)ctx->prev_img.ptr;
+    if ((rc = launch_class_finalize(ctx, (const double *)ctx->class_sum.ptr, n_cls, G_in, P, pimg))) return rc;
+    if ((rc = ensure(ctx, ctx->class_img, 2 * (size_t)(n_cell + G) * P * sizeof(float)))) return rc;
+    float *cimg = (float *)ctx->class_img.ptr;
+    if ((rc = run_conv(ctx, pimg, cells_in + G_in, h, w, Wp1, k_prev, L_prev, cimg))) return rc;
+    if ((rc = run_conv(ctx, pimg + (size_t)(cells_in + G_in) * P, cells_in + G_in, h, w, Wp2, k_prev, L_prev,
+                       cimg + (size_t)(n_cell + G) * P)))
+        return rc;
+    ctx->class_img_ready = true;
+    // the maps themselves, one batch of samples at a time
+    const size_t per_img = (size_t)G * P * sizeof(float);
+    int64_t nb = batch_images;
+    if (nb == 0) nb = std::max<int64_t>(1, (int64_t)(((size_t)1 << 30) / per_img));   // 1 GiB of maps per view
+    nb = std::min(nb, n_img);
+    if ((rc = ensure(ctx, ctx->maps1, (size_t)nb * per_img))) return rc;
+    if ((rc = ensure(ctx, ctx->maps2, (size_t)nb * per_img))) return rc;
+    float *m1 = (float *)ctx->maps1.ptr, *m2 = (float *)ctx->maps2.ptr;
+    for (int64_t i0 = 0; i0 < n_img; i0 += nb) {
+        const int64_t b = std::min(nb, n_img - i0);
+        if ((rc = run_conv(ctx, v1 + (size_t)i0 * G_in * P, b * G_in, h, w, Wp1, k_prev, L_prev, m1))) return rc;
+        if ((rc = run_conv(ctx, v2 + (size_t)i0 * G_in * P, b * G_in, h, w, Wp2, k_prev, L_prev, m2))) return rc;
+        if ((rc = launch_patch_gram(ctx, m1, m2, b * G, h, w, k, false, (double *)ctx->slots.ptr,
+                                    max_gram_slots(ctx, k), &ctx->slots_valid)))
+            return rc;
+        ctx->n_maps += b * G;
+    }
+    return ddcca_solve_filters(ctx, L, ridge, W1, W2, rho);
 }
 
 int ddcca_set_option(ddcca_ctx *ctx, int option, int value)

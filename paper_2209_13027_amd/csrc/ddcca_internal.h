@@ -42,6 +42,8 @@ struct ddcca_ctx {
     ddcca::Buffer slots;                    // [max_slots][tiles*256] double
     ddcca::Buffer class_sum;                // [2][n_cls*G][h*w] double
     ddcca::Buffer class_img;                // [2][n_cls*G + G][h*w] float
+    bool class_img_ready = false;           // class_img was filled directly (not from class_sum)
+    ddcca::Buffer prev_img;                 // sum images of the previous stage's inputs (next-stage learning)
     ddcca::Buffer stacked;                  // 3 x [tiles*256] double (main, class, total)
     ddcca::Buffer seg;                      // reduction segments
     ddcca::Buffer mats;                     // 5 x [D][D] double: C11 C22 C12 Cw CT

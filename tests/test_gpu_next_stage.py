@@ -1,0 +1,139 @@
+"""GPU parity of ddcca_learn_next_stage_filters (second-stage learning from the first stage's inputs, maps convolved
+batch by batch, class-conditioned sum images by linearity of the convolution) against
+
+  * the materialised route through the same library (ddcca_apply_stage + ddcca_learn_stage_filters): C11, C22, C12
+    equal up to the fp64 summation order across batches, Cw and CT up to the fp32 rounding of the sum images;
+  * the fp64 oracle, to the bars of the path: matrices <= 1e-4 relative (Frobenius), filters cosine >= 0.9999 where
+    the canonical correlations are separated, end-to-end histograms <= 1e-3 relative L1.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2209_13027_amd.workloads import WORKLOADS, make_views  # noqa: E402
+from paper_2209_13027_amd import pipeline  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2209_13027_amd.binding import Context
+    c = Context(0)
+    yield c
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def rel_fro(a, b):
+    return np.linalg.norm(a - b) / np.linalg.norm(b)
+
+
+def cosines(got, want):
+    g = got.reshape(got.shape[0], -1).astype(np.float64)
+    r = want.reshape(want.shape[0], -1).astype(np.float64)
+    return np.sum(g * r, axis=1) / (np.linalg.norm(g, axis=1) * np.linalg.norm(r, axis=1))
+
+
+def rand_problem(seed, n_img, h, w, n_cls):
+    rng = np.random.default_rng(seed)
+    # smooth + noise so that the first stage has separated canonical correlations
+    base = rng.standard_normal((n_img, h + 4, w + 4)).astype(np.float32)
+    smooth = sum(base[:, dy:dy + h, dx:dx + w] for dy in range(5) for dx in range(5)) / 5.0
+    v1 = (smooth + 0.3 * rng.standard_normal((n_img, h, w))).astype(np.float32)
+    v2 = (0.7 * smooth + 0.5 * rng.standard_normal((n_img, h, w)) + 2.0).astype(np.float32)
+    cls = (np.arange(n_img) % n_cls).astype(np.int32)
+    rng.shuffle(cls)
+    return v1, v2, cls
+
+
+def matrices_of_last_learning(ctx, k):
+    return {n: v.cpu().numpy() for n, v in ctx.corr_export(k).items()}
+
+
+@pytest.mark.parametrize("n_img,h,w,k,L1,L2,n_cls,batch", [
+    (12, 32, 32, 5, 4, 4, 3, 0),        # one batch
+    (12, 32, 32, 5, 4, 4, 3, 5),        # ragged batches 5 + 5 + 2
+    (7, 45, 70, 7, 8, 8, 2, 3),         # k = 7, ragged tiles
+    (5, 24, 40, 3, 3, 2, 5, 1),         # every sample its own class and its own batch
+    (6, 40, 36, 9, 8, 8, 1, 4),         # k = 9, a single class
+])
+def test_streamed_equals_materialised(ctx, n_img, h, w, k, L1, L2, n_cls, batch):
+    v1, v2, cls = rand_problem(900 + k + n_img, n_img, h, w, n_cls)
+    d1, d2, dc = dev(v1), dev(v2), dev(cls)
+    W1a, W2a, _ = ctx.learn_stage_filters(d1, d2, dc, 1, h, w, n_cls, k, L1)
+    y1, y2 = ctx.apply_stage(d1, W1a), ctx.apply_stage(d2, W2a)
+    Wm1, Wm2, rho_m = ctx.learn_stage_filters(y1, y2, dc, L1, h, w, n_cls, k, L2)
+    mats_m = matrices_of_last_learning(ctx, k)
+    Ws1, Ws2, rho_s = ctx.learn_next_stage_filters(d1, d2, dc, 1, h, w, n_cls, W1a, W2a, k, L2, batch_images=batch)
+    mats_s = matrices_of_last_learning(ctx, k)
+    ctx.status()
+    for name in ("C11", "C22", "C12"):
+        assert rel_fro(mats_s[name], mats_m[name]) <= 1e-13, name
+    for name in ("Cw", "CT"):
+        assert rel_fro(mats_s[name], mats_m[name]) <= 1e-6, name
+    assert np.allclose(rho_s.cpu().numpy(), rho_m.cpu().numpy(), rtol=1e-5)
+    # filters: compare where the leading correlations are separated (ratio of neighbours below 0.999)
+    rho = rho_m.cpu().numpy()
+    sep = np.ones(L2, dtype=bool)
+    sep[1:] &= rho[1:] < 0.999 * rho[:-1]
+    sep[:-1] &= rho[1:] < 0.999 * rho[:-1]
+    if sep.any():
+        assert cosines(Ws1.cpu().numpy(), Wm1.cpu().numpy())[sep].min() >= 1 - 1e-6
+        assert cosines(Ws2.cpu().numpy(), Wm2.cpu().numpy())[sep].min() >= 1 - 1e-6
+
+
+def test_streamed_matrices_against_oracle(ctx, oracle):
+    n_img, h, w, k, L1, n_cls = 9, 30, 44, 5, 4, 3
+    v1, v2, cls = rand_problem(77, n_img, h, w, n_cls)
+    d1, d2, dc = dev(v1), dev(v2), dev(cls)
+    W1a, W2a, _ = ctx.learn_stage_filters(d1, d2, dc, 1, h, w, n_cls, k, L1)
+    ctx.learn_next_stage_filters(d1, d2, dc, 1, h, w, n_cls, W1a, W2a, k, 4, batch_images=4)
+    got = matrices_of_last_learning(ctx, k)
+    # the oracle's own convolution of the same inputs with the filters the library learned, then its matrices
+    y1 = oracle.conv(v1.astype(np.float64), W1a.cpu().numpy().astype(np.float64)).reshape(-1, h, w)
+    y2 = oracle.conv(v2.astype(np.float64), W2a.cpu().numpy().astype(np.float64)).reshape(-1, h, w)
+    grp = np.tile(np.arange(L1, dtype=np.int32), n_img)
+    want = oracle.stage_matrices(y1, y2, np.repeat(cls, L1), grp, n_cls, L1, k)
+    for name in ("C11", "C22", "C12", "Cw", "CT"):
+        assert rel_fro(got[name], want[name]) <= 1e-4, name
+        assert rel_fro(got[name], want[name]) <= 5e-6, (name, "looser than expected for fp32 maps and products")
+
+
+def test_validation(ctx):
+    from paper_2209_13027_amd.binding import DdccaError
+    v1, v2, cls = rand_problem(5, 4, 16, 16, 2)
+    d1, d2, dc = dev(v1), dev(v2), dev(cls)
+    W = torch.zeros((4, 5, 5), dtype=torch.float32, device="cuda")
+    with pytest.raises(DdccaError):
+        ctx.learn_next_stage_filters(d1, d2, dc, 1, 16, 16, 2, W, W, 5, 4, batch_images=-1)
+    Wbig = torch.zeros((25, 5, 5), dtype=torch.float32, device="cuda")        # L_prev > k*k - 1
+    with pytest.raises(DdccaError):
+        ctx.learn_next_stage_filters(d1, d2, dc, 1, 16, 16, 2, Wbig, Wbig, 5, 4)
+    with pytest.raises(ValueError):
+        ctx.learn_next_stage_filters(d1, d2, dc, 2, 16, 16, 2, W, W, 5, 4)    # views do not hold G_in = 2 maps
+
+
+@pytest.mark.parametrize("name,mpc,batch", [("tiny", None, 16), ("small_face", 2, 0)])
+def test_end_to_end_with_streamed_learning(ctx, oracle, name, mpc, batch):
+    wl = WORKLOADS[name]
+    v1, v2, cls = make_views(wl, max_per_class=mpc)
+    d1, d2, dc = dev(v1), dev(v2), dev(cls)
+    model = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2, streamed=True, batch_images=batch)
+    feat = pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride)
+    ctx.status()
+    ref = oracle.two_stage(v1, v2, cls, wl.n_classes, wl.k, wl.L1, wl.L2, wl.block)
+    refs = [ref["stage1"]["W1"], ref["stage1"]["W2"], ref["stage2"]["W1"], ref["stage2"]["W2"]]
+    gaps = [ref["stage1"]["gap"], ref["stage1"]["gap"], ref["stage2"]["gap"], ref["stage2"]["gap"]]
+    for W, R, gap in zip(model["filters"], refs, gaps):
+        assert cosines(W.cpu().numpy(), R)[gap > 1e-3].min() >= 0.9999
+    assert np.allclose(model["rho"][1].cpu().numpy(), ref["stage2"]["rho"], rtol=1e-4)
+    got = feat.cpu().numpy()
+    assert got.shape == ref["hist"].shape
+    l1 = np.abs(got.astype(np.int64) - ref["hist"]).sum() / ref["hist"].sum()
+    assert l1 <= 1e-3, l1
