@@ -67,8 +67,9 @@ int ddcca_status(ddcca_ctx *ctx);
  * Accumulated: the sums over all patches of x1 x1^T, x2 x2^T, x1 x2^T, and per
  * (class, g) cell the pixel-wise sums of the member maps, from which the same-class
  * pair sum C_w and the all-pairs sum C_T follow (Section II-A: C~ = C_w - C_b,
- * C_b = C_T - C_w).  The result does not depend on how samples are split into
- * batches. */
+ * C_b = C_T - C_w).  The split of the samples into batches changes the result only
+ * through the order of the fp32 partial sums inside a batch (relative 1e-6 or less); for
+ * a given split the result is reproducible bit for bit. */
 int ddcca_corr_begin(ddcca_ctx *ctx, int k, int n_cls, int G, int h, int w);
 int ddcca_corr_accumulate(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls,
                           int64_t n_img);
@@ -169,7 +170,7 @@ int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v
  *                     2^-24 relative), another rounding order, several times the rate.
  * DDCCA_OPT_GRAM_ARITH selects the arithmetic of the patch-Gram accumulation (Section II-A
  * matrices) in the same way: DDCCA_GRAM_FP32 (default) or DDCCA_GRAM_BF16X3.  Accumulation
- * across tiles stays fp64 and the result does not depend on the batch split in either.
+ * across tiles stays fp64 in either.
  * Returns DDCCA_EINVAL for an unknown option or value, DDCCA_ESTATE when the Gram
  * arithmetic is changed between ddcca_corr_begin and the export / solve of that
  * accumulation. */
@@ -188,8 +189,8 @@ int ddcca_set_option(ddcca_ctx *ctx, int option, int value);
  *   v1, v2 : DEVICE, [n_img][G_in][h][w] float, the INPUTS of the previous stage
  *   Wp1, Wp2 : DEVICE, [L_prev][k_prev][k_prev] float, the previous stage's filters per view
  *   batch_images : samples whose maps exist at a time (0 = as many as fit 1 GiB per view);
- *                  the result does not depend on it beyond the rounding order of the fp64
- *                  accumulation across batches
+ *                  it changes the result only through the order of the fp32 partial sums
+ *                  inside a batch (relative 1e-6 or less)
  * Every batch is convolved into a scratch buffer of the context and accumulated at once.
  * The class-conditioned sum images (the C_w and C_T terms) are formed as the previous-stage
  * convolution of the inputs' sum images -- the convolution of Eq. 6 is linear -- so they

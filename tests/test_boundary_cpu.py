@@ -155,6 +155,35 @@ def test_validation_of_the_widened_calls(binding):
     lib.ddcca_destroy(h)
 
 
+def test_validation_of_next_stage_learning(binding):
+    """ddcca_learn_next_stage_filters: every argument check happens on the host, before any device work."""
+    lib = binding.lib()
+    h = make_ctx(binding)
+    one = ctypes.c_void_p(256)
+    E = binding.EINVAL
+
+    def call(v1=one, cls=one, n_img=4, G_in=1, hh=16, ww=16, n_cls=2, Wp=one, k_prev=5, L_prev=4, k=5, L=4,
+             ridge=1e-4, batch=0, W1=one):
+        return lib.ddcca_learn_next_stage_filters(h, v1, one, cls, n_img, G_in, hh, ww, n_cls, Wp, one, k_prev,
+                                                  L_prev, k, L, ridge, batch, W1, one, one)
+
+    assert call(v1=None) == E
+    assert call(cls=None) == E
+    assert call(Wp=None) == E
+    assert call(W1=None) == E
+    assert call(n_img=0) == E
+    assert call(k=4) == E and call(k_prev=11) == E
+    assert call(L=25) == E and call(L_prev=25) == E and call(L_prev=0) == E
+    assert call(G_in=0) == E
+    assert call(G_in=1024, L_prev=8) == E           # G_in * L_prev > 4096
+    assert call(ridge=0.0) == E
+    assert call(batch=-1) == E
+    assert b"batch" in lib.ddcca_last_error(h)
+    assert lib.ddcca_learn_next_stage_filters(None, one, one, one, 4, 1, 16, 16, 2, one, one, 5, 4, 5, 4, 1e-4, 0,
+                                              one, one, one) == E
+    lib.ddcca_destroy(h)
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys

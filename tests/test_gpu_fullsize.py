@@ -267,3 +267,27 @@ def test_end_to_end_on_a_slice(run, oracle):
     got = feat.cpu().numpy().astype(np.int64)
     l1 = np.abs(got - ref["hist"]).sum() / ref["hist"].sum()
     assert l1 <= 1e-3, l1
+
+
+def test_streamed_second_stage_learning_full_size(run):
+    """Second-stage learning from the inputs (maps convolved batch by batch, class sum images by linearity) at
+    full size against the materialised run of the fixture: the same matrices up to the order of the fp32 partial
+    sums, which follows the batch split (the bar of the batch-split test), and the fp32 rounding of the sum
+    images (Cw, CT); the same filters."""
+    wl, ctx = run.wl, run.ctx
+    M, h, w = run.v1.shape
+    W1a, W2a = run.model["filters"][0], run.model["filters"][1]
+    W1b, W2b, rho = ctx.learn_next_stage_filters(run.d1, run.d2, run.dc, 1, h, w, wl.n_classes, W1a, W2a, wl.k,
+                                                 wl.L2)
+    mats = {k: v.cpu().numpy() for k, v in ctx.corr_export(wl.k).items()}
+    ctx.status()
+    for name in ("C11", "C22", "C12", "Cw", "CT"):
+        assert np.linalg.norm(mats[name] - run.mats2[name]) <= 1e-6 * np.linalg.norm(run.mats2[name]), name
+    rho_m = run.model["rho"][1].cpu().numpy()
+    assert np.allclose(rho.cpu().numpy(), rho_m, rtol=1e-5)
+    sep = np.ones(wl.L2, dtype=bool)
+    sep[1:] &= rho_m[1:] < 0.999 * rho_m[:-1]
+    sep[:-1] &= rho_m[1:] < 0.999 * rho_m[:-1]
+    if sep.any():
+        assert filter_cosines(W1b.cpu().numpy(), run.filters[2].astype(np.float64))[sep].min() >= 1 - 1e-6
+        assert filter_cosines(W2b.cpu().numpy(), run.filters[3].astype(np.float64))[sep].min() >= 1 - 1e-6

@@ -2,7 +2,8 @@
 batch by batch, class-conditioned sum images by linearity of the convolution) against
 
   * the materialised route through the same library (ddcca_apply_stage + ddcca_learn_stage_filters): C11, C22, C12
-    equal up to the fp64 summation order across batches, Cw and CT up to the fp32 rounding of the sum images;
+    equal up to the summation order that follows the batch split (these small cases: fp64 only), Cw and CT up to
+    the fp32 rounding of the sum images;
   * the fp64 oracle, to the bars of the path: matrices <= 1e-4 relative (Frobenius), filters cosine >= 0.9999 where
     the canonical correlations are separated, end-to-end histograms <= 1e-3 relative L1.
 """
@@ -56,21 +57,24 @@ def matrices_of_last_learning(ctx, k):
     return {n: v.cpu().numpy() for n, v in ctx.corr_export(k).items()}
 
 
-@pytest.mark.parametrize("n_img,h,w,k,L1,L2,n_cls,batch", [
-    (12, 32, 32, 5, 4, 4, 3, 0),        # one batch
-    (12, 32, 32, 5, 4, 4, 3, 5),        # ragged batches 5 + 5 + 2
-    (7, 45, 70, 7, 8, 8, 2, 3),         # k = 7, ragged tiles
-    (5, 24, 40, 3, 3, 2, 5, 1),         # every sample its own class and its own batch
-    (6, 40, 36, 9, 8, 8, 1, 4),         # k = 9, a single class
+@pytest.mark.parametrize("n_img,G_in,h,w,k,L1,L2,n_cls,batch", [
+    (12, 1, 32, 32, 5, 4, 4, 3, 0),        # one batch
+    (12, 1, 32, 32, 5, 4, 4, 3, 5),        # ragged batches 5 + 5 + 2
+    (7, 1, 45, 70, 7, 8, 8, 2, 3),         # k = 7, ragged tiles
+    (5, 1, 24, 40, 3, 3, 2, 5, 1),         # every sample its own class and its own batch
+    (6, 1, 40, 36, 9, 8, 8, 1, 4),         # k = 9, a single class
+    (6, 3, 28, 36, 5, 4, 4, 2, 4),         # inputs that are themselves maps of an earlier stage (3 per sample)
 ])
-def test_streamed_equals_materialised(ctx, n_img, h, w, k, L1, L2, n_cls, batch):
-    v1, v2, cls = rand_problem(900 + k + n_img, n_img, h, w, n_cls)
+def test_streamed_equals_materialised(ctx, n_img, G_in, h, w, k, L1, L2, n_cls, batch):
+    v1, v2, cls = rand_problem(900 + k + n_img, n_img * G_in, h, w, n_cls)
+    cls = cls[:n_img].copy()
     d1, d2, dc = dev(v1), dev(v2), dev(cls)
-    W1a, W2a, _ = ctx.learn_stage_filters(d1, d2, dc, 1, h, w, n_cls, k, L1)
+    W1a, W2a, _ = ctx.learn_stage_filters(d1, d2, dc, G_in, h, w, n_cls, k, L1)
     y1, y2 = ctx.apply_stage(d1, W1a), ctx.apply_stage(d2, W2a)
-    Wm1, Wm2, rho_m = ctx.learn_stage_filters(y1, y2, dc, L1, h, w, n_cls, k, L2)
+    Wm1, Wm2, rho_m = ctx.learn_stage_filters(y1, y2, dc, G_in * L1, h, w, n_cls, k, L2)
     mats_m = matrices_of_last_learning(ctx, k)
-    Ws1, Ws2, rho_s = ctx.learn_next_stage_filters(d1, d2, dc, 1, h, w, n_cls, W1a, W2a, k, L2, batch_images=batch)
+    Ws1, Ws2, rho_s = ctx.learn_next_stage_filters(d1, d2, dc, G_in, h, w, n_cls, W1a, W2a, k, L2,
+                                                   batch_images=batch)
     mats_s = matrices_of_last_learning(ctx, k)
     ctx.status()
     for name in ("C11", "C22", "C12"):
