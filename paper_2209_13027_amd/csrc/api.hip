@@ -111,7 +111,8 @@ static int corr_finish(ddcca_ctx *ctx)
     if ((rc = ensure(ctx, ctx->class_img, 2 * (size_t)(n_cell + ctx->G) * P * sizeof(float)))) return rc;
     float *img = (float *)ctx->class_img.ptr;
     if (!ctx->class_img_ready &&
-        (rc = launch_class_finalize(ctx, (const double *)ctx->class_sum.ptr, ctx->n_cls, ctx->G, P, img)))
+        (rc = launch_class_finalize(ctx, (const double *)ctx->class_sum.ptr, ctx->n_cls, ctx->G, P, img,
+                                    ctx->cs_seg)))
         return rc;
     const size_t view_stride = (size_t)(n_cell + ctx->G) * P;
     const int max_slots = max_gram_slots(ctx, k);
@@ -199,7 +200,8 @@ int ddcca_corr_begin(ddcca_ctx *ctx, int k, int n_cls, int G, int h, int w)
     const size_t E = (size_t)gram_tiles(k) * 256;
     const int max_slots = max_gram_slots(ctx, k);
     if ((rc = ensure(ctx, ctx->slots, (size_t)max_slots * E * sizeof(double)))) return rc;
-    const size_t cs_bytes = 2 * (size_t)n_cls * G * P * sizeof(double);
+    const int cs_seg = class_sum_segments((int64_t)n_cls * G, P);
+    const size_t cs_bytes = (size_t)cs_seg * 2 * n_cls * G * P * sizeof(double);
     if ((rc = ensure(ctx, ctx->class_sum, cs_bytes))) return rc;
     DDCCA_HIP(ctx, hipMemsetAsync(ctx->class_sum.ptr, 0, cs_bytes, ctx->stream));
     if (!ctx->flags.ptr) {
@@ -207,6 +209,7 @@ int ddcca_corr_begin(ddcca_ctx *ctx, int k, int n_cls, int G, int h, int w)
         DDCCA_HIP(ctx, hipMemsetAsync(ctx->flags.ptr, 0, 4 * sizeof(int), ctx->stream));
     }
     ctx->k = k; ctx->n_cls = n_cls; ctx->G = G; ctx->h = h; ctx->w = w;
+    ctx->cs_seg = cs_seg;
     ctx->n_maps = 0;
     ctx->slots_valid = 0;
     ctx->corr_active = true;
@@ -229,7 +232,8 @@ int ddcca_corr_accumulate(ddcca_ctx *ctx, const float *v1, const float *v2, cons
     const int64_t n_maps = n_img * ctx->G;
     const int64_t P = (int64_t)ctx->h * ctx->w;
     if ((rc = launch_label_check(ctx, cls, n_img, ctx->n_cls, (int *)ctx->flags.ptr))) return rc;
-    if ((rc = launch_class_sum(ctx, v1, v2, cls, n_img, ctx->G, ctx->n_cls, P, (double *)ctx->class_sum.ptr)))
+    if ((rc = launch_class_sum(ctx, v1, v2, cls, n_img, ctx->G, ctx->n_cls, P, (double *)ctx->class_sum.ptr,
+                               ctx->cs_seg)))
         return rc;
     if ((rc = launch_patch_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, false, (double *)ctx->slots.ptr,
                                 max_gram_slots(ctx, ctx->k), &ctx->slots_valid)))
@@ -333,10 +337,16 @@ int ddcca_learn_next_stage_filters(ddcca_ctx *ctx, const float *v1, const float 
     const int64_t cells_in = (int64_t)n_cls * G_in, n_cell = (int64_t)n_cls * G;
     // class-conditioned sum images of the next stage = previous-stage convolution of the inputs' sum images
     if ((rc = launch_label_check(ctx, cls, n_img, n_cls, (int *)ctx->flags.ptr))) return rc;
-    if ((rc = launch_class_sum(ctx, v1, v2, cls, n_img, G_in, n_cls, P, (double *)ctx->class_sum.ptr))) return rc;
+    // (their own segmentation: the sum images of the inputs are 1/L_prev of the buffer corr_begin sized)
+    const int seg_in = class_sum_segments(cells_in, P);
+    const size_t cs_in = (size_t)seg_in * 2 * cells_in * P * sizeof(double);
+    if ((rc = ensure(ctx, ctx->class_sum, cs_in))) return rc;
+    DDCCA_HIP(ctx, hipMemsetAsync(ctx->class_sum.ptr, 0, cs_in, ctx->stream));
+    if ((rc = launch_class_sum(ctx, v1, v2, cls, n_img, G_in, n_cls, P, (double *)ctx->class_sum.ptr, seg_in)))
+        return rc;
     if ((rc = ensure(ctx, ctx->prev_img, 2 * (size_t)(cells_in + G_in) * P * sizeof(float)))) return rc;
     float *pimg = (float *)ctx->prev_img.ptr;
-    if ((rc = launch_class_finalize(ctx, (const double *)ctx->class_sum.ptr, n_cls, G_in, P, pimg))) return rc;
+    if ((rc = launch_class_finalize(ctx, (const double *)ctx->class_sum.ptr, n_cls, G_in, P, pimg, seg_in))) return rc;
     if ((rc = ensure(ctx, ctx->class_img, 2 * (size_t)(n_cell + G) * P * sizeof(float)))) return rc;
     float *cimg = (float *)ctx->class_img.ptr;
     if ((rc = run_conv(ctx, pimg, cells_in + G_in, h, w, Wp1, k_prev, L_prev, cimg))) return rc;

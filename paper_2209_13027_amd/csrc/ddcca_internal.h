@@ -40,7 +40,8 @@ struct ddcca_ctx {
     int64_t n_maps = 0;                     // maps accumulated so far (per view)
     int slots_valid = 0;                    // Gram partial slots holding data
     ddcca::Buffer slots;                    // [max_slots][tiles*256] double
-    ddcca::Buffer class_sum;                // [2][n_cls*G][h*w] double
+    ddcca::Buffer class_sum;                // [cs_seg][2][n_cls*G][h*w] double
+    int cs_seg = 1;                         // sample segments of the class-sum pass
     ddcca::Buffer class_img;                // [2][n_cls*G + G][h*w] float
     bool class_img_ready = false;           // class_img was filled directly (not from class_sum)
     ddcca::Buffer prev_img;                 // sum images of the previous stage's inputs (next-stage learning)
@@ -102,10 +103,11 @@ int launch_gram_reduce(ddcca_ctx *ctx, const double *slots, int n_slots, int k, 
 int launch_export(ddcca_ctx *ctx, const double *stacked_main, const double *stacked_cls,
                   const double *stacked_tot, int k, double n_patches, double *mats);
 int launch_label_check(ddcca_ctx *ctx, const int32_t *cls, int64_t n_img, int n_cls, int *flag);
+int class_sum_segments(int64_t n_cell, int64_t P);        // sample segments that fill the chip
 int launch_class_sum(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls, int64_t n_img,
-                     int G, int n_cls, int64_t P, double *sums /* [2][n_cls*G][P] */);
+                     int G, int n_cls, int64_t P, double *sums /* [n_seg][2][n_cls*G][P] */, int n_seg);
 int launch_class_finalize(ddcca_ctx *ctx, const double *sums, int n_cls, int G, int64_t P,
-                          float *img /* [2][n_cls*G + G][P] */);
+                          float *img /* [2][n_cls*G + G][P] */, int n_seg);
 int launch_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const double *Cw, const double *CT,
                  int k, int L, double ridge, float *W1, float *W2, double *rho);
 int launch_conv(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L,
