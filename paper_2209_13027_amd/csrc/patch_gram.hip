@@ -31,6 +31,7 @@ namespace ddcca {
 constexpr int GRAM_THREADS = 256;          // 4 wavefronts
 constexpr int GRAM_TH = 16;                // patch rows per tile
 constexpr int GRAM_TW_MAX = 128;           // patch columns per tile (multiple of 4)
+constexpr int GRAM_KU = 2;                 // k-steps whose operand reads and centre subtractions are grouped
 
 struct GramParams {
     const float *v1, *v2;                  // [n_maps][h][w]
@@ -106,37 +107,49 @@ __device__ __forceinline__ void gram_rows(const float *pix, int pitch, int rows,
     const int full = cols >> 2, tail = cols & 3;
     for (int py = pg; py < rows; py += G::NPG) {
         const float *prow = pix + py * pitch;
-        // Two k-steps per iteration with two operand sets: the operands of the next step are
-        // fetched before the MFMAs of the current one, so the LDS latency is covered.
-        float z0[NB], z1[NB];
-        if (full > 0) {
+        // KU k-steps per iteration, in phases: the LDS reads of the next KU steps (the two steps of a block
+        // pair up in one two-address read), the MFMAs of the KU current ones, then the centre subtractions
+        // of the next KU.  The fp32 matrix instructions do not overlap with the vector ALU on a SIMD, and
+        // every LDS read instruction costs the matrix pipeline about as much as two vector instructions
+        // (measured: 8 and 4 cycles per MFMA-free slot), so fewer, wider reads are what pays; more than two
+        // steps per group gain nothing further.
+        constexpr int KU = GRAM_KU;
+        float z[KU][NB];
+        const int groups = full / KU;
+        if (groups > 0) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) z0[b] = prow[pix_off[b]] - prow[cen_off[G::cen_index(b)]];
+            for (int u = 0; u < KU; ++u)
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    z[u][b] = prow[pix_off[b] + 4 * u] - prow[cen_off[G::cen_index(b)] + 4 * u];
         }
-        int kx = 0;
-        for (; kx + 1 < full; kx += 2) {
-            float pa[NB], pc[G::NCEN];
+        for (int kg = 0; kg < groups; ++kg) {
+            float pa[KU][NB], pc[KU][G::NCEN];
+            // operands of the next group of steps (the last group reads its own columns again)
+            const int nx = 4 * KU * (kg + 1 < groups ? kg + 1 : kg);
 #pragma unroll
-            for (int b = 0; b < NB; ++b) pa[b] = prow[pix_off[b] + 4 * (kx + 1)];
+            for (int u = 0; u < KU; ++u) {
 #pragma unroll
-            for (int v = 0; v < G::NCEN; ++v) pc[v] = prow[cen_off[v] + 4 * (kx + 1)];
-            __builtin_amdgcn_sched_group_barrier(0x100, NB + G::NCEN, 0);     // LDS reads first
+                for (int b = 0; b < NB; ++b) pa[u][b] = prow[pix_off[b] + nx + 4 * u];
+#pragma unroll
+                for (int v = 0; v < G::NCEN; ++v) pc[u][v] = prow[cen_off[v] + nx + 4 * u];
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, KU * (NB + G::NCEN), 0);     // LDS reads first
+#pragma unroll
+            for (int u = 0; u < KU; ++u) gram_mfma_step<G, ROLE>(z[u], acc);
+            __builtin_amdgcn_sched_group_barrier(0x008, KU * G::NACC, 0);           // then every MFMA of the group
+#pragma unroll
+            for (int u = 0; u < KU; ++u)
+#pragma unroll
+                for (int b = 0; b < NB; ++b) z[u][b] = pa[u][b] - pc[u][G::cen_index(b)];
+        }
+        for (int kx = groups * KU; kx < full; ++kx) {
+            float z0[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) z0[b] = prow[pix_off[b] + 4 * kx] - prow[cen_off[G::cen_index(b)] + 4 * kx];
             gram_mfma_step<G, ROLE>(z0, acc);
-            __builtin_amdgcn_sched_group_barrier(0x008, G::NACC, 0);    // then every MFMA of the step
-#pragma unroll
-            for (int b = 0; b < NB; ++b) z1[b] = pa[b] - pc[G::cen_index(b)];
-            const int nx = (kx + 2 < full) ? 4 * (kx + 2) : 4 * (kx + 1);
-#pragma unroll
-            for (int b = 0; b < NB; ++b) pa[b] = prow[pix_off[b] + nx];
-#pragma unroll
-            for (int v = 0; v < G::NCEN; ++v) pc[v] = prow[cen_off[v] + nx];
-            __builtin_amdgcn_sched_group_barrier(0x100, NB + G::NCEN, 0);
-            gram_mfma_step<G, ROLE>(z1, acc);
-            __builtin_amdgcn_sched_group_barrier(0x008, G::NACC, 0);
-#pragma unroll
-            for (int b = 0; b < NB; ++b) z0[b] = pa[b] - pc[G::cen_index(b)];
         }
-        if (full & 1) gram_mfma_step<G, ROLE>(z0, acc);
+        float z0[NB];
         if (tail) {                                   // ragged end of the row: patches past the image add 0
             const bool ok = q < tail;
 #pragma unroll
