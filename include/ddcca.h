@@ -188,7 +188,7 @@ int ddcca_set_option(ddcca_ctx *ctx, int option, int value);
  * ddcca_learn_stage_filters on the maps with G = G_in * L_prev.
  *   v1, v2 : DEVICE, [n_img][G_in][h][w] float, the INPUTS of the previous stage
  *   Wp1, Wp2 : DEVICE, [L_prev][k_prev][k_prev] float, the previous stage's filters per view
- *   batch_images : samples whose maps exist at a time (0 = as many as fit 1 GiB per view);
+ *   batch_images : samples whose maps exist at a time (0 = as many as fit 4 GiB per view);
  *                  it changes the result only through the order of the fp32 partial sums
  *                  inside a batch (relative 1e-6 or less)
  * Every batch is convolved into a scratch buffer of the context and accumulated at once.

@@ -357,7 +357,7 @@ int ddcca_learn_next_stage_filters(ddcca_ctx *ctx, const float *v1, const float 
     // the maps themselves, one batch of samples at a time
     const size_t per_img = (size_t)G * P * sizeof(float);
     int64_t nb = batch_images;
-    if (nb == 0) nb = std::max<int64_t>(1, (int64_t)(((size_t)1 << 30) / per_img));   // 1 GiB of maps per view
+    if (nb == 0) nb = std::max<int64_t>(1, (int64_t)(((size_t)4 << 30) / per_img));   // 4 GiB of maps per view
     nb = std::min(nb, n_img);
     if ((rc = ensure(ctx, ctx->maps1, (size_t)nb * per_img))) return rc;
     if ((rc = ensure(ctx, ctx->maps2, (size_t)nb * per_img))) return rc;
