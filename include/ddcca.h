@@ -218,6 +218,10 @@ enum {
 };
 /* While enabled, every kernel launch is bracketed by a pair of events. */
 int ddcca_profile_enable(ddcca_ctx *ctx, int on);
+/* Restrict the bracketing to the kernel ids whose bit is set (bit i = id i; default and ~0u: all).  A pair of
+ * events costs a few microseconds of stream time per launch, which a whole-path measurement that needs one
+ * kernel's durations need not pay for the others.  DDCCA_EINVAL for a mask without any known id. */
+int ddcca_profile_select(ddcca_ctx *ctx, unsigned int kernel_mask);
 /* Synchronises the stream; total_ms / launches since the last reset for one kernel id. */
 int ddcca_profile_read(ddcca_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches);
 int ddcca_profile_reset(ddcca_ctx *ctx);

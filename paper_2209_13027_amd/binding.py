@@ -25,7 +25,7 @@ EXPORTS = [
     "ddcca_dcca_solve", "ddcca_learn_stage_filters", "ddcca_apply_stage", "ddcca_hash_histogram",
     "ddcca_extract_features", "ddcca_hash_iq", "ddcca_extract_iq_features",
     "ddcca_apply_stage_hash", "ddcca_extract_features_fused", "ddcca_set_option",
-    "ddcca_learn_next_stage_filters",
+    "ddcca_learn_next_stage_filters", "ddcca_profile_select",
     "ddcca_profile_enable", "ddcca_profile_read", "ddcca_profile_reset",
 ]
 FEAT_COUNT_U16, FEAT_IQ_F32, FEAT_IQ_F16 = 0, 1, 2
@@ -86,6 +86,7 @@ def lib() -> ctypes.CDLL:
         l.ddcca_learn_next_stage_filters.argtypes = [vp, vp, vp, vp, i64, i, i, i, i, vp, vp, i, i, i, i, d, i64,
                                                      vp, vp, vp]
         l.ddcca_profile_enable.argtypes = [vp, i]
+        l.ddcca_profile_select.argtypes = [vp, ctypes.c_uint]
         l.ddcca_profile_read.argtypes = [vp, i, ctypes.POINTER(d), ctypes.POINTER(i64)]
         l.ddcca_profile_reset.argtypes = [vp]
         _lib = l
@@ -303,6 +304,11 @@ class Context:
     # ---- profiling -------------------------------------------------------------------
     def profile_enable(self, on: bool):
         self._check(lib().ddcca_profile_enable(self._h, 1 if on else 0))
+
+    def profile_select(self, names=None):
+        """Time only the named kernel families (KERNEL_NAMES) while profiling is on; None = all."""
+        mask = 0xFFFFFFFF if names is None else sum(1 << KERNEL_NAMES.index(n) for n in names)
+        self._check(lib().ddcca_profile_select(self._h, mask))
 
     def profile_reset(self):
         self._check(lib().ddcca_profile_reset(self._h))

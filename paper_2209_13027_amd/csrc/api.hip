@@ -51,7 +51,7 @@ int ensure(ddcca_ctx *ctx, Buffer &b, size_t bytes)
 
 ProfScope::ProfScope(ddcca_ctx *c, int kernel_id) : ctx(c), id(kernel_id)
 {
-    if (!ctx->prof) return;
+    if (!ctx->prof || !((ctx->prof_mask >> id) & 1u)) return;
     ProfSlot &s = ctx->prof_slot[id];
     if (s.used == s.start.size()) {
         hipEvent_t a = nullptr, b = nullptr;
@@ -67,7 +67,7 @@ ProfScope::ProfScope(ddcca_ctx *c, int kernel_id) : ctx(c), id(kernel_id)
 
 ProfScope::~ProfScope()
 {
-    if (!ctx->prof) return;
+    if (!ctx->prof || !((ctx->prof_mask >> id) & 1u)) return;
     ProfSlot &s = ctx->prof_slot[id];
     if (s.used >= s.stop.size()) return;
     (void)hipEventRecord(s.stop[s.used], ctx->stream);
@@ -203,7 +203,7 @@ int ddcca_corr_begin(ddcca_ctx *ctx, int k, int n_cls, int G, int h, int w)
     const int cs_seg = class_sum_segments((int64_t)n_cls * G, P);
     const size_t cs_bytes = (size_t)cs_seg * 2 * n_cls * G * P * sizeof(double);
     if ((rc = ensure(ctx, ctx->class_sum, cs_bytes))) return rc;
-    DDCCA_HIP(ctx, hipMemsetAsync(ctx->class_sum.ptr, 0, cs_bytes, ctx->stream));
+    if ((rc = launch_zero_sums(ctx, (double *)ctx->class_sum.ptr, cs_bytes / sizeof(double)))) return rc;
     if (!ctx->flags.ptr) {
         if ((rc = ensure(ctx, ctx->flags, 4 * sizeof(int)))) return rc;
         DDCCA_HIP(ctx, hipMemsetAsync(ctx->flags.ptr, 0, 4 * sizeof(int), ctx->stream));
@@ -341,7 +341,7 @@ int ddcca_learn_next_stage_filters(ddcca_ctx *ctx, const float *v1, const float 
     const int seg_in = class_sum_segments(cells_in, P);
     const size_t cs_in = (size_t)seg_in * 2 * cells_in * P * sizeof(double);
     if ((rc = ensure(ctx, ctx->class_sum, cs_in))) return rc;
-    DDCCA_HIP(ctx, hipMemsetAsync(ctx->class_sum.ptr, 0, cs_in, ctx->stream));
+    if ((rc = launch_zero_sums(ctx, (double *)ctx->class_sum.ptr, cs_in / sizeof(double)))) return rc;
     if ((rc = launch_class_sum(ctx, v1, v2, cls, n_img, G_in, n_cls, P, (double *)ctx->class_sum.ptr, seg_in)))
         return rc;
     if ((rc = ensure(ctx, ctx->prev_img, 2 * (size_t)(cells_in + G_in) * P * sizeof(float)))) return rc;
@@ -543,6 +543,14 @@ int ddcca_profile_enable(ddcca_ctx *ctx, int on)
 {
     if (!ctx) return DDCCA_EINVAL;
     ctx->prof = on != 0;
+    return DDCCA_OK;
+}
+
+int ddcca_profile_select(ddcca_ctx *ctx, unsigned int kernel_mask)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    if (!(kernel_mask & ((1u << DDCCA_K_COUNT) - 1u))) return fail(ctx, DDCCA_EINVAL, "profile mask selects no kernel");
+    ctx->prof_mask = kernel_mask;
     return DDCCA_OK;
 }
 

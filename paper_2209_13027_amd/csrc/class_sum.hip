@@ -8,6 +8,14 @@
 
 namespace ddcca {
 
+// Clears the sum images.  A kernel rather than a memset so that a caller may capture the learning calls into a
+// HIP graph (memset nodes are avoided).
+__global__ void zero_f64_kernel(double2 *__restrict__ p, int64_t n2)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n2; i += stride) p[i] = make_double2(0.0, 0.0);
+}
+
 __global__ void label_check_kernel(const int32_t *__restrict__ cls, int64_t n_img, int n_cls, int *flag)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -96,6 +104,17 @@ __global__ __launch_bounds__(256) void class_finalize_kernel(const double *__res
         for (int j = 0; j < 16; ++j) t += part[j][px];
         o[(n_cell + g) * P + p] = (float)t;
     }
+}
+
+int launch_zero_sums(ddcca_ctx *ctx, double *sums, size_t n)
+{
+    ProfScope prof(ctx, DDCCA_K_CLASS_SUM);
+    // n is even (two views) and the buffer comes from hipMalloc: double2 stores are aligned
+    const int64_t n2 = (int64_t)(n / 2);
+    const unsigned grid = (unsigned)std::min<int64_t>(4096, std::max<int64_t>(1, (n2 + 255) / 256));
+    hipLaunchKernelGGL(zero_f64_kernel, dim3(grid), dim3(256), 0, ctx->stream, reinterpret_cast<double2 *>(sums), n2);
+    DDCCA_HIP(ctx, hipGetLastError());
+    return DDCCA_OK;
 }
 
 int launch_label_check(ddcca_ctx *ctx, const int32_t *cls, int64_t n_img, int n_cls, int *flag)

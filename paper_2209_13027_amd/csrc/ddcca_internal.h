@@ -60,6 +60,7 @@ struct ddcca_ctx {
 
     // ---- profiling
     bool prof = false;
+    unsigned prof_mask = ~0u;               // kernel ids that are timed while prof is on
     ddcca::ProfSlot prof_slot[DDCCA_K_COUNT];
 };
 
@@ -104,6 +105,7 @@ int launch_export(ddcca_ctx *ctx, const double *stacked_main, const double *stac
                   const double *stacked_tot, int k, double n_patches, double *mats);
 int launch_label_check(ddcca_ctx *ctx, const int32_t *cls, int64_t n_img, int n_cls, int *flag);
 int class_sum_segments(int64_t n_cell, int64_t P);        // sample segments that fill the chip
+int launch_zero_sums(ddcca_ctx *ctx, double *sums, size_t n /* doubles, even */);
 int launch_class_sum(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls, int64_t n_img,
                      int G, int n_cls, int64_t P, double *sums /* [n_seg][2][n_cls*G][P] */, int n_seg);
 int launch_class_finalize(ddcca_ctx *ctx, const double *sums, int n_cls, int G, int64_t P,

@@ -34,3 +34,49 @@ def extract(ctx: Context, v1, v2, filters, k, L1, L2, block, stride, batch_image
     """dtype uint16: block histograms; float32 / float16: their information quality (Eq. 10).
     fused: second stage convolution and output layer in one kernel (same result, bit for bit)."""
     return ctx.extract_features(v1, v2, filters, k, L1, L2, block, stride, batch_images, out, dtype, fused)
+
+
+class GraphedPath:
+    """fit() + extract() of fixed device inputs, captured once into a HIP graph and replayed.
+
+    For launch-bound workloads (small images, few samples) the sixty-odd dependent launches of a step cost more
+    in launch gaps than in kernel time; a graph replays them back to back.  Everything the captured calls need
+    is allocated by one eager run first (the library grows its scratch on demand and a capture must not
+    allocate), the context lives on the capture stream, and the library clears its buffers with kernels, so the
+    graph holds kernel and copy nodes only.  Outputs are the tensors `filters`, `rho` and `feat`, rewritten by
+    every replay().  Class labels outside [0, n_cls) are reported by status() after a replay.
+    """
+
+    def __init__(self, v1, v2, cls, n_cls, k, L1, L2, block, stride, ridge=1e-4, batch_images=0,
+                 dtype=torch.uint16, fused=False, device=0, out=None, options=()):
+        """out: feature tensor to write (else one is allocated); options: (option, value) pairs for set_option."""
+        self.stream = torch.cuda.Stream(device)
+        self.stream.wait_stream(torch.cuda.current_stream(device))
+        with torch.cuda.stream(self.stream):
+            self.ctx = Context(device)
+            for opt, val in options:
+                self.ctx.set_option(opt, val)
+
+            def run():
+                model = fit(self.ctx, v1, v2, cls, n_cls, k, L1, L2, ridge)
+                feat = extract(self.ctx, v1, v2, model["filters"], k, L1, L2, block, stride, batch_images, out,
+                               dtype, fused)
+                return model, feat
+
+            run()                                   # eager: every scratch buffer reaches its final size
+            self.ctx.status()
+            self.graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(self.graph, stream=self.stream):
+                model, self.feat = run()
+        self.filters, self.rho = model["filters"], model["rho"]
+        self._inputs = (v1, v2, cls)               # the graph reads these buffers on every replay
+
+    def replay(self):
+        self.graph.replay()
+
+    def status(self):
+        self.ctx.status()
+
+    def close(self):
+        self.graph = None
+        self.ctx.close()

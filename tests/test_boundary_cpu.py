@@ -152,6 +152,12 @@ def test_validation_of_the_widened_calls(binding):
     assert lib.ddcca_set_option(h, binding.OPT_GRAM_ARITH, -1) == E
     assert lib.ddcca_set_option(h, 99, 0) == E
     assert lib.ddcca_set_option(None, binding.OPT_CONV_ARITH, 0) == E
+    # timing selection: any mask with a known kernel id; none is an error
+    assert lib.ddcca_profile_select(h, 1) == binding.OK
+    assert lib.ddcca_profile_select(h, 0xFFFFFFFF) == binding.OK
+    assert lib.ddcca_profile_select(h, 0) == E
+    assert lib.ddcca_profile_select(h, 1 << 20) == E
+    assert lib.ddcca_profile_select(None, 1) == E
     lib.ddcca_destroy(h)
 
 
