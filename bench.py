@@ -230,6 +230,7 @@ def main():
         pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride, batch, out=feat,
                          dtype=feat_dtype, fused=True)          # untimed: first launch loads the kernel
         ctx.profile_reset()
+        ctx.profile_select(["conv_hash_hist"])
         ctx.profile_enable(True)
         phases["extract_fused"] = timed(lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2,
                                                                  wl.block, wl.stride, batch, out=feat,
@@ -248,6 +249,7 @@ def main():
                                        batch, out=feat, dtype=feat_dtype)
         run()
         ctx.profile_reset()
+        ctx.profile_select(["conv"])
         ctx.profile_enable(True)
         phases["extract_conv_bf16x3"] = timed(run)
         ctx.profile_enable(False)
@@ -268,6 +270,7 @@ def main():
                              dtype=feat_dtype, fused=True)
         fast_step()
         ctx.profile_reset()
+        ctx.profile_select(["gram", "conv_hash_hist"])
         ctx.profile_enable(True)
         fast = timed(fast_step)
         ctx.profile_enable(False)
@@ -279,6 +282,7 @@ def main():
         fast["options"] = "gram bf16x3, conv bf16x3, fused last stage"
         ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
         ctx.set_option(OPT_GRAM_ARITH, GRAM_FP32)
+    ctx.profile_select(None)
     ctx.status()
 
     work = algorithmic_work(wl, M, feat.element_size())
