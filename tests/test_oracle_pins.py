@@ -409,6 +409,30 @@ def test_class_sums_equal_gram_of_class_sum_images(oracle):
     assert np.abs(ST - GT).max() <= 1e-12 * np.abs(ST).max()
 
 
+def test_second_stage_class_sums_from_the_inputs_sum_images(oracle):
+    # Eq. 6 is linear: the sum of a class's stage-1 maps is the stage-1 convolution of the class's sum image, so
+    # the second stage's Sw / ST follow from the INPUTS' sum images convolved with the stage-1 filters (the route
+    # the library's streamed second-stage learning takes); here on the oracle alone, in fp64
+    rng = np.random.default_rng(23)
+    n, h, w, k, L1 = 6, 8, 9, 3, 3
+    V1, V2 = rand_views(rng, n, h, w)
+    F1, F2 = rng.standard_normal((L1, k, k)), rng.standard_normal((L1, k, k))
+    cls = np.array([0, 1, 1, 0, 2, 1], dtype=np.int32)
+    Y1 = oracle.conv(V1, F1).reshape(n * L1, h, w)
+    Y2 = oracle.conv(V2, F2).reshape(n * L1, h, w)
+    Sw, ST = oracle.class_sums(Y1, Y2, np.repeat(cls, L1), np.tile(np.arange(L1, dtype=np.int32), n), 3, L1, k)
+    S1 = np.stack([V1[cls == c].sum(0) for c in range(3)])
+    S2 = np.stack([V2[cls == c].sum(0) for c in range(3)])
+    C1 = oracle.conv(S1, F1).reshape(3 * L1, h, w)               # cell (c, g) = conv of class c's sum image, filter g
+    C2 = oracle.conv(S2, F2).reshape(3 * L1, h, w)
+    _, _, G12 = oracle.corr_sums(C1, C2, k)
+    assert np.abs(Sw - G12).max() <= 1e-12 * np.abs(Sw).max()
+    T1 = oracle.conv(V1.sum(0, keepdims=True), F1).reshape(L1, h, w)
+    T2 = oracle.conv(V2.sum(0, keepdims=True), F2).reshape(L1, h, w)
+    _, _, GT = oracle.corr_sums(T1, T2, k)
+    assert np.abs(ST - GT).max() <= 1e-12 * np.abs(ST).max()
+
+
 def test_iq_probabilities_sum_to_one_and_hand_values(oracle):
     """Eq. 10 with one pseudo-count per bin: exp(-o) is a distribution over the bins of every block;
     a block of 4 pixels with codes {0, 0, 3, 1} over 4 bins gives p = 3/8, 2/8, 1/8, 2/8."""
