@@ -1,9 +1,11 @@
 // DCCA solve (Eq. 2-3) in one workgroup, fp64, matrices resident in LDS:
 //   B_d = C_dd + eps_d I (ridge), C~ = 2 C_w - C_T
 //   B_d = L_d L_d^T (Cholesky), L_d^{-1} formed in place, T = L_1^{-1} C~ L_2^{-T}
-//   T = U diag(sigma) V^T: one-sided (Hestenes) Jacobi rotations of column pairs of T in
-//   round-robin order, one 8-lane group per pair, one barrier per round; V is not
-//   accumulated (v = T^T u / sigma for the L leading triplets only)
+//   T = Q R by modified Gram-Schmidt (one barrier per column; only R is kept), then R^T = Z diag(sigma) W^T
+//   by one-sided (Hestenes) Jacobi rotations of column pairs of R^T in round-robin order, one 8-lane group
+//   per pair, one barrier per round.  The triangular factor takes a third fewer sweeps than T itself on the
+//   graded matrices of image patches, and T = (Q W) diag(sigma) Z^T: the right singular vectors v of T are
+//   the normalised columns the rotations end with, u = T v / sigma for the L leading triplets only
 //   w_1 = L_1^{-T} u,  w_2 = L_2^{-T} v,  rho = sigma
 // The leading L pairs are written as fp32 filters (Eq. 4-5: row-major k x k).
 #include "ddcca_internal.h"
@@ -210,11 +212,51 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
     }
     __syncthreads();
 
-    // ---- one-sided (Hestenes) Jacobi on T: A holds T^T (one column of T per row) -------------
+    // ---- A <- T^T (one column of T per row)
     for (int e = tid; e < DD; e += nt) {
         const int pcol = e / D, i = e - pcol * D;
         A[e] = C[i * D + pcol];
     }
+    // ---- T = Q R by modified Gram-Schmidt on the columns of T (rows of A); row j of R goes to row j of B.
+    //      Step j: every later column i takes r_ji = a_j . a_i / |a_j| and drops its component along a_j; a_j
+    //      itself is only read, so one barrier per step is enough.
+    for (int e = tid; e < DD; e += nt) B[e] = 0.0;
+    __syncthreads();
+    {
+        constexpr int MR = (D + 7) / 8, NG8 = SOLVE_THREADS / 8;
+        const int g8 = tid >> 3, m8 = tid & 7;
+        for (int j = 0; j < D; ++j) {
+            for (int i = j + g8; i < D; i += NG8) {
+                const double *aj = A + j * D;
+                double *ai = A + i * D;
+                double xj[MR], xi[MR];
+                double dj = 0.0, di = 0.0, unused = 0.0;
+#pragma unroll
+                for (int r = 0; r < MR; ++r) {
+                    const int e = m8 + 8 * r;
+                    xj[r] = e < D ? aj[e] : 0.0;
+                    xi[r] = e < D ? ai[e] : 0.0;
+                    dj += xj[r] * xj[r];
+                    di += xj[r] * xi[r];
+                }
+                group8_sum3(dj, di, unused);
+                const double rinv = dj > 0.0 ? fast_rsqrt(dj) : 0.0;
+                if (i == j) {
+                    if (m8 == 0) B[j * D + j] = dj * rinv;
+                } else {
+                    const double rji = di * rinv, coef = rji * rinv;
+#pragma unroll
+                    for (int r = 0; r < MR; ++r) {
+                        const int e = m8 + 8 * r;
+                        if (e < D) ai[e] = xi[r] - coef * xj[r];
+                    }
+                    if (m8 == 0) B[j * D + i] = rji;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    double *const J = B;                          // the rotations work on the rows of B = columns of R^T
     if (tid == 0) flag[0] = 0;
     __syncthreads();
     STAMP(4);
@@ -243,7 +285,7 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
                 }
                 const int pp = min(a, b), qq = max(a, b);
                 if (qq < D) {
-                    double *gp = A + pp * D, *gq = A + qq * D;
+                    double *gp = J + pp * D, *gq = J + qq * D;
                     double x[JR], y[JR];
 #pragma unroll
                     for (int r = 0; r < JR; ++r) {
@@ -299,7 +341,7 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
 
     // ---- squared singular values = squared column norms; order them (descending, index breaks ties)
     for (int col = grp; col < D; col += NGRP) {
-        const double *gp = A + col * D;
+        const double *gp = J + col * D;
         double al = 0.0;
         for (int i = l16; i < D; i += 16) al += gp[i] * gp[i];
         al = row16_sum(al);
@@ -317,22 +359,23 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
     }
     __syncthreads();
 
-    // ---- u_g = g_j / sigma_j into B[g][:];  v_g = T^T u_g (unscaled) into A[g][:] -------------
+    // ---- v_g = (column j of the rotated R^T) / sigma_j into A[g][:];  u_g = T v_g (unscaled) into B[g][:]
     for (int e = tid; e < L * D; e += nt) {
         const int g = e / D, i = e - g * D;
         const int j = order[g];
         const double l2 = lam[j];
-        B[e] = l2 > 0.0 ? A[j * D + i] * fast_rsqrt(l2) : 0.0;
+        A[e] = l2 > 0.0 ? J[j * D + i] * fast_rsqrt(l2) : 0.0;
     }
     __syncthreads();
     for (int e = tid; e < L * D; e += nt) {
-        const int g = e / D, c = e - g * D;
+        const int g = e / D, i = e - g * D;
         double s = 0.0;
-        for (int i = 0; i < D; ++i) s += C[i * D + c] * B[g * D + i];
-        A[e] = s;                                   // scaled to unit length below
+        for (int c = 0; c < D; ++c) s += C[i * D + c] * A[g * D + c];
+        B[e] = s;                                   // scaled to unit length below
     }
     __syncthreads();
-    // ---- w1 = L1^{-T} u: one 16-lane group per pair g; sign from the largest-magnitude entry
+    // ---- w1 = L1^{-T} u, u normalised to unit length: one 16-lane group per pair g; sign from the
+    //      largest-magnitude entry
     for (int e = tid; e < DD; e += nt) C[e] = p.gI1[e];
     __syncthreads();
     double sign_of[GPASS];
@@ -342,6 +385,10 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
         double sg = 1.0;
         if (g < L) {
             const double *u = B + g * D;
+            double nu = 0.0;
+            for (int i = l16; i < D; i += 16) nu += u[i] * u[i];
+            nu = row16_sum(nu);
+            const double scale = nu > 0.0 ? fast_rsqrt(nu) : 0.0;
             double w[NR];
             double best = -1.0;
 #pragma unroll
@@ -350,8 +397,8 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
                 double s = 0.0;
                 if (i < D)
                     for (int j = i; j < D; ++j) s += C[j * D + i] * u[j];
-                w[r] = s;
-                if (i < D) best = fmax(best, fabs(s));
+                w[r] = scale * s;
+                if (i < D) best = fmax(best, fabs(w[r]));
             }
             const double top = row16_max(best);
             int arg = 1 << 30;
@@ -380,7 +427,7 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
         sign_of[pass] = sg;
     }
     __syncthreads();
-    // ---- w2 = L2^{-T} v, v normalised to unit length, same sign --------------------------------
+    // ---- w2 = L2^{-T} v (v has unit length), same sign ------------------------------------------
     for (int e = tid; e < DD; e += nt) C[e] = p.gI2[e];
     __syncthreads();
 #pragma unroll
@@ -388,17 +435,13 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
         const int g = grp + pass * NGRP;
         if (g < L) {
             const double *v = A + g * D;
-            double nv = 0.0;
-            for (int i = l16; i < D; i += 16) nv += v[i] * v[i];
-            nv = row16_sum(nv);
-            const double scale = nv > 0.0 ? sign_of[pass] * fast_rsqrt(nv) : 0.0;
 #pragma unroll
             for (int r = 0; r < NR; ++r) {
                 const int i = l16 + 16 * r;
                 if (i < D) {
                     double s = 0.0;
                     for (int j = i; j < D; ++j) s += C[j * D + i] * v[j];
-                    p.W2[g * D + i] = (float)(scale * s);
+                    p.W2[g * D + i] = (float)(sign_of[pass] * s);
                 }
             }
         }
