@@ -109,6 +109,31 @@ def test_streamed_matrices_against_oracle(ctx, oracle):
         assert rel_fro(got[name], want[name]) <= 5e-6, (name, "looser than expected for fp32 maps and products")
 
 
+def test_streamed_learning_with_three_piece_arithmetic(oracle):
+    """The same call with the Gram and the convolution on three-piece bf16 operands: the bars of the path."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2209_13027_amd.binding import (Context, OPT_CONV_ARITH, CONV_BF16X3, OPT_GRAM_ARITH, GRAM_BF16X3)
+    c = Context(0)
+    c.set_option(OPT_CONV_ARITH, CONV_BF16X3)
+    c.set_option(OPT_GRAM_ARITH, GRAM_BF16X3)
+    n_img, h, w, k, L1, n_cls = 8, 36, 50, 7, 8, 4
+    v1, v2, cls = rand_problem(31, n_img, h, w, n_cls)
+    d1, d2, dc = dev(v1), dev(v2), dev(cls)
+    W1a, W2a, _ = c.learn_stage_filters(d1, d2, dc, 1, h, w, n_cls, k, L1)
+    c.learn_next_stage_filters(d1, d2, dc, 1, h, w, n_cls, W1a, W2a, k, 8, batch_images=3)
+    got = matrices_of_last_learning(c, k)
+    c.status()
+    y1 = oracle.conv(v1.astype(np.float64), W1a.cpu().numpy().astype(np.float64)).reshape(-1, h, w)
+    y2 = oracle.conv(v2.astype(np.float64), W2a.cpu().numpy().astype(np.float64)).reshape(-1, h, w)
+    grp = np.tile(np.arange(L1, dtype=np.int32), n_img)
+    want = oracle.stage_matrices(y1, y2, np.repeat(cls, L1), grp, n_cls, L1, k)
+    for name in ("C11", "C22", "C12", "Cw", "CT"):
+        assert rel_fro(got[name], want[name]) <= 1e-4, name
+        assert rel_fro(got[name], want[name]) <= 5e-6, (name, "looser than expected")
+    c.close()
+
+
 def test_validation(ctx):
     from paper_2209_13027_amd.binding import DdccaError
     v1, v2, cls = rand_problem(5, 4, 16, 16, 2)
