@@ -171,6 +171,15 @@ int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v
  * DDCCA_OPT_GRAM_ARITH selects the arithmetic of the patch-Gram accumulation (Section II-A
  * matrices) in the same way: DDCCA_GRAM_FP32 (default) or DDCCA_GRAM_BF16X3.  Accumulation
  * across tiles stays fp64 in either.
+ *   DDCCA_GRAM_LAG_FP32   the same matrices from the lag structure of the patch Gram: with the
+ *                     images extended by zeros, the raw Gram entry of taps a and b summed over
+ *                     all patch centres of the plane is the correlation of the two views at
+ *                     lag s_b - s_a, (2k-1)^2 values per view pair instead of k^4, computed on
+ *                     the fp32 matrix instructions and added up in fp64 row by row; the patches
+ *                     centred in the frame of width (k-1)/2 outside the image are accumulated by
+ *                     the dense kernel and subtracted.  Same result up to fp32 rounding (same
+ *                     bars), several times fewer matrix instructions.  k <= 7; k = 9 runs the
+ *                     dense fp32 kernel.
  * Returns DDCCA_EINVAL for an unknown option or value, DDCCA_ESTATE when the Gram
  * arithmetic is changed between ddcca_corr_begin and the export / solve of that
  * accumulation. */
@@ -180,6 +189,7 @@ int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v
 #define DDCCA_OPT_GRAM_ARITH 2
 #define DDCCA_GRAM_FP32      0
 #define DDCCA_GRAM_BF16X3    1
+#define DDCCA_GRAM_LAG_FP32  2
 int ddcca_set_option(ddcca_ctx *ctx, int option, int value);
 
 /* Learn the filters of the stage that follows a given stage (Section II-B: the second stage

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libddcca.so")
 SOURCES = ["api.hip", "patch_gram.hip", "class_sum.hip", "dcca_solve.hip", "conv_multi.hip", "hash_hist.hip",
-           "conv_hash_hist.hip", "conv_split.hip"]
+           "conv_hash_hist.hip", "conv_split.hip", "lag_gram.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall",
     # hipcc must not form packed fp32 instructions on this target

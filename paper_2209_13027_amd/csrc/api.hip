@@ -93,6 +93,42 @@ static void free_buffer(Buffer &b)
     b.bytes = 0;
 }
 
+// The Gram contribution of n_maps map pairs: the dense kernel, or the lag correlations plus the dense Gram of the
+// frame outside the image that they over-count.
+static int accumulate_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps)
+{
+    int rc;
+    if (ctx->lag_active) {
+        if ((rc = launch_lag_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, false, (double *)ctx->lag_slots.ptr,
+                                  max_lag_slots(ctx), &ctx->lag_valid)))
+            return rc;
+        return launch_patch_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, false, (double *)ctx->slots.ptr,
+                                 max_gram_slots(ctx, ctx->k), &ctx->slots_valid, true);
+    }
+    return launch_patch_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, false, (double *)ctx->slots.ptr,
+                             max_gram_slots(ctx, ctx->k), &ctx->slots_valid);
+}
+
+// Gram of the cross-view block of n_img image pairs into stacked_out (fresh slots), dense or lag-structured.
+static int cross_gram(ddcca_ctx *ctx, const float *img1, const float *img2, int64_t n_img, double *stacked_out)
+{
+    const int k = ctx->k;
+    int rc, valid = 0;
+    if ((rc = launch_patch_gram(ctx, img1, img2, n_img, ctx->h, ctx->w, k, true, (double *)ctx->slots.ptr,
+                                max_gram_slots(ctx, k), &valid, ctx->lag_active)))
+        return rc;
+    if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, valid, k, stacked_out))) return rc;
+    if (!ctx->lag_active) return DDCCA_OK;
+    int lvalid = 0;
+    if ((rc = launch_lag_gram(ctx, img1, img2, n_img, ctx->h, ctx->w, k, true, (double *)ctx->lag_slots.ptr,
+                              max_lag_slots(ctx), &lvalid)))
+        return rc;
+    if ((rc = launch_reduce_slots(ctx, (const double *)ctx->lag_slots.ptr, lvalid, LAG_SLOT_DOUBLES,
+                                  (double *)ctx->lag_R.ptr)))
+        return rc;
+    return launch_lag_to_stacked(ctx, (const double *)ctx->lag_R.ptr, stacked_out, k, true);
+}
+
 // Finish the accumulation: Gram partials -> stacked Gram, class sums -> class / total
 // images -> their Grams, then the five normalised matrices in ctx->mats.
 static int corr_finish(ddcca_ctx *ctx)
@@ -107,6 +143,12 @@ static int corr_finish(ddcca_ctx *ctx)
     if ((rc = ensure(ctx, ctx->mats, 5 * (size_t)D * D * sizeof(double)))) return rc;
     double *st = (double *)ctx->stacked.ptr;
     if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, ctx->slots_valid, k, st))) return rc;
+    if (ctx->lag_active) {
+        if ((rc = launch_reduce_slots(ctx, (const double *)ctx->lag_slots.ptr, ctx->lag_valid, LAG_SLOT_DOUBLES,
+                                      (double *)ctx->lag_R.ptr)))
+            return rc;
+        if ((rc = launch_lag_to_stacked(ctx, (const double *)ctx->lag_R.ptr, st, k, false))) return rc;
+    }
 
     if ((rc = ensure(ctx, ctx->class_img, 2 * (size_t)(n_cell + ctx->G) * P * sizeof(float)))) return rc;
     float *img = (float *)ctx->class_img.ptr;
@@ -115,15 +157,9 @@ static int corr_finish(ddcca_ctx *ctx)
                                     ctx->cs_seg)))
         return rc;
     const size_t view_stride = (size_t)(n_cell + ctx->G) * P;
-    const int max_slots = max_gram_slots(ctx, k);
-    int valid = 0;
-    if ((rc = launch_patch_gram(ctx, img, img + view_stride, n_cell, ctx->h, ctx->w, k, true,
-                                (double *)ctx->slots.ptr, max_slots, &valid))) return rc;
-    if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, valid, k, st + E))) return rc;
-    valid = 0;
-    if ((rc = launch_patch_gram(ctx, img + (size_t)n_cell * P, img + view_stride + (size_t)n_cell * P, ctx->G,
-                                ctx->h, ctx->w, k, true, (double *)ctx->slots.ptr, max_slots, &valid))) return rc;
-    if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, valid, k, st + 2 * E))) return rc;
+    if ((rc = cross_gram(ctx, img, img + view_stride, n_cell, st + E))) return rc;
+    if ((rc = cross_gram(ctx, img + (size_t)n_cell * P, img + view_stride + (size_t)n_cell * P, ctx->G, st + 2 * E)))
+        return rc;
     const double N = (double)ctx->n_maps * (double)P;
     if ((rc = launch_export(ctx, st, st + E, st + 2 * E, k, N, (double *)ctx->mats.ptr))) return rc;
     ctx->corr_exported = true;
@@ -157,8 +193,8 @@ void ddcca_destroy(ddcca_ctx *ctx)
     if (touched) {
         (void)hipSetDevice(ctx->device);
         (void)hipStreamSynchronize(ctx->stream);
-        for (Buffer *b : {&ctx->slots, &ctx->class_sum, &ctx->class_img, &ctx->stacked, &ctx->seg, &ctx->mats,
-                          &ctx->solve_ws, &ctx->flags, &ctx->maps1, &ctx->maps2, &ctx->iq_lut})
+        for (Buffer *b : {&ctx->lag_slots, &ctx->lag_R, &ctx->prev_img, &ctx->slots, &ctx->class_sum, &ctx->class_img,
+                          &ctx->stacked, &ctx->seg, &ctx->mats, &ctx->solve_ws, &ctx->flags, &ctx->maps1, &ctx->maps2, &ctx->iq_lut})
             free_buffer(*b);
         for (ProfSlot &s : ctx->prof_slot) {
             for (hipEvent_t e : s.start) (void)hipEventDestroy(e);
@@ -208,6 +244,12 @@ int ddcca_corr_begin(ddcca_ctx *ctx, int k, int n_cls, int G, int h, int w)
         if ((rc = ensure(ctx, ctx->flags, 4 * sizeof(int)))) return rc;
         DDCCA_HIP(ctx, hipMemsetAsync(ctx->flags.ptr, 0, 4 * sizeof(int), ctx->stream));
     }
+    ctx->lag_active = ctx->gram_arith == DDCCA_GRAM_LAG_FP32 && lag_supported(k);
+    if (ctx->lag_active) {
+        if ((rc = ensure(ctx, ctx->lag_slots, (size_t)max_lag_slots(ctx) * LAG_SLOT_DOUBLES * sizeof(double)))) return rc;
+        if ((rc = ensure(ctx, ctx->lag_R, (size_t)LAG_SLOT_DOUBLES * sizeof(double)))) return rc;
+    }
+    ctx->lag_valid = 0;
     ctx->k = k; ctx->n_cls = n_cls; ctx->G = G; ctx->h = h; ctx->w = w;
     ctx->cs_seg = cs_seg;
     ctx->n_maps = 0;
@@ -235,9 +277,7 @@ int ddcca_corr_accumulate(ddcca_ctx *ctx, const float *v1, const float *v2, cons
     if ((rc = launch_class_sum(ctx, v1, v2, cls, n_img, ctx->G, ctx->n_cls, P, (double *)ctx->class_sum.ptr,
                                ctx->cs_seg)))
         return rc;
-    if ((rc = launch_patch_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, false, (double *)ctx->slots.ptr,
-                                max_gram_slots(ctx, ctx->k), &ctx->slots_valid)))
-        return rc;
+    if ((rc = accumulate_gram(ctx, v1, v2, n_maps))) return rc;
     ctx->n_maps += n_maps;
     return DDCCA_OK;
 }
@@ -366,9 +406,7 @@ int ddcca_learn_next_stage_filters(ddcca_ctx *ctx, const float *v1, const float 
         const int64_t b = std::min(nb, n_img - i0);
         if ((rc = run_conv(ctx, v1 + (size_t)i0 * G_in * P, b * G_in, h, w, Wp1, k_prev, L_prev, m1))) return rc;
         if ((rc = run_conv(ctx, v2 + (size_t)i0 * G_in * P, b * G_in, h, w, Wp2, k_prev, L_prev, m2))) return rc;
-        if ((rc = launch_patch_gram(ctx, m1, m2, b * G, h, w, k, false, (double *)ctx->slots.ptr,
-                                    max_gram_slots(ctx, k), &ctx->slots_valid)))
-            return rc;
+        if ((rc = accumulate_gram(ctx, m1, m2, b * G))) return rc;
         ctx->n_maps += b * G;
     }
     return ddcca_solve_filters(ctx, L, ridge, W1, W2, rho);
@@ -384,7 +422,7 @@ int ddcca_set_option(ddcca_ctx *ctx, int option, int value)
             ctx->conv_arith = value;
             return DDCCA_OK;
         case DDCCA_OPT_GRAM_ARITH:
-            if (value != DDCCA_GRAM_FP32 && value != DDCCA_GRAM_BF16X3)
+            if (value != DDCCA_GRAM_FP32 && value != DDCCA_GRAM_BF16X3 && value != DDCCA_GRAM_LAG_FP32)
                 return fail(ctx, DDCCA_EINVAL, "unknown Gram arithmetic");
             if (ctx->corr_active && !ctx->corr_exported)
                 return fail(ctx, DDCCA_ESTATE, "cannot change the Gram arithmetic during an accumulation");

@@ -1,0 +1,115 @@
+"""GPU parity of the lag-structured patch-Gram accumulation (DDCCA_GRAM_LAG_FP32: lag correlations of the
+zero-extended images on the fp32 matrix instructions, minus the dense Gram of the patches centred in the frame
+outside the image) against the fp64 oracle, to the same bars as the dense kernel: relative Frobenius error of
+the five matrices <= 1e-4 required, <= 2e-6 expected (fp32 products, fp64 sums from one image row on)."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2209_13027_amd.binding import OPT_GRAM_ARITH, GRAM_LAG_FP32  # noqa: E402
+from paper_2209_13027_amd.workloads import WORKLOADS, make_views  # noqa: E402
+from paper_2209_13027_amd import pipeline  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2209_13027_amd.binding import Context
+    c = Context(0)
+    c.set_option(OPT_GRAM_ARITH, GRAM_LAG_FP32)
+    yield c
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def rel_fro(a, b):
+    return np.linalg.norm(a - b) / np.linalg.norm(b)
+
+
+def rand_views(rng, n, h, w):
+    v1 = rng.standard_normal((n, h, w)).astype(np.float32)
+    v2 = (np.abs(rng.standard_normal((n, h, w))) * 2 + 5).astype(np.float32)     # large DC level
+    return v1, v2
+
+
+def gpu_matrices(ctx, V1, V2, cls, n_cls, G, k, cuts=None):
+    n_img = len(cls)
+    h, w = V1.shape[-2:]
+    ctx.corr_begin(k, n_cls, G, h, w)
+    cuts = cuts or [0, n_img]
+    d1, d2, dc = dev(V1), dev(V2), dev(cls.astype(np.int32))
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        ctx.corr_accumulate(d1[a * G:b * G], d2[a * G:b * G], dc[a:b])
+    out = {k_: v.cpu().numpy() for k_, v in ctx.corr_export(k).items()}
+    ctx.status()
+    return out
+
+
+@pytest.mark.parametrize("n_img,G,h,w,k,n_cls", [
+    (8, 1, 32, 32, 5, 4),        # tiny geometry
+    (6, 1, 112, 92, 7, 3),       # small-face geometry
+    (4, 2, 40, 52, 9, 2),        # k=9: the dense kernel takes over
+    (5, 3, 21, 30, 3, 2),        # k=3, ragged rows (21) and columns (30 = 4*7+2)
+    (3, 1, 37, 133, 5, 3),       # two column tiles, ragged tail (133 = 4*33+1)
+    (2, 4, 16, 260, 7, 2),       # three column tiles
+    (1, 1, 3, 3, 7, 1),          # image smaller than the patch: every lag window leaves the image
+    (2, 1, 5, 40, 7, 2),         # image lower than the frame is wide
+    (3, 1, 50, 128, 5, 2),       # full-width tiles
+])
+def test_corr_matrices_lag(ctx, oracle, n_img, G, h, w, k, n_cls):
+    rng = np.random.default_rng(700 + k + h)
+    V1, V2 = rand_views(rng, n_img * G, h, w)
+    cls = rng.integers(0, n_cls, size=n_img).astype(np.int32)
+    got = gpu_matrices(ctx, V1, V2, cls, n_cls, G, k)
+    grp = np.tile(np.arange(G, dtype=np.int32), len(cls))
+    want = oracle.stage_matrices(V1, V2, np.repeat(cls, G), grp, n_cls, G, k)
+    for name in ("C11", "C22", "C12", "Cw", "CT"):
+        assert rel_fro(got[name], want[name]) <= 1e-4, name
+        assert rel_fro(got[name], want[name]) <= 2e-6, (name, "looser than expected for fp32 products")
+
+
+def test_corr_batch_split_invariance_lag(ctx):
+    rng = np.random.default_rng(44)
+    V1, V2 = rand_views(rng, 14, 24, 28)
+    cls = rng.integers(0, 3, size=7).astype(np.int32)
+    ref = gpu_matrices(ctx, V1, V2, cls, 3, 2, 5)
+    for cuts in ([0, 1, 7], [0, 3, 4, 7], list(range(8))):
+        got = gpu_matrices(ctx, V1, V2, cls, 3, 2, 5, cuts)
+        for name in ref:
+            assert rel_fro(got[name], ref[name]) <= 1e-6, (name, cuts)
+
+
+def test_gram_arith_cannot_change_mid_accumulation(ctx):
+    from paper_2209_13027_amd.binding import DdccaError, GRAM_FP32
+    ctx.corr_begin(5, 2, 1, 16, 16)
+    with pytest.raises(DdccaError):
+        ctx.set_option(OPT_GRAM_ARITH, GRAM_FP32)
+    z = torch.zeros((2, 16, 16), dtype=torch.float32, device="cuda")
+    ctx.corr_accumulate(z, z, torch.zeros(2, dtype=torch.int32, device="cuda"))
+    ctx.corr_export(5)
+
+
+@pytest.mark.parametrize("name,images", [("tiny", None), ("small_face", 3)])
+def test_end_to_end_lag(ctx, oracle, name, images):
+    wl = WORKLOADS[name]
+    v1, v2, cls = make_views(wl, max_per_class=images)
+    d1, d2, dc = dev(v1), dev(v2), dev(cls)
+    model = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
+    feat = pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride, 0)
+    ref = oracle.two_stage(v1, v2, cls, wl.n_classes, wl.k, wl.L1, wl.L2, wl.block, wl.stride)
+    for s in (0, 1):
+        st = ref["stage%d" % (s + 1)]
+        for d in (0, 1):
+            W = model["filters"][2 * s + d].cpu().numpy().reshape(-1, wl.k * wl.k)
+            F = st["F%d" % (d + 1)].reshape(-1, wl.k * wl.k)
+            cos = np.sum(W * F, axis=1) / (np.linalg.norm(W, axis=1) * np.linalg.norm(F, axis=1))
+            ok = st["gap"] > 1e-3
+            assert cos[ok].min() >= 0.9999
+    got = feat.cpu().numpy().astype(np.int64)
+    assert np.abs(got - ref["hist"]).sum() / ref["hist"].sum() <= 1e-3
