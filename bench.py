@@ -97,9 +97,10 @@ def main():
     ap.add_argument("--conv", default="fp32", choices=["fp32", "bf16x3"],
                     help="arithmetic of the stage convolution: fp32 matrix instructions (the headline path) or "
                          "three-piece bf16 operands on the bf16 matrix pipeline (same accuracy)")
-    ap.add_argument("--gram", default="fp32", choices=["fp32", "bf16x3"],
-                    help="arithmetic of the patch-Gram accumulation: fp32 matrix instructions (the headline path) "
-                         "or three-piece bf16 operands on the bf16 matrix pipeline (same accuracy)")
+    ap.add_argument("--gram", default="fp32", choices=["fp32", "bf16x3", "lag"],
+                    help="arithmetic of the patch-Gram accumulation: fp32 matrix instructions (the headline path), "
+                         "three-piece bf16 operands on the bf16 matrix pipeline (same accuracy), or the "
+                         "lag-structured form on the fp32 matrix instructions (k <= 7; same accuracy)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=0, help="images in the CPU-oracle sample (0 = default)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -123,9 +124,9 @@ def main():
     v1, v2, cls = make_views(wl)
     M = int(v1.shape[0])
     ctx = Context(0)
-    if args.gram == "bf16x3":
-        from paper_2209_13027_amd.binding import OPT_GRAM_ARITH, GRAM_BF16X3
-        ctx.set_option(OPT_GRAM_ARITH, GRAM_BF16X3)
+    if args.gram != "fp32":
+        from paper_2209_13027_amd.binding import OPT_GRAM_ARITH, GRAM_BF16X3, GRAM_LAG_FP32
+        ctx.set_option(OPT_GRAM_ARITH, GRAM_BF16X3 if args.gram == "bf16x3" else GRAM_LAG_FP32)
     if args.conv == "bf16x3":
         from paper_2209_13027_amd.binding import OPT_CONV_ARITH, CONV_BF16X3
         ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
@@ -209,8 +210,9 @@ def main():
     }
     # the same step captured once into a HIP graph and replayed (same kernels, no launch gaps)
     from paper_2209_13027_amd.binding import (OPT_CONV_ARITH as _OC, CONV_BF16X3 as _CB, OPT_GRAM_ARITH as _OG,
-                                              GRAM_BF16X3 as _GB)
-    opts = ([(_OC, _CB)] if args.conv == "bf16x3" else []) + ([(_OG, _GB)] if args.gram == "bf16x3" else [])
+                                              GRAM_BF16X3 as _GB, GRAM_LAG_FP32 as _GL)
+    opts = ([(_OC, _CB)] if args.conv == "bf16x3" else []) + ([(_OG, _GB)] if args.gram == "bf16x3" else []) + \
+           ([(_OG, _GL)] if args.gram == "lag" else [])
     graphed = pipeline.GraphedPath(d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2, wl.block, wl.stride,
                                    batch_images=batch, dtype=feat_dtype, fused=args.fused, out=feat, options=opts)
     graphed.replay()
@@ -257,12 +259,13 @@ def main():
         ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
     fast = None
     if args.conv == "fp32" and args.gram == "fp32" and not args.fused:
-        # The whole step once more with every widened option on: three-piece bf16 operands in the Gram and the
-        # convolution (same accuracy bars, see the parity tests) and the fused last stage.  Not part of `value`.
+        # The whole step once more with every widened option on: the lag-structured Gram (k <= 7; three-piece
+        # bf16 operands at k = 9), three-piece bf16 operands in the convolution (same accuracy bars, see the
+        # parity tests) and the fused last stage.  Not part of `value`.
         from paper_2209_13027_amd.binding import (OPT_CONV_ARITH, CONV_BF16X3, CONV_FP32, OPT_GRAM_ARITH,
-                                                  GRAM_BF16X3, GRAM_FP32)
+                                                  GRAM_BF16X3, GRAM_FP32, GRAM_LAG_FP32)
         ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
-        ctx.set_option(OPT_GRAM_ARITH, GRAM_BF16X3)
+        ctx.set_option(OPT_GRAM_ARITH, GRAM_LAG_FP32 if wl.k <= 7 else GRAM_BF16X3)
 
         def fast_step():
             mdl = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
@@ -279,7 +282,7 @@ def main():
         fast["gram_useful_tflops"] = (algorithmic_work(wl, M)["gram_flops"] / (fast["gram_ms"] * 1e-3) / 1e12
                                       if fast["gram_ms"] > 0 else 0.0)
         fast["conv_hash_hist_ms"] = pf["conv_hash_hist"]["ms"] / args.steps
-        fast["options"] = "gram bf16x3, conv bf16x3, fused last stage"
+        fast["options"] = ("gram lag-structured fp32" if wl.k <= 7 else "gram bf16x3") + ", conv bf16x3, fused last stage"
         ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
         ctx.set_option(OPT_GRAM_ARITH, GRAM_FP32)
     ctx.profile_select(None)

@@ -71,16 +71,21 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
         const int gy0 = ty * LAG_TH - K, gx0 = tx * p.tw - K;
         __syncthreads();                              // the previous tile is no longer read
         const float *s1 = p.v1 + mp * P, *s2 = p.v2 + mp * P;
-        for (int e = threadIdx.x; e < PH * PW; e += LAG_THREADS) {
-            const int yy = e / PW, xx = e - yy * PW;
-            const int gy = gy0 + yy, gx = gx0 + xx;
-            float a = 0.f, b = 0.f;
-            if (gy >= 0 && gy < p.h && gx >= 0 && gx < p.w) {
-                a = s1[(int64_t)gy * p.w + gx];
-                b = s2[(int64_t)gy * p.w + gx];
+        // wavefront w stages tile rows w, w+4, ...; lane l the columns l, l+64, ...
+        for (int yy = wave; yy < PH; yy += 4) {
+            const int gy = gy0 + yy;
+            const bool yok = gy >= 0 && gy < p.h;
+            const int64_t ro = (int64_t)gy * p.w;
+            for (int xx = lane; xx < PW; xx += 64) {
+                const int gx = gx0 + xx;
+                float a = 0.f, b = 0.f;
+                if (yok && gx >= 0 && gx < p.w) {
+                    a = s1[ro + gx];
+                    b = s2[ro + gx];
+                }
+                lds[yy * p.pitch + xx] = a;
+                lds[p.view_stride + yy * p.pitch + xx] = b;
             }
-            lds[yy * p.pitch + xx] = a;
-            lds[p.view_stride + yy * p.pitch + xx] = b;
         }
         __syncthreads();
         const int rows = min(LAG_TH, p.h - ty * LAG_TH);
@@ -90,7 +95,24 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
             const float *ra1 = lds + y * p.pitch + a_off, *rb1 = lds + y * p.pitch + b_off;
             const float *ra2 = ra1 + p.view_stride, *rb2 = rb1 + p.view_stride;
             floatx4 c11 = {0.f, 0.f, 0.f, 0.f}, c22 = {0.f, 0.f, 0.f, 0.f}, c12 = {0.f, 0.f, 0.f, 0.f};
-            for (int s = 0; s < steps; ++s) {
+            // two steps per iteration: their operands pair up in two-address LDS reads
+            int s = 0;
+            for (; s + 1 < steps; s += 2) {
+                const float a1 = ra1[4 * s], a1n = ra1[4 * s + 4], b2 = rb2[4 * s], b2n = rb2[4 * s + 4];
+                if (!CROSS) {
+                    const float a2 = ra2[4 * s], a2n = ra2[4 * s + 4], b1 = rb1[4 * s], b1n = rb1[4 * s + 4];
+                    c11 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, c11, 0, 0, 0);
+                    c22 = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b2, c22, 0, 0, 0);
+                    c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b2, c12, 0, 0, 0);
+                    c11 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1n, b1n, c11, 0, 0, 0);
+                    c22 = __builtin_amdgcn_mfma_f32_16x16x4f32(a2n, b2n, c22, 0, 0, 0);
+                    c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1n, b2n, c12, 0, 0, 0);
+                } else {
+                    c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b2, c12, 0, 0, 0);
+                    c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1n, b2n, c12, 0, 0, 0);
+                }
+            }
+            if (s < steps) {
                 const float a1 = ra1[4 * s], b2 = rb2[4 * s];
                 if (!CROSS) {
                     const float a2 = ra2[4 * s], b1 = rb1[4 * s];

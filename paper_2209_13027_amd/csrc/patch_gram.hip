@@ -363,7 +363,8 @@ __device__ __forceinline__ void gram_tile_fetch(const GramParams &p, int64_t ite
 #pragma unroll
     for (int jy = 0; jy < S::NJY; ++jy) {
         const int gy = gy0 + 4 * jy;
-        const bool yok = gy >= 0 && gy < p.h && wave + 4 * jy < S::PH;
+        // (rows below the last patch row's window are not read by anyone: short ring tiles skip their loads)
+        const bool yok = gy >= 0 && gy < p.h && wave + 4 * jy < g.rows + 2 * S::R;
 #pragma unroll
         for (int jx = 0; jx < S::NJX; ++jx) {
             const int gx = gx0 + 64 * jx;
@@ -659,13 +660,15 @@ int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t 
     ProfScope prof(ctx, cross_only ? DDCCA_K_GRAM_CROSS : DDCCA_K_GRAM);
     GramParams p;
     p.v1 = v1; p.v2 = v2; p.h = h; p.w = w;
-    const int w4 = (w + 3) & ~3;
-    // split wide images into equal column tiles of at most GRAM_TW_MAX patches
-    const int ntx = (w4 + GRAM_TW_MAX - 1) / GRAM_TW_MAX;
+    const int r = (k - 1) / 2;
+    // split wide images into equal column tiles of at most GRAM_TW_MAX patches; the ring's top and bottom bands
+    // are w + 2r patches wide and may use 8 more columns, so that one tile covers a band of a 128-wide image
+    const int wv = ring ? w + 2 * r : w, tw_max = ring ? GRAM_TW_MAX + 8 : GRAM_TW_MAX;
+    const int w4 = (wv + 3) & ~3;
+    const int ntx = (w4 + tw_max - 1) / tw_max;
     p.tw = (((w4 + ntx - 1) / ntx) + 3) & ~3;
     p.tiles_x = (w + p.tw - 1) / p.tw;
     p.tiles_y = (h + GRAM_TH - 1) / GRAM_TH;
-    const int r = (k - 1) / 2;
     p.ring = ring ? 1 : 0;
     p.ring_nbx = (w + 2 * r + p.tw - 1) / p.tw;
     p.ring_nby = p.tiles_y;

@@ -147,6 +147,8 @@ def test_validation_of_the_widened_calls(binding):
     # options: known values are accepted without a GPU, anything else is rejected
     assert lib.ddcca_set_option(h, binding.OPT_CONV_ARITH, binding.CONV_BF16X3) == binding.OK
     assert lib.ddcca_set_option(h, binding.OPT_GRAM_ARITH, binding.GRAM_BF16X3) == binding.OK
+    assert lib.ddcca_set_option(h, binding.OPT_GRAM_ARITH, binding.GRAM_LAG_FP32) == binding.OK
+    assert lib.ddcca_set_option(h, binding.OPT_GRAM_ARITH, 3) == E
     assert lib.ddcca_set_option(h, binding.OPT_GRAM_ARITH, binding.GRAM_FP32) == binding.OK
     assert lib.ddcca_set_option(h, binding.OPT_CONV_ARITH, 2) == E
     assert lib.ddcca_set_option(h, binding.OPT_GRAM_ARITH, -1) == E

@@ -36,15 +36,20 @@ class FullRun:
 
     def __init__(self, name, split=False):
         from paper_2209_13027_amd import pipeline
-        from paper_2209_13027_amd.binding import (Context, OPT_CONV_ARITH, CONV_BF16X3, OPT_GRAM_ARITH, GRAM_BF16X3)
+        from paper_2209_13027_amd.binding import (Context, OPT_CONV_ARITH, CONV_BF16X3, OPT_GRAM_ARITH, GRAM_BF16X3,
+                                                  GRAM_LAG_FP32)
         self.wl = wl = WORKLOADS[name]
-        self.split = split
+        lag = split == "lag"
+        self.split = split = split is True
         self.v1, self.v2, self.cls = make_views(wl)
         self.ctx = ctx = Context(0)
         if split:
             # three-piece bf16 operands in the Gram and in the convolution: the same checks, the same bars
             ctx.set_option(OPT_GRAM_ARITH, GRAM_BF16X3)
             ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
+        if lag:
+            # the lag-structured Gram (fp32 convolution): the same checks, the same bars
+            ctx.set_option(OPT_GRAM_ARITH, GRAM_LAG_FP32)
         self.d1, self.d2, self.dc = dev(self.v1), dev(self.v2), dev(self.cls)
         M, h, w = self.v1.shape
         # stage-1 matrices through the streamed API (same kernels and launch shapes as learn_stage_filters)
@@ -69,8 +74,9 @@ class FullRun:
 
 
 @pytest.fixture(scope="module", params=[("object", False), ("stress", False), ("large_scale", False),
-                                        ("object", True), ("stress", True), ("large_scale", True)],
-                ids=lambda p: p[0] + ("-bf16x3" if p[1] else ""))
+                                        ("object", True), ("stress", True), ("large_scale", True),
+                                        ("object", "lag"), ("large_scale", "lag")],
+                ids=lambda p: p[0] + ("-lag" if p[1] == "lag" else "-bf16x3" if p[1] else ""))
 def run(request):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
