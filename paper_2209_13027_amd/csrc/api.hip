@@ -93,40 +93,48 @@ static void free_buffer(Buffer &b)
     b.bytes = 0;
 }
 
-// The Gram contribution of n_maps map pairs: the dense kernel, or the lag correlations plus the dense Gram of the
-// frame outside the image that they over-count.
+// The Gram contribution of n_maps map pairs: the dense kernel, or the lag statistics.
 static int accumulate_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps)
 {
-    int rc;
-    if (ctx->lag_active) {
-        if ((rc = launch_lag_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, false, (double *)ctx->lag_slots.ptr,
-                                  max_lag_slots(ctx), &ctx->lag_valid)))
-            return rc;
-        return launch_patch_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, false, (double *)ctx->slots.ptr,
-                                 max_gram_slots(ctx, ctx->k), &ctx->slots_valid, true);
-    }
+    if (ctx->lag_active)
+        return launch_lag_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, false, (double *)ctx->lag_slots.ptr,
+                               max_lag_slots(ctx), &ctx->lag_valid, (double *)ctx->lag_col_slots.ptr,
+                               max_lag_col_slots(ctx), &ctx->lag_col_valid);
     return launch_patch_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, false, (double *)ctx->slots.ptr,
                              max_gram_slots(ctx, ctx->k), &ctx->slots_valid);
+}
+
+// lag statistics in the two slot sets -> stacked Gram
+static int lag_finish(ddcca_ctx *ctx, int valid, int col_valid, double *stacked_out, bool cross)
+{
+    const int k = ctx->k;
+    int rc;
+    if ((rc = launch_reduce_slots(ctx, (const double *)ctx->lag_slots.ptr, valid, (int)lag_slot_doubles(k),
+                                  (double *)ctx->lag_R.ptr)))
+        return rc;
+    if ((rc = launch_reduce_slots(ctx, (const double *)ctx->lag_col_slots.ptr, col_valid,
+                                  (int)lag_col_slot_doubles(k), (double *)ctx->lag_C.ptr)))
+        return rc;
+    return launch_lag_to_stacked(ctx, (const double *)ctx->lag_R.ptr, (const double *)ctx->lag_C.ptr, stacked_out, k,
+                                 ctx->h, ctx->w, cross);
 }
 
 // Gram of the cross-view block of n_img image pairs into stacked_out (fresh slots), dense or lag-structured.
 static int cross_gram(ddcca_ctx *ctx, const float *img1, const float *img2, int64_t n_img, double *stacked_out)
 {
     const int k = ctx->k;
-    int rc, valid = 0;
+    int rc, valid = 0, cvalid = 0;
+    if (ctx->lag_active) {
+        if ((rc = launch_lag_gram(ctx, img1, img2, n_img, ctx->h, ctx->w, k, true, (double *)ctx->lag_slots.ptr,
+                                  max_lag_slots(ctx), &valid, (double *)ctx->lag_col_slots.ptr,
+                                  max_lag_col_slots(ctx), &cvalid)))
+            return rc;
+        return lag_finish(ctx, valid, cvalid, stacked_out, true);
+    }
     if ((rc = launch_patch_gram(ctx, img1, img2, n_img, ctx->h, ctx->w, k, true, (double *)ctx->slots.ptr,
-                                max_gram_slots(ctx, k), &valid, ctx->lag_active)))
+                                max_gram_slots(ctx, k), &valid)))
         return rc;
-    if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, valid, k, stacked_out))) return rc;
-    if (!ctx->lag_active) return DDCCA_OK;
-    int lvalid = 0;
-    if ((rc = launch_lag_gram(ctx, img1, img2, n_img, ctx->h, ctx->w, k, true, (double *)ctx->lag_slots.ptr,
-                              max_lag_slots(ctx), &lvalid)))
-        return rc;
-    if ((rc = launch_reduce_slots(ctx, (const double *)ctx->lag_slots.ptr, lvalid, LAG_SLOT_DOUBLES,
-                                  (double *)ctx->lag_R.ptr)))
-        return rc;
-    return launch_lag_to_stacked(ctx, (const double *)ctx->lag_R.ptr, stacked_out, k, true);
+    return launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, valid, k, stacked_out);
 }
 
 // Finish the accumulation: Gram partials -> stacked Gram, class sums -> class / total
@@ -142,12 +150,10 @@ static int corr_finish(ddcca_ctx *ctx)
     if ((rc = ensure(ctx, ctx->stacked, 3 * E * sizeof(double)))) return rc;
     if ((rc = ensure(ctx, ctx->mats, 5 * (size_t)D * D * sizeof(double)))) return rc;
     double *st = (double *)ctx->stacked.ptr;
-    if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, ctx->slots_valid, k, st))) return rc;
     if (ctx->lag_active) {
-        if ((rc = launch_reduce_slots(ctx, (const double *)ctx->lag_slots.ptr, ctx->lag_valid, LAG_SLOT_DOUBLES,
-                                      (double *)ctx->lag_R.ptr)))
-            return rc;
-        if ((rc = launch_lag_to_stacked(ctx, (const double *)ctx->lag_R.ptr, st, k, false))) return rc;
+        if ((rc = lag_finish(ctx, ctx->lag_valid, ctx->lag_col_valid, st, false))) return rc;
+    } else if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, ctx->slots_valid, k, st))) {
+        return rc;
     }
 
     if ((rc = ensure(ctx, ctx->class_img, 2 * (size_t)(n_cell + ctx->G) * P * sizeof(float)))) return rc;
@@ -193,7 +199,7 @@ void ddcca_destroy(ddcca_ctx *ctx)
     if (touched) {
         (void)hipSetDevice(ctx->device);
         (void)hipStreamSynchronize(ctx->stream);
-        for (Buffer *b : {&ctx->lag_slots, &ctx->lag_R, &ctx->prev_img, &ctx->slots, &ctx->class_sum, &ctx->class_img,
+        for (Buffer *b : {&ctx->lag_slots, &ctx->lag_col_slots, &ctx->lag_R, &ctx->lag_C, &ctx->prev_img, &ctx->slots, &ctx->class_sum, &ctx->class_img,
                           &ctx->stacked, &ctx->seg, &ctx->mats, &ctx->solve_ws, &ctx->flags, &ctx->maps1, &ctx->maps2, &ctx->iq_lut})
             free_buffer(*b);
         for (ProfSlot &s : ctx->prof_slot) {
@@ -246,10 +252,15 @@ int ddcca_corr_begin(ddcca_ctx *ctx, int k, int n_cls, int G, int h, int w)
     }
     ctx->lag_active = ctx->gram_arith == DDCCA_GRAM_LAG_FP32 && lag_supported(k);
     if (ctx->lag_active) {
-        if ((rc = ensure(ctx, ctx->lag_slots, (size_t)max_lag_slots(ctx) * LAG_SLOT_DOUBLES * sizeof(double)))) return rc;
-        if ((rc = ensure(ctx, ctx->lag_R, (size_t)LAG_SLOT_DOUBLES * sizeof(double)))) return rc;
+        if ((rc = ensure(ctx, ctx->lag_slots, (size_t)max_lag_slots(ctx) * lag_slot_doubles(k) * sizeof(double))))
+            return rc;
+        if ((rc = ensure(ctx, ctx->lag_col_slots,
+                         (size_t)max_lag_col_slots(ctx) * lag_col_slot_doubles(k) * sizeof(double))))
+            return rc;
+        if ((rc = ensure(ctx, ctx->lag_R, lag_slot_doubles(k) * sizeof(double)))) return rc;
+        if ((rc = ensure(ctx, ctx->lag_C, lag_col_slot_doubles(k) * sizeof(double)))) return rc;
     }
-    ctx->lag_valid = 0;
+    ctx->lag_valid = ctx->lag_col_valid = 0;
     ctx->k = k; ctx->n_cls = n_cls; ctx->G = G; ctx->h = h; ctx->w = w;
     ctx->cs_seg = cs_seg;
     ctx->n_maps = 0;

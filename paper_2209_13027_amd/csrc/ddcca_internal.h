@@ -47,9 +47,9 @@ struct ddcca_ctx {
     ddcca::Buffer prev_img;                 // sum images of the previous stage's inputs (next-stage learning)
     ddcca::Buffer stacked;                  // 3 x [tiles*256] double (main, class, total)
     bool lag_active = false;                // this accumulation runs lag-structured (option + k <= 7)
-    int lag_valid = 0;                      // lag slots holding data
-    ddcca::Buffer lag_slots;                // [max_lag_slots][3*256] double
-    ddcca::Buffer lag_R;                    // reduced lag correlations [3*256] double
+    int lag_valid = 0, lag_col_valid = 0;   // lag slots holding data
+    ddcca::Buffer lag_slots, lag_col_slots; // per-workgroup lag statistics (rows / border columns)
+    ddcca::Buffer lag_R, lag_C;             // the same, reduced
     ddcca::Buffer seg;                      // reduction segments
     ddcca::Buffer mats;                     // 5 x [D][D] double: C11 C22 C12 Cw CT
     ddcca::Buffer solve_ws;                 // solver scratch (global part)
@@ -101,25 +101,27 @@ inline int gram_tiles(int k) { int nb = gram_blocks(k); return nb * (nb + 1) / 2
 // ---- kernel launchers (each validates nothing; callers have validated) --------------
 // cross_only: accumulate only the view-1 x view-2 block (the other tiles of the slots are
 // then undefined and must not be read).
-// ring: only the patches whose centre lies in the frame of width r around the image (zero outside the image,
-// their windows still touch it); the lag-structured accumulation subtracts their Gram
 int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w,
-                      int k, bool cross_only, double *slots, int max_slots, int *slots_valid, bool ring = false);
+                      int k, bool cross_only, double *slots, int max_slots, int *slots_valid);
 int max_gram_slots(ddcca_ctx *ctx, int k);
 int launch_gram_reduce(ddcca_ctx *ctx, const double *slots, int n_slots, int k, double *stacked);
 // the same fixed-order sum for slots of E doubles each
 int launch_reduce_slots(ddcca_ctx *ctx, const double *slots, int n_slots, int E, double *out);
 
 // ---- lag-structured accumulation (DDCCA_GRAM_LAG_FP32; k <= 7) ----------------------------------------
-constexpr int LAG_SLOT_DOUBLES = 3 * 256;   // lag correlations of the pairs (1,1), (2,2), (1,2): one 16 x 16 tile each
 bool lag_supported(int k);
 int max_lag_slots(ddcca_ctx *ctx);
-// adds the lag correlations of n_maps map pairs to the slots (cross_only: the (1,2) pair alone)
+int max_lag_col_slots(ddcca_ctx *ctx);
+size_t lag_slot_doubles(int k);       // lag correlations: all rows + the r top and r bottom rows, three pair types
+size_t lag_col_slot_doubles(int k);   // border columns and corners
+// adds the lag statistics of n_maps map pairs to the two slot sets (cross_only: the (1,2) pair alone)
 int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w, int k,
-                    bool cross_only, double *slots, int max_slots, int *slots_valid);
-// stacked <- (stacked Gram of y = x - x_centre over all patch centres of the plane, from the reduced lag
-// correlations R) - stacked (the same over the frame outside the image, from launch_patch_gram's ring mode)
-int launch_lag_to_stacked(ddcca_ctx *ctx, const double *R, double *stacked, int k, bool cross_only);
+                    bool cross_only, double *slots, int max_slots, int *slots_valid, double *col_slots,
+                    int max_col_slots, int *col_slots_valid);
+// stacked <- Gram of y = x - x_centre over the patches of the image, from the reduced statistics R (rows) and C
+// (columns), in the layout of the dense kernel's reduced slots
+int launch_lag_to_stacked(ddcca_ctx *ctx, const double *R, const double *C, double *stacked, int k, int h, int w,
+                          bool cross_only);
 int launch_export(ddcca_ctx *ctx, const double *stacked_main, const double *stacked_cls,
                   const double *stacked_tot, int k, double n_patches, double *mats);
 int launch_label_check(ddcca_ctx *ctx, const int32_t *cls, int64_t n_img, int n_cls, int *flag);

@@ -3,11 +3,13 @@
 // the plane depends only on the lag between the two taps:
 //     sum_p X[p + s_a] X'[p + s_b] = R_{s_b - s_a},    R_d = sum_u X[u] X'[u + d],
 // (2k-1)^2 lag correlations per view pair instead of k^4 entries.  The sum wanted runs over the patch centres
-// inside the image only; the centres outside it whose window still touches the image lie in a frame of width
-// r, a few per cent of all patches, and their Gram is accumulated by the dense kernel (ring mode) and
-// subtracted.  Everything else downstream (centre-pixel form, H M H export, solve) is unchanged:
-// lag_to_stacked_kernel writes  sum y y^T  for y = x - x_centre in the layout of the dense kernel's slots from
-//     S_y[a][b] = R(s_b - s_a) - R(s_c - s_a) - R(s_b - s_c) + R(0)          (c = the centre tap).
+// inside the image only: with u = p + s_a that is the same sum over u with up to r rows at the top or bottom and
+// up to r columns at the left or right of the image left out (which ones depends on the first tap a), so next to
+// R_d the kernels keep the contributions of the r first and last image rows (lag_gram_kernel, per border row)
+// and of the r first and last columns and the corners (lag_cols_kernel).  Everything downstream (centre-pixel
+// form, H M H export, solve) is unchanged: lag_to_stacked_kernel writes  sum y y^T  for y = x - x_centre in the
+// layout of the dense kernel's slots from
+//     S_y[a][b] = S_x[a][b] - S_x[a][c] - S_x[c][b] + S_x[c][c]          (c = the centre tap).
 //
 // The lag correlations run on v_mfma_f32_16x16x4_f32, one image row at a time: rows of the matrix instruction =
 // horizontal lag, columns = vertical lag, K = 4 consecutive pixels x' of the row:
@@ -54,11 +56,18 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
     const int64_t count = per + (blockIdx.x < extra ? 1 : 0);
     const int tiles = p.tiles_x * p.tiles_y;
     const int64_t P = (int64_t)p.h * p.w;
-    double accd[3][4];
+    constexpr int RR = (KS - 1) / 2;       // patch radius = border rows kept apart at the top and at the bottom
+    double accd[3][4], acct[3][4], accb[3][4];     // all rows; this wavefront's top / bottom border row
 #pragma unroll
     for (int t = 0; t < 3; ++t)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) accd[t][v] = 0.0;
+        for (int v = 0; v < 4; ++v) accd[t][v] = acct[t][v] = accb[t][v] = 0.0;
+    // Image row y is always handled by wavefront y % 4 (tiles start at multiples of 16), so the RR < 4 border
+    // rows at either end have one owner each: top row o belongs to wavefront o, bottom row h-1-o to
+    // wavefront (h-1-o) % 4.
+    const int o_top = wave, o_bot = (((p.h - 1 - wave) % 4) + 4) % 4;
+    const int y_top = (o_top < RR && o_top < p.h) ? o_top : -1;
+    const int y_bot = (o_bot < RR && o_bot < p.h) ? p.h - 1 - o_bot : -1;
     // A operand: image row y = tile row y + K, column x' - dx = tile column x' + K - (m - K)
     // B operand: image row y + dy = tile row y + m, column x' = tile column x' + K
     const int a_off = K * p.pitch + kk - m + 2 * K;
@@ -121,13 +130,19 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
                 }
                 c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b2, c12, 0, 0, 0);
             }
+            const int gy = ty * LAG_TH + y;
+            const bool is_top = gy == y_top, is_bot = gy == y_bot;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 if (!CROSS) {
                     accd[0][v] += (double)c11[v];
                     accd[1][v] += (double)c22[v];
+                    if (is_top) { acct[0][v] += (double)c11[v]; acct[1][v] += (double)c22[v]; }
+                    if (is_bot) { accb[0][v] += (double)c11[v]; accb[1][v] += (double)c22[v]; }
                 }
                 accd[2][v] += (double)c12[v];
+                if (is_top) acct[2][v] += (double)c12[v];
+                if (is_bot) accb[2][v] += (double)c12[v];
             }
         }
     }
@@ -146,34 +161,180 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
         }
         __syncthreads();
     }
-    double *slot = p.slots + (size_t)blockIdx.x * LAG_E;
+    // slot: [1 + 2 RR][LAG_E]: all rows, top rows 0 .. RR-1, bottom rows h-1 .. h-RR
+    double *slot = p.slots + (size_t)blockIdx.x * (1 + 2 * RR) * LAG_E;
     const bool rmw = (int)blockIdx.x < p.slots_valid;
     for (int e = threadIdx.x; e < LAG_E; e += LAG_THREADS) slot[e] = (rmw ? slot[e] : 0.0) + st[e];
+    // border rows: the owner writes its registers; rows the image does not have stay zero
+#pragma unroll
+    for (int o = 0; o < RR; ++o) {
+        if (o >= p.h && wave == 0 && !rmw) {
+            for (int e = lane; e < LAG_E; e += 64) {
+                slot[(1 + o) * LAG_E + e] = 0.0;
+                slot[(1 + RR + o) * LAG_E + e] = 0.0;
+            }
+        }
+    }
+    if (y_top >= 0) {
+        double *d = slot + (size_t)(1 + o_top) * LAG_E;
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int e = (t * 4 + v) * 64 + lane;
+                d[e] = (rmw ? d[e] : 0.0) + acct[t][v];
+            }
+    }
+    if (y_bot >= 0) {
+        double *d = slot + (size_t)(1 + RR + o_bot) * LAG_E;
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int e = (t * 4 + v) * 64 + lane;
+                d[e] = (rmw ? d[e] : 0.0) + accb[t][v];
+            }
+    }
 }
 
-// R_d of one view pair from a reduced slot: accumulator layout, row = horizontal lag index, column = vertical.
-__device__ __forceinline__ double lag_value(const double *R, int type, int dy, int dx, int K)
+// ---- border columns ------------------------------------------------------------------------------------
+// What the lag correlations over-count is the part of  sum_u X[u] X'[u + d]  whose u lies in the first or last
+// rows / columns of the image (which ones depends on the first tap, see lag_entry below).  The rows come out of
+// lag_gram_kernel; this kernel adds up, per border column c (r on either side) and lag d,
+//     colsum[c][d] = sum_y X[y][c] X'[y + dy][c + dx]
+// and keeps the terms of the r top and r bottom rows apart (the corners, which rows and columns both cover).
+// grid (image ranges, type x side); a thread owns (column offset, lag) and walks the image rows in chunks.
+// Slot of a workgroup row: [type][side][column offset][1 + 2r][(2K+1)^2] doubles, entry 0 of the fourth index
+// the column sum, 1 + o the term of top row o, 1 + r + o the term of bottom row h-1-o.
+constexpr int LAGC_ROWS = 64;              // image rows per chunk
+
+struct LagColParams {
+    const float *v1, *v2;
+    int h, w;
+    int64_t n_maps;
+    int types;                             // 3, or 1 (cross only: the (1,2) pair)
+    double *slots;                         // [gridDim.x][3][2][r][1 + 2r][NL*NL]
+    int slots_valid;
+};
+
+template <int KS>
+__global__ void lag_cols_kernel(LagColParams p)
 {
-    const int ix = dx + K, iy = dy + K;
+    constexpr int K = KS - 1, NL = 2 * K + 1, NLL = NL * NL, RR = (KS - 1) / 2;
+    constexpr int BW = RR + 2 * K;         // columns of the second operand's block (zeros outside the image)
+    constexpr int BH = LAGC_ROWS + 2 * K;
+    __shared__ float sa[LAGC_ROWS * RR];
+    __shared__ float sb[BH * BW];
+    const int type = p.types == 1 ? 2 : blockIdx.y >> 1, side = blockIdx.y & 1;
+    const float *va = type == 1 ? p.v2 : p.v1, *vb = type == 0 ? p.v1 : p.v2;
+    const int tid = threadIdx.x;
+    const bool active = tid < RR * NLL;
+    const int ox = active ? tid / NLL : 0, li = active ? tid - ox * NLL : 0;
+    const int dy = li / NL - K, dx = li % NL - K;
+    // first-operand column of offset ox and the image column the block's column 0 stands for
+    const int ca = side == 0 ? ox : p.w - 1 - ox;
+    const int cb0 = side == 0 ? -K : p.w - RR - K;
+    const int bcol = ca + dx - cb0;        // block column of the second operand: in [0, BW)
+    const int64_t per = p.n_maps / gridDim.x, extra = p.n_maps % gridDim.x;
+    const int64_t first = blockIdx.x * per + min((int64_t)blockIdx.x, extra);
+    const int64_t count = per + (blockIdx.x < extra ? 1 : 0);
+    const int64_t P = (int64_t)p.h * p.w;
+    double sum = 0.0, top[RR], bot[RR];
+#pragma unroll
+    for (int o = 0; o < RR; ++o) top[o] = bot[o] = 0.0;
+    for (int64_t m = first; m < first + count; ++m) {
+        const float *ia = va + m * P, *ib = vb + m * P;
+        for (int y0 = 0; y0 < p.h; y0 += LAGC_ROWS) {
+            const int rows = min(LAGC_ROWS, p.h - y0);
+            __syncthreads();
+            for (int e = tid; e < rows * RR; e += blockDim.x) {
+                const int yy = e / RR, o = e - yy * RR;
+                const int c = side == 0 ? o : p.w - 1 - o;
+                sa[e] = (c >= 0 && c < p.w) ? ia[(int64_t)(y0 + yy) * p.w + c] : 0.f;
+            }
+            for (int e = tid; e < (rows + 2 * K) * BW; e += blockDim.x) {
+                const int yy = e / BW, xx = e - yy * BW;
+                const int gy = y0 - K + yy, gx = cb0 + xx;
+                sb[e] = (gy >= 0 && gy < p.h && gx >= 0 && gx < p.w) ? ib[(int64_t)gy * p.w + gx] : 0.f;
+            }
+            __syncthreads();
+            if (active && ca >= 0 && ca < p.w) {
+                float acc = 0.f;
+                const float *pa = sa + ox, *pb = sb + (dy + K) * BW + bcol;
+                for (int yy = 0; yy < rows; ++yy) acc += pa[yy * RR] * pb[yy * BW];
+                sum += (double)acc;
+                // the terms of the border rows inside this chunk
+#pragma unroll
+                for (int o = 0; o < RR; ++o) {
+                    const int yt = o - y0, yb = p.h - 1 - o - y0;
+                    if (o < p.h && yt >= 0 && yt < rows) top[o] += (double)(pa[yt * RR] * pb[yt * BW]);
+                    if (o < p.h && yb >= 0 && yb < rows) bot[o] += (double)(pa[yb * RR] * pb[yb * BW]);
+                }
+            }
+        }
+    }
+    if (active) {
+        double *d = p.slots + ((((size_t)blockIdx.x * 3 + type) * 2 + side) * RR + ox) * (1 + 2 * RR) * NLL + li;
+        const bool rmw = (int)blockIdx.x < p.slots_valid;
+        d[0] = (rmw ? d[0] : 0.0) + sum;
+#pragma unroll
+        for (int o = 0; o < RR; ++o) {
+            d[(1 + o) * NLL] = (rmw ? d[(1 + o) * NLL] : 0.0) + top[o];
+            d[(1 + RR + o) * NLL] = (rmw ? d[(1 + RR + o) * NLL] : 0.0) + bot[o];
+        }
+    }
+}
+
+// ---- from the statistics to the stacked Gram --------------------------------------------------------------
+struct LagStats {
+    const double *R;                       // [1 + 2r][3][256]: reduced lag_gram_kernel slots
+    const double *C;                       // [3][2][r][1 + 2r][NL*NL]: reduced lag_cols_kernel slots
+    int ks, h, w, cross;
+};
+
+// lag correlation of one pair type from accumulator layout (row = horizontal lag index, column = vertical)
+__device__ __forceinline__ double lag_value(const double *R, int type, int iy, int ix)
+{
     return R[(type * 4 + (ix & 3)) * 64 + 16 * (ix >> 2) + iy];
 }
 
-// S_x[(d,a)][(d',b)] = sum over all patch centres of X_d[p + s_a] X_d'[p + s_b] = R^{dd'}(s_b - s_a);
-// R^{21}(d) = R^{12}(-d).
-__device__ __forceinline__ double lag_raw(const double *R, int d, int a, int d2, int b, int ks, int K, bool cross)
+// sum over the patch centres p INSIDE the image of X[p + s_a] X'[p + s_b] for the pair type (X, X'), a the tap
+// of X: with u = p + s_a, u runs over the image minus the rows and columns that p + s_a can reach only from
+// outside -- the first s rows if s = s_a.y > 0, the last -s if s < 0, the same for the columns -- so
+//     = R(d) - (those rows of R) - (those columns) + (their corners),    d = s_b - s_a.
+__device__ double lag_entry(const LagStats &st, int type, int a, int b)
 {
+    const int ks = st.ks, r = (ks - 1) / 2, K = ks - 1, NL = 2 * K + 1, NLL = NL * NL;
     const int ay = a / ks, ax = a - ay * ks, by = b / ks, bx = b - by * ks;
-    if (d == d2) return cross ? 0.0 : lag_value(R, d, by - ay, bx - ax, K);
-    return d == 0 ? lag_value(R, 2, by - ay, bx - ax, K) : lag_value(R, 2, ay - by, ax - bx, K);
+    const int iy = by - ay + K, ix = bx - ax + K;
+    const int sy = ay - r, sx = ax - r;
+    const int ysd = sy > 0 ? 0 : 1, yn = min(sy > 0 ? sy : -sy, st.h);
+    const int xsd = sx > 0 ? 0 : 1, xn = min(sx > 0 ? sx : -sx, st.w);
+    double v = lag_value(st.R, type, iy, ix);
+    for (int o = 0; o < yn; ++o) v -= lag_value(st.R + (size_t)(1 + ysd * r + o) * 768, type, iy, ix);
+    const double *cb = st.C + ((size_t)(type * 2 + xsd) * r) * (1 + 2 * r) * NLL + iy * NL + ix;
+    for (int o = 0; o < xn; ++o) {
+        const double *c = cb + (size_t)o * (1 + 2 * r) * NLL;
+        v -= c[0];
+        for (int oy = 0; oy < yn; ++oy) v += c[(1 + ysd * r + oy) * NLL];
+    }
+    return v;
 }
 
-// stacked[e] = (Gram of y = x - x_centre over all patch centres of the plane, from the lag correlations R)
-//              - stacked[e] (the same Gram over the frame outside the image, from the dense kernel's ring mode),
-// element e in the slot layout of the dense kernel: tile (bi, bj) number t, register v, lane l hold entry
-// (16 bi + 4 (l / 16) + v, 16 bj + l % 16) of the stacked 2(D-1) x 2(D-1) matrix.
-__global__ void lag_to_stacked_kernel(const double *__restrict__ R, double *__restrict__ stacked, int ks, int cross)
+// S_x[(d,a)][(d',b)] over the patch centres inside the image; the (2,1) pair is the (1,2) pair with the taps swapped
+__device__ __forceinline__ double lag_raw(const LagStats &st, int d, int a, int d2, int b)
 {
-    const int D = ks * ks, DR = D - 1, CEN = (D - 1) / 2, K = ks - 1;
+    if (d == d2) return st.cross ? 0.0 : lag_entry(st, d, a, b);
+    return d == 0 ? lag_entry(st, 2, a, b) : lag_entry(st, 2, b, a);
+}
+
+// stacked[e] = Gram of y = x - x_centre over the patches of the image, element e in the slot layout of the dense
+// kernel: tile (bi, bj) number t, register v, lane l hold entry (16 bi + 4 (l / 16) + v, 16 bj + l % 16) of the
+// stacked 2(D-1) x 2(D-1) matrix;  S_y[a][b] = S_x[a][b] - S_x[a][c] - S_x[c][b] + S_x[c][c], c the centre tap.
+__global__ void lag_to_stacked_kernel(LagStats st, double *__restrict__ stacked)
+{
+    const int ks = st.ks;
+    const int D = ks * ks, DR = D - 1, CEN = (D - 1) / 2;
     const int NB = (2 * DR) / 16, NT = NB * (NB + 1) / 2;
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= NT * 256) return;
@@ -188,14 +349,19 @@ __global__ void lag_to_stacked_kernel(const double *__restrict__ R, double *__re
     const int d = row >= DR ? 1 : 0, d2 = col >= DR ? 1 : 0;
     const int ar = row - d * DR, br = col - d2 * DR;
     const int a = ar >= CEN ? ar + 1 : ar, b = br >= CEN ? br + 1 : br;
-    const bool cr = cross != 0;
-    const double s = lag_raw(R, d, a, d2, b, ks, K, cr) - lag_raw(R, d, a, d2, CEN, ks, K, cr) -
-                     lag_raw(R, d, CEN, d2, b, ks, K, cr) + lag_raw(R, d, CEN, d2, CEN, ks, K, cr);
-    stacked[e] = s - stacked[e];
+    stacked[e] = lag_raw(st, d, a, d2, b) - lag_raw(st, d, a, d2, CEN) - lag_raw(st, d, CEN, d2, b) +
+                 lag_raw(st, d, CEN, d2, CEN);
 }
 
 bool lag_supported(int k) { return 2 * (k - 1) + 1 <= 16; }
 int max_lag_slots(ddcca_ctx *ctx) { return ctx->n_cu * 6; }
+int max_lag_col_slots(ddcca_ctx *ctx) { return ctx->n_cu; }
+size_t lag_slot_doubles(int k) { return (size_t)(1 + 2 * ((k - 1) / 2)) * LAG_E; }
+size_t lag_col_slot_doubles(int k)
+{
+    const int r = (k - 1) / 2, nl = 2 * (k - 1) + 1;
+    return (size_t)3 * 2 * r * (1 + 2 * r) * nl * nl;
+}
 
 template <int KS>
 static void lag_launch(ddcca_ctx *ctx, const LagParams &p, int grid, size_t lds, bool cross)
@@ -205,13 +371,14 @@ static void lag_launch(ddcca_ctx *ctx, const LagParams &p, int grid, size_t lds,
 }
 
 int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w, int k,
-                    bool cross_only, double *slots, int max_slots, int *slots_valid)
+                    bool cross_only, double *slots, int max_slots, int *slots_valid, double *col_slots,
+                    int max_col_slots, int *col_slots_valid)
 {
     ProfScope prof(ctx, cross_only ? DDCCA_K_GRAM_CROSS : DDCCA_K_GRAM);
     if (!lag_supported(k)) return fail(ctx, DDCCA_EINVAL, "the lag-structured Gram needs k <= 7");
     LagParams p;
     p.v1 = v1; p.v2 = v2; p.h = h; p.w = w;
-    const int K = k - 1;
+    const int K = k - 1, r = (k - 1) / 2;
     const int w4 = (w + 3) & ~3;
     const int ntx = (w4 + LAG_TW_MAX - 1) / LAG_TW_MAX;
     p.tw = (((w4 + ntx - 1) / ntx) + 3) & ~3;
@@ -228,23 +395,45 @@ int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_
     p.slots = slots;
     p.slots_valid = *slots_valid;
     const int grid = (int)std::min<int64_t>(max_slots, std::max<int64_t>(p.n_items, 1));
+    // the border columns and corners of the same maps
+    LagColParams c;
+    c.v1 = v1; c.v2 = v2; c.h = h; c.w = w; c.n_maps = n_maps;
+    c.types = cross_only ? 1 : 3;
+    c.slots = col_slots;
+    c.slots_valid = *col_slots_valid;
+    const int cgrid = (int)std::min<int64_t>(max_col_slots, std::max<int64_t>(n_maps, 1));
+    const int nl = 2 * K + 1;
+    const int cthreads = (r * nl * nl + 63) / 64 * 64;
+    const dim3 cg(cgrid, cross_only ? 2 : 6);
     switch (k) {
-        case 3: lag_launch<3>(ctx, p, grid, lds, cross_only); break;
-        case 5: lag_launch<5>(ctx, p, grid, lds, cross_only); break;
-        case 7: lag_launch<7>(ctx, p, grid, lds, cross_only); break;
+        case 3:
+            lag_launch<3>(ctx, p, grid, lds, cross_only);
+            hipLaunchKernelGGL(lag_cols_kernel<3>, cg, dim3(cthreads), 0, ctx->stream, c);
+            break;
+        case 5:
+            lag_launch<5>(ctx, p, grid, lds, cross_only);
+            hipLaunchKernelGGL(lag_cols_kernel<5>, cg, dim3(cthreads), 0, ctx->stream, c);
+            break;
+        case 7:
+            lag_launch<7>(ctx, p, grid, lds, cross_only);
+            hipLaunchKernelGGL(lag_cols_kernel<7>, cg, dim3(cthreads), 0, ctx->stream, c);
+            break;
         default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
     }
     DDCCA_HIP(ctx, hipGetLastError());
     *slots_valid = std::max(*slots_valid, grid);
+    *col_slots_valid = std::max(*col_slots_valid, cgrid);
     return DDCCA_OK;
 }
 
-int launch_lag_to_stacked(ddcca_ctx *ctx, const double *R, double *stacked, int k, bool cross_only)
+int launch_lag_to_stacked(ddcca_ctx *ctx, const double *R, const double *C, double *stacked, int k, int h, int w,
+                          bool cross_only)
 {
     ProfScope prof(ctx, DDCCA_K_REDUCE);
     const int E = gram_tiles(k) * 256;
-    hipLaunchKernelGGL(lag_to_stacked_kernel, dim3((E + 255) / 256), dim3(256), 0, ctx->stream, R, stacked, k,
-                       cross_only ? 1 : 0);
+    LagStats st;
+    st.R = R; st.C = C; st.ks = k; st.h = h; st.w = w; st.cross = cross_only ? 1 : 0;
+    hipLaunchKernelGGL(lag_to_stacked_kernel, dim3((E + 255) / 256), dim3(256), 0, ctx->stream, st, stacked);
     DDCCA_HIP(ctx, hipGetLastError());
     return DDCCA_OK;
 }

@@ -44,47 +44,7 @@ struct GramParams {
     int flush_items;                       // items between fp64 flushes
     double *slots;                         // [n_slots][NT*256]
     int slots_valid;                       // slots below this hold earlier partial sums
-    int tiles;                             // tiles per map: tiles_x*tiles_y, or the ring tiles
-    int ring, ring_nbx, ring_nby;          // ring mode: only the patches whose centre lies outside the image
 };
-
-// The patches of one work item: map m, first patch centre (oy, ox) in image coordinates, rows x cols patches.
-// Ring mode covers the frame of width R around the image (patch centres outside it whose window still touches
-// it): top and bottom bands of R rows over the widened width w + 2R, then left and right bands of R columns.
-struct GramTile {
-    int64_t m;
-    int oy, ox, rows, cols;
-};
-
-__device__ __forceinline__ GramTile gram_item_tile(const GramParams &p, int64_t item, int R)
-{
-    GramTile g;
-    g.m = item / p.tiles;
-    const int t = (int)(item - g.m * p.tiles);
-    if (!p.ring) {
-        const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
-        g.oy = ty * GRAM_TH;
-        g.ox = tx * p.tw;
-        g.rows = min(GRAM_TH, p.h - g.oy);
-        g.cols = min(p.tw, p.w - g.ox);
-    } else if (t < 2 * p.ring_nbx) {
-        const bool top = t < p.ring_nbx;
-        const int tx = top ? t : t - p.ring_nbx;
-        g.oy = top ? -R : p.h;
-        g.rows = R;
-        g.ox = tx * p.tw - R;
-        g.cols = min(p.tw, p.w + 2 * R - tx * p.tw);
-    } else {
-        const int u = t - 2 * p.ring_nbx;
-        const bool left = u < p.ring_nby;
-        const int ty = left ? u : u - p.ring_nby;
-        g.ox = left ? -R : p.w;
-        g.cols = R;
-        g.oy = ty * GRAM_TH;
-        g.rows = min(GRAM_TH, p.h - g.oy);
-    }
-    return g;
-}
 
 // Compile-time geometry.  TSPLIT wavefronts share one group of patch rows and split the
 // tile list between them (tile t belongs to role t % TSPLIT), which keeps the
@@ -350,21 +310,22 @@ struct GramStage {
 // Issue the global loads of one tile (both views) into registers; elements outside the image
 // (zero padding) or outside the tile read as 0.
 template <int KS>
-__device__ __forceinline__ void gram_tile_fetch(const GramParams &p, int64_t item, int pw,
+__device__ __forceinline__ void gram_tile_fetch(const GramParams &p, int64_t item, int tiles, int pw,
                                                 float (&ra)[GramStage<KS>::NJY][GramStage<KS>::NJX],
                                                 float (&rb)[GramStage<KS>::NJY][GramStage<KS>::NJX])
 {
     using S = GramStage<KS>;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const GramTile g = gram_item_tile(p, item, S::R);
-    const int gy0 = g.oy - S::R + wave, gx0 = g.ox - S::R + lane;
+    const int64_t m = item / tiles;
+    const int t = (int)(item - m * tiles);
+    const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
+    const int gy0 = ty * GRAM_TH - S::R + wave, gx0 = tx * p.tw - S::R + lane;
     const int64_t P = (int64_t)p.h * p.w;
-    const float *s1 = p.v1 + g.m * P, *s2 = p.v2 + g.m * P;
+    const float *s1 = p.v1 + m * P, *s2 = p.v2 + m * P;
 #pragma unroll
     for (int jy = 0; jy < S::NJY; ++jy) {
         const int gy = gy0 + 4 * jy;
-        // (rows below the last patch row's window are not read by anyone: short ring tiles skip their loads)
-        const bool yok = gy >= 0 && gy < p.h && wave + 4 * jy < g.rows + 2 * S::R;
+        const bool yok = gy >= 0 && gy < p.h && wave + 4 * jy < S::PH;
 #pragma unroll
         for (int jx = 0; jx < S::NJX; ++jx) {
             const int gx = gx0 + 64 * jx;
@@ -458,6 +419,7 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
     const int64_t per = p.n_items / gridDim.x, extra = p.n_items % gridDim.x;
     const int64_t first = blockIdx.x * per + min((int64_t)blockIdx.x, extra);
     const int64_t count = per + (blockIdx.x < extra ? 1 : 0);
+    const int tiles = p.tiles_x * p.tiles_y;
     double *my_slot = p.slots + (size_t)blockIdx.x * NT * 256;
     bool rmw = (int)blockIdx.x < p.slots_valid;
     int since_flush = 0;
@@ -466,7 +428,7 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
     float ra[S::NJY][S::NJX], rb[S::NJY][S::NJX];
     if (count > 0) {
         // first tile: its own DC estimate, then into buffer 0
-        gram_tile_fetch<KS>(p, first, pw, ra, rb);
+        gram_tile_fetch<KS>(p, first, tiles, pw, ra, rb);
         float s1 = 0.f, s2 = 0.f;
         if (wave == 0) {
 #pragma unroll
@@ -499,10 +461,13 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
         const float *pix = lds + cur * p.buf_stride;
         const bool more = it + 1 < count;
         // the next tile travels from HBM to registers while this one is contracted
-        if (more) gram_tile_fetch<KS>(p, item + 1, pw, ra, rb);
+        if (more) gram_tile_fetch<KS>(p, item + 1, tiles, pw, ra, rb);
 
-        const GramTile g = gram_item_tile(p, item, R);
-        const int rows = g.rows, cols = g.cols;
+        const int64_t m = item / tiles;
+        const int t = (int)(item - m * tiles);
+        const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
+        const int rows = min(GRAM_TH, p.h - ty * GRAM_TH);
+        const int cols = min(p.tw, p.w - tx * p.tw);
         if constexpr (SPLIT) {
             if (TSPLIT == 1 || role == 0) gram_rows_split<G, 0>(pix, p.pitch, rows, cols, pg, q, pix_off, cen_off, acc);
             else gram_rows_split<G, TSPLIT - 1>(pix, p.pitch, rows, cols, pg, q, pix_off, cen_off, acc);
@@ -655,25 +620,19 @@ static int gram_launch(ddcca_ctx *ctx, const GramParams &p, int grid, size_t lds
 }
 
 int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w, int k,
-                      bool cross_only, double *slots, int max_slots, int *slots_valid, bool ring)
+                      bool cross_only, double *slots, int max_slots, int *slots_valid)
 {
     ProfScope prof(ctx, cross_only ? DDCCA_K_GRAM_CROSS : DDCCA_K_GRAM);
     GramParams p;
     p.v1 = v1; p.v2 = v2; p.h = h; p.w = w;
-    const int r = (k - 1) / 2;
-    // split wide images into equal column tiles of at most GRAM_TW_MAX patches; the ring's top and bottom bands
-    // are w + 2r patches wide and may use 8 more columns, so that one tile covers a band of a 128-wide image
-    const int wv = ring ? w + 2 * r : w, tw_max = ring ? GRAM_TW_MAX + 8 : GRAM_TW_MAX;
-    const int w4 = (wv + 3) & ~3;
-    const int ntx = (w4 + tw_max - 1) / tw_max;
+    const int w4 = (w + 3) & ~3;
+    // split wide images into equal column tiles of at most GRAM_TW_MAX patches
+    const int ntx = (w4 + GRAM_TW_MAX - 1) / GRAM_TW_MAX;
     p.tw = (((w4 + ntx - 1) / ntx) + 3) & ~3;
     p.tiles_x = (w + p.tw - 1) / p.tw;
     p.tiles_y = (h + GRAM_TH - 1) / GRAM_TH;
-    p.ring = ring ? 1 : 0;
-    p.ring_nbx = (w + 2 * r + p.tw - 1) / p.tw;
-    p.ring_nby = p.tiles_y;
-    p.tiles = ring ? 2 * p.ring_nbx + 2 * p.ring_nby : p.tiles_x * p.tiles_y;
-    p.n_items = n_maps * p.tiles;
+    p.n_items = n_maps * p.tiles_x * p.tiles_y;
+    const int r = (k - 1) / 2;
     // row pitch: >= tile width + halo, and congruent to k+3 mod 32 so that the window
     // rows a lane group touches fall into distinct LDS banks
     const bool split = ctx->gram_arith == DDCCA_GRAM_BF16X3;
