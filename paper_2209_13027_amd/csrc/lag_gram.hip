@@ -72,66 +72,69 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
     // B operand: image row y + dy = tile row y + m, column x' = tile column x' + K
     const int a_off = K * p.pitch + kk - m + 2 * K;
     const int b_off = m * p.pitch + kk + K;
+    // Tile staging: thread (wave w, lane l) owns tile elements (row w + 4 jy, column l + 64 jx).  The loads of the
+    // next tile are issued before the current one is contracted and written to LDS afterwards, so their latency
+    // hides behind the matrix work.
+    constexpr int NJY = (LAG_TH + 2 * K + 3) / 4, NJX = (LAG_TW_MAX + 2 * K + 63) / 64;
+    float fa[NJY][NJX], fb[NJY][NJX];
+    auto fetch = [&](int64_t item) {
+        const int64_t mp = item / tiles;
+        const int t = (int)(item - mp * tiles);
+        const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
+        const int gy0 = ty * LAG_TH - K + wave, gx0 = tx * p.tw - K + lane;
+        const float *s1 = p.v1 + mp * P, *s2 = p.v2 + mp * P;
+#pragma unroll
+        for (int jy = 0; jy < NJY; ++jy) {
+            const int gy = gy0 + 4 * jy;
+            const bool yok = gy >= 0 && gy < p.h && wave + 4 * jy < PH;
+#pragma unroll
+            for (int jx = 0; jx < NJX; ++jx) {
+                const int gx = gx0 + 64 * jx;
+                float a = 0.f, b = 0.f;
+                if (yok && gx >= 0 && gx < p.w && lane + 64 * jx < PW) {
+                    const int64_t o = (int64_t)gy * p.w + gx;
+                    a = s1[o];
+                    b = s2[o];
+                }
+                fa[jy][jx] = a;
+                fb[jy][jx] = b;
+            }
+        }
+    };
+    auto store = [&]() {
+#pragma unroll
+        for (int jy = 0; jy < NJY; ++jy) {
+            const int yy = wave + 4 * jy;
+#pragma unroll
+            for (int jx = 0; jx < NJX; ++jx) {
+                const int xx = lane + 64 * jx;
+                if (yy < PH && xx < PW) {
+                    lds[yy * p.pitch + xx] = fa[jy][jx];
+                    lds[p.view_stride + yy * p.pitch + xx] = fb[jy][jx];
+                }
+            }
+        }
+    };
+    if (count > 0) {
+        fetch(first);
+        store();
+    }
+    __syncthreads();
     for (int64_t it = 0; it < count; ++it) {
         const int64_t item = first + it;
         const int64_t mp = item / tiles;
         const int t = (int)(item - mp * tiles);
         const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
-        const int gy0 = ty * LAG_TH - K, gx0 = tx * p.tw - K;
-        __syncthreads();                              // the previous tile is no longer read
-        const float *s1 = p.v1 + mp * P, *s2 = p.v2 + mp * P;
-        // wavefront w stages tile rows w, w+4, ...; lane l the columns l, l+64, ...
-        for (int yy = wave; yy < PH; yy += 4) {
-            const int gy = gy0 + yy;
-            const bool yok = gy >= 0 && gy < p.h;
-            const int64_t ro = (int64_t)gy * p.w;
-            for (int xx = lane; xx < PW; xx += 64) {
-                const int gx = gx0 + xx;
-                float a = 0.f, b = 0.f;
-                if (yok && gx >= 0 && gx < p.w) {
-                    a = s1[ro + gx];
-                    b = s2[ro + gx];
-                }
-                lds[yy * p.pitch + xx] = a;
-                lds[p.view_stride + yy * p.pitch + xx] = b;
-            }
-        }
-        __syncthreads();
+        const bool more = it + 1 < count;
+        if (more) fetch(item + 1);
         const int rows = min(LAG_TH, p.h - ty * LAG_TH);
         const int cols = min(p.tw, p.w - tx * p.tw);
         const int steps = (cols + 3) >> 2;            // tw is a multiple of 4: columns past the image hold zeros
-        for (int y = wave; y < rows; y += 4) {
-            const float *ra1 = lds + y * p.pitch + a_off, *rb1 = lds + y * p.pitch + b_off;
-            const float *ra2 = ra1 + p.view_stride, *rb2 = rb1 + p.view_stride;
-            floatx4 c11 = {0.f, 0.f, 0.f, 0.f}, c22 = {0.f, 0.f, 0.f, 0.f}, c12 = {0.f, 0.f, 0.f, 0.f};
-            // two steps per iteration: their operands pair up in two-address LDS reads
-            int s = 0;
-            for (; s + 1 < steps; s += 2) {
-                const float a1 = ra1[4 * s], a1n = ra1[4 * s + 4], b2 = rb2[4 * s], b2n = rb2[4 * s + 4];
-                if (!CROSS) {
-                    const float a2 = ra2[4 * s], a2n = ra2[4 * s + 4], b1 = rb1[4 * s], b1n = rb1[4 * s + 4];
-                    c11 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, c11, 0, 0, 0);
-                    c22 = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b2, c22, 0, 0, 0);
-                    c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b2, c12, 0, 0, 0);
-                    c11 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1n, b1n, c11, 0, 0, 0);
-                    c22 = __builtin_amdgcn_mfma_f32_16x16x4f32(a2n, b2n, c22, 0, 0, 0);
-                    c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1n, b2n, c12, 0, 0, 0);
-                } else {
-                    c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b2, c12, 0, 0, 0);
-                    c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1n, b2n, c12, 0, 0, 0);
-                }
-            }
-            if (s < steps) {
-                const float a1 = ra1[4 * s], b2 = rb2[4 * s];
-                if (!CROSS) {
-                    const float a2 = ra2[4 * s], b1 = rb1[4 * s];
-                    c11 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, c11, 0, 0, 0);
-                    c22 = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b2, c22, 0, 0, 0);
-                }
-                c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b2, c12, 0, 0, 0);
-            }
-            const int gy = ty * LAG_TH + y;
-            const bool is_top = gy == y_top, is_bot = gy == y_bot;
+        // The fp32 accumulators are added to the fp64 registers after every image row: the raw products carry the
+        // DC level of the images, and sums over several rows of a view with a large DC level already cost a digit
+        // (measured 3e-6 instead of 1e-6 relative on C22 when a tile's four rows were summed in fp32).
+        floatx4 c11 = {0.f, 0.f, 0.f, 0.f}, c22 = {0.f, 0.f, 0.f, 0.f}, c12 = {0.f, 0.f, 0.f, 0.f};
+        auto flush = [&](bool is_top, bool is_bot) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 if (!CROSS) {
@@ -144,6 +147,67 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
                 if (is_top) acct[2][v] += (double)c12[v];
                 if (is_bot) accb[2][v] += (double)c12[v];
             }
+            c11 = floatx4{0.f, 0.f, 0.f, 0.f};
+            c22 = floatx4{0.f, 0.f, 0.f, 0.f};
+            c12 = floatx4{0.f, 0.f, 0.f, 0.f};
+        };
+        for (int y = wave; y < rows; y += 4) {
+            const float *ra1 = lds + y * p.pitch + a_off, *rb1 = lds + y * p.pitch + b_off;
+            const float *ra2 = ra1 + p.view_stride, *rb2 = rb1 + p.view_stride;
+            const int gy = ty * LAG_TH + y;
+            const bool is_top = gy == y_top, is_bot = gy == y_bot;
+            // Two steps form a pair whose operands come in two-address LDS reads; the pairs alternate between
+            // two operand sets so that the reads of the next pair are in flight during the MFMAs of this one.
+            // o[] = a1, a1', b2, b2' (and a2, a2', b1, b1' unless only the cross pair is wanted)
+            auto load_pair = [&](float (&o)[8], int q) {
+                o[0] = ra1[8 * q]; o[1] = ra1[8 * q + 4];
+                o[2] = rb2[8 * q]; o[3] = rb2[8 * q + 4];
+                if (!CROSS) {
+                    o[4] = ra2[8 * q]; o[5] = ra2[8 * q + 4];
+                    o[6] = rb1[8 * q]; o[7] = rb1[8 * q + 4];
+                }
+                __builtin_amdgcn_sched_group_barrier(0x100, CROSS ? 2 : 4, 0);     // LDS reads first
+            };
+            auto mfma_pair = [&](const float (&o)[8]) {
+                if (!CROSS) {
+                    c11 = __builtin_amdgcn_mfma_f32_16x16x4f32(o[0], o[6], c11, 0, 0, 0);
+                    c22 = __builtin_amdgcn_mfma_f32_16x16x4f32(o[4], o[2], c22, 0, 0, 0);
+                }
+                c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(o[0], o[2], c12, 0, 0, 0);
+                if (!CROSS) {
+                    c11 = __builtin_amdgcn_mfma_f32_16x16x4f32(o[1], o[7], c11, 0, 0, 0);
+                    c22 = __builtin_amdgcn_mfma_f32_16x16x4f32(o[5], o[3], c22, 0, 0, 0);
+                }
+                c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(o[1], o[3], c12, 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, CROSS ? 2 : 6, 0);     // then the MFMAs of the pair
+            };
+            const int np = steps >> 1;
+            float oa[8], ob[8];
+            if (np > 0) load_pair(oa, 0);
+            int ip = 0;
+            for (; ip + 1 < np; ip += 2) {
+                load_pair(ob, ip + 1);
+                mfma_pair(oa);
+                load_pair(oa, min(ip + 2, np - 1));        // (an even count reads its last pair once more)
+                mfma_pair(ob);
+            }
+            if (ip < np) mfma_pair(oa);
+            if (steps & 1) {
+                const int s = steps - 1;
+                const float a1 = ra1[4 * s], b2 = rb2[4 * s];
+                if (!CROSS) {
+                    const float a2 = ra2[4 * s], b1 = rb1[4 * s];
+                    c11 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, c11, 0, 0, 0);
+                    c22 = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b2, c22, 0, 0, 0);
+                }
+                c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b2, c12, 0, 0, 0);
+            }
+            flush(is_top, is_bot);
+        }
+        __syncthreads();                              // every wavefront is done with the tile
+        if (more) {
+            store();
+            __syncthreads();
         }
     }
     // workgroup total in fp64: the wavefronts add in order, then the slot takes it
@@ -261,6 +325,7 @@ __global__ void lag_cols_kernel(LagColParams p)
             if (active && ca >= 0 && ca < p.w) {
                 float acc = 0.f;
                 const float *pa = sa + ox, *pb = sb + (dy + K) * BW + bcol;
+#pragma unroll 8
                 for (int yy = 0; yy < rows; ++yy) acc += pa[yy * RR] * pb[yy * BW];
                 sum += (double)acc;
                 // the terms of the border rows inside this chunk
