@@ -175,11 +175,11 @@ int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v
  *                     images extended by zeros, the raw Gram entry of taps a and b summed over
  *                     all patch centres of the plane is the correlation of the two views at
  *                     lag s_b - s_a, (2k-1)^2 values per view pair instead of k^4, computed on
- *                     the fp32 matrix instructions and added up in fp64 row by row; the patches
- *                     centred in the frame of width (k-1)/2 outside the image are accumulated by
- *                     the dense kernel and subtracted.  Same result up to fp32 rounding (same
- *                     bars), several times fewer matrix instructions.  k <= 7; k = 9 runs the
- *                     dense fp32 kernel.
+ *                     the fp32 matrix instructions and added up in fp64 row by row; the terms
+ *                     of the first and last (k-1)/2 image rows and columns, which the centres
+ *                     outside the image contribute, are kept apart and taken out exactly.
+ *                     Same result up to fp32 rounding (same bars), several times fewer matrix
+ *                     instructions.  k <= 7; k = 9 runs the dense fp32 kernel.
  * Returns DDCCA_EINVAL for an unknown option or value, DDCCA_ESTATE when the Gram
  * arithmetic is changed between ddcca_corr_begin and the export / solve of that
  * accumulation. */
