@@ -281,6 +281,8 @@ def main():
         fast["gram_ms"] = pf["gram"]["ms"] / args.steps
         fast["gram_useful_tflops"] = (algorithmic_work(wl, M)["gram_flops"] / (fast["gram_ms"] * 1e-3) / 1e12
                                       if fast["gram_ms"] > 0 else 0.0)
+        fast["gram_useful_tflops_note"] = ("flop of the dense formulation per second of Gram time: above the fp32 "
+                                           "MFMA peak when the lag-structured form does the work")
         fast["conv_hash_hist_ms"] = pf["conv_hash_hist"]["ms"] / args.steps
         fast["options"] = ("gram lag-structured fp32" if wl.k <= 7 else "gram bf16x3") + ", conv bf16x3, fused last stage"
         ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
