@@ -267,85 +267,189 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
 // lag_gram_kernel; this kernel adds up, per border column c (r on either side) and lag d,
 //     colsum[c][d] = sum_y X[y][c] X'[y + dy][c + dx]
 // and keeps the terms of the r top and r bottom rows apart (the corners, which rows and columns both cover).
-// grid (image ranges, type x side); a thread owns (column offset, lag) and walks the image rows in chunks.
-// Slot of a workgroup row: [type][side][column offset][1 + 2r][(2K+1)^2] doubles, entry 0 of the fourth index
-// the column sum, 1 + o the term of top row o, 1 + r + o the term of bottom row h-1-o.
-constexpr int LAGC_ROWS = 64;              // image rows per chunk
+// The column sums are the lag kernel's contraction turned by ninety degrees, one column at a time:
+//     A[dy][y'] = X[y' - dy][c],   B[y'][dx] = X'[y'][c + dx],   D[dy][dx] += sum_y' A B     (y' = y + dy),
+// on v_mfma_f32_16x16x4_f32 with K = 4 consecutive rows; the corner terms are single products on the vector ALU.
+// grid (image ranges, side); a workgroup stages, per chunk of rows, the r + 2K columns next to its side of both
+// views; the (column, pair type) chains are dealt to the four wavefronts, the corner entries to the threads.
+// Slot of a workgroup row: [type][side][column offset] x ( 256 doubles: the column sums in accumulator layout,
+// row = vertical lag index; then [2r][(2K+1)^2]: the terms of top row o (index o) and bottom row h-1-o (r + o) ).
+constexpr int LAGC_ROWS = 64;              // image rows per chunk (a multiple of 4)
+constexpr int LAGC_THREADS = 256;
 
 struct LagColParams {
     const float *v1, *v2;
     int h, w;
     int64_t n_maps;
     int types;                             // 3, or 1 (cross only: the (1,2) pair)
-    double *slots;                         // [gridDim.x][3][2][r][1 + 2r][NL*NL]
+    double *slots;                         // [gridDim.x][3][2][r][256 + 2r*NL*NL]
     int slots_valid;
 };
 
 template <int KS>
-__global__ void lag_cols_kernel(LagColParams p)
+__global__ __launch_bounds__(LAGC_THREADS, 3) void lag_cols_kernel(LagColParams p)
 {
     constexpr int K = KS - 1, NL = 2 * K + 1, NLL = NL * NL, RR = (KS - 1) / 2;
-    constexpr int BW = RR + 2 * K;         // columns of the second operand's block (zeros outside the image)
-    constexpr int BH = LAGC_ROWS + 2 * K;
-    __shared__ float sa[LAGC_ROWS * RR];
-    __shared__ float sb[BH * BW];
-    const int type = p.types == 1 ? 2 : blockIdx.y >> 1, side = blockIdx.y & 1;
-    const float *va = type == 1 ? p.v2 : p.v1, *vb = type == 0 ? p.v1 : p.v2;
-    const int tid = threadIdx.x;
-    const bool active = tid < RR * NLL;
-    const int ox = active ? tid / NLL : 0, li = active ? tid - ox * NLL : 0;
-    const int dy = li / NL - K, dx = li % NL - K;
-    // first-operand column of offset ox and the image column the block's column 0 stands for
-    const int ca = side == 0 ? ox : p.w - 1 - ox;
-    const int cb0 = side == 0 ? -K : p.w - RR - K;
-    const int bcol = ca + dx - cb0;        // block column of the second operand: in [0, BW)
+    constexpr int BW = RR + 2 * K;         // staged columns: the r border columns and K more on either side
+    constexpr int BH = LAGC_ROWS + 2 * K;  // staged rows: the chunk and K more on either side
+    constexpr int ENTRY = 256 + 2 * RR * NLL;                      // doubles per (type, side, column)
+    constexpr int NCH = (3 * RR + 3) / 4;                          // chains per wavefront at most
+    constexpr int NCE = (3 * RR * NLL + LAGC_THREADS - 1) / LAGC_THREADS;   // (type, column, lag) triples per thread
+    __shared__ float sb[2][BH * BW];       // view d: rows y0 - K .., columns cb0 .. (zeros outside the image)
+    const int side = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = min(lane & 15, NL - 1), kk = lane >> 4;
+    const int cb0 = side == 0 ? -K : p.w - RR - K;                 // image column of staged column 0
+    const int ntype = p.types;                                     // 3: pairs (1,1) (2,2) (1,2); 1: (1,2) only
+    const int nchain = RR * ntype;
     const int64_t per = p.n_maps / gridDim.x, extra = p.n_maps % gridDim.x;
     const int64_t first = blockIdx.x * per + min((int64_t)blockIdx.x, extra);
     const int64_t count = per + (blockIdx.x < extra ? 1 : 0);
     const int64_t P = (int64_t)p.h * p.w;
-    double sum = 0.0, top[RR], bot[RR];
+    // (a workgroup adds few images' single products per corner entry: fp32 is enough there; fp64 from the slot on)
+    double colsum[NCH][4];
+    float corner[NCE][2 * RR];
 #pragma unroll
-    for (int o = 0; o < RR; ++o) top[o] = bot[o] = 0.0;
-    for (int64_t m = first; m < first + count; ++m) {
-        const float *ia = va + m * P, *ib = vb + m * P;
-        for (int y0 = 0; y0 < p.h; y0 += LAGC_ROWS) {
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) colsum[c][v] = 0.0;
+    // corner terms: thread-owned triples (pair type, column offset, lag), number tid + 256 j; per triple the 2r
+    // border rows.  Decoded once: staged offsets of the two factors inside a staged row, and the views.
+    int cor_a[NCE], cor_b[NCE];            // offset of X[.][ca] and of X'[. + dy][ca + dx] relative to the row start
+    bool cor_on[NCE], cor_a2[NCE], cor_b2[NCE];
+#pragma unroll
+    for (int j = 0; j < NCE; ++j) {
+        const int e = tid + LAGC_THREADS * j;
+        const int li = e % NLL, rest = e / NLL;
+        const int ox = rest % RR, ti = rest / RR;
+        const int t = ntype == 1 ? 2 : ti;
+        const int ca = side == 0 ? ox : p.w - 1 - ox;
+        cor_on[j] = e < ntype * RR * NLL && ca >= 0 && ca < p.w;
+        cor_a[j] = ca - cb0;
+        cor_b[j] = (li / NL - K) * BW + (ca - cb0) + li % NL - K;
+        cor_a2[j] = t == 1;
+        cor_b2[j] = t != 0;
+#pragma unroll
+        for (int q = 0; q < 2 * RR; ++q) corner[j][q] = 0.f;
+    }
+    // (image, chunk) pairs in one sequence; the loads of the next pair are issued before this one is worked on
+    // and written to LDS afterwards
+    constexpr int NST = (BH * BW + LAGC_THREADS - 1) / LAGC_THREADS;
+    const int nchunk = (p.h + LAGC_ROWS - 1) / LAGC_ROWS;
+    const int64_t total = count * nchunk;
+    float f1[NST], f2[NST];
+    auto fetch = [&](int64_t it) {
+        const int64_t mp = first + it / nchunk;
+        const int y0 = (int)(it % nchunk) * LAGC_ROWS;
+        const int rows = min(LAGC_ROWS, p.h - y0);
+        const float *i1 = p.v1 + mp * P, *i2 = p.v2 + mp * P;
+#pragma unroll
+        for (int j = 0; j < NST; ++j) {
+            const int e = tid + LAGC_THREADS * j;
+            const int yy = e / BW, xx = e - yy * BW;
+            const int gy = y0 - K + yy, gx = cb0 + xx;
+            // (all BH rows are written: the last steps of a ragged chunk read up to three rows past rows + 2K)
+            const bool ok = e < BH * BW && yy < rows + 2 * K && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
+            f1[j] = ok ? i1[(int64_t)gy * p.w + gx] : 0.f;
+            f2[j] = ok ? i2[(int64_t)gy * p.w + gx] : 0.f;
+        }
+    };
+    auto store = [&]() {
+#pragma unroll
+        for (int j = 0; j < NST; ++j) {
+            const int e = tid + LAGC_THREADS * j;
+            if (e < BH * BW) {
+                sb[0][e] = f1[j];
+                sb[1][e] = f2[j];
+            }
+        }
+    };
+    if (total > 0) {
+        fetch(0);
+        store();
+    }
+    __syncthreads();
+    for (int64_t it = 0; it < total; ++it) {
+        {
+            const int y0 = (int)(it % nchunk) * LAGC_ROWS;
             const int rows = min(LAGC_ROWS, p.h - y0);
-            __syncthreads();
-            for (int e = tid; e < rows * RR; e += blockDim.x) {
-                const int yy = e / RR, o = e - yy * RR;
-                const int c = side == 0 ? o : p.w - 1 - o;
-                sa[e] = (c >= 0 && c < p.w) ? ia[(int64_t)(y0 + yy) * p.w + c] : 0.f;
-            }
-            for (int e = tid; e < (rows + 2 * K) * BW; e += blockDim.x) {
-                const int yy = e / BW, xx = e - yy * BW;
-                const int gy = y0 - K + yy, gx = cb0 + xx;
-                sb[e] = (gy >= 0 && gy < p.h && gx >= 0 && gx < p.w) ? ib[(int64_t)gy * p.w + gx] : 0.f;
-            }
-            __syncthreads();
-            if (active && ca >= 0 && ca < p.w) {
-                float acc = 0.f;
-                const float *pa = sa + ox, *pb = sb + (dy + K) * BW + bcol;
-#pragma unroll 8
-                for (int yy = 0; yy < rows; ++yy) acc += pa[yy * RR] * pb[yy * BW];
-                sum += (double)acc;
-                // the terms of the border rows inside this chunk
+            const bool more = it + 1 < total;
+            if (more) fetch(it + 1);
+            // column sums: chain (column offset ox, pair type) number ox * ntype + t belongs to wavefront chain % 4;
+            // the chains of a wavefront advance together, one step each at a time
+            const int steps = (rows + 3) >> 2;                     // rows past the image hold zeros
+            const float *pa[NCH], *pb[NCH];
+            bool on[NCH];
+            floatx4 d[NCH];
 #pragma unroll
-                for (int o = 0; o < RR; ++o) {
-                    const int yt = o - y0, yb = p.h - 1 - o - y0;
-                    if (o < p.h && yt >= 0 && yt < rows) top[o] += (double)(pa[yt * RR] * pb[yt * BW]);
-                    if (o < p.h && yb >= 0 && yb < rows) bot[o] += (double)(pa[yb * RR] * pb[yb * BW]);
+            for (int c = 0; c < NCH; ++c) {
+                const int chain = wave + 4 * c;
+                const int ox = chain / ntype, t = ntype == 1 ? 2 : chain - ox * ntype;
+                const int ca = side == 0 ? ox : p.w - 1 - ox;      // image column of the first operand
+                on[c] = chain < nchain && ca >= 0 && ca < p.w;
+                const int cx = on[c] ? ca - cb0 : K;
+                // A: row y' - dy = staged row 4s + kk - m + 2K, column ca;  B: row y' = staged row 4s + kk + K,
+                // column ca + dx = staged column (ca - cb0) + m - K
+                pa[c] = sb[t == 1 ? 1 : 0] + (kk - m + 2 * K) * BW + cx;
+                pb[c] = sb[t == 0 ? 0 : 1] + (kk + K) * BW + cx + m - K;
+                d[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+            }
+            for (int s = 0; s < steps; ++s) {
+#pragma unroll
+                for (int c = 0; c < NCH; ++c)
+                    if (on[c]) d[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(pa[c][4 * s * BW], pb[c][4 * s * BW], d[c], 0, 0, 0);
+            }
+#pragma unroll
+            for (int c = 0; c < NCH; ++c)
+                if (on[c])
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) colsum[c][v] += (double)d[c][v];
+            // corner terms of the border rows inside this chunk: q = o (top row o) or RR + o (bottom row h-1-o)
+#pragma unroll
+            for (int q = 0; q < 2 * RR; ++q) {
+                const int o = q < RR ? q : q - RR;
+                const int gy = q < RR ? o : p.h - 1 - o;
+                if (o < p.h && gy >= y0 && gy < y0 + rows) {        // uniform over the workgroup
+                    const int ro = (gy - y0 + K) * BW;
+#pragma unroll
+                    for (int j = 0; j < NCE; ++j)
+                        if (cor_on[j])
+                            corner[j][q] += sb[cor_a2[j] ? 1 : 0][ro + cor_a[j]] * sb[cor_b2[j] ? 1 : 0][ro + cor_b[j]];
                 }
+            }
+            __syncthreads();                              // every wavefront is done with the staged block
+            if (more) {
+                store();
+                __syncthreads();
             }
         }
     }
-    if (active) {
-        double *d = p.slots + ((((size_t)blockIdx.x * 3 + type) * 2 + side) * RR + ox) * (1 + 2 * RR) * NLL + li;
-        const bool rmw = (int)blockIdx.x < p.slots_valid;
-        d[0] = (rmw ? d[0] : 0.0) + sum;
+    // slot
+    const bool rmw = (int)blockIdx.x < p.slots_valid;
+    double *slot = p.slots + (size_t)blockIdx.x * 3 * 2 * RR * ENTRY;
 #pragma unroll
-        for (int o = 0; o < RR; ++o) {
-            d[(1 + o) * NLL] = (rmw ? d[(1 + o) * NLL] : 0.0) + top[o];
-            d[(1 + RR + o) * NLL] = (rmw ? d[(1 + RR + o) * NLL] : 0.0) + bot[o];
+    for (int c = 0; c < NCH; ++c) {
+        const int chain = wave + 4 * c;
+        if (chain < nchain) {
+            const int ox = chain / ntype, t = ntype == 1 ? 2 : chain - ox * ntype;
+            double *d = slot + ((size_t)(t * 2 + side) * RR + ox) * ENTRY;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int e = v * 64 + lane;
+                d[e] = (rmw ? d[e] : 0.0) + colsum[c][v];
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NCE; ++j) {
+        const int e = tid + LAGC_THREADS * j;
+        if (e < ntype * RR * NLL) {
+            const int li = e % NLL, rest = e / NLL;
+            const int ox = rest % RR, ti = rest / RR;
+            const int t = ntype == 1 ? 2 : ti;
+            double *d = slot + ((size_t)(t * 2 + side) * RR + ox) * ENTRY + 256 + li;
+#pragma unroll
+            for (int q = 0; q < 2 * RR; ++q) d[q * NLL] = (rmw ? d[q * NLL] : 0.0) + (double)corner[j][q];
         }
     }
 }
@@ -353,7 +457,7 @@ __global__ void lag_cols_kernel(LagColParams p)
 // ---- from the statistics to the stacked Gram --------------------------------------------------------------
 struct LagStats {
     const double *R;                       // [1 + 2r][3][256]: reduced lag_gram_kernel slots
-    const double *C;                       // [3][2][r][1 + 2r][NL*NL]: reduced lag_cols_kernel slots
+    const double *C;                       // [3][2][r][256 + 2r*NL*NL]: reduced lag_cols_kernel slots
     int ks, h, w, cross;
 };
 
@@ -377,11 +481,11 @@ __device__ double lag_entry(const LagStats &st, int type, int a, int b)
     const int xsd = sx > 0 ? 0 : 1, xn = min(sx > 0 ? sx : -sx, st.w);
     double v = lag_value(st.R, type, iy, ix);
     for (int o = 0; o < yn; ++o) v -= lag_value(st.R + (size_t)(1 + ysd * r + o) * 768, type, iy, ix);
-    const double *cb = st.C + ((size_t)(type * 2 + xsd) * r) * (1 + 2 * r) * NLL + iy * NL + ix;
+    const int entry = 256 + 2 * r * NLL;
     for (int o = 0; o < xn; ++o) {
-        const double *c = cb + (size_t)o * (1 + 2 * r) * NLL;
-        v -= c[0];
-        for (int oy = 0; oy < yn; ++oy) v += c[(1 + ysd * r + oy) * NLL];
+        const double *c = st.C + ((size_t)(type * 2 + xsd) * r + o) * entry;
+        v -= c[(iy & 3) * 64 + 16 * (iy >> 2) + ix];                 // column sum: row = vertical lag index
+        for (int oy = 0; oy < yn; ++oy) v += c[256 + (ysd * r + oy) * NLL + iy * NL + ix];
     }
     return v;
 }
@@ -420,12 +524,12 @@ __global__ void lag_to_stacked_kernel(LagStats st, double *__restrict__ stacked)
 
 bool lag_supported(int k) { return 2 * (k - 1) + 1 <= 16; }
 int max_lag_slots(ddcca_ctx *ctx) { return ctx->n_cu * 6; }
-int max_lag_col_slots(ddcca_ctx *ctx) { return ctx->n_cu; }
+int max_lag_col_slots(ddcca_ctx *ctx) { return ctx->n_cu * 3 / 2; }   // x 2 sides: three workgroups per CU
 size_t lag_slot_doubles(int k) { return (size_t)(1 + 2 * ((k - 1) / 2)) * LAG_E; }
 size_t lag_col_slot_doubles(int k)
 {
     const int r = (k - 1) / 2, nl = 2 * (k - 1) + 1;
-    return (size_t)3 * 2 * r * (1 + 2 * r) * nl * nl;
+    return (size_t)3 * 2 * r * (256 + 2 * r * nl * nl);
 }
 
 template <int KS>
@@ -443,7 +547,7 @@ int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_
     if (!lag_supported(k)) return fail(ctx, DDCCA_EINVAL, "the lag-structured Gram needs k <= 7");
     LagParams p;
     p.v1 = v1; p.v2 = v2; p.h = h; p.w = w;
-    const int K = k - 1, r = (k - 1) / 2;
+    const int K = k - 1;
     const int w4 = (w + 3) & ~3;
     const int ntx = (w4 + LAG_TW_MAX - 1) / LAG_TW_MAX;
     p.tw = (((w4 + ntx - 1) / ntx) + 3) & ~3;
@@ -467,9 +571,8 @@ int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_
     c.slots = col_slots;
     c.slots_valid = *col_slots_valid;
     const int cgrid = (int)std::min<int64_t>(max_col_slots, std::max<int64_t>(n_maps, 1));
-    const int nl = 2 * K + 1;
-    const int cthreads = (r * nl * nl + 63) / 64 * 64;
-    const dim3 cg(cgrid, cross_only ? 2 : 6);
+    const int cthreads = LAGC_THREADS;
+    const dim3 cg(cgrid, 2);
     switch (k) {
         case 3:
             lag_launch<3>(ctx, p, grid, lds, cross_only);
