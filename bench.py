@@ -100,7 +100,7 @@ def main():
     ap.add_argument("--gram", default="fp32", choices=["fp32", "bf16x3", "lag"],
                     help="arithmetic of the patch-Gram accumulation: fp32 matrix instructions (the headline path), "
                          "three-piece bf16 operands on the bf16 matrix pipeline (same accuracy), or the "
-                         "lag-structured form on the fp32 matrix instructions (k <= 7; same accuracy)")
+                         "lag-structured form on the fp32 matrix instructions (same accuracy)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=0, help="images in the CPU-oracle sample (0 = default)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -259,13 +259,13 @@ def main():
         ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
     fast = None
     if args.conv == "fp32" and args.gram == "fp32" and not args.fused:
-        # The whole step once more with every widened option on: the lag-structured Gram (k <= 7; three-piece
-        # bf16 operands at k = 9), three-piece bf16 operands in the convolution (same accuracy bars, see the
-        # parity tests) and the fused last stage.  Not part of `value`.
+        # The whole step once more with every widened option on: the lag-structured Gram, three-piece bf16
+        # operands in the convolution (same accuracy bars, see the parity tests) and the fused last stage.
+        # Not part of `value`.
         from paper_2209_13027_amd.binding import (OPT_CONV_ARITH, CONV_BF16X3, CONV_FP32, OPT_GRAM_ARITH,
-                                                  GRAM_BF16X3, GRAM_FP32, GRAM_LAG_FP32)
+                                                  GRAM_FP32, GRAM_LAG_FP32)
         ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
-        ctx.set_option(OPT_GRAM_ARITH, GRAM_LAG_FP32 if wl.k <= 7 else GRAM_BF16X3)
+        ctx.set_option(OPT_GRAM_ARITH, GRAM_LAG_FP32)
 
         def fast_step():
             mdl = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
@@ -284,7 +284,7 @@ def main():
         fast["gram_useful_tflops_note"] = ("flop of the dense formulation per second of Gram time: above the fp32 "
                                            "MFMA peak when the lag-structured form does the work")
         fast["conv_hash_hist_ms"] = pf["conv_hash_hist"]["ms"] / args.steps
-        fast["options"] = ("gram lag-structured fp32" if wl.k <= 7 else "gram bf16x3") + ", conv bf16x3, fused last stage"
+        fast["options"] = "gram lag-structured fp32, conv bf16x3, fused last stage"
         ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
         ctx.set_option(OPT_GRAM_ARITH, GRAM_FP32)
     ctx.profile_select(None)

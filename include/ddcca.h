@@ -179,7 +179,11 @@ int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v
  *                     of the first and last (k-1)/2 image rows and columns, which the centres
  *                     outside the image contribute, are kept apart and taken out exactly.
  *                     Same result up to fp32 rounding (same bars), several times fewer matrix
- *                     instructions.  k <= 7; k = 9 runs the dense fp32 kernel.
+ *                     instructions.  k = 9 has 17 lags per axis against the 16 rows of the
+ *                     matrix instruction: it keeps the lags -8 .. 7 for the four ordered view
+ *                     pairs, reads a lag with a component +8 as the exchanged pair at the
+ *                     negated lag, and sums the one remaining tap pair (opposite patch
+ *                     corners) directly.
  * Returns DDCCA_EINVAL for an unknown option or value, DDCCA_ESTATE when the Gram
  * arithmetic is changed between ddcca_corr_begin and the export / solve of that
  * accumulation. */

@@ -46,7 +46,7 @@ struct ddcca_ctx {
     bool class_img_ready = false;           // class_img was filled directly (not from class_sum)
     ddcca::Buffer prev_img;                 // sum images of the previous stage's inputs (next-stage learning)
     ddcca::Buffer stacked;                  // 3 x [tiles*256] double (main, class, total)
-    bool lag_active = false;                // this accumulation runs lag-structured (option + k <= 7)
+    bool lag_active = false;                // this accumulation runs lag-structured (option set)
     int lag_valid = 0, lag_col_valid = 0;   // lag slots holding data
     ddcca::Buffer lag_slots, lag_col_slots; // per-workgroup lag statistics (rows / border columns)
     ddcca::Buffer lag_R, lag_C;             // the same, reduced
@@ -108,11 +108,11 @@ int launch_gram_reduce(ddcca_ctx *ctx, const double *slots, int n_slots, int k, 
 // the same fixed-order sum for slots of E doubles each
 int launch_reduce_slots(ddcca_ctx *ctx, const double *slots, int n_slots, int E, double *out);
 
-// ---- lag-structured accumulation (DDCCA_GRAM_LAG_FP32; k <= 7) ----------------------------------------
+// ---- lag-structured accumulation (DDCCA_GRAM_LAG_FP32) ----------------------------------------
 bool lag_supported(int k);
 int max_lag_slots(ddcca_ctx *ctx);
 int max_lag_col_slots(ddcca_ctx *ctx);
-size_t lag_slot_doubles(int k);       // lag correlations: all rows + the r top and r bottom rows, three pair types
+size_t lag_slot_doubles(int k);       // lag correlations: all rows + the r top and r bottom rows, per pair type
 size_t lag_col_slot_doubles(int k);   // border columns and corners
 // adds the lag statistics of n_maps map pairs to the two slot sets (cross_only: the (1,2) pair alone)
 int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w, int k,

@@ -17,7 +17,10 @@
 // Three products per step (view 1 x view 1, 2 x 2, 1 x 2) against 21 / 6 tiles of the dense kernel at k = 7 / 5.
 // The raw products carry the DC level of the images, which the differences to the centre pixel of the dense
 // kernel do not, so the fp32 accumulators are added to fp64 registers after every image row.
-// k <= 7 only: 2k-1 lags per axis have to fit the 16 rows of the instruction.
+// k = 9 has 17 lags per axis, one more than the instruction has rows: there the lags -8 .. 7 are kept for the
+// four ORDERED pair types (1,1) (2,2) (1,2) (2,1), an entry whose lag has a component +8 is taken as the
+// transposed entry (S_x[a][b] of the pair (d,d') = S_x[b][a] of (d',d), lag negated), and the single tap pair
+// whose lag is (+8,-8) -- opposite corners of the patch -- is summed directly by lag_special_kernel.
 #include "ddcca_internal.h"
 
 namespace ddcca {
@@ -27,25 +30,43 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int LAG_THREADS = 256;
 constexpr int LAG_TH = 16;                 // image rows per tile
 constexpr int LAG_TW_MAX = 128;            // image columns per tile (multiple of 4)
-constexpr int LAG_E = 3 * 256;             // doubles per slot: three 16 x 16 tiles (11, 22, 12) in accumulator layout
+
+template <int KS>
+struct LagGeom {
+    static constexpr int K = KS - 1;                   // largest lag
+    static constexpr int RR = (KS - 1) / 2;            // patch radius = border rows / columns kept apart
+    static constexpr bool WIDE = 2 * K + 1 > 16;       // k = 9: lags -K .. 7 only, four ordered pair types
+    static constexpr int NL = WIDE ? 16 : 2 * K + 1;   // lags per axis: -K .. NL - 1 - K
+    static constexpr int NLL = NL * NL;
+    static constexpr int NTY = WIDE ? 4 : 3;           // pair types (1,1) (2,2) (1,2) [(2,1)]
+    static constexpr int E = NTY * 256;                // doubles per row set: one 16 x 16 tile per type
+    static constexpr int SLOT = (1 + 2 * RR) * E + (WIDE ? 8 : 0);   // lag_gram_kernel slot (+ lag_special_kernel's)
+};
+// view (0 / 1) of the first and of the second factor of a pair type
+__host__ __device__ constexpr int lag_view_a(int t) { return (t == 1 || t == 3) ? 1 : 0; }
+__host__ __device__ constexpr int lag_view_b(int t) { return (t == 1 || t == 2) ? 1 : 0; }
 
 struct LagParams {
     const float *v1, *v2;                  // [n_maps][h][w]
     int h, w, tiles_x, tiles_y, tw;
     int pitch, view_stride;                // LDS floats per tile row / per view
     int64_t n_items;                       // n_maps * tiles_y * tiles_x
-    double *slots;                         // [grid][LAG_E]
+    double *slots;                         // [grid][(1 + 2r) E (+ 8 at k = 9)]
     int slots_valid;                       // slots below this hold earlier sums
 };
 
 // One workgroup walks a contiguous range of (map, tile) items.  A tile is LAG_TH image rows x tw columns with a
 // halo of K = k-1 on every side (zeros outside the image), both views.  Wavefront w owns tile rows w, w+4, ...
+// CROSS: only the pair types that mix the views.
 template <int KS, bool CROSS>
 __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
 {
-    constexpr int K = KS - 1;              // largest lag
-    constexpr int NL = 2 * K + 1;          // lags per axis
-    static_assert(NL <= 16, "the lags of one axis must fit the 16 rows of the matrix instruction");
+    using G = LagGeom<KS>;
+    constexpr int K = G::K, NL = G::NL, RR = G::RR, NTY = G::NTY;
+    constexpr bool SAME = !CROSS;                  // types 0, 1 wanted
+    constexpr bool T21 = G::WIDE;                  // type 3 wanted
+    constexpr bool NEED2 = SAME || T21;            // the view-2 first factor and the view-1 second factor are used
+    constexpr int NMF = (SAME ? 2 : 0) + 1 + (T21 ? 1 : 0);   // matrix instructions per step
     extern __shared__ float lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = min(lane & 15, NL - 1);  // lag index of this lane's row / column (rows past NL repeat the last)
@@ -56,13 +77,12 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
     const int64_t count = per + (blockIdx.x < extra ? 1 : 0);
     const int tiles = p.tiles_x * p.tiles_y;
     const int64_t P = (int64_t)p.h * p.w;
-    constexpr int RR = (KS - 1) / 2;       // patch radius = border rows kept apart at the top and at the bottom
-    double accd[3][4], acct[3][4], accb[3][4];     // all rows; this wavefront's top / bottom border row
+    double accd[NTY][4], acct[NTY][4], accb[NTY][4];     // all rows; this wavefront's top / bottom border row
 #pragma unroll
-    for (int t = 0; t < 3; ++t)
+    for (int t = 0; t < NTY; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) accd[t][v] = acct[t][v] = accb[t][v] = 0.0;
-    // Image row y is always handled by wavefront y % 4 (tiles start at multiples of 16), so the RR < 4 border
+    // Image row y is always handled by wavefront y % 4 (tiles start at multiples of 16), so the RR <= 4 border
     // rows at either end have one owner each: top row o belongs to wavefront o, bottom row h-1-o to
     // wavefront (h-1-o) % 4.
     const int o_top = wave, o_bot = (((p.h - 1 - wave) % 4) + 4) % 4;
@@ -133,23 +153,30 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
         // The fp32 accumulators are added to the fp64 registers after every image row: the raw products carry the
         // DC level of the images, and sums over several rows of a view with a large DC level already cost a digit
         // (measured 3e-6 instead of 1e-6 relative on C22 when a tile's four rows were summed in fp32).
-        floatx4 c11 = {0.f, 0.f, 0.f, 0.f}, c22 = {0.f, 0.f, 0.f, 0.f}, c12 = {0.f, 0.f, 0.f, 0.f};
+        floatx4 c[NTY];
+#pragma unroll
+        for (int t2 = 0; t2 < NTY; ++t2) c[t2] = floatx4{0.f, 0.f, 0.f, 0.f};
         auto flush = [&](bool is_top, bool is_bot) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                if (!CROSS) {
-                    accd[0][v] += (double)c11[v];
-                    accd[1][v] += (double)c22[v];
-                    if (is_top) { acct[0][v] += (double)c11[v]; acct[1][v] += (double)c22[v]; }
-                    if (is_bot) { accb[0][v] += (double)c11[v]; accb[1][v] += (double)c22[v]; }
+            for (int t2 = 0; t2 < NTY; ++t2) {
+                if ((t2 < 2 && !SAME) || (t2 == 3 && !T21)) continue;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    accd[t2][v] += (double)c[t2][v];
+                    if (is_top) acct[t2][v] += (double)c[t2][v];
+                    if (is_bot) accb[t2][v] += (double)c[t2][v];
                 }
-                accd[2][v] += (double)c12[v];
-                if (is_top) acct[2][v] += (double)c12[v];
-                if (is_bot) accb[2][v] += (double)c12[v];
+                c[t2] = floatx4{0.f, 0.f, 0.f, 0.f};
             }
-            c11 = floatx4{0.f, 0.f, 0.f, 0.f};
-            c22 = floatx4{0.f, 0.f, 0.f, 0.f};
-            c12 = floatx4{0.f, 0.f, 0.f, 0.f};
+        };
+        // one step: a1 x b1 -> (1,1), a2 x b2 -> (2,2), a1 x b2 -> (1,2), a2 x b1 -> (2,1)
+        auto step = [&](float a1, float b2, float a2, float b1) {
+            if (SAME) {
+                c[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, c[0], 0, 0, 0);
+                c[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b2, c[1], 0, 0, 0);
+            }
+            c[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b2, c[2], 0, 0, 0);
+            if (T21) c[NTY - 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b1, c[NTY - 1], 0, 0, 0);
         };
         for (int y = wave; y < rows; y += 4) {
             const float *ra1 = lds + y * p.pitch + a_off, *rb1 = lds + y * p.pitch + b_off;
@@ -158,28 +185,20 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
             const bool is_top = gy == y_top, is_bot = gy == y_bot;
             // Two steps form a pair whose operands come in two-address LDS reads; the pairs alternate between
             // two operand sets so that the reads of the next pair are in flight during the MFMAs of this one.
-            // o[] = a1, a1', b2, b2' (and a2, a2', b1, b1' unless only the cross pair is wanted)
+            // o[] = a1, a1', b2, b2', a2, a2', b1, b1'
             auto load_pair = [&](float (&o)[8], int q) {
                 o[0] = ra1[8 * q]; o[1] = ra1[8 * q + 4];
                 o[2] = rb2[8 * q]; o[3] = rb2[8 * q + 4];
-                if (!CROSS) {
+                if (NEED2) {
                     o[4] = ra2[8 * q]; o[5] = ra2[8 * q + 4];
                     o[6] = rb1[8 * q]; o[7] = rb1[8 * q + 4];
                 }
-                __builtin_amdgcn_sched_group_barrier(0x100, CROSS ? 2 : 4, 0);     // LDS reads first
+                __builtin_amdgcn_sched_group_barrier(0x100, NEED2 ? 4 : 2, 0);     // LDS reads first
             };
             auto mfma_pair = [&](const float (&o)[8]) {
-                if (!CROSS) {
-                    c11 = __builtin_amdgcn_mfma_f32_16x16x4f32(o[0], o[6], c11, 0, 0, 0);
-                    c22 = __builtin_amdgcn_mfma_f32_16x16x4f32(o[4], o[2], c22, 0, 0, 0);
-                }
-                c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(o[0], o[2], c12, 0, 0, 0);
-                if (!CROSS) {
-                    c11 = __builtin_amdgcn_mfma_f32_16x16x4f32(o[1], o[7], c11, 0, 0, 0);
-                    c22 = __builtin_amdgcn_mfma_f32_16x16x4f32(o[5], o[3], c22, 0, 0, 0);
-                }
-                c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(o[1], o[3], c12, 0, 0, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, CROSS ? 2 : 6, 0);     // then the MFMAs of the pair
+                step(o[0], o[2], o[4], o[6]);
+                step(o[1], o[3], o[5], o[7]);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2 * NMF, 0);           // then the MFMAs of the pair
             };
             const int np = steps >> 1;
             float oa[8], ob[8];
@@ -194,13 +213,7 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
             if (ip < np) mfma_pair(oa);
             if (steps & 1) {
                 const int s = steps - 1;
-                const float a1 = ra1[4 * s], b2 = rb2[4 * s];
-                if (!CROSS) {
-                    const float a2 = ra2[4 * s], b1 = rb1[4 * s];
-                    c11 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, c11, 0, 0, 0);
-                    c22 = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b2, c22, 0, 0, 0);
-                }
-                c12 = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b2, c12, 0, 0, 0);
+                step(ra1[4 * s], rb2[4 * s], NEED2 ? ra2[4 * s] : 0.f, NEED2 ? rb1[4 * s] : 0.f);
             }
             flush(is_top, is_bot);
         }
@@ -216,7 +229,7 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
     for (int wv = 0; wv < 4; ++wv) {
         if (wave == wv) {
 #pragma unroll
-            for (int t = 0; t < 3; ++t)
+            for (int t = 0; t < NTY; ++t)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int e = (t * 4 + v) * 64 + lane;
@@ -225,24 +238,24 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
         }
         __syncthreads();
     }
-    // slot: [1 + 2 RR][LAG_E]: all rows, top rows 0 .. RR-1, bottom rows h-1 .. h-RR
-    double *slot = p.slots + (size_t)blockIdx.x * (1 + 2 * RR) * LAG_E;
+    // slot: [1 + 2 RR][E]: all rows, top rows 0 .. RR-1, bottom rows h-1 .. h-RR
+    double *slot = p.slots + (size_t)blockIdx.x * G::SLOT;
     const bool rmw = (int)blockIdx.x < p.slots_valid;
-    for (int e = threadIdx.x; e < LAG_E; e += LAG_THREADS) slot[e] = (rmw ? slot[e] : 0.0) + st[e];
+    for (int e = threadIdx.x; e < G::E; e += LAG_THREADS) slot[e] = (rmw ? slot[e] : 0.0) + st[e];
     // border rows: the owner writes its registers; rows the image does not have stay zero
 #pragma unroll
     for (int o = 0; o < RR; ++o) {
         if (o >= p.h && wave == 0 && !rmw) {
-            for (int e = lane; e < LAG_E; e += 64) {
-                slot[(1 + o) * LAG_E + e] = 0.0;
-                slot[(1 + RR + o) * LAG_E + e] = 0.0;
+            for (int e = lane; e < G::E; e += 64) {
+                slot[(1 + o) * G::E + e] = 0.0;
+                slot[(1 + RR + o) * G::E + e] = 0.0;
             }
         }
     }
     if (y_top >= 0) {
-        double *d = slot + (size_t)(1 + o_top) * LAG_E;
+        double *d = slot + (size_t)(1 + o_top) * G::E;
 #pragma unroll
-        for (int t = 0; t < 3; ++t)
+        for (int t = 0; t < NTY; ++t)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int e = (t * 4 + v) * 64 + lane;
@@ -250,9 +263,9 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
             }
     }
     if (y_bot >= 0) {
-        double *d = slot + (size_t)(1 + RR + o_bot) * LAG_E;
+        double *d = slot + (size_t)(1 + RR + o_bot) * G::E;
 #pragma unroll
-        for (int t = 0; t < 3; ++t)
+        for (int t = 0; t < NTY; ++t)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int e = (t * 4 + v) * 64 + lane;
@@ -275,32 +288,37 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
 // Slot of a workgroup row: [type][side][column offset] x ( 256 doubles: the column sums in accumulator layout,
 // row = vertical lag index; then [2r][(2K+1)^2]: the terms of top row o (index o) and bottom row h-1-o (r + o) ).
 constexpr int LAGC_ROWS = 64;              // image rows per chunk (a multiple of 4)
-constexpr int LAGC_THREADS = 256;
+// threads: 256, at k = 9 512 (sixteen chains and 4096 corner triples to share out)
+template <int KS>
+constexpr int lagc_threads() { return LagGeom<KS>::WIDE ? 512 : 256; }
 
 struct LagColParams {
     const float *v1, *v2;
     int h, w;
     int64_t n_maps;
-    int types;                             // 3, or 1 (cross only: the (1,2) pair)
-    double *slots;                         // [gridDim.x][3][2][r][256 + 2r*NL*NL]
+    int cross;                             // only the pair types that mix the views: (1,2) [and (2,1) at k = 9]
+    double *slots;                         // [gridDim.x][NTY][2][r][256 + 2r*NL*NL]
     int slots_valid;
 };
 
 template <int KS>
-__global__ __launch_bounds__(LAGC_THREADS, 3) void lag_cols_kernel(LagColParams p)
+__global__ __launch_bounds__(lagc_threads<KS>(), LagGeom<KS>::WIDE ? 2 : 3) void lag_cols_kernel(LagColParams p)
 {
-    constexpr int K = KS - 1, NL = 2 * K + 1, NLL = NL * NL, RR = (KS - 1) / 2;
+    using G = LagGeom<KS>;
+    constexpr int K = G::K, NL = G::NL, NLL = G::NLL, RR = G::RR, NTY = G::NTY;
+    constexpr int LAGC_THREADS = lagc_threads<KS>(), NW = LAGC_THREADS / 64;
     constexpr int BW = RR + 2 * K;         // staged columns: the r border columns and K more on either side
     constexpr int BH = LAGC_ROWS + 2 * K;  // staged rows: the chunk and K more on either side
     constexpr int ENTRY = 256 + 2 * RR * NLL;                      // doubles per (type, side, column)
-    constexpr int NCH = (3 * RR + 3) / 4;                          // chains per wavefront at most
-    constexpr int NCE = (3 * RR * NLL + LAGC_THREADS - 1) / LAGC_THREADS;   // (type, column, lag) triples per thread
+    constexpr int NCH = (NTY * RR + NW - 1) / NW;                  // chains per wavefront at most
+    constexpr int NCE = (NTY * RR * NLL + LAGC_THREADS - 1) / LAGC_THREADS;   // (type, column, lag) triples per thread
     __shared__ float sb[2][BH * BW];       // view d: rows y0 - K .., columns cb0 .. (zeros outside the image)
     const int side = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = min(lane & 15, NL - 1), kk = lane >> 4;
     const int cb0 = side == 0 ? -K : p.w - RR - K;                 // image column of staged column 0
-    const int ntype = p.types;                                     // 3: pairs (1,1) (2,2) (1,2); 1: (1,2) only
+    const int ntype = p.cross ? NTY - 2 : NTY;                     // pair types wanted: all, or those from (1,2) on
+    const int t0 = p.cross ? 2 : 0;
     const int nchain = RR * ntype;
     const int64_t per = p.n_maps / gridDim.x, extra = p.n_maps % gridDim.x;
     const int64_t first = blockIdx.x * per + min((int64_t)blockIdx.x, extra);
@@ -322,13 +340,13 @@ __global__ __launch_bounds__(LAGC_THREADS, 3) void lag_cols_kernel(LagColParams 
         const int e = tid + LAGC_THREADS * j;
         const int li = e % NLL, rest = e / NLL;
         const int ox = rest % RR, ti = rest / RR;
-        const int t = ntype == 1 ? 2 : ti;
+        const int t = t0 + ti;
         const int ca = side == 0 ? ox : p.w - 1 - ox;
         cor_on[j] = e < ntype * RR * NLL && ca >= 0 && ca < p.w;
         cor_a[j] = ca - cb0;
         cor_b[j] = (li / NL - K) * BW + (ca - cb0) + li % NL - K;
-        cor_a2[j] = t == 1;
-        cor_b2[j] = t != 0;
+        cor_a2[j] = lag_view_a(t) == 1;
+        cor_b2[j] = lag_view_b(t) == 1;
 #pragma unroll
         for (int q = 0; q < 2 * RR; ++q) corner[j][q] = 0.f;
     }
@@ -375,7 +393,7 @@ __global__ __launch_bounds__(LAGC_THREADS, 3) void lag_cols_kernel(LagColParams 
             const int rows = min(LAGC_ROWS, p.h - y0);
             const bool more = it + 1 < total;
             if (more) fetch(it + 1);
-            // column sums: chain (column offset ox, pair type) number ox * ntype + t belongs to wavefront chain % 4;
+            // column sums: chain (column offset ox, pair type) number ox * ntype + t belongs to wavefront chain % NW;
             // the chains of a wavefront advance together, one step each at a time
             const int steps = (rows + 3) >> 2;                     // rows past the image hold zeros
             const float *pa[NCH], *pb[NCH];
@@ -383,15 +401,15 @@ __global__ __launch_bounds__(LAGC_THREADS, 3) void lag_cols_kernel(LagColParams 
             floatx4 d[NCH];
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
-                const int chain = wave + 4 * c;
-                const int ox = chain / ntype, t = ntype == 1 ? 2 : chain - ox * ntype;
+                const int chain = wave + NW * c;
+                const int ox = chain / ntype, t = t0 + chain - ox * ntype;
                 const int ca = side == 0 ? ox : p.w - 1 - ox;      // image column of the first operand
                 on[c] = chain < nchain && ca >= 0 && ca < p.w;
                 const int cx = on[c] ? ca - cb0 : K;
                 // A: row y' - dy = staged row 4s + kk - m + 2K, column ca;  B: row y' = staged row 4s + kk + K,
                 // column ca + dx = staged column (ca - cb0) + m - K
-                pa[c] = sb[t == 1 ? 1 : 0] + (kk - m + 2 * K) * BW + cx;
-                pb[c] = sb[t == 0 ? 0 : 1] + (kk + K) * BW + cx + m - K;
+                pa[c] = sb[lag_view_a(t)] + (kk - m + 2 * K) * BW + cx;
+                pb[c] = sb[lag_view_b(t)] + (kk + K) * BW + cx + m - K;
                 d[c] = floatx4{0.f, 0.f, 0.f, 0.f};
             }
             for (int s = 0; s < steps; ++s) {
@@ -426,12 +444,12 @@ __global__ __launch_bounds__(LAGC_THREADS, 3) void lag_cols_kernel(LagColParams 
     }
     // slot
     const bool rmw = (int)blockIdx.x < p.slots_valid;
-    double *slot = p.slots + (size_t)blockIdx.x * 3 * 2 * RR * ENTRY;
+    double *slot = p.slots + (size_t)blockIdx.x * NTY * 2 * RR * ENTRY;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        const int chain = wave + 4 * c;
+        const int chain = wave + NW * c;
         if (chain < nchain) {
-            const int ox = chain / ntype, t = ntype == 1 ? 2 : chain - ox * ntype;
+            const int ox = chain / ntype, t = t0 + chain - ox * ntype;
             double *d = slot + ((size_t)(t * 2 + side) * RR + ox) * ENTRY;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
@@ -446,7 +464,7 @@ __global__ __launch_bounds__(LAGC_THREADS, 3) void lag_cols_kernel(LagColParams 
         if (e < ntype * RR * NLL) {
             const int li = e % NLL, rest = e / NLL;
             const int ox = rest % RR, ti = rest / RR;
-            const int t = ntype == 1 ? 2 : ti;
+            const int t = t0 + ti;
             double *d = slot + ((size_t)(t * 2 + side) * RR + ox) * ENTRY + 256 + li;
 #pragma unroll
             for (int q = 0; q < 2 * RR; ++q) d[q * NLL] = (rmw ? d[q * NLL] : 0.0) + (double)corner[j][q];
@@ -454,10 +472,63 @@ __global__ __launch_bounds__(LAGC_THREADS, 3) void lag_cols_kernel(LagColParams 
     }
 }
 
+// ---- the opposite-corner tap pair at k = 9 -----------------------------------------------------------------
+// The one tap pair whose lag (+K, -K) no transposition brings into the range the matrix instruction holds:
+// a* = top right tap, b* = bottom left tap.  Per ordered pair type (X, X')
+//     V = sum over the patch centres p inside the image of  X[p + s_a*] X'[p + s_b*],
+// summed directly, in fp64, into the eight doubles that follow a lag_gram_kernel slot (same grid, same slots).
+struct LagSpecialParams {
+    const float *v1, *v2;
+    int h, w, r;
+    int64_t n_maps;
+    double *slots;                         // slot b: slots + b * slot_doubles + tail
+    size_t slot_doubles, tail;
+    int slots_valid;
+};
+
+__global__ __launch_bounds__(256) void lag_special_kernel(LagSpecialParams p)
+{
+    __shared__ double part[4][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hp = p.h - 2 * p.r, wp = p.w - 2 * p.r;          // patch centres per column / row
+    double s[4] = {0.0, 0.0, 0.0, 0.0};
+    if (hp > 0 && wp > 0) {
+        const int64_t pp = (int64_t)hp * wp, total = p.n_maps * pp;
+        const int64_t per = total / gridDim.x, extra = total % gridDim.x;
+        const int64_t first = blockIdx.x * per + min((int64_t)blockIdx.x, extra);
+        const int64_t end = first + per + (blockIdx.x < extra ? 1 : 0);
+        const int64_t P = (int64_t)p.h * p.w;
+        for (int64_t e = first + tid; e < end; e += 256) {
+            const int64_t mp = e / pp;
+            const int rem = (int)(e - mp * pp);
+            const int py = rem / wp + p.r, px = rem % wp + p.r;
+            const int64_t ua = mp * P + (int64_t)(py - p.r) * p.w + px + p.r;     // p + s_a*: r up, r to the right
+            const int64_t ub = mp * P + (int64_t)(py + p.r) * p.w + px - p.r;     // p + s_b*: r down, r to the left
+            const double a1 = p.v1[ua], a2 = p.v2[ua], b1 = p.v1[ub], b2 = p.v2[ub];
+            s[0] += a1 * b1;
+            s[1] += a2 * b2;
+            s[2] += a1 * b2;
+            s[3] += a2 * b1;
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s[t] += __shfl_down(s[t], off, 64);
+        if (lane == 0) part[wave][t] = s[t];
+    }
+    __syncthreads();
+    if (tid < 4) {
+        double *d = p.slots + (size_t)blockIdx.x * p.slot_doubles + p.tail + tid;
+        const double v = part[0][tid] + part[1][tid] + part[2][tid] + part[3][tid];
+        *d = ((int)blockIdx.x < p.slots_valid ? *d : 0.0) + v;
+    }
+}
+
 // ---- from the statistics to the stacked Gram --------------------------------------------------------------
 struct LagStats {
-    const double *R;                       // [1 + 2r][3][256]: reduced lag_gram_kernel slots
-    const double *C;                       // [3][2][r][256 + 2r*NL*NL]: reduced lag_cols_kernel slots
+    const double *R;                       // [1 + 2r][NTY][256] (+ 8 at k = 9): reduced lag_gram_kernel slots
+    const double *C;                       // [NTY][2][r][256 + 2r*NL*NL]: reduced lag_cols_kernel slots
     int ks, h, w, cross;
 };
 
@@ -467,20 +538,38 @@ __device__ __forceinline__ double lag_value(const double *R, int type, int iy, i
     return R[(type * 4 + (ix & 3)) * 64 + 16 * (ix >> 2) + iy];
 }
 
+// the pair type with the two views exchanged
+__device__ __forceinline__ int lag_type_swapped(int t) { return t == 2 ? 3 : t == 3 ? 2 : t; }
+
 // sum over the patch centres p INSIDE the image of X[p + s_a] X'[p + s_b] for the pair type (X, X'), a the tap
 // of X: with u = p + s_a, u runs over the image minus the rows and columns that p + s_a can reach only from
 // outside -- the first s rows if s = s_a.y > 0, the last -s if s < 0, the same for the columns -- so
 //     = R(d) - (those rows of R) - (those columns) + (their corners),    d = s_b - s_a.
+// k = 9 keeps the lags -K .. K-1 only: a lag with a component +K is looked up as the same sum with the factors
+// exchanged (pair type swapped, taps swapped, lag negated), the lags (+K,-K) and (-K,+K) as the directly summed
+// opposite-corner value.
 __device__ double lag_entry(const LagStats &st, int type, int a, int b)
 {
-    const int ks = st.ks, r = (ks - 1) / 2, K = ks - 1, NL = 2 * K + 1, NLL = NL * NL;
-    const int ay = a / ks, ax = a - ay * ks, by = b / ks, bx = b - by * ks;
-    const int iy = by - ay + K, ix = bx - ax + K;
+    const int ks = st.ks, r = (ks - 1) / 2, K = ks - 1;
+    const bool wide = 2 * K + 1 > 16;
+    const int NL = wide ? 16 : 2 * K + 1, NLL = NL * NL, E = (wide ? 4 : 3) * 256;
+    int ay = a / ks, ax = a - ay * ks, by = b / ks, bx = b - by * ks;
+    int iy = by - ay + K, ix = bx - ax + K;
+    if (wide && (iy == 2 * K || ix == 2 * K)) {
+        const double *special = st.R + (size_t)(1 + 2 * r) * E;
+        if (iy == 2 * K && ix == 0) return special[type];
+        if (ix == 2 * K && iy == 0) return special[lag_type_swapped(type)];
+        type = lag_type_swapped(type);
+        int t = ay; ay = by; by = t;
+        t = ax; ax = bx; bx = t;
+        iy = by - ay + K;
+        ix = bx - ax + K;
+    }
     const int sy = ay - r, sx = ax - r;
     const int ysd = sy > 0 ? 0 : 1, yn = min(sy > 0 ? sy : -sy, st.h);
     const int xsd = sx > 0 ? 0 : 1, xn = min(sx > 0 ? sx : -sx, st.w);
     double v = lag_value(st.R, type, iy, ix);
-    for (int o = 0; o < yn; ++o) v -= lag_value(st.R + (size_t)(1 + ysd * r + o) * 768, type, iy, ix);
+    for (int o = 0; o < yn; ++o) v -= lag_value(st.R + (size_t)(1 + ysd * r + o) * E, type, iy, ix);
     const int entry = 256 + 2 * r * NLL;
     for (int o = 0; o < xn; ++o) {
         const double *c = st.C + ((size_t)(type * 2 + xsd) * r + o) * entry;
@@ -522,21 +611,29 @@ __global__ void lag_to_stacked_kernel(LagStats st, double *__restrict__ stacked)
                  lag_raw(st, d, CEN, d2, CEN);
 }
 
-bool lag_supported(int k) { return 2 * (k - 1) + 1 <= 16; }
+bool lag_supported(int k) { return k == 3 || k == 5 || k == 7 || k == 9; }
 int max_lag_slots(ddcca_ctx *ctx) { return ctx->n_cu * 6; }
 int max_lag_col_slots(ddcca_ctx *ctx) { return ctx->n_cu * 3 / 2; }   // x 2 sides: three workgroups per CU
-size_t lag_slot_doubles(int k) { return (size_t)(1 + 2 * ((k - 1) / 2)) * LAG_E; }
+static bool lag_wide(int k) { return 2 * (k - 1) + 1 > 16; }
+static size_t lag_row_set_doubles(int k) { return (size_t)(lag_wide(k) ? 4 : 3) * 256; }
+size_t lag_slot_doubles(int k)
+{
+    return (size_t)(1 + 2 * ((k - 1) / 2)) * lag_row_set_doubles(k) + (lag_wide(k) ? 8 : 0);
+}
 size_t lag_col_slot_doubles(int k)
 {
-    const int r = (k - 1) / 2, nl = 2 * (k - 1) + 1;
-    return (size_t)3 * 2 * r * (256 + 2 * r * nl * nl);
+    const int r = (k - 1) / 2, nl = lag_wide(k) ? 16 : 2 * (k - 1) + 1;
+    return (size_t)(lag_wide(k) ? 4 : 3) * 2 * r * (256 + 2 * r * nl * nl);
 }
 
 template <int KS>
-static void lag_launch(ddcca_ctx *ctx, const LagParams &p, int grid, size_t lds, bool cross)
+static void lag_launch(ddcca_ctx *ctx, const LagParams &p, int grid, size_t lds, bool cross, const LagColParams &c,
+                       dim3 cgrid)
 {
+    static_assert(LagGeom<KS>::RR <= 4, "one owner wavefront per border row");
     if (cross) hipLaunchKernelGGL((lag_gram_kernel<KS, true>), dim3(grid), dim3(LAG_THREADS), lds, ctx->stream, p);
     else hipLaunchKernelGGL((lag_gram_kernel<KS, false>), dim3(grid), dim3(LAG_THREADS), lds, ctx->stream, p);
+    hipLaunchKernelGGL(lag_cols_kernel<KS>, cgrid, dim3(lagc_threads<KS>()), 0, ctx->stream, c);
 }
 
 int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w, int k,
@@ -544,7 +641,8 @@ int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_
                     int max_col_slots, int *col_slots_valid)
 {
     ProfScope prof(ctx, cross_only ? DDCCA_K_GRAM_CROSS : DDCCA_K_GRAM);
-    if (!lag_supported(k)) return fail(ctx, DDCCA_EINVAL, "the lag-structured Gram needs k <= 7");
+    if (!lag_supported(k)) return fail(ctx, DDCCA_EINVAL, "the lag-structured Gram needs k in {3, 5, 7, 9}");
+    if (n_maps < 1 || h < 1 || w < 1) return fail(ctx, DDCCA_EINVAL, "lag-structured Gram: empty input");
     LagParams p;
     p.v1 = v1; p.v2 = v2; p.h = h; p.w = w;
     const int K = k - 1;
@@ -560,33 +658,35 @@ int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_
     while (pitch % 32 != 17) ++pitch;
     p.pitch = pitch;
     p.view_stride = (LAG_TH + 2 * K) * pitch + 8;
-    const size_t lds = std::max<size_t>((size_t)2 * p.view_stride * sizeof(float), (size_t)LAG_E * sizeof(double));
+    const size_t lds = std::max<size_t>((size_t)2 * p.view_stride * sizeof(float),
+                                        lag_row_set_doubles(k) * sizeof(double));
+    if (p.tw > LAG_TW_MAX || lds > 64 * 1024) return fail(ctx, DDCCA_EINVAL, "lag-structured Gram: tile too large");
     p.slots = slots;
     p.slots_valid = *slots_valid;
     const int grid = (int)std::min<int64_t>(max_slots, std::max<int64_t>(p.n_items, 1));
     // the border columns and corners of the same maps
     LagColParams c;
     c.v1 = v1; c.v2 = v2; c.h = h; c.w = w; c.n_maps = n_maps;
-    c.types = cross_only ? 1 : 3;
+    c.cross = cross_only ? 1 : 0;
     c.slots = col_slots;
     c.slots_valid = *col_slots_valid;
     const int cgrid = (int)std::min<int64_t>(max_col_slots, std::max<int64_t>(n_maps, 1));
-    const int cthreads = LAGC_THREADS;
     const dim3 cg(cgrid, 2);
     switch (k) {
-        case 3:
-            lag_launch<3>(ctx, p, grid, lds, cross_only);
-            hipLaunchKernelGGL(lag_cols_kernel<3>, cg, dim3(cthreads), 0, ctx->stream, c);
-            break;
-        case 5:
-            lag_launch<5>(ctx, p, grid, lds, cross_only);
-            hipLaunchKernelGGL(lag_cols_kernel<5>, cg, dim3(cthreads), 0, ctx->stream, c);
-            break;
-        case 7:
-            lag_launch<7>(ctx, p, grid, lds, cross_only);
-            hipLaunchKernelGGL(lag_cols_kernel<7>, cg, dim3(cthreads), 0, ctx->stream, c);
-            break;
+        case 3: lag_launch<3>(ctx, p, grid, lds, cross_only, c, cg); break;
+        case 5: lag_launch<5>(ctx, p, grid, lds, cross_only, c, cg); break;
+        case 7: lag_launch<7>(ctx, p, grid, lds, cross_only, c, cg); break;
+        case 9: lag_launch<9>(ctx, p, grid, lds, cross_only, c, cg); break;
         default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
+    }
+    if (lag_wide(k)) {
+        LagSpecialParams sp;
+        sp.v1 = v1; sp.v2 = v2; sp.h = h; sp.w = w; sp.r = (k - 1) / 2; sp.n_maps = n_maps;
+        sp.slots = slots;
+        sp.slot_doubles = lag_slot_doubles(k);
+        sp.tail = sp.slot_doubles - 8;
+        sp.slots_valid = *slots_valid;
+        hipLaunchKernelGGL(lag_special_kernel, dim3(grid), dim3(256), 0, ctx->stream, sp);
     }
     DDCCA_HIP(ctx, hipGetLastError());
     *slots_valid = std::max(*slots_valid, grid);

@@ -75,7 +75,7 @@ class FullRun:
 
 @pytest.fixture(scope="module", params=[("object", False), ("stress", False), ("large_scale", False),
                                         ("object", True), ("stress", True), ("large_scale", True),
-                                        ("object", "lag"), ("large_scale", "lag")],
+                                        ("object", "lag"), ("large_scale", "lag"), ("stress", "lag")],
                 ids=lambda p: p[0] + ("-lag" if p[1] == "lag" else "-bf16x3" if p[1] else ""))
 def run(request):
     if not torch.cuda.is_available():

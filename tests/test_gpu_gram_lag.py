@@ -54,7 +54,12 @@ def gpu_matrices(ctx, V1, V2, cls, n_cls, G, k, cuts=None):
 @pytest.mark.parametrize("n_img,G,h,w,k,n_cls", [
     (8, 1, 32, 32, 5, 4),        # tiny geometry
     (6, 1, 112, 92, 7, 3),       # small-face geometry
-    (4, 2, 40, 52, 9, 2),        # k=9: the dense kernel takes over
+    (4, 2, 40, 52, 9, 2),        # k=9: sixteen of the seventeen lags, four ordered pair types, the corner pair
+    (2, 1, 20, 133, 9, 2),       # k=9, two column tiles, ragged
+    (1, 1, 3, 3, 9, 1),          # k=9, image smaller than the patch
+    (2, 1, 7, 40, 9, 2),         # k=9, image lower than the patch
+    (2, 1, 50, 128, 9, 3),       # k=9, full-width tiles
+    (3, 1, 9, 9, 9, 2),          # k=9, image as large as one patch: one term in the opposite-corner sum
     (5, 3, 21, 30, 3, 2),        # k=3, ragged rows (21) and columns (30 = 4*7+2)
     (3, 1, 37, 133, 5, 3),       # two column tiles, ragged tail (133 = 4*33+1)
     (2, 4, 16, 260, 7, 2),       # three column tiles
