@@ -68,7 +68,8 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
     constexpr bool NEED2 = SAME || T21;            // the view-2 first factor and the view-1 second factor are used
     constexpr int NMF = (SAME ? 2 : 0) + 1 + (T21 ? 1 : 0);   // matrix instructions per step
     extern __shared__ float lds[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: what depends on it stays on the scalar unit
     const int m = min(lane & 15, NL - 1);  // lag index of this lane's row / column (rows past NL repeat the last)
     const int kk = lane >> 4;
     const int PH = LAG_TH + 2 * K, PW = p.tw + 2 * K;
@@ -156,16 +157,29 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
         floatx4 c[NTY];
 #pragma unroll
         for (int t2 = 0; t2 < NTY; ++t2) c[t2] = floatx4{0.f, 0.f, 0.f, 0.f};
+        // (is_top / is_bot are the same for the whole wavefront.  The empty asm statements keep the compiler from
+        // turning the rare border-row additions into unconditional ones with selects, and from holding the
+        // converted values of the common path in registers for them.)
         auto flush = [&](bool is_top, bool is_bot) {
+            auto border = [&](double (&acc)[NTY][4]) {
+#pragma unroll
+                for (int t2 = 0; t2 < NTY; ++t2) {
+                    if ((t2 < 2 && !SAME) || (t2 == 3 && !T21)) continue;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        float x = c[t2][v];
+                        asm volatile("" : "+v"(x));
+                        acc[t2][v] += (double)x;
+                    }
+                }
+            };
+            if (is_top) border(acct);
+            if (is_bot) border(accb);
 #pragma unroll
             for (int t2 = 0; t2 < NTY; ++t2) {
                 if ((t2 < 2 && !SAME) || (t2 == 3 && !T21)) continue;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    accd[t2][v] += (double)c[t2][v];
-                    if (is_top) acct[t2][v] += (double)c[t2][v];
-                    if (is_bot) accb[t2][v] += (double)c[t2][v];
-                }
+                for (int v = 0; v < 4; ++v) accd[t2][v] += (double)c[t2][v];
                 c[t2] = floatx4{0.f, 0.f, 0.f, 0.f};
             }
         };
@@ -314,7 +328,8 @@ __global__ __launch_bounds__(lagc_threads<KS>(), LagGeom<KS>::WIDE ? 2 : 3) void
     constexpr int NCE = (NTY * RR * NLL + LAGC_THREADS - 1) / LAGC_THREADS;   // (type, column, lag) triples per thread
     __shared__ float sb[2][BH * BW];       // view d: rows y0 - K .., columns cb0 .. (zeros outside the image)
     const int side = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: what depends on it stays on the scalar unit
     const int m = min(lane & 15, NL - 1), kk = lane >> 4;
     const int cb0 = side == 0 ? -K : p.w - RR - K;                 // image column of staged column 0
     const int ntype = p.cross ? NTY - 2 : NTY;                     // pair types wanted: all, or those from (1,2) on
@@ -489,7 +504,8 @@ struct LagSpecialParams {
 __global__ __launch_bounds__(256) void lag_special_kernel(LagSpecialParams p)
 {
     __shared__ double part[4][4];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: what depends on it stays on the scalar unit
     const int hp = p.h - 2 * p.r, wp = p.w - 2 * p.r;          // patch centres per column / row
     double s[4] = {0.0, 0.0, 0.0, 0.0};
     if (hp > 0 && wp > 0) {
