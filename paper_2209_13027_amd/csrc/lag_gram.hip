@@ -199,13 +199,15 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
             const bool is_top = gy == y_top, is_bot = gy == y_bot;
             // Two steps form a pair whose operands come in two-address LDS reads; the pairs alternate between
             // two operand sets so that the reads of the next pair are in flight during the MFMAs of this one.
-            // o[] = a1, a1', b2, b2', a2, a2', b1, b1'
-            auto load_pair = [&](float (&o)[8], int q) {
-                o[0] = ra1[8 * q]; o[1] = ra1[8 * q + 4];
-                o[2] = rb2[8 * q]; o[3] = rb2[8 * q + 4];
+            // The four operand streams advance through one running pointer each, every read at a constant
+            // offset from it.  o[] = a1, a1', b2, b2', a2, a2', b1, b1'
+            const float *qa1 = ra1, *qb2 = rb2, *qa2 = ra2, *qb1 = rb1;
+            auto load_pair = [&](float (&o)[8], int off) {
+                o[0] = qa1[off]; o[1] = qa1[off + 4];
+                o[2] = qb2[off]; o[3] = qb2[off + 4];
                 if (NEED2) {
-                    o[4] = ra2[8 * q]; o[5] = ra2[8 * q + 4];
-                    o[6] = rb1[8 * q]; o[7] = rb1[8 * q + 4];
+                    o[4] = qa2[off]; o[5] = qa2[off + 4];
+                    o[6] = qb1[off]; o[7] = qb1[off + 4];
                 }
                 __builtin_amdgcn_sched_group_barrier(0x100, NEED2 ? 4 : 2, 0);     // LDS reads first
             };
@@ -219,10 +221,13 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
             if (np > 0) load_pair(oa, 0);
             int ip = 0;
             for (; ip + 1 < np; ip += 2) {
-                load_pair(ob, ip + 1);
+                load_pair(ob, 8);
                 mfma_pair(oa);
-                load_pair(oa, min(ip + 2, np - 1));        // (an even count reads its last pair once more)
+                // (after the last pair of an even count this reads one pair further, at most tw + 2K + 7 floats
+                // into the tile row: inside the row pitch or, in a view's last row, the pad behind it; unused)
+                load_pair(oa, 16);
                 mfma_pair(ob);
+                qa1 += 16; qb2 += 16; qa2 += 16; qb1 += 16;
             }
             if (ip < np) mfma_pair(oa);
             if (steps & 1) {
