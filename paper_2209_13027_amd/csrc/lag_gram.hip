@@ -68,6 +68,9 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
     constexpr bool NEED2 = SAME || T21;            // the view-2 first factor and the view-1 second factor are used
     constexpr int NMF = (SAME ? 2 : 0) + 1 + (T21 ? 1 : 0);   // matrix instructions per step
     extern __shared__ float lds[];
+    typedef __attribute__((address_space(3))) float lds_float;
+    typedef __attribute__((address_space(3))) char lds_char;
+    const lds_char *const lds_base = (const lds_char *)lds;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: what depends on it stays on the scalar unit
     const int m = min(lane & 15, NL - 1);  // lag index of this lane's row / column (rows past NL repeat the last)
@@ -201,13 +204,17 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
             // two operand sets so that the reads of the next pair are in flight during the MFMAs of this one.
             // The four operand streams advance through one running pointer each, every read at a constant
             // offset from it.  o[] = a1, a1', b2, b2', a2, a2', b1, b1'
-            const float *qa1 = ra1, *qb2 = rb2, *qa2 = ra2, *qb1 = rb1;
+            // (byte addresses inside LDS, made opaque so that each stays ONE register that the reads offset)
+            unsigned qa1 = (unsigned)((y * p.pitch + a_off) * 4), qb2 = (unsigned)((p.view_stride + y * p.pitch + b_off) * 4);
+            unsigned qa2 = qa1 + (unsigned)p.view_stride * 4, qb1 = qb2 - (unsigned)p.view_stride * 4;
+            asm volatile("" : "+v"(qa1), "+v"(qb2), "+v"(qa2), "+v"(qb1));
+            auto at = [&](unsigned q, int off) { return *(const lds_float *)(lds_base + q + 4 * off); };
             auto load_pair = [&](float (&o)[8], int off) {
-                o[0] = qa1[off]; o[1] = qa1[off + 4];
-                o[2] = qb2[off]; o[3] = qb2[off + 4];
+                o[0] = at(qa1, off); o[1] = at(qa1, off + 4);
+                o[2] = at(qb2, off); o[3] = at(qb2, off + 4);
                 if (NEED2) {
-                    o[4] = qa2[off]; o[5] = qa2[off + 4];
-                    o[6] = qb1[off]; o[7] = qb1[off + 4];
+                    o[4] = at(qa2, off); o[5] = at(qa2, off + 4);
+                    o[6] = at(qb1, off); o[7] = at(qb1, off + 4);
                 }
                 __builtin_amdgcn_sched_group_barrier(0x100, NEED2 ? 4 : 2, 0);     // LDS reads first
             };
@@ -227,7 +234,7 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
                 // into the tile row: inside the row pitch or, in a view's last row, the pad behind it; unused)
                 load_pair(oa, 16);
                 mfma_pair(ob);
-                qa1 += 16; qb2 += 16; qa2 += 16; qb1 += 16;
+                qa1 += 64; qb2 += 64; qa2 += 64; qb1 += 64;
             }
             if (ip < np) mfma_pair(oa);
             if (steps & 1) {
