@@ -14,7 +14,8 @@
 // The lag correlations run on v_mfma_f32_16x16x4_f32, one image row at a time: rows of the matrix instruction =
 // horizontal lag, columns = vertical lag, K = 4 consecutive pixels x' of the row:
 //     A[dx][x'] = X[y][x' - dx],   B[x'][dy] = X'[y + dy][x'],   D[dx][dy] += sum_x' A B.
-// Three products per step (view 1 x view 1, 2 x 2, 1 x 2) against 21 / 6 tiles of the dense kernel at k = 7 / 5.
+// Three products per step (view 1 x view 1, 2 x 2, 1 x 2; four at k = 9) against 21 / 6 tiles of the dense kernel
+// at k = 7 / 5.
 // The raw products carry the DC level of the images, which the differences to the centre pixel of the dense
 // kernel do not, so the fp32 accumulators are added to fp64 registers after every image row.
 // k = 9 has 17 lags per axis, one more than the instruction has rows: there the lags -8 .. 7 are kept for the
@@ -310,9 +311,9 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
 //     A[dy][y'] = X[y' - dy][c],   B[y'][dx] = X'[y'][c + dx],   D[dy][dx] += sum_y' A B     (y' = y + dy),
 // on v_mfma_f32_16x16x4_f32 with K = 4 consecutive rows; the corner terms are single products on the vector ALU.
 // grid (image ranges, side); a workgroup stages, per chunk of rows, the r + 2K columns next to its side of both
-// views; the (column, pair type) chains are dealt to the four wavefronts, the corner entries to the threads.
+// views; the (column, pair type) chains are dealt to the wavefronts, the corner entries to the threads.
 // Slot of a workgroup row: [type][side][column offset] x ( 256 doubles: the column sums in accumulator layout,
-// row = vertical lag index; then [2r][(2K+1)^2]: the terms of top row o (index o) and bottom row h-1-o (r + o) ).
+// row = vertical lag index; then [2r][NL^2]: the terms of top row o (index o) and bottom row h-1-o (r + o) ).
 constexpr int LAGC_ROWS = 64;              // image rows per chunk (a multiple of 4)
 // threads: 256, at k = 9 512 (sixteen chains and 4096 corner triples to share out)
 template <int KS>
