@@ -29,19 +29,32 @@ namespace ddcca {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int LAG_THREADS = 256;
-constexpr int LAG_TH = 16;                 // image rows per tile
 constexpr int LAG_TW_MAX = 128;            // image columns per tile (multiple of 4)
 
+// Geometry of the lag statistics for patch side KS.  The four ORDERED pair types (1,1) (2,2) (1,2) (2,1) are kept
+// for every k, so that a horizontal lag dx < 0 can be read as the exchanged pair at the negated lag and the rows
+// of the matrix instruction only have to hold dx = 0 .. K: RG consecutive image rows then share one instruction
+// (rows (rho, dx), rho = image row inside the group; columns = vertical offset from the group's first row,
+// c = rho + dy + K).  k = 9 keeps dx = -K .. K-1 in its sixteen rows, one image row at a time.
 template <int KS>
 struct LagGeom {
     static constexpr int K = KS - 1;                   // largest lag
     static constexpr int RR = (KS - 1) / 2;            // patch radius = border rows / columns kept apart
-    static constexpr bool WIDE = 2 * K + 1 > 16;       // k = 9: lags -K .. 7 only, four ordered pair types
-    static constexpr int NL = WIDE ? 16 : 2 * K + 1;   // lags per axis: -K .. NL - 1 - K
+    static constexpr bool WIDE = 2 * K + 1 > 16;       // k = 9
+    static constexpr int NL = WIDE ? 16 : 2 * K + 1;   // lags per axis in the border-column statistics: -K .. NL-1-K
     static constexpr int NLL = NL * NL;
-    static constexpr int NTY = WIDE ? 4 : 3;           // pair types (1,1) (2,2) (1,2) [(2,1)]
+    static constexpr int NTY = 4;                      // pair types (1,1) (2,2) (1,2) (2,1)
     static constexpr int E = NTY * 256;                // doubles per row set: one 16 x 16 tile per type
-    static constexpr int SLOT = (1 + 2 * RR) * E + (WIDE ? 8 : 0);   // lag_gram_kernel slot (+ lag_special_kernel's)
+    static constexpr int NJ = WIDE ? 16 : K + 1;       // horizontal lags held per image row
+    static constexpr int DX0 = WIDE ? -K : 0;          // the first of them
+    static constexpr int RG = 16 / NJ;                 // image rows per matrix instruction
+    static constexpr int CMAX = WIDE ? 15 : RG - 1 + 2 * K;   // last column in use
+    static constexpr int TH = KS == 5 ? 24 : KS == 3 ? 20 : 16;   // image rows per tile: a multiple of 4 RG
+    static constexpr int NTG = (RR + RG - 1) / RG;     // row groups that hold one of the RR top rows
+    static constexpr int NBG = (RR - 1 + RG - 1) / RG + 1;   // ... bottom rows (whatever the image height)
+    static constexpr int SETS = 1 + NTG + NBG;         // all rows; top groups; bottom groups
+    static constexpr int SLOT = SETS * E + (WIDE ? 8 : 0);   // lag_gram_kernel slot (+ lag_special_kernel's)
+    static_assert(CMAX <= 15 && RG * NJ <= 16 && TH % (4 * RG) == 0 && NTG <= 4 && NBG <= 4, "lag geometry");
 };
 // view (0 / 1) of the first and of the second factor of a pair type
 __host__ __device__ constexpr int lag_view_a(int t) { return (t == 1 || t == 3) ? 1 : 0; }
@@ -52,61 +65,65 @@ struct LagParams {
     int h, w, tiles_x, tiles_y, tw;
     int pitch, view_stride;                // LDS floats per tile row / per view
     int64_t n_items;                       // n_maps * tiles_y * tiles_x
-    double *slots;                         // [grid][(1 + 2r) E (+ 8 at k = 9)]
+    double *slots;                         // [grid][SLOT]
     int slots_valid;                       // slots below this hold earlier sums
 };
 
-// One workgroup walks a contiguous range of (map, tile) items.  A tile is LAG_TH image rows x tw columns with a
-// halo of K = k-1 on every side (zeros outside the image), both views.  Wavefront w owns tile rows w, w+4, ...
+// One workgroup walks a contiguous range of (map, tile) items.  A tile is TH image rows x tw columns with a halo
+// of K = k-1 on every side (zeros outside the image), both views.  Wavefront w owns the row groups w, w+4, ... of
+// a tile; tiles start at multiples of 4 RG rows, so row group gi of the IMAGE always belongs to wavefront gi % 4.
 // CROSS: only the pair types that mix the views.
 template <int KS, bool CROSS>
 __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
 {
     using G = LagGeom<KS>;
-    constexpr int K = G::K, NL = G::NL, RR = G::RR, NTY = G::NTY;
+    constexpr int K = G::K, RR = G::RR, NTY = G::NTY, RG = G::RG, TH = G::TH, NTG = G::NTG, NBG = G::NBG;
     constexpr bool SAME = !CROSS;                  // types 0, 1 wanted
-    constexpr bool T21 = G::WIDE;                  // type 3 wanted
-    constexpr bool NEED2 = SAME || T21;            // the view-2 first factor and the view-1 second factor are used
-    constexpr int NMF = (SAME ? 2 : 0) + 1 + (T21 ? 1 : 0);   // matrix instructions per step
+    constexpr int NMF = SAME ? 4 : 2;              // matrix instructions per step
     extern __shared__ float lds[];
     typedef __attribute__((address_space(3))) float lds_float;
     typedef __attribute__((address_space(3))) char lds_char;
     const lds_char *const lds_base = (const lds_char *)lds;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: what depends on it stays on the scalar unit
-    const int m = min(lane & 15, NL - 1);  // lag index of this lane's row / column (rows past NL repeat the last)
+    // this lane's row (rho, dx) of the A operand and column c of the B operand (rows / columns past the ones in
+    // use repeat the last)
+    const int irow = min(lane & 15, RG * G::NJ - 1);
+    const int rho = irow / G::NJ, dx = irow - rho * G::NJ + G::DX0;
+    const int ccol = min(lane & 15, G::CMAX);
     const int kk = lane >> 4;
-    const int PH = LAG_TH + 2 * K, PW = p.tw + 2 * K;
+    const int PH = TH + 2 * K, PW = p.tw + 2 * K;
     const int64_t per = p.n_items / gridDim.x, extra = p.n_items % gridDim.x;
     const int64_t first = blockIdx.x * per + min((int64_t)blockIdx.x, extra);
     const int64_t count = per + (blockIdx.x < extra ? 1 : 0);
     const int tiles = p.tiles_x * p.tiles_y;
     const int64_t P = (int64_t)p.h * p.w;
-    double accd[NTY][4], acct[NTY][4], accb[NTY][4];     // all rows; this wavefront's top / bottom border row
+    double accd[NTY][4], acct[NTY][4], accb[NTY][4];     // all rows; this wavefront's top / bottom row group
 #pragma unroll
     for (int t = 0; t < NTY; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) accd[t][v] = acct[t][v] = accb[t][v] = 0.0;
-    // Image row y is always handled by wavefront y % 4 (tiles start at multiples of 16), so the RR <= 4 border
-    // rows at either end have one owner each: top row o belongs to wavefront o, bottom row h-1-o to
-    // wavefront (h-1-o) % 4.
-    const int o_top = wave, o_bot = (((p.h - 1 - wave) % 4) + 4) % 4;
-    const int y_top = (o_top < RR && o_top < p.h) ? o_top : -1;
-    const int y_bot = (o_bot < RR && o_bot < p.h) ? p.h - 1 - o_bot : -1;
-    // A operand: image row y = tile row y + K, column x' - dx = tile column x' + K - (m - K)
-    // B operand: image row y + dy = tile row y + m, column x' = tile column x' + K
-    const int a_off = K * p.pitch + kk - m + 2 * K;
-    const int b_off = m * p.pitch + kk + K;
+    // Row groups that hold border rows: the top ones are groups 0 .. NTG-1 (owners: wavefronts 0 .. NTG-1), the
+    // bottom ones the groups gb0 .. glast of the rows h-RR .. h-1 (at most NBG <= 4 consecutive groups: one owner
+    // each).  A wavefront keeps the sums of its top group and of its bottom group in register sets of their own.
+    const int gb0 = max(0, p.h - RR) / RG, glast = (p.h - 1) / RG;
+    const int my_top = (wave < NTG && wave * RG < p.h) ? wave : -1;
+    const int cand = gb0 + ((wave - gb0 % 4) + 4) % 4;
+    const int my_bot = cand <= glast ? cand : -1;
+    // A operand: image row y0 + rho = tile row y + rho + K, column x' - dx = tile column x' + K - dx
+    // B operand: image row y0 + c - K = tile row y + c, column x' = tile column x' + K
+    const int a_off = (rho + K) * p.pitch + kk - dx + K;
+    const int b_off = ccol * p.pitch + kk + K;
     // Tile staging: thread (wave w, lane l) owns tile elements (row w + 4 jy, column l + 64 jx).  The loads of the
     // next tile are issued before the current one is contracted and written to LDS afterwards, so their latency
     // hides behind the matrix work.
-    constexpr int NJY = (LAG_TH + 2 * K + 3) / 4, NJX = (LAG_TW_MAX + 2 * K + 63) / 64;
+    constexpr int NJY = (TH + 2 * K + 3) / 4, NJX = (LAG_TW_MAX + 2 * K + 63) / 64;
     float fa[NJY][NJX], fb[NJY][NJX];
     auto fetch = [&](int64_t item) {
         const int64_t mp = item / tiles;
         const int t = (int)(item - mp * tiles);
         const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
-        const int gy0 = ty * LAG_TH - K + wave, gx0 = tx * p.tw - K + lane;
+        const int gy0 = ty * TH - K + wave, gx0 = tx * p.tw - K + lane;
         const float *s1 = p.v1 + mp * P, *s2 = p.v2 + mp * P;
 #pragma unroll
         for (int jy = 0; jy < NJY; ++jy) {
@@ -152,23 +169,24 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
         const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
         const bool more = it + 1 < count;
         if (more) fetch(item + 1);
-        const int rows = min(LAG_TH, p.h - ty * LAG_TH);
+        const int rows = min(TH, p.h - ty * TH);
         const int cols = min(p.tw, p.w - tx * p.tw);
         const int steps = (cols + 3) >> 2;            // tw is a multiple of 4: columns past the image hold zeros
-        // The fp32 accumulators are added to the fp64 registers after every image row: the raw products carry the
-        // DC level of the images, and sums over several rows of a view with a large DC level already cost a digit
-        // (measured 3e-6 instead of 1e-6 relative on C22 when a tile's four rows were summed in fp32).
+        // The fp32 accumulators are added to the fp64 registers after every row group (a sum along ONE image row
+        // per accumulator row): the raw products carry the DC level of the images, and sums over several rows of
+        // a view with a large DC level already cost a digit (measured 3e-6 instead of 1e-6 relative on C22 when
+        // four rows were summed in fp32).
         floatx4 c[NTY];
 #pragma unroll
         for (int t2 = 0; t2 < NTY; ++t2) c[t2] = floatx4{0.f, 0.f, 0.f, 0.f};
         // (is_top / is_bot are the same for the whole wavefront.  The empty asm statements keep the compiler from
-        // turning the rare border-row additions into unconditional ones with selects, and from holding the
+        // turning the rare border-group additions into unconditional ones with selects, and from holding the
         // converted values of the common path in registers for them.)
         auto flush = [&](bool is_top, bool is_bot) {
             auto border = [&](double (&acc)[NTY][4]) {
 #pragma unroll
                 for (int t2 = 0; t2 < NTY; ++t2) {
-                    if ((t2 < 2 && !SAME) || (t2 == 3 && !T21)) continue;
+                    if (t2 < 2 && !SAME) continue;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         float x = c[t2][v];
@@ -181,7 +199,7 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
             if (is_bot) border(accb);
 #pragma unroll
             for (int t2 = 0; t2 < NTY; ++t2) {
-                if ((t2 < 2 && !SAME) || (t2 == 3 && !T21)) continue;
+                if (t2 < 2 && !SAME) continue;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) accd[t2][v] += (double)c[t2][v];
                 c[t2] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -194,13 +212,15 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
                 c[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b2, c[1], 0, 0, 0);
             }
             c[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b2, c[2], 0, 0, 0);
-            if (T21) c[NTY - 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b1, c[NTY - 1], 0, 0, 0);
+            c[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b1, c[3], 0, 0, 0);
         };
-        for (int y = wave; y < rows; y += 4) {
+        const int g_tile = ty * (TH / RG);            // image row group of the tile's first
+        for (int g = wave; g * RG < rows; g += 4) {
+            const int y = g * RG;                     // first tile row of the group
             const float *ra1 = lds + y * p.pitch + a_off, *rb1 = lds + y * p.pitch + b_off;
             const float *ra2 = ra1 + p.view_stride, *rb2 = rb1 + p.view_stride;
-            const int gy = ty * LAG_TH + y;
-            const bool is_top = gy == y_top, is_bot = gy == y_bot;
+            const int gi = g_tile + g;
+            const bool is_top = gi == my_top, is_bot = gi == my_bot;
             // Two steps form a pair whose operands come in two-address LDS reads; the pairs alternate between
             // two operand sets so that the reads of the next pair are in flight during the MFMAs of this one.
             // The four operand streams advance through one running pointer each, every read at a constant
@@ -213,11 +233,9 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
             auto load_pair = [&](float (&o)[8], int off) {
                 o[0] = at(qa1, off); o[1] = at(qa1, off + 4);
                 o[2] = at(qb2, off); o[3] = at(qb2, off + 4);
-                if (NEED2) {
-                    o[4] = at(qa2, off); o[5] = at(qa2, off + 4);
-                    o[6] = at(qb1, off); o[7] = at(qb1, off + 4);
-                }
-                __builtin_amdgcn_sched_group_barrier(0x100, NEED2 ? 4 : 2, 0);     // LDS reads first
+                o[4] = at(qa2, off); o[5] = at(qa2, off + 4);
+                o[6] = at(qb1, off); o[7] = at(qb1, off + 4);
+                __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);                 // LDS reads first
             };
             auto mfma_pair = [&](const float (&o)[8]) {
                 step(o[0], o[2], o[4], o[6]);
@@ -240,7 +258,7 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
             if (ip < np) mfma_pair(oa);
             if (steps & 1) {
                 const int s = steps - 1;
-                step(ra1[4 * s], rb2[4 * s], NEED2 ? ra2[4 * s] : 0.f, NEED2 ? rb1[4 * s] : 0.f);
+                step(ra1[4 * s], rb2[4 * s], ra2[4 * s], rb1[4 * s]);
             }
             flush(is_top, is_bot);
         }
@@ -265,22 +283,20 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
         }
         __syncthreads();
     }
-    // slot: [1 + 2 RR][E]: all rows, top rows 0 .. RR-1, bottom rows h-1 .. h-RR
+    // slot: [SETS][E]: all rows, top row groups 0 .. NTG-1, bottom row groups gb0 .. gb0 + NBG-1
     double *slot = p.slots + (size_t)blockIdx.x * G::SLOT;
     const bool rmw = (int)blockIdx.x < p.slots_valid;
     for (int e = threadIdx.x; e < G::E; e += LAG_THREADS) slot[e] = (rmw ? slot[e] : 0.0) + st[e];
-    // border rows: the owner writes its registers; rows the image does not have stay zero
-#pragma unroll
-    for (int o = 0; o < RR; ++o) {
-        if (o >= p.h && wave == 0 && !rmw) {
-            for (int e = lane; e < G::E; e += 64) {
-                slot[(1 + o) * G::E + e] = 0.0;
-                slot[(1 + RR + o) * G::E + e] = 0.0;
-            }
+    // border groups: the owner writes its registers; sets of groups the image does not have are cleared
+    if (!rmw) {
+        for (int set = 0; set < NTG + NBG; ++set) {
+            const bool owned = set < NTG ? set * RG < p.h : gb0 + (set - NTG) <= glast;
+            if (!owned)
+                for (int e = threadIdx.x; e < G::E; e += LAG_THREADS) slot[(size_t)(1 + set) * G::E + e] = 0.0;
         }
     }
-    if (y_top >= 0) {
-        double *d = slot + (size_t)(1 + o_top) * G::E;
+    if (my_top >= 0) {
+        double *d = slot + (size_t)(1 + my_top) * G::E;
 #pragma unroll
         for (int t = 0; t < NTY; ++t)
 #pragma unroll
@@ -289,8 +305,8 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
                 d[e] = (rmw ? d[e] : 0.0) + acct[t][v];
             }
     }
-    if (y_bot >= 0) {
-        double *d = slot + (size_t)(1 + RR + o_bot) * G::E;
+    if (my_bot >= 0) {
+        double *d = slot + (size_t)(1 + NTG + my_bot - gb0) * G::E;
 #pragma unroll
         for (int t = 0; t < NTY; ++t)
 #pragma unroll
@@ -315,9 +331,12 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
 // Slot of a workgroup row: [type][side][column offset] x ( 256 doubles: the column sums in accumulator layout,
 // row = vertical lag index; then [2r][NL^2]: the terms of top row o (index o) and bottom row h-1-o (r + o) ).
 constexpr int LAGC_ROWS = 64;              // image rows per chunk (a multiple of 4)
-// threads: 256, at k = 9 512 (sixteen chains and 4096 corner triples to share out)
+// threads: 256, from k = 7 on 512 (twelve / sixteen chains and 2028 / 4096 corner triples to share out)
 template <int KS>
-constexpr int lagc_threads() { return LagGeom<KS>::WIDE ? 512 : 256; }
+constexpr int lagc_threads() { return KS >= 7 ? 512 : 256; }
+// wavefronts per SIMD the register budget is cut for
+template <int KS>
+constexpr int lagc_waves() { return KS >= 9 ? 2 : KS >= 7 ? 4 : 3; }
 
 struct LagColParams {
     const float *v1, *v2;
@@ -329,7 +348,7 @@ struct LagColParams {
 };
 
 template <int KS>
-__global__ __launch_bounds__(lagc_threads<KS>(), LagGeom<KS>::WIDE ? 2 : 3) void lag_cols_kernel(LagColParams p)
+__global__ __launch_bounds__(lagc_threads<KS>(), lagc_waves<KS>()) void lag_cols_kernel(LagColParams p)
 {
     using G = LagGeom<KS>;
     constexpr int K = G::K, NL = G::NL, NLL = G::NLL, RR = G::RR, NTY = G::NTY;
@@ -556,49 +575,80 @@ __global__ __launch_bounds__(256) void lag_special_kernel(LagSpecialParams p)
 
 // ---- from the statistics to the stacked Gram --------------------------------------------------------------
 struct LagStats {
-    const double *R;                       // [1 + 2r][NTY][256] (+ 8 at k = 9): reduced lag_gram_kernel slots
-    const double *C;                       // [NTY][2][r][256 + 2r*NL*NL]: reduced lag_cols_kernel slots
+    const double *R;                       // [SETS][4][256] (+ 8 at k = 9): reduced lag_gram_kernel slots
+    const double *C;                       // [4][2][r][256 + 2r*NL*NL]: reduced lag_cols_kernel slots
     int ks, h, w, cross;
 };
 
-// lag correlation of one pair type from accumulator layout (row = horizontal lag index, column = vertical)
-__device__ __forceinline__ double lag_value(const double *R, int type, int iy, int ix)
-{
-    return R[(type * 4 + (ix & 3)) * 64 + 16 * (ix >> 2) + iy];
-}
-
 // the pair type with the two views exchanged
 __device__ __forceinline__ int lag_type_swapped(int t) { return t == 2 ? 3 : t == 3 ? 2 : t; }
+
+// host / device copy of the geometry for a run-time k
+struct LagShape {
+    int K, r, wide, NL, NJ, DX0, RG, NTG, NBG;
+    __host__ __device__ explicit LagShape(int ks)
+    {
+        K = ks - 1;
+        r = (ks - 1) / 2;
+        wide = 2 * K + 1 > 16;
+        NL = wide ? 16 : 2 * K + 1;
+        NJ = wide ? 16 : K + 1;
+        DX0 = wide ? -K : 0;
+        RG = 16 / NJ;
+        NTG = (r + RG - 1) / RG;
+        NBG = (r - 1 + RG - 1) / RG + 1;
+    }
+};
+
+// one element of a 16 x 16 row set in accumulator layout: row (rho, dx), column c
+__device__ __forceinline__ double lag_set_value(const LagStats &st, const LagShape &g, int set, int type, int rho,
+                                                int dx, int c)
+{
+    const int i = rho * g.NJ + dx - g.DX0;
+    return st.R[(size_t)set * 1024 + (type * 4 + (i & 3)) * 64 + 16 * (i >> 2) + c];
+}
 
 // sum over the patch centres p INSIDE the image of X[p + s_a] X'[p + s_b] for the pair type (X, X'), a the tap
 // of X: with u = p + s_a, u runs over the image minus the rows and columns that p + s_a can reach only from
 // outside -- the first s rows if s = s_a.y > 0, the last -s if s < 0, the same for the columns -- so
 //     = R(d) - (those rows of R) - (those columns) + (their corners),    d = s_b - s_a.
-// k = 9 keeps the lags -K .. K-1 only: a lag with a component +K is looked up as the same sum with the factors
-// exchanged (pair type swapped, taps swapped, lag negated), the lags (+K,-K) and (-K,+K) as the directly summed
-// opposite-corner value.
+// The statistics hold the horizontal lags 0 .. K only (k = 9: -K .. K-1, vertical ones likewise): any other lag
+// is looked up as the same sum with the factors exchanged (pair type swapped, taps swapped, lag negated), at
+// k = 9 the lags (+K,-K) and (-K,+K) as the directly summed opposite-corner value.
 __device__ double lag_entry(const LagStats &st, int type, int a, int b)
 {
-    const int ks = st.ks, r = (ks - 1) / 2, K = ks - 1;
-    const bool wide = 2 * K + 1 > 16;
-    const int NL = wide ? 16 : 2 * K + 1, NLL = NL * NL, E = (wide ? 4 : 3) * 256;
+    const int ks = st.ks;
+    const LagShape g(ks);
+    const int r = g.r, K = g.K, NL = g.NL, NLL = NL * NL;
     int ay = a / ks, ax = a - ay * ks, by = b / ks, bx = b - by * ks;
-    int iy = by - ay + K, ix = bx - ax + K;
-    if (wide && (iy == 2 * K || ix == 2 * K)) {
-        const double *special = st.R + (size_t)(1 + 2 * r) * E;
-        if (iy == 2 * K && ix == 0) return special[type];
-        if (ix == 2 * K && iy == 0) return special[lag_type_swapped(type)];
+    int dy = by - ay, dx = bx - ax;
+    const bool out_of_range = g.wide ? (dy == K || dx == K) : dx < 0;
+    if (out_of_range) {
+        if (g.wide) {
+            const double *special = st.R + (size_t)(1 + g.NTG + g.NBG) * 1024;
+            if (dy == K && dx == -K) return special[type];
+            if (dx == K && dy == -K) return special[lag_type_swapped(type)];
+        }
         type = lag_type_swapped(type);
         int t = ay; ay = by; by = t;
         t = ax; ax = bx; bx = t;
-        iy = by - ay + K;
-        ix = bx - ax + K;
+        dy = -dy;
+        dx = -dx;
     }
     const int sy = ay - r, sx = ax - r;
     const int ysd = sy > 0 ? 0 : 1, yn = min(sy > 0 ? sy : -sy, st.h);
     const int xsd = sx > 0 ? 0 : 1, xn = min(sx > 0 ? sx : -sx, st.w);
-    double v = lag_value(st.R, type, iy, ix);
-    for (int o = 0; o < yn; ++o) v -= lag_value(st.R + (size_t)(1 + ysd * r + o) * E, type, iy, ix);
+    // all rows: the image rows of a group sit in different accumulator rows
+    double v = 0.0;
+    for (int rho = 0; rho < g.RG; ++rho) v += lag_set_value(st, g, 0, type, rho, dx, rho + dy + K);
+    // minus the yn first (ysd = 0) or last (ysd = 1) image rows
+    const int gb0 = max(0, st.h - r) / g.RG;
+    for (int o = 0; o < yn; ++o) {
+        const int y = ysd == 0 ? o : st.h - 1 - o;
+        const int set = ysd == 0 ? 1 + y / g.RG : 1 + g.NTG + (y / g.RG - gb0);
+        v -= lag_set_value(st, g, set, type, y % g.RG, dx, y % g.RG + dy + K);
+    }
+    const int iy = dy + K, ix = dx + K;                 // lag indices of the border-column statistics
     const int entry = 256 + 2 * r * NLL;
     for (int o = 0; o < xn; ++o) {
         const double *c = st.C + ((size_t)(type * 2 + xsd) * r + o) * entry;
@@ -644,22 +694,23 @@ bool lag_supported(int k) { return k == 3 || k == 5 || k == 7 || k == 9; }
 int max_lag_slots(ddcca_ctx *ctx) { return ctx->n_cu * 6; }
 int max_lag_col_slots(ddcca_ctx *ctx) { return ctx->n_cu * 3 / 2; }   // x 2 sides: three workgroups per CU
 static bool lag_wide(int k) { return 2 * (k - 1) + 1 > 16; }
-static size_t lag_row_set_doubles(int k) { return (size_t)(lag_wide(k) ? 4 : 3) * 256; }
+static int lag_tile_rows(int k) { return k == 5 ? LagGeom<5>::TH : k == 3 ? LagGeom<3>::TH : 16; }
 size_t lag_slot_doubles(int k)
 {
-    return (size_t)(1 + 2 * ((k - 1) / 2)) * lag_row_set_doubles(k) + (lag_wide(k) ? 8 : 0);
+    const LagShape g(k);
+    return (size_t)(1 + g.NTG + g.NBG) * 1024 + (lag_wide(k) ? 8 : 0);
 }
 size_t lag_col_slot_doubles(int k)
 {
-    const int r = (k - 1) / 2, nl = lag_wide(k) ? 16 : 2 * (k - 1) + 1;
-    return (size_t)(lag_wide(k) ? 4 : 3) * 2 * r * (256 + 2 * r * nl * nl);
+    const LagShape g(k);
+    return (size_t)4 * 2 * g.r * (256 + 2 * g.r * g.NL * g.NL);
 }
 
 template <int KS>
 static void lag_launch(ddcca_ctx *ctx, const LagParams &p, int grid, size_t lds, bool cross, const LagColParams &c,
                        dim3 cgrid)
 {
-    static_assert(LagGeom<KS>::RR <= 4, "one owner wavefront per border row");
+    static_assert(LagGeom<KS>::SLOT == (1 + LagGeom<KS>::NTG + LagGeom<KS>::NBG) * 1024 + (LagGeom<KS>::WIDE ? 8 : 0), "slot layout");
     if (cross) hipLaunchKernelGGL((lag_gram_kernel<KS, true>), dim3(grid), dim3(LAG_THREADS), lds, ctx->stream, p);
     else hipLaunchKernelGGL((lag_gram_kernel<KS, false>), dim3(grid), dim3(LAG_THREADS), lds, ctx->stream, p);
     hipLaunchKernelGGL(lag_cols_kernel<KS>, cgrid, dim3(lagc_threads<KS>()), 0, ctx->stream, c);
@@ -679,16 +730,17 @@ int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_
     const int ntx = (w4 + LAG_TW_MAX - 1) / LAG_TW_MAX;
     p.tw = (((w4 + ntx - 1) / ntx) + 3) & ~3;
     p.tiles_x = (w + p.tw - 1) / p.tw;
-    p.tiles_y = (h + LAG_TH - 1) / LAG_TH;
+    const int TH = lag_tile_rows(k);
+    p.tiles_y = (h + TH - 1) / TH;
     p.n_items = n_maps * p.tiles_x * p.tiles_y;
     // row pitch: tile width + halo, congruent to 17 mod 32 so that the rows y .. y + 2K a B operand reads fall
     // into different banks
     int pitch = p.tw + 2 * K + 4;
     while (pitch % 32 != 17) ++pitch;
     p.pitch = pitch;
-    p.view_stride = (LAG_TH + 2 * K) * pitch + 8;
+    p.view_stride = (TH + 2 * K) * pitch + 8;
     const size_t lds = std::max<size_t>((size_t)2 * p.view_stride * sizeof(float),
-                                        lag_row_set_doubles(k) * sizeof(double));
+                                        (size_t)1024 * sizeof(double));
     if (p.tw > LAG_TW_MAX || lds > 64 * 1024) return fail(ctx, DDCCA_EINVAL, "lag-structured Gram: tile too large");
     p.slots = slots;
     p.slots_valid = *slots_valid;
