@@ -49,7 +49,7 @@ struct LagGeom {
     static constexpr int DX0 = WIDE ? -K : 0;          // the first of them
     static constexpr int RG = 16 / NJ;                 // image rows per matrix instruction
     static constexpr int CMAX = WIDE ? 15 : RG - 1 + 2 * K;   // last column in use
-    static constexpr int TH = KS == 5 ? 24 : KS == 3 ? 20 : 16;   // image rows per tile: a multiple of 4 RG
+    static constexpr int TH = KS == 7 ? 24 : KS == 5 ? 24 : KS == 3 ? 20 : 16;   // image rows per tile: a multiple of 4 RG
     static constexpr int NTG = (RR + RG - 1) / RG;     // row groups that hold one of the RR top rows
     static constexpr int NBG = (RR - 1 + RG - 1) / RG + 1;   // ... bottom rows (whatever the image height)
     static constexpr int SETS = 1 + NTG + NBG;         // all rows; top groups; bottom groups
@@ -694,7 +694,10 @@ bool lag_supported(int k) { return k == 3 || k == 5 || k == 7 || k == 9; }
 int max_lag_slots(ddcca_ctx *ctx) { return ctx->n_cu * 6; }
 int max_lag_col_slots(ddcca_ctx *ctx) { return ctx->n_cu * 3 / 2; }   // x 2 sides: three workgroups per CU
 static bool lag_wide(int k) { return 2 * (k - 1) + 1 > 16; }
-static int lag_tile_rows(int k) { return k == 5 ? LagGeom<5>::TH : k == 3 ? LagGeom<3>::TH : 16; }
+static int lag_tile_rows(int k)
+{
+    return k == 3 ? LagGeom<3>::TH : k == 5 ? LagGeom<5>::TH : k == 7 ? LagGeom<7>::TH : LagGeom<9>::TH;
+}
 size_t lag_slot_doubles(int k)
 {
     const LagShape g(k);
