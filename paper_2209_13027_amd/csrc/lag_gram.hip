@@ -5,23 +5,25 @@
 // (2k-1)^2 lag correlations per view pair instead of k^4 entries.  The sum wanted runs over the patch centres
 // inside the image only: with u = p + s_a that is the same sum over u with up to r rows at the top or bottom and
 // up to r columns at the left or right of the image left out (which ones depends on the first tap a), so next to
-// R_d the kernels keep the contributions of the r first and last image rows (lag_gram_kernel, per border row)
+// R_d the kernels keep the contributions of the r first and last image rows (lag_gram_kernel, per row group)
 // and of the r first and last columns and the corners (lag_cols_kernel).  Everything downstream (centre-pixel
 // form, H M H export, solve) is unchanged: lag_to_stacked_kernel writes  sum y y^T  for y = x - x_centre in the
 // layout of the dense kernel's slots from
 //     S_y[a][b] = S_x[a][b] - S_x[a][c] - S_x[c][b] + S_x[c][c]          (c = the centre tap).
 //
-// The lag correlations run on v_mfma_f32_16x16x4_f32, one image row at a time: rows of the matrix instruction =
-// horizontal lag, columns = vertical lag, K = 4 consecutive pixels x' of the row:
-//     A[dx][x'] = X[y][x' - dx],   B[x'][dy] = X'[y + dy][x'],   D[dx][dy] += sum_x' A B.
-// Three products per step (view 1 x view 1, 2 x 2, 1 x 2; four at k = 9) against 21 / 6 tiles of the dense kernel
-// at k = 7 / 5.
+// The lag correlations run on v_mfma_f32_16x16x4_f32 along image rows, K = 4 consecutive pixels x' of a row per
+// instruction.  All four ORDERED view pairs (1,1) (2,2) (1,2) (2,1) are kept, so a horizontal lag dx < 0 is read
+// as the exchanged pair at the negated lag and the rows of the instruction only hold dx = 0 .. k-1; RG = 2 / 3 /
+// 5 image rows (k = 7 / 5 / 3) then share one instruction (geometry: LagGeom below):
+//     A[(rho,dx)][x'] = X[y0 + rho][x' - dx],   B[x'][c] = X'[y0 + c - (k-1)][x'],
+//     D[(rho,dx)][rho + dy + k-1] += sum_x' A B   = lag (dy, dx) of image row y0 + rho.
 // The raw products carry the DC level of the images, which the differences to the centre pixel of the dense
-// kernel do not, so the fp32 accumulators are added to fp64 registers after every image row.
-// k = 9 has 17 lags per axis, one more than the instruction has rows: there the lags -8 .. 7 are kept for the
-// four ORDERED pair types (1,1) (2,2) (1,2) (2,1), an entry whose lag has a component +8 is taken as the
-// transposed entry (S_x[a][b] of the pair (d,d') = S_x[b][a] of (d',d), lag negated), and the single tap pair
-// whose lag is (+8,-8) -- opposite corners of the patch -- is summed directly by lag_special_kernel.
+// kernel do not, so the fp32 accumulators (each a sum along one image row) are added to fp64 registers after
+// every row group.
+// k = 9 has 17 vertical lags, one more than the instruction has columns: there an instruction holds one image
+// row and the lags -8 .. 7 on both axes, an entry whose lag has a component +8 is taken as the transposed entry
+// (S_x[a][b] of the pair (d,d') = S_x[b][a] of (d',d), lag negated), and the single tap pair whose lag is
+// (+8,-8) -- opposite corners of the patch -- is summed directly by lag_special_kernel.
 #include "ddcca_internal.h"
 
 namespace ddcca {
