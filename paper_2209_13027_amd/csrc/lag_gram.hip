@@ -749,6 +749,10 @@ int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_
     if (p.tw > LAG_TW_MAX || lds > 64 * 1024) return fail(ctx, DDCCA_EINVAL, "lag-structured Gram: tile too large");
     p.slots = slots;
     p.slots_valid = *slots_valid;
+    // (the sum images of the class-conditioned matrices are few: one workgroup per CU keeps their slot
+    // reduction, which reads every slot written, short)
+    if (cross_only) max_slots = std::min(max_slots, ctx->n_cu);
+    if (cross_only) max_col_slots = std::min(max_col_slots, std::max(1, ctx->n_cu / 2));
     const int grid = (int)std::min<int64_t>(max_slots, std::max<int64_t>(p.n_items, 1));
     // the border columns and corners of the same maps
     LagColParams c;
