@@ -224,8 +224,9 @@ def run_gpu_path(ctx, wl, v1, v2, cls, batch_images=0):
     return model, feat
 
 
-def check_against_oracle(oracle, wl, v1, v2, cls, model, feat):
-    ref = oracle.two_stage(v1, v2, cls, wl.n_classes, wl.k, wl.L1, wl.L2, wl.block)
+def check_against_oracle(oracle, wl, v1, v2, cls, model, feat, ref=None):
+    if ref is None:
+        ref = oracle.two_stage(v1, v2, cls, wl.n_classes, wl.k, wl.L1, wl.L2, wl.block)
     names = ["stage1.W1", "stage1.W2", "stage2.W1", "stage2.W2"]
     refs = [ref["stage1"]["W1"], ref["stage1"]["W2"], ref["stage2"]["W1"], ref["stage2"]["W2"]]
     gaps = [ref["stage1"]["gap"], ref["stage1"]["gap"], ref["stage2"]["gap"], ref["stage2"]["gap"]]
@@ -274,4 +275,24 @@ def test_end_to_end_small_face_full(ctx, oracle):
     wl = WORKLOADS["small_face"]
     v1, v2, cls = make_views(wl)
     model, feat = run_gpu_path(ctx, wl, v1, v2, cls)
-    check_against_oracle(oracle, wl, v1, v2, cls, model, feat)
+    ref, _ = check_against_oracle(oracle, wl, v1, v2, cls, model, feat)
+    # the launch configuration bench.py times: second stage learned from the inputs, maps batch by batch
+    from paper_2209_13027_amd import pipeline
+    from paper_2209_13027_amd.binding import (OPT_GRAM_ARITH, GRAM_FP32, GRAM_LAG_FP32, OPT_CONV_ARITH, CONV_FP32,
+                                              CONV_BF16X3)
+    d1, d2, dc = dev(v1), dev(v2), dev(cls)
+    model = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
+    feat = pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride)
+    ctx.status()
+    check_against_oracle(oracle, wl, v1, v2, cls, model, feat, ref)
+    # and its widened step: lag-structured Gram, three-piece convolution, fused last stage
+    ctx.set_option(OPT_GRAM_ARITH, GRAM_LAG_FP32)
+    ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
+    try:
+        model = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
+        feat = pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride, fused=True)
+        ctx.status()
+    finally:
+        ctx.set_option(OPT_GRAM_ARITH, GRAM_FP32)
+        ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
+    check_against_oracle(oracle, wl, v1, v2, cls, model, feat, ref)
