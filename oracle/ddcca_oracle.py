@@ -11,7 +11,10 @@ Section / equation numbers refer to the paper (Section II: model; Section III: b
 Pins (tests/test_oracle_*.py): patch sums, brute-force Gram, batch-split invariance
 (Eq. 15), pair-loop C_w / C_b, eigen residuals and library cross-checks for the solve,
 brute-forced objective (Eq. 2-3), conv/Gram tie, histogram sums and bincount,
-information quality (Eq. 10): probabilities sum to one, hand-computed block, monotone.
+information quality (Eq. 10): probabilities sum to one, hand-computed block, monotone;
+the composite routines: second-stage C_w / C_b of learn_two_stage against explicit
+image-pair loops over maps that scipy computes per image, extract_features per image and
+per map against scipy correlation + bincount.
 Numeric values of filters / features on the paper's own data: parity unpinned (the
 paper prints no intermediate value and its data sets are not available).
 """

@@ -452,3 +452,79 @@ def test_iq_probabilities_sum_to_one_and_hand_values(oracle):
     # all pixels of a block share one code: p = (area+1)/(area+bins) for it
     full = oracle.iq_features(np.array([49, 0, 0, 0, 0, 0, 0, 0]), 49)
     assert abs(full[0] - math.log(57.0 / 50.0)) < 1e-15 and abs(full[1] - math.log(57.0)) < 1e-14
+
+
+# ------------------------------------------------------------------ composite path (Sec. II-B on II-A; Eq. 6-12)
+def scipy_maps(img, F):
+    """[h,w] image x [L,k,k] filters -> [L,h,w] by scipy's zero-filled 'same' cross-correlation."""
+    return np.stack([scipy.signal.correlate2d(img, f, mode="same", boundary="fill", fillvalue=0.0) for f in F])
+
+
+def test_learn_two_stage_second_stage_pairs_by_image_and_map_index(oracle):
+    """The second stage is learned on the stage-1 maps: map g of image m carries the class of image m and pairs
+    only with map g of the other view.  Its C_w / C_b are rebuilt here with explicit loops over image pairs
+    (m, m') and the map index g from maps that scipy computes one image at a time, so a mislabelled map (class
+    and group arrays exchanged or misordered inside learn_two_stage) shows up in every entry."""
+    rng = np.random.default_rng(31)
+    M, h, w, k, L1, L2 = 6, 7, 6, 3, 2, 3
+    V1, V2 = rand_views(rng, M, h, w)
+    cls = np.array([0, 1, 1, 0, 1, 0], dtype=np.int32)
+    res = oracle.learn_two_stage(V1, V2, cls, 2, k, L1, L2)
+    s1, s2 = res["stage1"], res["stage2"]
+    Y = [np.stack([scipy_maps(V[m], F) for m in range(M)]) for V, F in ((V1, s1["F1"]), (V2, s1["F2"]))]
+    X1 = [window_patches(Y[0][:, g], k) for g in range(L1)]          # per g: [M,h,w,D]
+    X2 = [window_patches(Y[1][:, g], k) for g in range(L1)]
+    D = k * k
+    N = M * L1 * h * w
+    Cw, Cb, C11, C22, C12 = (np.zeros((D, D)) for _ in range(5))
+    for g in range(L1):
+        for m in range(M):
+            C11 += np.einsum("yxa,yxb->ab", X1[g][m], X1[g][m])
+            C22 += np.einsum("yxa,yxb->ab", X2[g][m], X2[g][m])
+            C12 += np.einsum("yxa,yxb->ab", X1[g][m], X2[g][m])
+            for mm in range(M):
+                pair = np.einsum("yxa,yxb->ab", X1[g][m], X2[g][mm])
+                if cls[m] == cls[mm]:
+                    Cw += pair
+                else:
+                    Cb += pair
+    assert s2["N"] == N
+    for name, want in (("Cw", Cw), ("Cb", Cb), ("C11", C11), ("C22", C22), ("C12", C12)):
+        assert np.abs(s2[name] - want / N).max() <= 1e-11 * np.abs(want / N).max(), name
+    assert np.abs(s2["Ctilde"] - (Cw - Cb) / N).max() <= 1e-11 * np.abs(Cw / N).max()
+    # the maps handed on are the stage-1 maps in (image, g) order
+    assert np.abs(res["Y1"].reshape(M, L1, h, w) - Y[0]).max() <= 1e-12 * np.abs(Y[0]).max()
+    assert np.abs(res["Y2"].reshape(M, L1, h, w) - Y[1]).max() <= 1e-12 * np.abs(Y[1]).max()
+    # and the stage-2 filters solve Eq. 2-3 for THESE matrices: rho = w1^T C~ w2, B-normalised
+    B1 = C11 / N + 1e-4 * np.trace(C11 / N) / D * np.eye(D)
+    for l in range(L2):
+        w1, w2 = s2["W1"][l], s2["W2"][l]
+        assert abs(w1 @ B1 @ w1 - 1.0) <= 1e-10
+        assert abs(w1 @ ((Cw - Cb) / N) @ w2 - s2["rho"][l]) <= 1e-10 * max(1.0, abs(s2["rho"][l]))
+
+
+def test_extract_features_layout_one_image_and_map_at_a_time(oracle):
+    """hist[m][d][g] is the block histogram of the hashed second-stage maps of stage-1 map g of image m in view d
+    (Eq. 6-12).  Rebuilt per image and per map with scipy's correlation, a written-out hash and numpy.bincount; the
+    filters are random and all different, so any exchange of views, stages, g and l, or image order fails."""
+    rng = np.random.default_rng(32)
+    M, h, w, k, L1, L2, b, s = 3, 11, 10, 3, 3, 3, 4, 2
+    V = rand_views(rng, M, h, w)
+    V = (V[0], V[1] - V[1].mean())          # both views take both signs, or the codes would be trivial
+    F = [rng.standard_normal((L, k, k)) for L in (L1, L1, L2, L2)]
+    out = oracle.extract_features(V[0], V[1], F, k, L1, L2, b, s)
+    nby, nbx = (h - b) // s + 1, (w - b) // s + 1
+    assert out["hist"].shape == (M, 2, L1, nby, nbx, 1 << L2)
+    seen = set()
+    for m in range(M):
+        for d in range(2):
+            Y = scipy_maps(V[d][m], F[d])
+            for g in range(L1):
+                Z = scipy_maps(Y[g], F[2 + d])
+                Q = sum((Z[l] > 0).astype(np.int64) << l for l in range(L2))
+                for i in range(nby):
+                    for j in range(nbx):
+                        want = np.bincount(Q[i * s:i * s + b, j * s:j * s + b].ravel(), minlength=1 << L2)
+                        assert np.array_equal(out["hist"][m, d, g, i, j], want), (m, d, g, i, j)
+                seen.add(Q.tobytes())
+    assert len(seen) == M * 2 * L1           # every (image, view, g) has its own code map: the check can tell them apart
