@@ -40,6 +40,8 @@ extern "C" {
 #define DDCCA_EHIP      (-4)   /* HIP runtime error (no GPU, launch failure, ...) */
 #define DDCCA_EOVERFLOW (-5)   /* a histogram count would not fit uint16 (block area > 65535) */
 #define DDCCA_ELABEL    (-6)   /* a class label outside [0, n_cls) was seen on the device */
+#define DDCCA_ENUMERIC  (-7)   /* the DCCA solve broke down on the device: C_dd + ridge not positive definite
+                                  (NaN/Inf in the matrices, ridge too small), or no convergence */
 
 #define DDCCA_MIN_K   3
 #define DDCCA_MAX_K   9
@@ -56,7 +58,13 @@ void ddcca_destroy(ddcca_ctx *ctx);
 const char *ddcca_last_error(const ddcca_ctx *ctx);
 
 /* Synchronise the context's stream and report sticky device-side conditions
- * (DDCCA_ELABEL) or a pending HIP error. */
+ * (DDCCA_ELABEL, DDCCA_ENUMERIC; the condition is cleared by the call that reports it)
+ * or a pending HIP error.  The calls above the device cannot see these conditions when
+ * they return (nothing synchronises), so: samples with a bad label are left out of C_w
+ * and C_T, and every solve that runs while that condition is pending writes NaN filters
+ * and NaN rho instead of filters of inconsistent matrices; a solve that breaks down
+ * leaves whatever its arithmetic produced (NaN for a non-positive pivot).  A caller that
+ * replays captured work calls ddcca_status after the replay. */
 int ddcca_status(ddcca_ctx *ctx);
 
 /* ---- correlation accumulation, streamed over batches (Section III, Eq. 13-15) -------

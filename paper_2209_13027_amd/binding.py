@@ -15,7 +15,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libddcca.so")
 
-OK, EINVAL, ESTATE, ENOMEM, EHIP, EOVERFLOW, ELABEL = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, ESTATE, ENOMEM, EHIP, EOVERFLOW, ELABEL, ENUMERIC = 0, -1, -2, -3, -4, -5, -6, -7
 K_GRAM, K_CLASS_SUM, K_REDUCE, K_SOLVE, K_CONV, K_HASH_HIST, K_GRAM_CROSS, K_CONV_HASH_HIST, K_COUNT = range(9)
 KERNEL_NAMES = ["gram", "class_sum", "reduce", "solve", "conv", "hash_hist", "gram_cross", "conv_hash_hist"]
 

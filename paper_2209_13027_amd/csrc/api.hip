@@ -49,6 +49,15 @@ int ensure(ddcca_ctx *ctx, Buffer &b, size_t bytes)
     return DDCCA_OK;
 }
 
+int ensure_flags(ddcca_ctx *ctx)
+{
+    if (ctx->flags.ptr) return DDCCA_OK;
+    int rc;
+    if ((rc = ensure(ctx, ctx->flags, 4 * sizeof(int)))) return rc;
+    DDCCA_HIP(ctx, hipMemsetAsync(ctx->flags.ptr, 0, 4 * sizeof(int), ctx->stream));
+    return DDCCA_OK;
+}
+
 ProfScope::ProfScope(ddcca_ctx *c, int kernel_id) : ctx(c), id(kernel_id)
 {
     if (!ctx->prof || !((ctx->prof_mask >> id) & 1u)) return;
@@ -183,7 +192,7 @@ int ddcca_create(ddcca_ctx **out, int device, void *hip_stream)
 {
     if (!out) return DDCCA_EINVAL;
     *out = nullptr;
-    if (device < 0) return DDCCA_EINVAL;
+    if (device < 0 || device >= MAX_DEVICES) return DDCCA_EINVAL;
     ddcca_ctx *ctx = new (std::nothrow) ddcca_ctx();
     if (!ctx) return DDCCA_ENOMEM;
     ctx->device = device;
@@ -221,9 +230,13 @@ int ddcca_status(ddcca_ctx *ctx)
     if (ctx->flags.ptr) {
         int host[4] = {0, 0, 0, 0};
         DDCCA_HIP(ctx, hipMemcpy(host, ctx->flags.ptr, sizeof(host), hipMemcpyDeviceToHost));
-        if (host[0]) {
+        if (host[0] || host[1] || host[2]) {
             DDCCA_HIP(ctx, hipMemset(ctx->flags.ptr, 0, sizeof(host)));
-            return fail(ctx, DDCCA_ELABEL, "class label outside [0, n_cls) seen on the device");
+            if (host[0]) return fail(ctx, DDCCA_ELABEL, "class label outside [0, n_cls) seen on the device");
+            if (host[1])
+                return fail(ctx, DDCCA_ENUMERIC,
+                            "DCCA solve: C_dd + ridge is not positive definite (NaN/Inf input or ridge too small)");
+            return fail(ctx, DDCCA_ENUMERIC, "DCCA solve: the Jacobi rotations did not converge");
         }
     }
     return DDCCA_OK;
@@ -246,10 +259,7 @@ int ddcca_corr_begin(ddcca_ctx *ctx, int k, int n_cls, int G, int h, int w)
     const size_t cs_bytes = (size_t)cs_seg * 2 * n_cls * G * P * sizeof(double);
     if ((rc = ensure(ctx, ctx->class_sum, cs_bytes))) return rc;
     if ((rc = launch_zero_sums(ctx, (double *)ctx->class_sum.ptr, cs_bytes / sizeof(double)))) return rc;
-    if (!ctx->flags.ptr) {
-        if ((rc = ensure(ctx, ctx->flags, 4 * sizeof(int)))) return rc;
-        DDCCA_HIP(ctx, hipMemsetAsync(ctx->flags.ptr, 0, 4 * sizeof(int), ctx->stream));
-    }
+    if ((rc = ensure_flags(ctx))) return rc;
     ctx->lag_active = ctx->gram_arith == DDCCA_GRAM_LAG_FP32 && lag_supported(k);
     if (ctx->lag_active) {
         if ((rc = ensure(ctx, ctx->lag_slots, (size_t)max_lag_slots(ctx) * lag_slot_doubles(k) * sizeof(double))))

@@ -486,10 +486,10 @@ __global__ __launch_bounds__(GROUP_THREADS) void conv_hash_hist_group_kernel(Fus
 template <typename Kernel>
 static int fused_set_lds(ddcca_ctx *ctx, Kernel kernel, bool *done)
 {
-    if (!*done) {
+    if (!done[ctx->device]) {          // per device: the attribute is set on that device's code object
         DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            FUSED_LDS_BYTES));
-        *done = true;
+        done[ctx->device] = true;
     }
     return DDCCA_OK;
 }
@@ -501,13 +501,13 @@ template <int KS, int NG> constexpr int ring_rows_together() { return NG == 1 &&
 template <int KS, int NBX, int NG>
 static int fused_launch(ddcca_ctx *ctx, FusedParams p, int64_t n, bool ring)
 {
-    static bool ring2_attr = false, ring1_attr = false, group_attr = false;
+    static bool ring2_attr[MAX_DEVICES] = {}, ring1_attr[MAX_DEVICES] = {}, group_attr[MAX_DEVICES] = {};
     constexpr int RU2 = ring_rows_together<KS, NG>();
     const bool two = ring && RU2 == 2 && p.th >= 2 * RING_WAVES;
     int rc;
-    if ((rc = !ring ? fused_set_lds(ctx, conv_hash_hist_group_kernel<KS, NBX, NG>, &group_attr)
-              : two ? fused_set_lds(ctx, conv_hash_hist_ring_kernel<KS, NBX, NG, RU2>, &ring2_attr)
-                    : fused_set_lds(ctx, conv_hash_hist_ring_kernel<KS, NBX, NG, 1>, &ring1_attr)))
+    if ((rc = !ring ? fused_set_lds(ctx, conv_hash_hist_group_kernel<KS, NBX, NG>, group_attr)
+              : two ? fused_set_lds(ctx, conv_hash_hist_ring_kernel<KS, NBX, NG, RU2>, ring2_attr)
+                    : fused_set_lds(ctx, conv_hash_hist_ring_kernel<KS, NBX, NG, 1>, ring1_attr)))
         return rc;
     p.tile_floats = ring ? RingGeom<KS, NBX>::tile_floats(p.th) : FusedGeom<KS, NBX>::tile_floats(GROUP_TH);
     const size_t lds = ((size_t)p.hist_words + p.lut_words + (size_t)p.tile_floats * (ring ? 2 : 1)) * 4;

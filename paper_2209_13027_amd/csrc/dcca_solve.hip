@@ -17,22 +17,16 @@ constexpr int SOLVE_MAX_SWEEPS = 40;
 constexpr double SOLVE_TOL = 1e-15;      // rotate while |g_p . g_q| > tol * |g_p| |g_q|
 constexpr double SOLVE_QUAD = 1e-8;      // a sweep whose largest cosine was below this is the last one
 
-#ifdef DDCCA_SOLVE_STAMPS
-#define STAMP(i) do { if (threadIdx.x == 0) p.stamps[i] = wall_clock64(); } while (0)
-#else
-#define STAMP(i) do { } while (0)
-#endif
-
 struct SolveParams {
-#ifdef DDCCA_SOLVE_STAMPS
-    long long *stamps;
-#endif
     const double *C11, *C22, *Cw, *CT;
     int L;
     double ridge;
     double *gI1, *gI2;          // global scratch: the two inverse Cholesky factors
     float *W1, *W2;
     double *rho;
+    int *flags;                 // device int[4]: [0] bad class label seen during the accumulation (read: the
+                                // outputs are then NaN), [1] a Cholesky pivot was not positive and finite,
+                                // [2] the rotations did not converge within SOLVE_MAX_SWEEPS (both written)
 };
 
 // Sum over the 16 lanes of a DPP row (lanes 16r .. 16r+15), result in every lane of the row.
@@ -124,8 +118,8 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
     int *order = ip, *flag = ip + D;
     const int tid = threadIdx.x, nt = SOLVE_THREADS;
     const int grp = tid >> 4, l16 = tid & 15;
+    const bool poisoned = p.flags[0] != 0;
 
-    STAMP(0);
     // ---- load, symmetrise, ridge -----------------------------------------------------
     for (int e = tid; e < DD; e += nt) {
         const int i = e / D, j = e - i * D;
@@ -145,7 +139,6 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
     else if (tid < 2 * D) B[(tid - D) * D + (tid - D)] += red[1];
     __syncthreads();
 
-    STAMP(1);
     // ---- Cholesky of both matrices (lower factor, in place), half of the workgroup each;
     //      a half is 32 row-groups of 16 lanes ---------------------------------------------
     {
@@ -155,6 +148,7 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
         const int ty = t >> 4, tx = t & 15;
         for (int j = 0; j < D; ++j) {
             const double piv = m[j * D + j];
+            if (t == 0 && !(piv > 0.0 && piv <= 1.7976931348623157e308)) p.flags[1] = 1;
             const double rd = fast_rsqrt(piv);
             for (int i = j + 1 + t; i < D; i += half) m[i * D + j] *= rd;
             __syncthreads();
@@ -165,7 +159,6 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
             }
             __syncthreads();
         }
-        STAMP(2);
         // ---- in-place inverse of the lower factor, last column first: with the trailing block
         //      already inverted, column j of the inverse is -(1/l_jj) * Linv[j+1:, j+1:] * l[j+1:, j]
         constexpr int RP = (D + 31) / 32;
@@ -190,7 +183,6 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
             __syncthreads();
         }
     }
-    STAMP(3);
     // ---- T = L1^{-1} C~ L2^{-T}:  X = A*C -> B (B saved to global first), T = X * inv2^T -> C
     for (int e = tid; e < DD; e += nt) p.gI2[e] = B[e];
     __syncthreads();
@@ -259,7 +251,6 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
     double *const J = B;                          // the rotations work on the rows of B = columns of R^T
     if (tid == 0) flag[0] = 0;
     __syncthreads();
-    STAMP(4);
 
     // A group of 8 lanes owns one column pair per round: it forms the three inner products and
     // the rotation that makes the two columns orthogonal, and applies it.  Pairs of one round
@@ -270,6 +261,7 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
     constexpr int JR = (D + 7) / 8;              // rows of a column held by one lane of the group
     static_assert(N_PAIRS <= SOLVE_THREADS / 8, "one 8-lane group per pair");
     const int jg = tid >> 3, l8 = tid & 7;
+    int coarse = 1;
     for (int sweep = 0; sweep < SOLVE_MAX_SWEEPS; ++sweep) {
         for (int round = 0; round < N_ROUNDS; ++round) {
             if (jg < N_PAIRS) {
@@ -326,18 +318,15 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
             }
             __syncthreads();
         }
-        const int coarse = flag[0];
+        coarse = flag[0];
         __syncthreads();
         if (tid == 0) flag[0] = 0;
-#ifdef DDCCA_SOLVE_STAMPS
-        if (tid == 0) p.stamps[9] = sweep + 1;
-#endif
         __syncthreads();
         // Cyclic Jacobi converges quadratically: once every pair of a sweep was orthogonal to
         // SOLVE_QUAD (cosine), the rotations of that sweep leave cosines of order SOLVE_QUAD^2.
         if (!coarse) break;
     }
-    STAMP(5);
+    if (coarse && tid == 0) p.flags[2] = 1;
 
     // ---- squared singular values = squared column norms; order them (descending, index breaks ties)
     for (int col = grp; col < D; col += NGRP) {
@@ -417,11 +406,11 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
 #pragma unroll
             for (int r = 0; r < NR; ++r) {
                 const int i = l16 + 16 * r;
-                if (i < D) p.W1[g * D + i] = (float)(sg * w[r]);
+                if (i < D) p.W1[g * D + i] = poisoned ? __builtin_nanf("") : (float)(sg * w[r]);
             }
             if (l16 == 0) {
                 const double l2 = lam[order[g]];
-                p.rho[g] = l2 > 0.0 ? sqrt(l2) : 0.0;
+                p.rho[g] = poisoned ? __builtin_nan("") : l2 > 0.0 ? sqrt(l2) : 0.0;
             }
         }
         sign_of[pass] = sg;
@@ -441,12 +430,11 @@ __global__ __launch_bounds__(SOLVE_THREADS) void dcca_solve_kernel(SolveParams p
                 if (i < D) {
                     double s = 0.0;
                     for (int j = i; j < D; ++j) s += C[j * D + i] * v[j];
-                    p.W2[g * D + i] = (float)(sign_of[pass] * s);
+                    p.W2[g * D + i] = poisoned ? __builtin_nanf("") : (float)(sign_of[pass] * s);
                 }
             }
         }
     }
-    STAMP(6);
 }
 
 template <int KS>
@@ -454,31 +442,29 @@ static int solve_launch(ddcca_ctx *ctx, const SolveParams &p)
 {
     constexpr int D = KS * KS;
     const size_t lds = (size_t)(3 * D * D + 2 * D + 8) * sizeof(double) + (size_t)(D + 4) * sizeof(int);
-    static bool attr_set = false;
-    if (!attr_set) {
+    static bool attr_set[MAX_DEVICES] = {};      // the attribute belongs to the kernel's code object on ONE device
+    if (!attr_set[ctx->device]) {
         DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)dcca_solve_kernel<KS>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_set = true;
+        attr_set[ctx->device] = true;
     }
     hipLaunchKernelGGL(dcca_solve_kernel<KS>, dim3(1), dim3(SOLVE_THREADS), lds, ctx->stream, p);
     DDCCA_HIP(ctx, hipGetLastError());
     return DDCCA_OK;
 }
 
-#ifndef DDCCA_SOLVE_STAMPS
-int launch_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const double *Cw, const double *CT, int k,
-                 int L, double ridge, float *W1, float *W2, double *rho)
+// ws: 2*D*D doubles of device scratch (the two inverse Cholesky factors); flags: device int[4]
+static int solve_with(ddcca_ctx *ctx, const double *C11, const double *C22, const double *Cw, const double *CT, int k,
+                      int L, double ridge, float *W1, float *W2, double *rho, double *ws, int *flags)
 {
-    ProfScope prof(ctx, DDCCA_K_SOLVE);
     const int D = k * k;
-    int rc;
-    if ((rc = ensure(ctx, ctx->solve_ws, 2 * (size_t)D * D * sizeof(double)))) return rc;
     SolveParams p;
     p.C11 = C11; p.C22 = C22; p.Cw = Cw; p.CT = CT;
     p.L = L; p.ridge = ridge;
-    p.gI1 = (double *)ctx->solve_ws.ptr;
-    p.gI2 = p.gI1 + (size_t)D * D;
+    p.gI1 = ws;
+    p.gI2 = ws + (size_t)D * D;
     p.W1 = W1; p.W2 = W2; p.rho = rho;
+    p.flags = flags;
     switch (k) {
         case 3: return solve_launch<3>(ctx, p);
         case 5: return solve_launch<5>(ctx, p);
@@ -487,6 +473,17 @@ int launch_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const dou
         default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
     }
 }
-#endif
+
+int launch_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const double *Cw, const double *CT, int k,
+                 int L, double ridge, float *W1, float *W2, double *rho)
+{
+    const int D = k * k;
+    int rc;
+    if ((rc = ensure(ctx, ctx->solve_ws, 2 * (size_t)D * D * sizeof(double)))) return rc;
+    if ((rc = ensure_flags(ctx))) return rc;
+    ProfScope prof(ctx, DDCCA_K_SOLVE);
+    return solve_with(ctx, C11, C22, Cw, CT, k, L, ridge, W1, W2, rho, (double *)ctx->solve_ws.ptr,
+                      (int *)ctx->flags.ptr);
+}
 
 }  // namespace ddcca

@@ -53,7 +53,7 @@ struct ddcca_ctx {
     ddcca::Buffer seg;                      // reduction segments
     ddcca::Buffer mats;                     // 5 x [D][D] double: C11 C22 C12 Cw CT
     ddcca::Buffer solve_ws;                 // solver scratch (global part)
-    ddcca::Buffer flags;                    // int[4]: [0] label error
+    ddcca::Buffer flags;                    // int[4]: [0] label error, [1] Cholesky pivot, [2] Jacobi sweeps exhausted
     ddcca::Buffer maps1, maps2;             // extract_features scratch
     ddcca::Buffer iq_lut;                   // information-quality table of the output layer
     int64_t iq_lut_total = 0;               // block area + bins the table was built for (0 = none)
@@ -74,6 +74,8 @@ int fail(ddcca_ctx *ctx, int code, const std::string &msg);
 int hip_fail(ddcca_ctx *ctx, hipError_t e, const char *what);
 int ensure(ddcca_ctx *ctx, Buffer &b, size_t bytes);     // grow; contents undefined after growth
 int device_ready(ddcca_ctx *ctx);                        // set device, query CU count
+int ensure_flags(ddcca_ctx *ctx);                        // the device int[4] of sticky conditions, zeroed once
+constexpr int MAX_DEVICES = 64;                          // per-device host tables (kernel attributes) are this long
 
 #define DDCCA_HIP(ctx, call)                                         \
     do {                                                             \

@@ -607,11 +607,11 @@ int max_gram_slots(ddcca_ctx *ctx, int k) { return ctx->n_cu * gram_shape(k).wav
 template <int KS, int TSPLIT, bool CROSS, int WPE, bool SPLIT>
 static int gram_launch(ddcca_ctx *ctx, const GramParams &p, int grid, size_t lds)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
+    static bool attr_set[MAX_DEVICES] = {};      // per device: the attribute is set on that device's code object
+    if (!attr_set[ctx->device]) {
         DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)patch_gram_kernel<KS, TSPLIT, CROSS, WPE, SPLIT>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_set = true;
+        attr_set[ctx->device] = true;
     }
     hipLaunchKernelGGL((patch_gram_kernel<KS, TSPLIT, CROSS, WPE, SPLIT>), dim3(grid), dim3(GRAM_THREADS), lds,
                        ctx->stream, p);

@@ -210,6 +210,67 @@ def test_dcca_solve_max_filters(ctx, oracle):
     assert np.abs(filter_cosines(W1.cpu().numpy(), sol["W1"]))[ok].min() >= 0.9999
 
 
+def test_bad_label_poisons_the_filters(ctx):
+    """A label outside [0, n_cls) leaves its sample out of C_w / C_T: the solve of such an accumulation writes
+    NaN instead of filters of inconsistent matrices, and ddcca_status reports and clears the condition."""
+    from paper_2209_13027_amd.binding import DdccaError, ELABEL
+    rng = np.random.default_rng(45)
+    V1, V2 = rand_views(rng, 4, 16, 16)
+    bad = dev(np.array([0, 1, 5, 1], dtype=np.int32))
+    W1, W2, rho = ctx.learn_stage_filters(dev(V1), dev(V2), bad, 1, 16, 16, 2, 5, 4)
+    assert torch.isnan(W1).all() and torch.isnan(W2).all() and torch.isnan(rho).all()
+    with pytest.raises(DdccaError) as e:
+        ctx.status()
+    assert e.value.code == ELABEL
+    good = dev(np.array([0, 1, 0, 1], dtype=np.int32))
+    W1, W2, rho = ctx.learn_stage_filters(dev(V1), dev(V2), good, 1, 16, 16, 2, 5, 4)
+    ctx.status()
+    assert torch.isfinite(W1).all() and torch.isfinite(W2).all() and torch.isfinite(rho).all()
+
+
+def test_solve_reports_an_indefinite_matrix(ctx, oracle):
+    """C11 with a negative direction (or NaN) cannot be Cholesky-factored: the condition is reported by
+    ddcca_status as DDCCA_ENUMERIC instead of passing silently; the next good solve is clean again."""
+    from paper_2209_13027_amd.binding import DdccaError, ENUMERIC
+    rng = np.random.default_rng(46)
+    V1, V2 = rand_views(rng, 6, 12, 12)
+    cls = np.array([0, 1, 2, 0, 1, 2], np.int32)
+    mats = oracle.stage_matrices(V1, V2, cls, np.zeros(6, np.int32), 3, 1, 3)
+    for spoil in ("negative", "nan"):
+        C11 = mats["C11"].copy()
+        if spoil == "negative":
+            C11 -= 2.0 * np.linalg.eigvalsh(C11).max() * np.eye(9)
+        else:
+            C11[4, 4] = np.nan
+        ctx.dcca_solve(dev(C11), dev(mats["C22"]), dev(mats["Cw"]), dev(mats["CT"]), 3, 4)
+        with pytest.raises(DdccaError) as e:
+            ctx.status()
+        assert e.value.code == ENUMERIC, spoil
+    W1, _, rho = ctx.dcca_solve(dev(mats["C11"]), dev(mats["C22"]), dev(mats["Cw"]), dev(mats["CT"]), 3, 4)
+    ctx.status()
+    sol = oracle.dcca_solve(mats["C11"], mats["C22"], mats["Ctilde"], 4)
+    assert np.allclose(rho.cpu().numpy(), sol["rho"], rtol=1e-8)
+
+
+@pytest.mark.parametrize("k", [3, 5, 7, 9])
+def test_constant_images_give_finite_filters(ctx, k):
+    """A constant image has a zero patch Gram away from the border and a rank-deficient one overall; with every
+    image constant (and view 2 constant too) C_dd is singular far beyond the constant direction.  The ridge keeps
+    the solve finite: filters and rho are finite numbers and no breakdown is reported."""
+    n, h, w = 6, 24, 20
+    V1 = np.full((n, h, w), 3.0, dtype=np.float32)
+    V2 = np.full((n, h, w), 7.0, dtype=np.float32)
+    cls = dev(np.array([0, 1, 2, 0, 1, 2], np.int32))
+    W1, W2, rho = ctx.learn_stage_filters(dev(V1), dev(V2), cls, 1, h, w, 3, k, 4)
+    ctx.status()
+    assert torch.isfinite(W1).all() and torch.isfinite(W2).all() and torch.isfinite(rho).all()
+    # one non-constant image among constant ones: still finite
+    V1[0] = np.random.default_rng(3).standard_normal((h, w)).astype(np.float32)
+    W1, W2, rho = ctx.learn_stage_filters(dev(V1), dev(V2), cls, 1, h, w, 3, k, 4)
+    ctx.status()
+    assert torch.isfinite(W1).all() and torch.isfinite(W2).all() and torch.isfinite(rho).all()
+
+
 # ------------------------------------------------------------------ learn_stage_filters / end to end
 def hist_rel_l1(got, want):
     return np.abs(got.astype(np.int64) - want).sum() / want.sum()
