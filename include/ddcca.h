@@ -99,6 +99,22 @@ int ddcca_dcca_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const
                      const double *CT, int k, int L, double ridge, float *W1, float *W2,
                      double *rho);
 
+/* ddcca_dcca_solve for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernel, same results bit for bit; the call makes no hipMalloc / hipFree and records no
+ * timing events (ddcca_profile_* does not see it).  The kernel's scratch -- two D x D
+ * double matrices and the int[4] of sticky conditions -- is a file-scope device array of
+ * 104 992 bytes sized for k = 9, the largest k of the library (a larger k is DDCCA_EINVAL
+ * like everywhere else); each GPU the library runs on holds its copy until the process
+ * ends.  All contexts and calls on one GPU share that array: calls of this function that
+ * overlap on one GPU (different streams or threads) race; calls on one stream are
+ * ordered and safe.  Nothing in it needs to start at zero except the condition flags,
+ * which are zero when the library is loaded and are cleared by the ddcca_status call that
+ * reports them -- on the context that made the call, for the whole GPU. */
+int ddcca_dcca_solve_noalloc(ddcca_ctx *ctx, const double *C11, const double *C22,
+                             const double *Cw, const double *CT, int k, int L, double ridge,
+                             float *W1, float *W2, double *rho);
+
 /* ---- the four calls of the path ----------------------------------------------------- */
 
 /* Learn one stage's filters from all samples at once (Section II-A; begin +

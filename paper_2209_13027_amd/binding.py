@@ -22,7 +22,7 @@ KERNEL_NAMES = ["gram", "class_sum", "reduce", "solve", "conv", "hash_hist", "gr
 EXPORTS = [
     "ddcca_create", "ddcca_destroy", "ddcca_last_error", "ddcca_status",
     "ddcca_corr_begin", "ddcca_corr_accumulate", "ddcca_corr_export", "ddcca_solve_filters",
-    "ddcca_dcca_solve", "ddcca_learn_stage_filters", "ddcca_apply_stage", "ddcca_hash_histogram",
+    "ddcca_dcca_solve", "ddcca_dcca_solve_noalloc", "ddcca_learn_stage_filters", "ddcca_apply_stage", "ddcca_hash_histogram",
     "ddcca_extract_features", "ddcca_hash_iq", "ddcca_extract_iq_features",
     "ddcca_apply_stage_hash", "ddcca_extract_features_fused", "ddcca_set_option",
     "ddcca_learn_next_stage_filters", "ddcca_profile_select",
@@ -74,6 +74,7 @@ def lib() -> ctypes.CDLL:
         l.ddcca_corr_export.argtypes = [vp, vp, vp, vp, vp, vp]
         l.ddcca_solve_filters.argtypes = [vp, i, d, vp, vp, vp]
         l.ddcca_dcca_solve.argtypes = [vp, vp, vp, vp, vp, i, i, d, vp, vp, vp]
+        l.ddcca_dcca_solve_noalloc.argtypes = [vp, vp, vp, vp, vp, i, i, d, vp, vp, vp]
         l.ddcca_learn_stage_filters.argtypes = [vp, vp, vp, vp, i64, i, i, i, i, i, i, d, vp, vp, vp]
         l.ddcca_apply_stage.argtypes = [vp, vp, i64, i, i, vp, i, i, vp]
         l.ddcca_hash_histogram.argtypes = [vp, vp, i64, i, i, i, i, i, i, i, vp]
@@ -171,6 +172,14 @@ class Context:
                                            _ptr(W1, torch.float32, "W1"), _ptr(W2, torch.float32, "W2"),
                                            _ptr(rho, torch.float64, "rho")))
         return W1, W2, rho
+
+    def dcca_solve_noalloc(self, C11, C22, Cw, CT, k, L, ridge, W1, W2, rho):
+        """ddcca_dcca_solve without any allocation: the caller brings the outputs W1, W2 ([L, k, k] float32) and rho
+        ([L] float64); nothing is allocated here or in the library."""
+        self._check(lib().ddcca_dcca_solve_noalloc(
+            self._h, _ptr(C11, torch.float64, "C11"), _ptr(C22, torch.float64, "C22"), _ptr(Cw, torch.float64, "Cw"),
+            _ptr(CT, torch.float64, "CT"), k, L, ridge, _ptr(W1, torch.float32, "W1"), _ptr(W2, torch.float32, "W2"),
+            _ptr(rho, torch.float64, "rho")))
 
     def learn_stage_filters(self, v1, v2, cls, G, h, w, n_cls, k, L, ridge=1e-4):
         """v1, v2: [n_img*G, h, w] (or [n_img, G, h, w]) float32; cls: [n_img] int32."""

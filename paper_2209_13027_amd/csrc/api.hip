@@ -227,18 +227,22 @@ int ddcca_status(ddcca_ctx *ctx)
     int rc;
     if ((rc = device_ready(ctx))) return rc;
     DDCCA_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    if (ctx->flags.ptr) {
-        int host[4] = {0, 0, 0, 0};
-        DDCCA_HIP(ctx, hipMemcpy(host, ctx->flags.ptr, sizeof(host), hipMemcpyDeviceToHost));
-        if (host[0] || host[1] || host[2]) {
-            DDCCA_HIP(ctx, hipMemset(ctx->flags.ptr, 0, sizeof(host)));
-            if (host[0]) return fail(ctx, DDCCA_ELABEL, "class label outside [0, n_cls) seen on the device");
-            if (host[1])
-                return fail(ctx, DDCCA_ENUMERIC,
-                            "DCCA solve: C_dd + ridge is not positive definite (NaN/Inf input or ridge too small)");
-            return fail(ctx, DDCCA_ENUMERIC, "DCCA solve: the Jacobi rotations did not converge");
-        }
+    int host[4] = {0, 0, 0, 0};
+    if (ctx->static_solve_used) {
+        ctx->static_solve_used = false;
+        if ((rc = static_solve_flags(ctx, host))) return rc;
     }
+    if (ctx->flags.ptr) {
+        int own[4] = {0, 0, 0, 0};
+        DDCCA_HIP(ctx, hipMemcpy(own, ctx->flags.ptr, sizeof(own), hipMemcpyDeviceToHost));
+        if (own[0] || own[1] || own[2]) DDCCA_HIP(ctx, hipMemset(ctx->flags.ptr, 0, sizeof(own)));
+        for (int i = 0; i < 4; ++i) host[i] |= own[i];
+    }
+    if (host[0]) return fail(ctx, DDCCA_ELABEL, "class label outside [0, n_cls) seen on the device");
+    if (host[1])
+        return fail(ctx, DDCCA_ENUMERIC,
+                    "DCCA solve: C_dd + ridge is not positive definite (NaN/Inf input or ridge too small)");
+    if (host[2]) return fail(ctx, DDCCA_ENUMERIC, "DCCA solve: the Jacobi rotations did not converge");
     return DDCCA_OK;
 }
 
@@ -353,6 +357,17 @@ int ddcca_dcca_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const
     if (!C11 || !C22 || !Cw || !CT) return fail(ctx, DDCCA_EINVAL, "null matrix pointer");
     if ((rc = device_ready(ctx))) return rc;
     return launch_solve(ctx, C11, C22, Cw, CT, k, L, ridge, W1, W2, rho);
+}
+
+int ddcca_dcca_solve_noalloc(ddcca_ctx *ctx, const double *C11, const double *C22, const double *Cw,
+                             const double *CT, int k, int L, double ridge, float *W1, float *W2, double *rho)
+{
+    if (!ctx) return DDCCA_EINVAL;
+    int rc;
+    if ((rc = check_solve_args(ctx, k, L, ridge, W1, W2, rho))) return rc;
+    if (!C11 || !C22 || !Cw || !CT) return fail(ctx, DDCCA_EINVAL, "null matrix pointer");
+    if ((rc = device_ready(ctx))) return rc;
+    return launch_solve_static(ctx, C11, C22, Cw, CT, k, L, ridge, W1, W2, rho);
 }
 
 int ddcca_learn_stage_filters(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls, int64_t n_img,

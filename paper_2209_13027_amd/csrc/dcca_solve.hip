@@ -486,4 +486,54 @@ int launch_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const dou
                       (int *)ctx->flags.ptr);
 }
 
+// ---- the solve for callers that cannot allocate ------------------------------------------------------------
+// The kernel's global scratch (the two inverse Cholesky factors, 2*D*D doubles) and its int[4] of sticky
+// conditions live in one file-scope device array instead of context buffers.  Every GPU holds its own copy of the
+// array at its own address; the name below is only the host-side handle of the symbol, so host code never passes
+// it to a kernel: the address on a device comes from hipGetSymbolAddress, once per device, with that device
+// current, and is kept in static_ptr[].
+constexpr size_t STATIC_WS_DOUBLES = 2 * (size_t)(DDCCA_MAX_K * DDCCA_MAX_K) * (DDCCA_MAX_K * DDCCA_MAX_K);
+constexpr size_t STATIC_SCRATCH_DOUBLES = STATIC_WS_DOUBLES + 2;            // + int[4]
+static __device__ __align__(256) double scratch[STATIC_SCRATCH_DOUBLES];    // 104 992 bytes per GPU, zero at load
+static double *static_ptr[MAX_DEVICES] = {};
+
+static int static_scratch(ddcca_ctx *ctx, double **ws, int **flags)
+{
+    if (!static_ptr[ctx->device]) {
+        double *ptr = nullptr;
+        DDCCA_HIP(ctx, hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(ctx, DDCCA_EHIP, "hipGetSymbolAddress returned a null address for the solve scratch");
+        static_ptr[ctx->device] = ptr;
+    }
+    *ws = static_ptr[ctx->device];
+    *flags = reinterpret_cast<int *>(static_ptr[ctx->device] + STATIC_WS_DOUBLES);
+    return DDCCA_OK;
+}
+
+int launch_solve_static(ddcca_ctx *ctx, const double *C11, const double *C22, const double *Cw, const double *CT,
+                        int k, int L, double ridge, float *W1, float *W2, double *rho)
+{
+    if ((size_t)2 * k * k * k * k > STATIC_WS_DOUBLES)
+        return fail(ctx, DDCCA_EINVAL, "k exceeds what the static solve scratch holds (k <= 9)");
+    double *ws = nullptr;
+    int *flags = nullptr;
+    int rc;
+    if ((rc = static_scratch(ctx, &ws, &flags))) return rc;
+    ctx->static_solve_used = true;
+    return solve_with(ctx, C11, C22, Cw, CT, k, L, ridge, W1, W2, rho, ws, flags);
+}
+
+// The sticky conditions of the static variant on this context's device: copied to host[4]; cleared on the device
+// when any is set.  Synchronous (ddcca_status only).
+int static_solve_flags(ddcca_ctx *ctx, int host[4])
+{
+    double *ws = nullptr;
+    int *flags = nullptr;
+    int rc;
+    if ((rc = static_scratch(ctx, &ws, &flags))) return rc;
+    DDCCA_HIP(ctx, hipMemcpy(host, flags, 4 * sizeof(int), hipMemcpyDeviceToHost));
+    if (host[0] || host[1] || host[2]) DDCCA_HIP(ctx, hipMemset(flags, 0, 4 * sizeof(int)));
+    return DDCCA_OK;
+}
+
 }  // namespace ddcca

@@ -54,6 +54,7 @@ struct ddcca_ctx {
     ddcca::Buffer mats;                     // 5 x [D][D] double: C11 C22 C12 Cw CT
     ddcca::Buffer solve_ws;                 // solver scratch (global part)
     ddcca::Buffer flags;                    // int[4]: [0] label error, [1] Cholesky pivot, [2] Jacobi sweeps exhausted
+    bool static_solve_used = false;         // ddcca_dcca_solve_noalloc ran: its conditions sit in the static scratch
     ddcca::Buffer maps1, maps2;             // extract_features scratch
     ddcca::Buffer iq_lut;                   // information-quality table of the output layer
     int64_t iq_lut_total = 0;               // block area + bins the table was built for (0 = none)
@@ -135,6 +136,10 @@ int launch_class_finalize(ddcca_ctx *ctx, const double *sums, int n_cls, int G, 
                           float *img /* [2][n_cls*G + G][P] */, int n_seg);
 int launch_solve(ddcca_ctx *ctx, const double *C11, const double *C22, const double *Cw, const double *CT,
                  int k, int L, double ridge, float *W1, float *W2, double *rho);
+// the same solve with its scratch in a file-scope device array (no allocation, no timing events)
+int launch_solve_static(ddcca_ctx *ctx, const double *C11, const double *C22, const double *Cw, const double *CT,
+                        int k, int L, double ridge, float *W1, float *W2, double *rho);
+int static_solve_flags(ddcca_ctx *ctx, int host[4]);
 int launch_conv(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L,
                 float *out);
 // the same with three-piece bf16 operands (DDCCA_CONV_BF16X3)
