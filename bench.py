@@ -2,14 +2,19 @@
 """Benchmark of the two-stage DDCCANet hot path on one MI355X.
 
 One "step" = the whole path on one synthetic workload, inputs already in HBM:
-  learn stage-1 filters -> apply stage 1 (both views) -> learn stage-2 filters on the maps
-  -> extract_features (stage-1 conv, stage-2 conv, hashing + block histograms) for all images.
-Prints ONE JSON line: images/s, the roofline of the dominant kernel (patch-Gram, fp32 MFMA),
-per-kernel figures, and the CPU oracle timed on a bounded sample of the same workload.
+  learn the stage-1 filters -> learn the stage-2 filters from the same inputs (the stage-1 maps of the training
+  set are convolved batch by batch into library scratch and accumulated at once, never held as a whole)
+  -> extract_features for all images (stage-1 conv, stage-2 conv with the maps of a batch materialised,
+  hashing + block histograms).
+Prints ONE JSON line.  `value` is on the headline workload (default: large_scale, the largest single-GPU
+configuration); `other_workloads` carries images/s and the per-kernel figures of the other configurations measured
+in the same run; `roofline` is the dominant kernel (patch-Gram, fp32 MFMA) timed with HIP events on the library's
+stream; `cpu_baseline` is the CPU oracle on a bounded sample of the headline workload.
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -21,7 +26,8 @@ if ROOT not in sys.path:
 
 PEAK_MFMA_FP32_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
-PEAK_FP32_VALU_TFLOPS = 157.3
+ALL_WORKLOADS = ["large_scale", "stress", "object", "small_face", "tiny"]
+CPU_SAMPLE_IMAGES = {"tiny": 40, "small_face": 400, "object": 128, "large_scale": 257, "stress": 16}
 
 
 def algorithmic_work(wl, M, feat_bytes=2):
@@ -77,60 +83,32 @@ def run_cpu_baseline(wl, budget_images):
     n = int(v1.shape[0])
     return {
         "value": n / dt, "unit": "images/s", "cores": oracle.num_threads(), "kind": "oracle",
-        "sample": f"{n} of {wl.M} images ({per_class} per class), whole path (learn both stages + extract), "
-                  f"fp64, {dt:.1f} s",
+        "sample": f"{n} of {wl.M} images of {wl.name} ({per_class} per class), whole path (learn both stages + "
+                  f"extract), fp64, {dt:.1f} s",
     }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="small_face")
-    ap.add_argument("--features", default="counts", choices=["counts", "iq_f32", "iq_f16"],
-                    help="output layer: uint16 block histograms (the headline path) or the information-quality "
-                         "values -log p(t) as fp32 / fp16")
-    ap.add_argument("--fused", action="store_true",
-                    help="time the path with the second stage convolution fused into the output layer (the "
-                         "stage-2 maps are never written); the default materialises them")
-    ap.add_argument("--conv", default="fp32", choices=["fp32", "bf16x3"],
-                    help="arithmetic of the stage convolution: fp32 matrix instructions (the headline path) or "
-                         "three-piece bf16 operands on the bf16 matrix pipeline (same accuracy)")
-    ap.add_argument("--gram", default="fp32", choices=["fp32", "bf16x3", "lag"],
-                    help="arithmetic of the patch-Gram accumulation: fp32 matrix instructions (the headline path), "
-                         "three-piece bf16 operands on the bf16 matrix pipeline (same accuracy), or the "
-                         "lag-structured form on the fp32 matrix instructions (same accuracy)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-images", type=int, default=0, help="images in the CPU-oracle sample (0 = default)")
-    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
-                    help="before the steps, run one plain device copy of this many MiB (a kernel of known "
-                         "traffic that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives are part of it); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-
+def measure(name, args, K, W, detail):
+    """All figures of one workload.  detail: the comparison legs too (phases, fused / bf16x3 extraction, the cost of
+    the timing events)."""
     import torch
     from paper_2209_13027_amd import pipeline
-    from paper_2209_13027_amd.binding import Context
+    from paper_2209_13027_amd.binding import (Context, OPT_CONV_ARITH, CONV_BF16X3, CONV_FP32, OPT_GRAM_ARITH,
+                                              GRAM_FP32, GRAM_BF16X3, GRAM_LAG_FP32)
     from paper_2209_13027_amd.workloads import WORKLOADS, make_views
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    wl = WORKLOADS[args.workload]
+    wl = WORKLOADS[name]
+    tg = time.perf_counter()
     v1, v2, cls = make_views(wl)
+    gen_s = time.perf_counter() - tg
     M = int(v1.shape[0])
     ctx = Context(0)
     if args.gram != "fp32":
-        from paper_2209_13027_amd.binding import OPT_GRAM_ARITH, GRAM_BF16X3, GRAM_LAG_FP32
         ctx.set_option(OPT_GRAM_ARITH, GRAM_BF16X3 if args.gram == "bf16x3" else GRAM_LAG_FP32)
     if args.conv == "bf16x3":
-        from paper_2209_13027_amd.binding import OPT_CONV_ARITH, CONV_BF16X3
         ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
     d1, d2, dc = torch.from_numpy(v1).cuda(), torch.from_numpy(v2).cuda(), torch.from_numpy(cls).cuda()
+    del v1, v2
     by, bx = wl.blocks
     feat_dtype = {"counts": torch.uint16, "iq_f32": torch.float32, "iq_f16": torch.float16}[args.features]
     feat = torch.empty((M, 2, wl.L1, by, bx, 1 << wl.L2), dtype=feat_dtype, device="cuda")
@@ -148,122 +126,98 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    for _ in range(W):
         step()
     torch.cuda.synchronize()
     ctx.status()
 
     # timed region: HIP events recorded by the library on its stream around the launches of the dominant kernel
-    # (the patch-Gram) only, so that the other sixty launches of a step do not pay for event pairs
+    # (the patch-Gram) only, so that the other launches of a step do not pay for event pairs
     ctx.profile_reset()
     ctx.profile_select(["gram"])
     ctx.profile_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(K):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ctx.profile_enable(False)
     prof_gram = ctx.profile_read()["gram"]
 
-    # the same steps with every kernel family bracketed by events: the per-kernel figures of `kernels`
+    # a few more steps with every kernel family bracketed by events: the per-kernel figures of `kernels`
+    K2 = K if not detail else min(K, 5)
     ctx.profile_reset()
     ctx.profile_select(None)
     ctx.profile_enable(True)
     torch.cuda.synchronize()
     ta = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(K2):
         step()
     torch.cuda.synchronize()
     dt_all = time.perf_counter() - ta
     ctx.profile_enable(False)
     prof = ctx.profile_read()
-
-    # the same region once more without events, to show their cost
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt_plain = time.perf_counter() - t1
     ctx.status()
 
-    # learning and extraction timed apart, one synchronised repetition at a time (mean and min over K)
-    def timed(fn):
+    def timed(fn, reps):
         ts = []
-        for _ in range(args.steps):
+        for _ in range(reps):
             torch.cuda.synchronize()
             t = time.perf_counter()
             fn()
             torch.cuda.synchronize()
             ts.append(time.perf_counter() - t)
-        return {"ms_mean": sum(ts) / len(ts) * 1e3, "ms_min": min(ts) * 1e3,
+        return {"ms_mean": sum(ts) / len(ts) * 1e3, "ms_min": min(ts) * 1e3, "reps": reps,
                 "images_per_s": M / (sum(ts) / len(ts))}
-    model = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
-    phases = {
-        "learn": timed(lambda: pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)),
-        "extract": timed(lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block,
-                                                  wl.stride, batch, out=feat, dtype=feat_dtype,
-                                                  fused=args.fused)),
-        "e2e": timed(step),
-    }
-    # the same step captured once into a HIP graph and replayed (same kernels, no launch gaps)
-    from paper_2209_13027_amd.binding import (OPT_CONV_ARITH as _OC, CONV_BF16X3 as _CB, OPT_GRAM_ARITH as _OG,
-                                              GRAM_BF16X3 as _GB, GRAM_LAG_FP32 as _GL)
-    opts = ([(_OC, _CB)] if args.conv == "bf16x3" else []) + ([(_OG, _GB)] if args.gram == "bf16x3" else []) + \
-           ([(_OG, _GL)] if args.gram == "lag" else [])
-    graphed = pipeline.GraphedPath(d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2, wl.block, wl.stride,
-                                   batch_images=batch, dtype=feat_dtype, fused=args.fused, out=feat, options=opts)
-    graphed.replay()
-    graphed.status()
-    phases["e2e_graph"] = timed(graphed.replay)
-    torch.cuda.synchronize()
-    tg = time.perf_counter()
-    for _ in range(args.steps):
-        graphed.replay()
-    torch.cuda.synchronize()
-    phases["e2e_graph"]["ms_back_to_back"] = (time.perf_counter() - tg) / args.steps * 1e3
-    graphed.status()
-    graphed.close()
-    del graphed
-    if not args.fused:
-        # the same extraction with the second stage fused into the output layer, for comparison
-        pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride, batch, out=feat,
-                         dtype=feat_dtype, fused=True)          # untimed: first launch loads the kernel
-        ctx.profile_reset()
-        ctx.profile_select(["conv_hash_hist"])
-        ctx.profile_enable(True)
-        phases["extract_fused"] = timed(lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2,
-                                                                 wl.block, wl.stride, batch, out=feat,
-                                                                 dtype=feat_dtype, fused=True))
-        ctx.profile_enable(False)
-        pf = ctx.profile_read()["conv_hash_hist"]
-        phases["extract_fused"]["conv_hash_hist_ms"] = pf["ms"] / args.steps
-        phases["extract_fused"]["e2e_images_per_s"] = M / ((phases["learn"]["ms_mean"]
-                                                            + phases["extract_fused"]["ms_mean"]) * 1e-3)
-    conv_split = None
-    if args.conv == "fp32" and not args.fused:
-        # the same extraction with the three-piece bf16 convolution (same accuracy), for comparison
-        from paper_2209_13027_amd.binding import OPT_CONV_ARITH, CONV_BF16X3, CONV_FP32
-        ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
-        run = lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride,
-                                       batch, out=feat, dtype=feat_dtype)
-        run()
-        ctx.profile_reset()
-        ctx.profile_select(["conv"])
-        ctx.profile_enable(True)
-        phases["extract_conv_bf16x3"] = timed(run)
-        ctx.profile_enable(False)
-        conv_split = ctx.profile_read()["conv"]["ms"] / args.steps
-        ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
+
+    phases, dt_plain = {}, None
+    plain_path = args.conv == "fp32" and args.gram == "fp32" and not args.fused
+    if detail:
+        # the same region without events, to show their cost
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(K2):
+            step()
+        torch.cuda.synchronize()
+        dt_plain = time.perf_counter() - t1
+        # learning and extraction timed apart, one synchronised repetition at a time
+        model = pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
+        phases["learn"] = timed(lambda: pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2), K2)
+        phases["extract"] = timed(lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block,
+                                                           wl.stride, batch, out=feat, dtype=feat_dtype,
+                                                           fused=args.fused), K2)
+        if not args.fused:
+            # the same extraction with the second stage fused into the output layer, for comparison
+            run = lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride,
+                                           batch, out=feat, dtype=feat_dtype, fused=True)
+            run()                                             # untimed: first launch loads the kernel
+            ctx.profile_reset()
+            ctx.profile_select(["conv_hash_hist"])
+            ctx.profile_enable(True)
+            phases["extract_fused"] = timed(run, K2)
+            ctx.profile_enable(False)
+            phases["extract_fused"]["conv_hash_hist_ms"] = ctx.profile_read()["conv_hash_hist"]["ms"] / K2
+            phases["extract_fused"]["e2e_images_per_s"] = M / ((phases["learn"]["ms_mean"]
+                                                                + phases["extract_fused"]["ms_mean"]) * 1e-3)
+        if args.conv == "fp32" and not args.fused:
+            # the same extraction with the three-piece bf16 convolution (same accuracy), for comparison
+            ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
+            run = lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride,
+                                           batch, out=feat, dtype=feat_dtype)
+            run()
+            ctx.profile_reset()
+            ctx.profile_select(["conv"])
+            ctx.profile_enable(True)
+            phases["extract_conv_bf16x3"] = timed(run, K2)
+            ctx.profile_enable(False)
+            phases["extract_conv_bf16x3"]["conv_ms"] = ctx.profile_read()["conv"]["ms"] / K2
+            ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
     fast = None
-    if args.conv == "fp32" and args.gram == "fp32" and not args.fused:
+    if plain_path:
         # The whole step once more with every widened option on: the lag-structured Gram, three-piece bf16
         # operands in the convolution (same accuracy bars, see the parity tests) and the fused last stage.
         # Not part of `value`.
-        from paper_2209_13027_amd.binding import (OPT_CONV_ARITH, CONV_BF16X3, CONV_FP32, OPT_GRAM_ARITH,
-                                                  GRAM_FP32, GRAM_LAG_FP32)
         ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
         ctx.set_option(OPT_GRAM_ARITH, GRAM_LAG_FP32)
 
@@ -275,16 +229,12 @@ def main():
         ctx.profile_reset()
         ctx.profile_select(["gram", "conv_hash_hist"])
         ctx.profile_enable(True)
-        fast = timed(fast_step)
+        fast = timed(fast_step, K2)
         ctx.profile_enable(False)
         pf = ctx.profile_read()
-        fast["gram_ms"] = pf["gram"]["ms"] / args.steps
-        fast["gram_useful_tflops"] = (algorithmic_work(wl, M)["gram_flops"] / (fast["gram_ms"] * 1e-3) / 1e12
-                                      if fast["gram_ms"] > 0 else 0.0)
-        fast["gram_useful_tflops_note"] = ("flop of the dense formulation per second of Gram time: above the fp32 "
-                                           "MFMA peak when the lag-structured form does the work")
-        fast["conv_hash_hist_ms"] = pf["conv_hash_hist"]["ms"] / args.steps
-        fast["options"] = "gram lag-structured fp32, conv bf16x3, fused last stage"
+        fast["gram_ms"] = pf["gram"]["ms"] / K2
+        fast["conv_hash_hist_ms"] = pf["conv_hash_hist"]["ms"] / K2
+        fast["options"] = "gram lag-structured fp32, conv bf16x3, fused last stage (same parity bars)"
         ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
         ctx.set_option(OPT_GRAM_ARITH, GRAM_FP32)
     ctx.profile_select(None)
@@ -292,74 +242,147 @@ def main():
 
     work = algorithmic_work(wl, M, feat.element_size())
     L1v, P = wl.L1, wl.h * wl.w
-    K = args.steps
     gram_ms = prof_gram["ms"] / max(1, prof_gram["launches"])
     gram_flops_per_launch = work["gram_flops"] * K / max(1, prof_gram["launches"])
     gram_tflops = gram_flops_per_launch / (gram_ms * 1e-3) / 1e12 if gram_ms > 0 else 0.0
-    conv_ms = prof["conv"]["ms"] / K
-    hist_ms = prof["hash_hist"]["ms"] / K
-    fused_ms = prof["conv_hash_hist"]["ms"] / K
-    fused_flops = 2 * M * L1v * P * 2 * wl.D * wl.L2
-    fused_bytes = 2 * M * L1v * (P * 4 + by * bx * (1 << wl.L2) * feat.element_size())
+    conv_ms = prof["conv"]["ms"] / K2
+    hist_ms = prof["hash_hist"]["ms"] / K2
+    fused_ms = prof["conv_hash_hist"]["ms"] / K2
+    per = lambda x, ms: x / (ms * 1e-3) if ms > 0 else 0.0
+    conv_gbs, conv_tf = per(work["conv_bytes"], conv_ms) / 1e9, per(work["conv_flops"], conv_ms) / 1e12
     kernels = {
-        "gram": {"ms_per_step": prof["gram"]["ms"] / K, "launches_per_step": prof["gram"]["launches"] / K,
+        "gram": {"ms_per_step": prof["gram"]["ms"] / K2, "launches_per_step": prof["gram"]["launches"] / K2,
                  "useful_tflops": gram_tflops, "frac_mfma_fp32": gram_tflops / PEAK_MFMA_FP32_TFLOPS},
-        "gram_cross": {"ms_per_step": prof["gram_cross"]["ms"] / K,
-                       "launches_per_step": prof["gram_cross"]["launches"] / K,
-                       "useful_tflops": work["gram_cross_flops"] * K / (prof["gram_cross"]["ms"] * 1e-3) / 1e12
-                       if prof["gram_cross"]["ms"] > 0 else 0.0},
-        "class_sum": {"ms_per_step": prof["class_sum"]["ms"] / K,
-                      "gbs": work["class_sum_bytes"] / (prof["class_sum"]["ms"] / K * 1e-3) / 1e9
-                      if prof["class_sum"]["ms"] > 0 else 0.0},
-        "reduce": {"ms_per_step": prof["reduce"]["ms"] / K},
-        "solve": {"ms_per_step": prof["solve"]["ms"] / K, "launches_per_step": prof["solve"]["launches"] / K},
-        "conv": {"ms_per_step": conv_ms, "gbs": work["conv_bytes"] / (conv_ms * 1e-3) / 1e9 if conv_ms > 0 else 0.0,
-                 "frac_hbm": work["conv_bytes"] / (conv_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if conv_ms > 0 else 0.0,
-                 "tflops": work["conv_flops"] / (conv_ms * 1e-3) / 1e12 if conv_ms > 0 else 0.0},
-        "hash_hist": {"ms_per_step": hist_ms,
-                      "gbs": work["hist_bytes"] / (hist_ms * 1e-3) / 1e9 if hist_ms > 0 else 0.0,
-                      "frac_hbm": work["hist_bytes"] / (hist_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if hist_ms > 0 else 0.0},
+        "gram_cross": {"ms_per_step": prof["gram_cross"]["ms"] / K2,
+                       "launches_per_step": prof["gram_cross"]["launches"] / K2,
+                       "useful_tflops": per(work["gram_cross_flops"] * K2, prof["gram_cross"]["ms"]) / 1e12},
+        "class_sum": {"ms_per_step": prof["class_sum"]["ms"] / K2,
+                      "gbs": per(work["class_sum_bytes"], prof["class_sum"]["ms"] / K2) / 1e9},
+        "reduce": {"ms_per_step": prof["reduce"]["ms"] / K2},
+        "solve": {"ms_per_step": prof["solve"]["ms"] / K2, "launches_per_step": prof["solve"]["launches"] / K2},
+        # the convolution is priced against both roofs: HBM (algorithmic bytes) and the fp32 matrix pipeline
+        # (algorithmic flop; the executed matrix work is (k+1)/k of it) -- the larger fraction names the binding one
+        "conv": {"ms_per_step": conv_ms, "gbs": conv_gbs, "frac_hbm": conv_gbs / PEAK_HBM_GBS, "tflops": conv_tf,
+                 "frac_mfma_fp32": conv_tf / PEAK_MFMA_FP32_TFLOPS, "arithmetic": args.conv},
+        "hash_hist": {"ms_per_step": hist_ms, "gbs": per(work["hist_bytes"], hist_ms) / 1e9,
+                      "frac_hbm": per(work["hist_bytes"], hist_ms) / 1e9 / PEAK_HBM_GBS},
     }
-    if conv_split:
+    if "extract_conv_bf16x3" in phases:
         # extraction only: stage 1 once per view plus stage 2
         xbytes = 2 * M * P * (4 + 4 * L1v) + 2 * M * L1v * P * (4 + 4 * wl.L2)
-        kernels["conv_bf16x3_extract"] = {"ms_per_extract": conv_split, "gbs": xbytes / (conv_split * 1e-3) / 1e9,
-                                          "frac_hbm": xbytes / (conv_split * 1e-3) / 1e9 / PEAK_HBM_GBS}
+        cs = phases["extract_conv_bf16x3"]["conv_ms"]
+        kernels["conv_bf16x3_extract"] = {"ms_per_extract": cs, "gbs": per(xbytes, cs) / 1e9,
+                                          "frac_hbm": per(xbytes, cs) / 1e9 / PEAK_HBM_GBS}
     if fused_ms > 0:
         # stage-2 conv bytes and flops move from "conv" into the fused kernel
+        fused_flops = 2 * M * L1v * P * 2 * wl.D * wl.L2
+        fused_bytes = 2 * M * L1v * (P * 4 + by * bx * (1 << wl.L2) * feat.element_size())
         s1_bytes = 2 * (2 * M * P * (4 + 4 * L1v))
-        kernels["conv"]["gbs"] = s1_bytes / (conv_ms * 1e-3) / 1e9 if conv_ms > 0 else 0.0
+        kernels["conv"]["gbs"] = per(s1_bytes, conv_ms) / 1e9
         kernels["conv"]["frac_hbm"] = kernels["conv"]["gbs"] / PEAK_HBM_GBS
-        kernels["conv"]["tflops"] = 2 * (2 * M * P * 2 * wl.D * L1v) / (conv_ms * 1e-3) / 1e12 if conv_ms > 0 else 0.0
+        kernels["conv"]["tflops"] = per(2 * (2 * M * P * 2 * wl.D * L1v), conv_ms) / 1e12
+        kernels["conv"]["frac_mfma_fp32"] = kernels["conv"]["tflops"] / PEAK_MFMA_FP32_TFLOPS
         del kernels["hash_hist"]
-        kernels["conv_hash_hist"] = {"ms_per_step": fused_ms, "tflops": fused_flops / (fused_ms * 1e-3) / 1e12,
-                                     "frac_mfma_fp32": fused_flops / (fused_ms * 1e-3) / 1e12 / PEAK_MFMA_FP32_TFLOPS,
-                                     "gbs": fused_bytes / (fused_ms * 1e-3) / 1e9}
-    out = {
-        "metric": "images/s for 2-stage DDCCANet extraction (learn both stages + extract features)",
-        "value": M * K / dt, "unit": "images/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
-        "ms_per_step": dt / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        kernels["conv_hash_hist"] = {"ms_per_step": fused_ms, "tflops": per(fused_flops, fused_ms) / 1e12,
+                                     "frac_mfma_fp32": per(fused_flops, fused_ms) / 1e12 / PEAK_MFMA_FP32_TFLOPS,
+                                     "gbs": per(fused_bytes, fused_ms) / 1e9}
+    traffic = measured_traffic(wl.name, "patch_gram_kernel", ", false,")
+    res = {
+        "value": M * K / dt, "ms_per_step": dt / K * 1e3, "steps": K, "warmup": W,
         "config": {"workload": wl.name, "images": M, "classes": wl.n_classes, "h": wl.h, "w": wl.w, "k": wl.k,
                    "L1": wl.L1, "L2": wl.L2, "block": wl.block, "stride": wl.stride, "bins": 1 << wl.L2,
                    "feature_len": wl.feature_len, "features": args.features,
                    "fused_last_stage": bool(args.fused), "conv_arithmetic": args.conv,
-                   "gram_arithmetic": args.gram},
-        "roofline": {"bound": "mfma", "kernel": "patch_gram_kernel (all-tiles variant: the Gram over the input maps)", "achieved": gram_tflops,
-                     "peak": PEAK_MFMA_FP32_TFLOPS, "unit": "TFLOP/s", "frac": gram_tflops / PEAK_MFMA_FP32_TFLOPS,
-                     "traffic": measured_traffic(wl.name, "patch_gram_kernel", ", false,"), "avg_launch_ms": gram_ms,
+                   "gram_arithmetic": args.gram, "second_stage_learning": "streamed from the inputs",
+                   "input_generation_s": round(gen_s, 1)},
+        "roofline": {"bound": "mfma", "kernel": "patch_gram_kernel (all-tiles variant: the Gram over the input maps)",
+                     "achieved": gram_tflops, "peak": PEAK_MFMA_FP32_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gram_tflops / PEAK_MFMA_FP32_TFLOPS, "traffic": traffic,
+                     "traffic_source": ("profiles/traffic.json (rocprofv3 --pmc passes of this command, committed; "
+                                        "not re-measured in this run)" if traffic is not None else None),
+                     "avg_launch_ms": gram_ms, "launches_per_step": prof_gram["launches"] / K,
                      "algorithmic_flop_per_launch": gram_flops_per_launch},
         "kernels": kernels,
-        "phases": phases,
-        "widened_path": fast,
-        "ms_per_step_without_events": dt_plain / K * 1e3,
-        "ms_per_step_with_all_kernels_timed": dt_all / K * 1e3,
+        "kernel_steps": K2,
+        "ms_per_step_with_all_kernels_timed": dt_all / K2 * 1e3,
     }
-    if not args.no_cpu_baseline:
-        default_images = {"tiny": 40, "small_face": 400, "object": 128, "large_scale": 257, "stress": 16}
-        n_cpu = args.cpu_images or default_images.get(wl.name, 64)
-        out["cpu_baseline"] = run_cpu_baseline(wl, n_cpu)
+    if phases:
+        res["phases"] = phases
+    if fast:
+        res["widened_path"] = fast
+    if dt_plain is not None:
+        res["ms_per_step_without_events"] = dt_plain / K2 * 1e3
     ctx.close()
+    del feat, d1, d2, dc
+    gc.collect()
+    torch.cuda.empty_cache()
+    return wl, res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="large_scale", choices=ALL_WORKLOADS,
+                    help="the headline workload (value, roofline, cpu_baseline); default: the largest configuration")
+    ap.add_argument("--others", default="all",
+                    help="'all' (default): also measure the other configurations and report them under "
+                         "other_workloads; 'none'; or a comma-separated list of workload names")
+    ap.add_argument("--features", default="counts", choices=["counts", "iq_f32", "iq_f16"],
+                    help="output layer: uint16 block histograms (the headline path) or the information-quality "
+                         "values -log p(t) as fp32 / fp16")
+    ap.add_argument("--fused", action="store_true",
+                    help="time the path with the second stage convolution fused into the output layer (the "
+                         "stage-2 maps are never written); the default materialises them")
+    ap.add_argument("--conv", default="fp32", choices=["fp32", "bf16x3"],
+                    help="arithmetic of the stage convolution: fp32 matrix instructions (the headline path) or "
+                         "three-piece bf16 operands on the bf16 matrix pipeline (same accuracy)")
+    ap.add_argument("--gram", default="fp32", choices=["fp32", "bf16x3", "lag"],
+                    help="arithmetic of the patch-Gram accumulation: fp32 matrix instructions (the headline path), "
+                         "three-piece bf16 operands on the bf16 matrix pipeline (same accuracy), or the "
+                         "lag-structured form on the fp32 matrix instructions (same accuracy)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-detail", action="store_true", help="skip the comparison legs of the headline workload")
+    ap.add_argument("--cpu-images", type=int, default=0, help="images in the CPU-oracle sample (0 = default)")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="before the steps, run one plain device copy of this many MiB (a kernel of known "
+                         "traffic that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+
+    wl, head = measure(args.workload, args, args.steps, args.warmup, not args.no_detail)
+    out = {
+        "metric": "images/s for 2-stage DDCCANet extraction (learn both stages + extract features)",
+        "value": head.pop("value"), "unit": "images/s", "n_gpus": 1, "steps": head.pop("steps"),
+        "warmup": head.pop("warmup"), "ms_per_step": head.pop("ms_per_step"), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+    }
+    out.update(head)
+    if args.others == "all":
+        others = [n for n in ALL_WORKLOADS if n != args.workload]
+    elif args.others in ("", "none"):
+        others = []
+    else:
+        others = [n for n in args.others.split(",") if n and n != args.workload]
+    if others:
+        out["other_workloads"] = {}
+        for name in others:
+            # steps sized so that a workload's timed region stays within a few seconds
+            k_o = max(3, min(args.steps, 20))
+            _, res = measure(name, args, k_o, min(args.warmup, 2), False)
+            out["other_workloads"][name] = {"images_per_s": res.pop("value"), **res}
+    if not args.no_cpu_baseline:
+        n_cpu = args.cpu_images or CPU_SAMPLE_IMAGES.get(wl.name, 64)
+        out["cpu_baseline"] = run_cpu_baseline(wl, n_cpu)
     print(json.dumps(out))
 
 
