@@ -1,129 +1,408 @@
 // Stage convolution (Eq. 6) on the bf16 matrix pipeline with three-piece operands (see conv_split.h):
-// same interface, tiling and output stores as the fp32 kernel of conv_multi.hip, fp32-grade accuracy.
+// out[n][g][y][x] = sum W[g][dy][dx] in[n][y+dy-r][x+dx-r], zero padding, same size, fp32-grade accuracy.
 //
-// One workgroup: a 32-row x (32*NBX)-column output tile of one image, all L filters.  The input tile with
-// its halo is split once, while it is staged, into three planes of packed bf16 pairs in LDS; the filter
-// pieces live in registers.  Wavefront w owns tile rows w, w+4, ...
+// Implicit GEMM without an im2col buffer, on v_mfma_f32_16x16x32_bf16:
+//   rows (A operand)  : (filter g, x-shift s), g < 8, s in {0,1}      -> 16 rows
+//   cols (B operand)  : 16 pixel positions x = x0 + 2c of one image row
+//   K                 : taps (dy, dx'), dx' in 0..k (both shifts: k+1 columns, an even number), taken as pairs
+//                       (dx', dx'+1), dx' even.  A pair is one 32-bit word of a tile stored as packed bf16 pairs;
+//                       a lane feeds an instruction with four pairs (a "group"), one instruction covers four
+//                       groups (lane / 16): 1 / 1 / 2 / 3 instructions per piece product for k = 3 / 5 / 7 / 9.
+//   => D[(g,s)][c]    = out[g][y][x0+2c+s]; each lane ends with (x, x+1) pairs of two output planes, written as
+//                       8-byte stores that form 128-byte row segments.
+// The kernel is persistent: a workgroup walks a contiguous range of (image, tile) items.  The filter pieces are
+// built once and stay in registers.  The input tile with its halo is split once into three planes of packed pairs
+// in LDS; there are two such buffers, and the next tile travels HBM -> registers while the current one is
+// contracted and is split into the other buffer afterwards (one barrier per tile).
+// LDS banks: the four groups of an instruction read four different tap rows (or row ends), two groups per half
+// wavefront; the plane pitch is chosen so that the 16 consecutive words of one group and those of its partner
+// fall into disjoint banks, and a group whose slot holds no tap reads its partner's words (a broadcast).
 #include "conv_split.h"
 
 namespace ddcca {
 
-constexpr int CSPLIT_THREADS = 256;
-constexpr int CSPLIT_TH = 32;
-constexpr int CSPLIT_XB = 32;
-constexpr int CSPLIT_MAX_NBX = 4;
+constexpr int CSPLIT_XB = 32;           // pixels per column block (16 columns x 2 shifts)
+constexpr int CSPLIT_MAX_NBX = 4;       // column blocks per tile
+constexpr int CSPLIT_TH_MAX = 32;       // tile rows
+constexpr int CSPLIT_WG_PER_CU = 2;
 
-template <int KS, int NBX>
-__global__ __launch_bounds__(CSPLIT_THREADS) void conv_split_kernel(const float *__restrict__ in, int h, int w,
-                                                                   const float *__restrict__ W, int L,
-                                                                   float *__restrict__ out, int tiles_x, int tiles_y)
-{
-    typedef SplitGeom<KS, NBX, CSPLIT_TH> G;
-    constexpr int R = G::R, TW = G::TW, STEPS = G::STEPS;
-    __shared__ unsigned int planes[3 * G::PLANE];
-    const int tiles = tiles_x * tiles_y;
-    const int64_t n = blockIdx.x / tiles;
-    const int t = blockIdx.x - (int)n * tiles;
-    const int tx = t % tiles_x, ty = t / tiles_x;
-    const int64_t P = (int64_t)h * w;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int q = lane >> 4, c = lane & 15;
-    // staged columns [gxa, gxa + COLS): gxa = the multiple of 4 at or below the first halo column; pairs are
-    // packed starting at the first halo column's parity so that every window of a lane starts on a word
-    const int gy0 = ty * CSPLIT_TH - R, gx0 = tx * TW - R;
-    const int gxa = gx0 & ~3, shx = gx0 - gxa, po = shx & 1;
+// RU consecutive output rows share the pixel operands: the taps of output row y+u are the input rows
+// y+u .. y+u+k-1, so RU rows together read the k+RU-1 input rows y .. y+k+RU-2; one set of operand registers
+// (the pairs of those input rows, in slots that are the same for all RU rows) feeds RU accumulator sets, each with
+// its own filter pieces (tap row = input row - u, zero where that is outside 0..k-1).  That divides the LDS
+// traffic per output by RU, which is what bounds this kernel: an instruction's pixel operand is 1 KiB per
+// wavefront, the six piece products reuse three such operands, and four SIMDs at full matrix rate would ask the
+// LDS for exactly its 128 bytes per cycle.
+template <int KS, int NBX, int RU>
+struct SplitConv {
+    static constexpr int R = (KS - 1) / 2;
+    static constexpr int KW = KS + 1;              // tap columns incl. the shift (even)
+    static constexpr int RP = KW / 2;              // pairs per tap row
+    static constexpr int JROWS = KS + RU - 1;      // input rows under RU output rows
+    static constexpr int PAIRS = JROWS * RP;
+    static constexpr int KG = (PAIRS + 3) / 4;     // groups of four pairs
+    static constexpr int STEPS = (KG + 3) / 4;     // matrix instructions per piece product and output row
+    static constexpr int TW = NBX * CSPLIT_XB;
+    static constexpr int PH_MAX = CSPLIT_TH_MAX + 2 * R;
+    static constexpr int COLS = (TW + KW + 6) / 4 * 4;   // staged pixels per tile row (row start a multiple of 4)
+    static constexpr int V4 = COLS / 4;
+    // staged columns start at the multiple of 4 at or below the first halo column tx*TW - R (TW is a multiple of
+    // 4, so the distance SHX and the pair parity PO are the same for every tile)
+    static constexpr int SHX = (4 - R % 4) % 4;
+    static constexpr int PO = SHX & 1;
+    // words per plane row: at least COLS/2, and congruent to RES modulo MOD (the bank rule above)
+    static constexpr int MOD = KS == 3 ? 16 : 32;
+    static constexpr int RES = KS == 3 ? 8 : KS == 9 ? 17 : 16;
+    static constexpr int MINP = COLS / 2;
+    static constexpr int PWORDS = MINP + (RES - MINP % MOD + MOD) % MOD;
+    static constexpr int PLANE = PH_MAX * PWORDS;  // words per plane
+    static constexpr int BUF = 3 * PLANE;          // words per buffer (h, m, l planes)
+
+    // The pair in slot i of group q of instruction t: input row j (relative to the first output row's first tap
+    // row) and pair dxp, i.e. tap columns 2*dxp and 2*dxp + 1.  Row-major over the pairs, except k = 5 with one
+    // output row (three pairs per tap row): there group q holds row q and the fourth slots of groups 0..2 hold the
+    // pairs of row 4, so that partner groups again read words one plane row apart.
+    __device__ static bool slot(int t, int q, int i, int &j, int &dxp)
     {
-        const float *src = in + n * P;
-        const bool vec4 = (w & 3) == 0 && (((uintptr_t)src) & 15) == 0;
-        for (int e = threadIdx.x; e < G::PH * G::V4; e += CSPLIT_THREADS) {
-            const int yy = e / G::V4, xv = e - yy * G::V4;
-            const int gy = gy0 + yy, gx = gxa + 4 * xv;
-            float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f, v4 = 0.f;
-            if (gy >= 0 && gy < h) {
-                const float *row = src + (int64_t)gy * w;
-                if (vec4 && gx >= 0 && gx + 3 < w) {
-                    const float4 v = *reinterpret_cast<const float4 *>(row + gx);
-                    v0 = v.x; v1 = v.y; v2 = v.z; v3 = v.w;
-                } else {
-                    if (gx >= 0 && gx < w) v0 = row[gx];
-                    if (gx + 1 >= 0 && gx + 1 < w) v1 = row[gx + 1];
-                    if (gx + 2 >= 0 && gx + 2 < w) v2 = row[gx + 2];
-                    if (gx + 3 >= 0 && gx + 3 < w) v3 = row[gx + 3];
-                }
-                if (po && gx + 4 >= 0 && gx + 4 < w) v4 = row[gx + 4];
-            }
-            // word i of a plane row holds pixels (2i + po, 2i + 1 + po) of the staged row
-            const int idx = yy * G::PWORDS + 2 * xv;
-            if (po) {
-                split_store_pair(planes, G::PLANE, idx, v1, v2);
-                split_store_pair(planes, G::PLANE, idx + 1, v3, v4);
-            } else {
-                split_store_pair(planes, G::PLANE, idx, v0, v1);
-                split_store_pair(planes, G::PLANE, idx + 1, v2, v3);
-            }
+        if (KS == 5 && RU == 1) {
+            if (t > 0) return false;
+            if (i < 3) { j = q; dxp = i; return true; }
+            j = 4; dxp = q;
+            return q < 3;
         }
+        const int pair = 4 * (4 * t + q) + i;
+        j = pair / RP;
+        dxp = pair - j * RP;
+        return pair < PAIRS;
     }
-    int toff[STEPS][4];
-    split_offsets<G>(q, toff);
-    SplitOperand wa[STEPS][3];
-    split_weights<G, KS, true>(W, L, 0, q, c, wa);
-    __syncthreads();
+};
 
-    const int rows = min(CSPLIT_TH, h - ty * CSPLIT_TH);
-    const int gx_lane = tx * TW + 2 * c;
-    // first pixel of the lane's windows: staged column shx + 2c  ->  word (shx - po) / 2 + c
-    const unsigned int *lane_base = planes + (shx - po) / 2 + c;
+struct ConvSplitParams {
+    const float *in;
+    const float *W;
+    float *out;
+    int h, w, L, tiles_x, tiles_y, th;
+    long long n_items;          // images * tiles
+};
 
-    for (int g0 = 0; g0 < L; g0 += 8) {
-        if (g0 > 0) split_weights<G, KS, true>(W, L, g0, q, c, wa);
-        // uniform per workgroup: every store of this pass is an aligned float2 (w even: pairs never straddle the edge)
-        const bool fast = (w & 1) == 0 && (((uintptr_t)out) & 7) == 0 && g0 + 8 <= L;
-        const int nfull = min(NBX, (w - tx * TW) / CSPLIT_XB);   // column blocks of this tile fully inside the image
-        // lane (q,c) ends with planes g0+2q (acc[0..1]) and g0+2q+1 (acc[2..3]) at columns x, x+1
-        const int ga = g0 + 2 * q;
-        for (int r = wave; r < rows; r += 4) {
-            floatx4 acc[1][NBX];
-            split_rows<G, NBX, 1>(lane_base + r * G::PWORDS, 0, G::PLANE, toff, wa, acc);
-            const int gy = ty * CSPLIT_TH + r;
-            float *dst = out + (n * L + ga) * P + (int64_t)gy * w + gx_lane;
-            if (fast) {
+// A operand of lane (q, c) for output row u of a row group: row c of the instruction is filter g0 + c/2, shift
+// c%2; per instruction and piece the four pairs of group q, tap row = input row - u.
+template <class G, int KS>
+__device__ __forceinline__ void split_weights(const float *W, int L, int g0, int u, int q, int c,
+                                              SplitOperand (&wa)[G::STEPS][3])
+{
+    const int g = g0 + (c >> 1), s = c & 1;
 #pragma unroll
-                for (int e = 0; e < 2; ++e)
+    for (int t = 0; t < G::STEPS; ++t) {
 #pragma unroll
-                    for (int b = 0; b < NBX; ++b)
-                        if (b < nfull || gx_lane + b * CSPLIT_XB < w)
-                            *reinterpret_cast<float2 *>(dst + e * P + b * CSPLIT_XB) =
-                                make_float2(acc[0][b][2 * e], acc[0][b][2 * e + 1]);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    if (ga + e >= L) continue;
-#pragma unroll
-                    for (int b = 0; b < NBX; ++b) {
-                        const int gx = gx_lane + b * CSPLIT_XB;
-                        if (gx < w) dst[e * P + b * CSPLIT_XB] = acc[0][b][2 * e];
-                        if (gx + 1 < w) dst[e * P + b * CSPLIT_XB + 1] = acc[0][b][2 * e + 1];
-                    }
-                }
+        for (int i = 0; i < 4; ++i) {
+            int j, dxp;
+            const bool valid = G::slot(t, q, i, j, dxp);
+            const int dy = j - u, dx = 2 * dxp;
+            float v0 = 0.f, v1 = 0.f;
+            if (valid && dy >= 0 && dy < KS && g < L) {
+                if (dx - s >= 0 && dx - s < KS) v0 = W[(g * KS + dy) * KS + dx - s];
+                if (dx + 1 - s >= 0 && dx + 1 - s < KS) v1 = W[(g * KS + dy) * KS + dx + 1 - s];
             }
+            split3_pair(v0, v1, wa[t][0].w[i], wa[t][1].w[i], wa[t][2].w[i]);
         }
     }
 }
 
-template <int KS, int NBX>
-static void conv_split_launch_nbx(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int L,
-                                  float *out)
+// Word offsets (inside a plane, relative to the lane's pixel pair of the tile row of the first output row) of the
+// four pairs of this lane's group, per instruction.  A slot without a pair (its filter pieces are zero) reads what
+// the partner group of the half wavefront reads, else what group 0 reads.
+template <class G>
+__device__ __forceinline__ void split_offsets(int q, int (&toff)[G::STEPS][4])
 {
-    const int tiles_x = (w + NBX * CSPLIT_XB - 1) / (NBX * CSPLIT_XB);
-    const int tiles_y = (h + CSPLIT_TH - 1) / CSPLIT_TH;
-    const int64_t tiles = (int64_t)tiles_x * tiles_y;
-    const int64_t per_launch = std::max<int64_t>(1, ((int64_t)1 << 30) / tiles);   // grid.x stays below 2^31
-    for (int64_t n0 = 0; n0 < n; n0 += per_launch) {
-        const int64_t nb = std::min(per_launch, n - n0);
-        hipLaunchKernelGGL((conv_split_kernel<KS, NBX>), dim3((unsigned)(nb * tiles)), dim3(CSPLIT_THREADS), 0,
-                           ctx->stream, in + n0 * (int64_t)h * w, h, w, W, L, out + n0 * L * (int64_t)h * w, tiles_x,
-                           tiles_y);
+#pragma unroll
+    for (int t = 0; t < G::STEPS; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int j, dxp;
+            if (!G::slot(t, q, i, j, dxp) && !((q & 1) && G::slot(t, q - 1, i, j, dxp))) G::slot(t, 0, i, j, dxp);
+            toff[t][i] = j * G::PWORDS + dxp;
+        }
+}
+
+// The part of a tile a thread carries from HBM to LDS in one pass: NV chunks of four staged pixels (+ the fifth
+// pixel when the pairs straddle the chunks).  A tile takes PASSES passes of THREADS * NV chunks.
+template <class G, int THREADS>
+struct TileRegs {
+    static constexpr int CHUNKS = G::PH_MAX * G::V4;
+    static constexpr int NV_ALL = (CHUNKS + THREADS - 1) / THREADS;
+    static constexpr int NV = NV_ALL < 12 ? NV_ALL : 12;
+    static constexpr int PASSES = (CHUNKS + THREADS * NV - 1) / (THREADS * NV);
+    float v[NV][4 + G::PO];
+};
+
+// Where chunk j of thread `tid` sits: tile row yy, first staged column 4*xv; whether the tile row is inside the image.
+template <class G, int THREADS>
+__device__ __forceinline__ void chunk_pos(int e0, int tid, int j, int &yy, int &xv)
+{
+    const int e = e0 + tid + j * THREADS;
+    yy = e / G::V4;
+    xv = e - yy * G::V4;
+}
+
+// Issue the loads of a tile.  Every load reads a valid address (the first pixels of the image stand in for what
+// lies outside it) and nothing uses the values here: store_tile replaces the stand-ins by zeros, so all loads of a
+// thread are in flight together and no branch surrounds them.  VEC4: w and the image base allow 16-byte loads
+// (w a multiple of 4; the first staged column is one too, so a chunk lies wholly inside the image or outside).
+template <class G, int THREADS, bool VEC4>
+__device__ __forceinline__ void load_tile(TileRegs<G, THREADS> &t, int e0, int tid, const float *src, int h, int w,
+                                          int gy0, int gxa, int ph)
+{
+#pragma unroll
+    for (int j = 0; j < TileRegs<G, THREADS>::NV; ++j) {
+        int yy, xv;
+        chunk_pos<G, THREADS>(e0, tid, j, yy, xv);
+        const int gy = gy0 + yy, gx = gxa + 4 * xv;
+        const bool rowok = yy < ph && gy >= 0 && gy < h;
+        const float *row = src + (int64_t)(rowok ? gy : 0) * w;
+        if (VEC4) {
+            const bool ok = rowok && gx >= 0 && gx < w;
+            const float4 v = *reinterpret_cast<const float4 *>(row + (ok ? gx : 0));
+            t.v[j][0] = v.x; t.v[j][1] = v.y; t.v[j][2] = v.z; t.v[j][3] = v.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) t.v[j][i] = row[rowok && gx + i >= 0 && gx + i < w ? gx + i : 0];
+        }
+        if (G::PO) t.v[j][4 * G::PO] = row[rowok && gx + 4 >= 0 && gx + 4 < w ? gx + 4 : 0];
     }
+}
+
+// Split the carried pixels into the three planes of one buffer: word i of a plane row holds the pieces of the
+// staged pixels (2i + PO, 2i + 1 + PO); pixels outside the image are zero.
+template <class G, int THREADS>
+__device__ __forceinline__ void store_tile(const TileRegs<G, THREADS> &t, int e0, int tid, unsigned int *planes, int h,
+                                           int w, int gy0, int gxa, int ph)
+{
+#pragma unroll
+    for (int j = 0; j < TileRegs<G, THREADS>::NV; ++j) {
+        int yy, xv;
+        chunk_pos<G, THREADS>(e0, tid, j, yy, xv);
+        if (yy >= ph) continue;
+        const int gy = gy0 + yy, gx = gxa + 4 * xv;
+        const bool rowok = gy >= 0 && gy < h;
+        float v[5];
+#pragma unroll
+        for (int i = 0; i < 4 + G::PO; ++i) v[i] = rowok && gx + i >= 0 && gx + i < w ? t.v[j][i] : 0.f;
+        unsigned int *dst = planes + yy * G::PWORDS + 2 * xv;
+        unsigned ha, ma, la, hb, mb, lb;
+        split3_pair(v[G::PO], v[1 + G::PO], ha, ma, la);
+        split3_pair(v[2 + G::PO], v[3 + G::PO], hb, mb, lb);
+        dst[0] = ha; dst[1] = hb;
+        dst[G::PLANE] = ma; dst[G::PLANE + 1] = mb;
+        dst[2 * G::PLANE] = la; dst[2 * G::PLANE + 1] = lb;
+    }
+}
+
+// The pixel operand of one instruction slot set: the h, m and l pieces of this lane's four pairs.
+struct PixelOperand {
+    SplitOperand h, m, l;
+};
+
+template <class G>
+__device__ __forceinline__ void read_operand(PixelOperand &o, const unsigned int *src, const int (&off)[4])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o.h.w[i] = src[off[i]];
+        o.m.w[i] = src[G::PLANE + off[i]];
+        o.l.w[i] = src[2 * G::PLANE + off[i]];
+    }
+}
+
+// RU consecutive output rows x NBX column blocks: acc[u][b] = the 16 x 16 outputs of row u, block b.  prow: word of
+// the lane's first pixel pair in the tile row of the first output row, plane of the h pieces.  The work goes in
+// sets of one instruction slot set x CB column blocks; the operands of the next set are read while the products
+// of the current one run, and inside a set consecutive instructions belong to different accumulators (RU rows, or
+// two column blocks when there is a single row).
+template <class G, int NBX, int RU>
+__device__ __forceinline__ void split_rows(const unsigned int *prow, const int (&toff)[G::STEPS][4],
+                                           const SplitOperand (&wa)[RU][G::STEPS][3], floatx4 (&acc)[RU][NBX])
+{
+#pragma unroll
+    for (int u = 0; u < RU; ++u)
+#pragma unroll
+        for (int b = 0; b < NBX; ++b) acc[u][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+    constexpr int CB = 1;     // (two blocks per set for single-row kernels was tried: k = 9 runs out of registers)
+    constexpr int NB = NBX / CB, N = G::STEPS * NB;
+    PixelOperand op[2][CB];
+#pragma unroll
+    for (int k = 0; k < CB; ++k) read_operand<G>(op[0][k], prow + k * 16, toff[0]);
+#pragma unroll
+    for (int idx = 0; idx < N; ++idx) {
+        const int t = idx / NB, b0 = (idx - t * NB) * CB;
+        if (idx + 1 < N) {
+            const int t2 = (idx + 1) / NB, b2 = (idx + 1 - t2 * NB) * CB;
+#pragma unroll
+            for (int k = 0; k < CB; ++k) read_operand<G>(op[(idx + 1) & 1][k], prow + (b2 + k) * 16, toff[t2]);
+        }
+        // the reads above are issued before the products below (the scheduler would otherwise sink them to their
+        // use and expose the LDS latency to the matrix pipeline)
+        __builtin_amdgcn_sched_barrier(0);
+        // small terms first: (h,l') (l,h') (m,m') (h,m') (m,h') (h,h')
+        constexpr int WP[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+        for (int pr = 0; pr < 6; ++pr)
+#pragma unroll
+            for (int k = 0; k < CB; ++k) {
+                const PixelOperand &o = op[idx & 1][k];
+                const bf16x8 pix = pr == 0 ? o.l.v : (pr == 2 || pr == 3) ? o.m.v : o.h.v;
+#pragma unroll
+                for (int u = 0; u < RU; ++u)
+                    acc[u][b0 + k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[u][t][WP[pr]].v, pix, acc[u][b0 + k], 0, 0, 0);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <int KS, int NBX, int RU, int WAVES, bool VEC4>
+__global__ __launch_bounds__(WAVES * 64) void conv_split_kernel(ConvSplitParams p)
+{
+    typedef SplitConv<KS, NBX, RU> G;
+    constexpr int R = G::R, TW = G::TW, STEPS = G::STEPS, THREADS = WAVES * 64;
+    typedef TileRegs<G, THREADS> Regs;
+    static_assert(Regs::PASSES == 1, "a tile is carried in one pass");
+    extern __shared__ unsigned int planes[];                       // two buffers of G::BUF words
+    // workgroup b takes items b, b + grid, b + 2 grid, ...: at any time the workgroups of the chip write one
+    // moving window of neighbouring tiles
+    const long long item0 = blockIdx.x, istep = gridDim.x, item1 = p.n_items;
+    if (item0 >= item1) return;
+    const int h = p.h, w = p.w, L = p.L, th = p.th;
+    const int64_t P = (int64_t)h * w;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int q = lane >> 4, c = lane & 15;
+    const int tiles = p.tiles_x * p.tiles_y;
+    const int ph = th + 2 * R;
+
+    int toff[STEPS][4];
+    split_offsets<G>(q, toff);
+    // first pixel of the lane's windows: staged column SHX + 2c  ->  word (SHX - PO) / 2 + c
+    const int lane_word = (G::SHX - G::PO) / 2 + c;
+    Regs regs;
+
+    for (int g0 = 0; g0 < L; g0 += 8) {
+        SplitOperand wa[RU][STEPS][3];
+#pragma unroll
+        for (int u = 0; u < RU; ++u) split_weights<G, KS>(p.W, L, g0, u, q, c, wa[u]);
+        // position of the first item
+        int64_t n = item0 / tiles;
+        int t0 = (int)(item0 - n * tiles);
+        int ty = t0 / p.tiles_x, tx = t0 - ty * p.tiles_x;
+        // and the step to the next one, as images and tiles
+        const int64_t dn = istep / tiles;
+        const int dt = (int)(istep - dn * tiles);
+        load_tile<G, THREADS, VEC4>(regs, 0, threadIdx.x, p.in + n * P, h, w, ty * th - R, tx * TW - R - G::SHX, ph);
+        store_tile<G, THREADS>(regs, 0, threadIdx.x, planes, h, w, ty * th - R, tx * TW - R - G::SHX, ph);
+        __syncthreads();
+        int cur = 0;
+        // uniform: every store of this pass is an aligned float2 (w even: pairs never straddle the edge)
+        const bool fast = (w & 1) == 0 && (((uintptr_t)p.out) & 7) == 0 && g0 + 8 <= L;
+        // lane (q,c) ends with planes g0+2q (acc[0..1]) and g0+2q+1 (acc[2..3]) at columns x, x+1
+        const int ga = g0 + 2 * q;
+        for (long long item = item0; item < item1; item += istep) {
+            // the item after this one
+            t0 += dt;
+            int64_t n2 = n + dn;
+            if (t0 >= tiles) { t0 -= tiles; ++n2; }
+            const int ty2 = t0 / p.tiles_x, tx2 = t0 - ty2 * p.tiles_x;
+            const bool more = item + istep < item1;
+            if (more)
+                load_tile<G, THREADS, VEC4>(regs, 0, threadIdx.x, p.in + n2 * P, h, w, ty2 * th - R,
+                                            tx2 * TW - R - G::SHX, ph);
+
+            const unsigned int *buf = planes + cur * G::BUF + lane_word;
+            const int rows = min(th, h - ty * th);
+            const int gx_lane = tx * TW + 2 * c;
+            const int nfull = min(NBX, (w - tx * TW) / CSPLIT_XB);   // column blocks fully inside the image
+            for (int r = RU * wave; r < rows; r += RU * WAVES) {
+                // (a row group that runs past the tile's last row reads staged rows of the buffer all the same
+                // and its surplus rows are not written)
+                floatx4 acc[RU][NBX];
+                split_rows<G, NBX, RU>(buf + r * G::PWORDS, toff, wa, acc);
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    if (r + u >= rows) continue;
+                    const int gy = ty * th + r + u;
+                    float *dst = p.out + (n * L + ga) * P + (int64_t)gy * w + gx_lane;
+                    if (fast) {
+#pragma unroll
+                        for (int e = 0; e < 2; ++e)
+#pragma unroll
+                            for (int b = 0; b < NBX; ++b)
+                                if (b < nfull || gx_lane + b * CSPLIT_XB < w)
+                                    *reinterpret_cast<float2 *>(dst + e * P + b * CSPLIT_XB) =
+                                        make_float2(acc[u][b][2 * e], acc[u][b][2 * e + 1]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            if (ga + e >= L) continue;
+#pragma unroll
+                            for (int b = 0; b < NBX; ++b) {
+                                const int gx = gx_lane + b * CSPLIT_XB;
+                                if (gx < w) dst[e * P + b * CSPLIT_XB] = acc[u][b][2 * e];
+                                if (gx + 1 < w) dst[e * P + b * CSPLIT_XB + 1] = acc[u][b][2 * e + 1];
+                            }
+                        }
+                    }
+                }
+            }
+            // the other buffer was last read before the barrier that ended the previous item
+            if (more)
+                store_tile<G, THREADS>(regs, 0, threadIdx.x, planes + (cur ^ 1) * G::BUF, h, w, ty2 * th - R,
+                                       tx2 * TW - R - G::SHX, ph);
+            __syncthreads();
+            cur ^= 1;
+            n = n2; ty = ty2; tx = tx2;
+        }
+    }
+}
+
+// Output rows that share their pixel operands, and wavefronts per workgroup, per patch size.
+template <int KS> struct SplitShape { static constexpr int RU = 1, WAVES = 4; };
+template <> struct SplitShape<7> { static constexpr int RU = 2, WAVES = 4; };
+template <> struct SplitShape<3> { static constexpr int RU = 2, WAVES = 4; };
+
+template <int KS, int NBX, bool VEC4>
+static int conv_split_launch_vec(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int L,
+                                 float *out)
+{
+    constexpr int RU = SplitShape<KS>::RU, WAVES = SplitShape<KS>::WAVES;
+    typedef SplitConv<KS, NBX, RU> G;
+    static_assert(2 * G::BUF * 4 * CSPLIT_WG_PER_CU <= 160 * 1024, "two workgroups per compute unit must fit in LDS");
+    static bool attr_set[MAX_DEVICES] = {};      // per device: the attribute is set on that device's code object
+    if (!attr_set[ctx->device]) {
+        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)conv_split_kernel<KS, NBX, RU, WAVES, VEC4>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * G::BUF * 4));
+        attr_set[ctx->device] = true;
+    }
+    ConvSplitParams p;
+    p.in = in; p.W = W; p.out = out; p.h = h; p.w = w; p.L = L;
+    p.tiles_x = (w + G::TW - 1) / G::TW;
+    // equal tile heights of at most CSPLIT_TH_MAX rows, a multiple of the rows one pass of the workgroup covers
+    constexpr int PASS = RU * WAVES;
+    const int nty = (h + CSPLIT_TH_MAX - 1) / CSPLIT_TH_MAX;
+    p.th = std::min(CSPLIT_TH_MAX, ((h + nty - 1) / nty + PASS - 1) / PASS * PASS);
+    p.tiles_y = (h + p.th - 1) / p.th;
+    p.n_items = (long long)n * p.tiles_x * p.tiles_y;
+    const unsigned grid = (unsigned)std::min(p.n_items, (long long)CSPLIT_WG_PER_CU * ctx->n_cu);
+    hipLaunchKernelGGL((conv_split_kernel<KS, NBX, RU, WAVES, VEC4>), dim3(grid), dim3(WAVES * 64), 2 * G::BUF * 4,
+                       ctx->stream, p);
+    DDCCA_HIP(ctx, hipGetLastError());
+    return DDCCA_OK;
+}
+
+template <int KS, int NBX>
+static int conv_split_launch_nbx(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int L,
+                                 float *out)
+{
+    // 16-byte loads when every image row starts on a 16-byte boundary
+    if ((w & 3) == 0 && (((uintptr_t)in) & 15) == 0) return conv_split_launch_vec<KS, NBX, true>(ctx, in, n, h, w, W, L, out);
+    return conv_split_launch_vec<KS, NBX, false>(ctx, in, n, h, w, W, L, out);
 }
 
 template <int KS>
@@ -135,13 +414,11 @@ static int conv_split_launch(ddcca_ctx *ctx, const float *in, int64_t n, int h, 
     const int tiles_x = (xblocks + CSPLIT_MAX_NBX - 1) / CSPLIT_MAX_NBX;
     const int nbx = (xblocks + tiles_x - 1) / tiles_x;
     switch (nbx) {
-        case 1: conv_split_launch_nbx<KS, 1>(ctx, in, n, h, w, W, L, out); break;
-        case 2: conv_split_launch_nbx<KS, 2>(ctx, in, n, h, w, W, L, out); break;
-        case 3: conv_split_launch_nbx<KS, 3>(ctx, in, n, h, w, W, L, out); break;
-        default: conv_split_launch_nbx<KS, 4>(ctx, in, n, h, w, W, L, out); break;
+        case 1: return conv_split_launch_nbx<KS, 1>(ctx, in, n, h, w, W, L, out);
+        case 2: return conv_split_launch_nbx<KS, 2>(ctx, in, n, h, w, W, L, out);
+        case 3: return conv_split_launch_nbx<KS, 3>(ctx, in, n, h, w, W, L, out);
+        default: return conv_split_launch_nbx<KS, 4>(ctx, in, n, h, w, W, L, out);
     }
-    DDCCA_HIP(ctx, hipGetLastError());
-    return DDCCA_OK;
 }
 
 int launch_conv_split(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L,

@@ -163,23 +163,6 @@ __device__ __forceinline__ void gram_rows(const float *pix, int pitch, int rows,
 }
 
 // ---- three-piece bf16 operands --------------------------------------------------------------------------
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ unsigned bf16_pair(float a, float b)
-{
-    return __builtin_bit_cast(unsigned, __builtin_convertvector(floatx2{a, b}, bf16x2));
-}
-
-// The three pieces of the pair (a, b), each as bf16(a) | bf16(b) << 16.
-__device__ __forceinline__ void split3_pair(float a, float b, unsigned &h, unsigned &m, unsigned &l)
-{
-    h = bf16_pair(a, b);
-    const float ra = a - __uint_as_float(h << 16), rb = b - __uint_as_float(h & 0xffff0000u);
-    m = bf16_pair(ra, rb);
-    l = bf16_pair(ra - __uint_as_float(m << 16), rb - __uint_as_float(m & 0xffff0000u));
-}
-
 // One K = 32 step: six piece products per tile, product by product across the tiles (consecutive
 // instructions write different accumulators), small terms first.
 template <typename G, int ROLE>
