@@ -93,8 +93,8 @@ def measure(name, args, K, W, detail):
     the timing events)."""
     import torch
     from paper_2209_13027_amd import pipeline
-    from paper_2209_13027_amd.binding import (Context, OPT_CONV_ARITH, CONV_BF16X3, CONV_FP32, OPT_GRAM_ARITH,
-                                              GRAM_FP32, GRAM_BF16X3, GRAM_LAG_FP32)
+    from paper_2209_13027_amd.binding import (Context, OPT_CONV_ARITH, CONV_BF16X3, CONV_FP32, CONV_AUTO,
+                                              OPT_GRAM_ARITH, GRAM_FP32, GRAM_BF16X3, GRAM_LAG_FP32)
     from paper_2209_13027_amd.workloads import WORKLOADS, make_views
 
     wl = WORKLOADS[name]
@@ -105,8 +105,9 @@ def measure(name, args, K, W, detail):
     ctx = Context(0)
     if args.gram != "fp32":
         ctx.set_option(OPT_GRAM_ARITH, GRAM_BF16X3 if args.gram == "bf16x3" else GRAM_LAG_FP32)
-    if args.conv == "bf16x3":
-        ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
+    conv_opt = {"auto": CONV_AUTO, "fp32": CONV_FP32, "bf16x3": CONV_BF16X3}[args.conv]
+    ctx.set_option(OPT_CONV_ARITH, conv_opt)
+    conv_is_split = args.conv == "bf16x3" or (args.conv == "auto" and wl.k >= 5)
     d1, d2, dc = torch.from_numpy(v1).cuda(), torch.from_numpy(v2).cuda(), torch.from_numpy(cls).cuda()
     del v1, v2
     by, bx = wl.blocks
@@ -172,7 +173,7 @@ def measure(name, args, K, W, detail):
                 "images_per_s": M / (sum(ts) / len(ts))}
 
     phases, dt_plain = {}, None
-    plain_path = args.conv == "fp32" and args.gram == "fp32" and not args.fused
+    plain_path = args.conv == "auto" and args.gram == "fp32" and not args.fused
     if detail:
         # the same region without events, to show their cost
         torch.cuda.synchronize()
@@ -200,19 +201,21 @@ def measure(name, args, K, W, detail):
             phases["extract_fused"]["conv_hash_hist_ms"] = ctx.profile_read()["conv_hash_hist"]["ms"] / K2
             phases["extract_fused"]["e2e_images_per_s"] = M / ((phases["learn"]["ms_mean"]
                                                                 + phases["extract_fused"]["ms_mean"]) * 1e-3)
-        if args.conv == "fp32" and not args.fused:
-            # the same extraction with the three-piece bf16 convolution (same accuracy), for comparison
-            ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
+        if not args.fused:
+            # the same extraction with the other convolution arithmetic (same accuracy bars), for comparison
+            other, other_name = (CONV_FP32, "fp32") if conv_is_split else (CONV_BF16X3, "bf16x3")
+            ctx.set_option(OPT_CONV_ARITH, other)
             run = lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride,
                                            batch, out=feat, dtype=feat_dtype)
             run()
             ctx.profile_reset()
             ctx.profile_select(["conv"])
             ctx.profile_enable(True)
-            phases["extract_conv_bf16x3"] = timed(run, K2)
+            phases["extract_conv_other"] = timed(run, K2)
             ctx.profile_enable(False)
-            phases["extract_conv_bf16x3"]["conv_ms"] = ctx.profile_read()["conv"]["ms"] / K2
-            ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
+            phases["extract_conv_other"]["conv_ms"] = ctx.profile_read()["conv"]["ms"] / K2
+            phases["extract_conv_other"]["arithmetic"] = other_name
+            ctx.set_option(OPT_CONV_ARITH, conv_opt)
     fast = None
     if plain_path:
         # The whole step once more with every widened option on: the lag-structured Gram, three-piece bf16
@@ -234,8 +237,8 @@ def measure(name, args, K, W, detail):
         pf = ctx.profile_read()
         fast["gram_ms"] = pf["gram"]["ms"] / K2
         fast["conv_hash_hist_ms"] = pf["conv_hash_hist"]["ms"] / K2
-        fast["options"] = "gram lag-structured fp32, conv bf16x3, fused last stage (same parity bars)"
-        ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
+        fast["options"] = "gram lag-structured fp32, conv bf16x3 (every k), fused last stage (same parity bars)"
+        ctx.set_option(OPT_CONV_ARITH, conv_opt)
         ctx.set_option(OPT_GRAM_ARITH, GRAM_FP32)
     ctx.profile_select(None)
     ctx.status()
@@ -260,19 +263,20 @@ def measure(name, args, K, W, detail):
                       "gbs": per(work["class_sum_bytes"], prof["class_sum"]["ms"] / K2) / 1e9},
         "reduce": {"ms_per_step": prof["reduce"]["ms"] / K2},
         "solve": {"ms_per_step": prof["solve"]["ms"] / K2, "launches_per_step": prof["solve"]["launches"] / K2},
-        # the convolution is priced against both roofs: HBM (algorithmic bytes) and the fp32 matrix pipeline
-        # (algorithmic flop; the executed matrix work is (k+1)/k of it) -- the larger fraction names the binding one
+        # the convolution against HBM (algorithmic bytes); its useful fp32-equivalent flop rate beside it (with the
+        # fp32 matrix instructions that rate is capped at k/(k+1) of 157.3 TFLOP/s; three-piece bf16 operands run six
+        # bf16 instructions per fp32 product set on the 2.5 PFLOP/s pipeline)
         "conv": {"ms_per_step": conv_ms, "gbs": conv_gbs, "frac_hbm": conv_gbs / PEAK_HBM_GBS, "tflops": conv_tf,
-                 "frac_mfma_fp32": conv_tf / PEAK_MFMA_FP32_TFLOPS, "arithmetic": args.conv},
+                 "arithmetic": "bf16x3" if conv_is_split else "fp32"},
         "hash_hist": {"ms_per_step": hist_ms, "gbs": per(work["hist_bytes"], hist_ms) / 1e9,
                       "frac_hbm": per(work["hist_bytes"], hist_ms) / 1e9 / PEAK_HBM_GBS},
     }
-    if "extract_conv_bf16x3" in phases:
+    if "extract_conv_other" in phases:
         # extraction only: stage 1 once per view plus stage 2
         xbytes = 2 * M * P * (4 + 4 * L1v) + 2 * M * L1v * P * (4 + 4 * wl.L2)
-        cs = phases["extract_conv_bf16x3"]["conv_ms"]
-        kernels["conv_bf16x3_extract"] = {"ms_per_extract": cs, "gbs": per(xbytes, cs) / 1e9,
-                                          "frac_hbm": per(xbytes, cs) / 1e9 / PEAK_HBM_GBS}
+        cs = phases["extract_conv_other"]["conv_ms"]
+        kernels["conv_%s_extract" % phases["extract_conv_other"]["arithmetic"]] = {
+            "ms_per_extract": cs, "gbs": per(xbytes, cs) / 1e9, "frac_hbm": per(xbytes, cs) / 1e9 / PEAK_HBM_GBS}
     if fused_ms > 0:
         # stage-2 conv bytes and flops move from "conv" into the fused kernel
         fused_flops = 2 * M * L1v * P * 2 * wl.D * wl.L2
@@ -281,7 +285,6 @@ def measure(name, args, K, W, detail):
         kernels["conv"]["gbs"] = per(s1_bytes, conv_ms) / 1e9
         kernels["conv"]["frac_hbm"] = kernels["conv"]["gbs"] / PEAK_HBM_GBS
         kernels["conv"]["tflops"] = per(2 * (2 * M * P * 2 * wl.D * L1v), conv_ms) / 1e12
-        kernels["conv"]["frac_mfma_fp32"] = kernels["conv"]["tflops"] / PEAK_MFMA_FP32_TFLOPS
         del kernels["hash_hist"]
         kernels["conv_hash_hist"] = {"ms_per_step": fused_ms, "tflops": per(fused_flops, fused_ms) / 1e12,
                                      "frac_mfma_fp32": per(fused_flops, fused_ms) / 1e12 / PEAK_MFMA_FP32_TFLOPS,
@@ -292,7 +295,7 @@ def measure(name, args, K, W, detail):
         "config": {"workload": wl.name, "images": M, "classes": wl.n_classes, "h": wl.h, "w": wl.w, "k": wl.k,
                    "L1": wl.L1, "L2": wl.L2, "block": wl.block, "stride": wl.stride, "bins": 1 << wl.L2,
                    "feature_len": wl.feature_len, "features": args.features,
-                   "fused_last_stage": bool(args.fused), "conv_arithmetic": args.conv,
+                   "fused_last_stage": bool(args.fused), "conv_arithmetic": "bf16x3 (three-piece, fp32-grade)" if conv_is_split else "fp32",
                    "gram_arithmetic": args.gram, "second_stage_learning": "streamed from the inputs",
                    "input_generation_s": round(gen_s, 1)},
         "roofline": {"bound": "mfma", "kernel": "patch_gram_kernel (all-tiles variant: the Gram over the input maps)",
@@ -335,9 +338,10 @@ def main():
     ap.add_argument("--fused", action="store_true",
                     help="time the path with the second stage convolution fused into the output layer (the "
                          "stage-2 maps are never written); the default materialises them")
-    ap.add_argument("--conv", default="fp32", choices=["fp32", "bf16x3"],
-                    help="arithmetic of the stage convolution: fp32 matrix instructions (the headline path) or "
-                         "three-piece bf16 operands on the bf16 matrix pipeline (same accuracy)")
+    ap.add_argument("--conv", default="auto", choices=["auto", "fp32", "bf16x3"],
+                    help="arithmetic of the stage convolution: the library default (three-piece bf16 operands on the "
+                         "bf16 matrix pipeline from k = 5 on, fp32 matrix instructions at k = 3; same accuracy), or "
+                         "one of the two for every k")
     ap.add_argument("--gram", default="fp32", choices=["fp32", "bf16x3", "lag"],
                     help="arithmetic of the patch-Gram accumulation: fp32 matrix instructions (the headline path), "
                          "three-piece bf16 operands on the bf16 matrix pipeline (same accuracy), or the "

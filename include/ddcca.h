@@ -172,26 +172,31 @@ int ddcca_extract_iq_features(ddcca_ctx *ctx, const float *v1, const float *v2, 
 /* ---- fused last stage ------------------------------------------------------------------
  * Eq. 6 with the L2 filters W followed by the output layer (Eq. 7-12) in one kernel: the L2
  * maps of every input map are hashed and counted as they are computed and never written.
- * The result is bit-identical to ddcca_apply_stage followed by ddcca_hash_iq (the
- * contraction runs in the same order).  in: [n][h][w]; W: [L2][k][k]; out as ddcca_hash_iq. */
+ * The result is bit-identical to ddcca_apply_stage with DDCCA_CONV_FP32 followed by
+ * ddcca_hash_iq (the contraction runs in the same order).  in: [n][h][w]; W: [L2][k][k]; out as ddcca_hash_iq. */
 int ddcca_apply_stage_hash(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W,
                            int k, int L2, int block_h, int block_w, int stride_y, int stride_x,
                            int feat_type, void *out);
-/* ddcca_extract_iq_features with the second stage and the output layer fused: same output,
- * bit for bit; only the stage-1 maps of a batch are held in context scratch. */
+/* ddcca_extract_iq_features with the second stage and the output layer fused: the same
+ * output, bit for bit when the convolution arithmetic is DDCCA_CONV_FP32 (otherwise up to
+ * the sign of map values that round to one side of zero or the other); only the stage-1
+ * maps of a batch are held in context scratch. */
 int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h,
                                  int w, const ddcca_model *model, int feat_type, void *feat);
 
 /* ---- options ---------------------------------------------------------------------------
  * DDCCA_OPT_CONV_ARITH selects the arithmetic of the stage convolution (Eq. 6) in
- * ddcca_apply_stage and in both stages of ddcca_extract_features / ddcca_extract_iq_features
- * (the fused last stage always uses the fp32 instructions: it is bound by its vector
- * work, not by the matrix unit):
- *   DDCCA_CONV_FP32   (default) fp32 products and sums on the fp32 matrix instructions;
+ * ddcca_apply_stage, ddcca_learn_next_stage_filters and both stages of
+ * ddcca_extract_features / ddcca_extract_iq_features (the fused last stage always uses the
+ * fp32 instructions: it is bound by its vector work, not by the matrix unit):
+ *   DDCCA_CONV_FP32   fp32 products and sums on the fp32 matrix instructions;
  *   DDCCA_CONV_BF16X3 every fp32 operand split exactly into three bf16 pieces and the six
  *                     significant piece products summed in fp32 on the bf16 matrix pipeline:
  *                     the accuracy of an fp32 dot product (the dropped products are below
- *                     2^-24 relative), another rounding order, several times the rate.
+ *                     2^-24 relative), another rounding order, several times the matrix rate;
+ *   DDCCA_CONV_AUTO   (default) the faster of the two for the patch size: DDCCA_CONV_BF16X3
+ *                     from k = 5 on (there the fp32 matrix instructions, not the memory,
+ *                     bound the fp32 kernel), DDCCA_CONV_FP32 at k = 3.
  * DDCCA_OPT_GRAM_ARITH selects the arithmetic of the patch-Gram accumulation (Section II-A
  * matrices) in the same way: DDCCA_GRAM_FP32 (default) or DDCCA_GRAM_BF16X3.  Accumulation
  * across tiles stays fp64 in either.
@@ -214,6 +219,7 @@ int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v
 #define DDCCA_OPT_CONV_ARITH 1
 #define DDCCA_CONV_FP32      0
 #define DDCCA_CONV_BF16X3    1
+#define DDCCA_CONV_AUTO      2
 #define DDCCA_OPT_GRAM_ARITH 2
 #define DDCCA_GRAM_FP32      0
 #define DDCCA_GRAM_BF16X3    1

@@ -387,8 +387,8 @@ int ddcca_learn_stage_filters(ddcca_ctx *ctx, const float *v1, const float *v2, 
 
 static int run_conv(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L, float *out)
 {
-    return ctx->conv_arith == DDCCA_CONV_BF16X3 ? launch_conv_split(ctx, in, n, h, w, W, k, L, out)
-                                                : launch_conv(ctx, in, n, h, w, W, k, L, out);
+    const bool split = ctx->conv_arith == DDCCA_CONV_BF16X3 || (ctx->conv_arith == DDCCA_CONV_AUTO && k >= 5);
+    return split ? launch_conv_split(ctx, in, n, h, w, W, k, L, out) : launch_conv(ctx, in, n, h, w, W, k, L, out);
 }
 
 int ddcca_learn_next_stage_filters(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls, int64_t n_img,
@@ -453,7 +453,7 @@ int ddcca_set_option(ddcca_ctx *ctx, int option, int value)
     if (!ctx) return DDCCA_EINVAL;
     switch (option) {
         case DDCCA_OPT_CONV_ARITH:
-            if (value != DDCCA_CONV_FP32 && value != DDCCA_CONV_BF16X3)
+            if (value != DDCCA_CONV_FP32 && value != DDCCA_CONV_BF16X3 && value != DDCCA_CONV_AUTO)
                 return fail(ctx, DDCCA_EINVAL, "unknown convolution arithmetic");
             ctx->conv_arith = value;
             return DDCCA_OK;

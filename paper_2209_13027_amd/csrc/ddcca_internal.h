@@ -60,7 +60,7 @@ struct ddcca_ctx {
     int64_t iq_lut_total = 0;               // block area + bins the table was built for (0 = none)
     int iq_lut_n = 0;
 
-    int conv_arith = DDCCA_CONV_FP32;       // DDCCA_OPT_CONV_ARITH
+    int conv_arith = DDCCA_CONV_AUTO;       // DDCCA_OPT_CONV_ARITH
     int gram_arith = DDCCA_GRAM_FP32;       // DDCCA_OPT_GRAM_ARITH
 
     // ---- profiling

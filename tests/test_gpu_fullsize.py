@@ -36,13 +36,16 @@ class FullRun:
 
     def __init__(self, name, split=False):
         from paper_2209_13027_amd import pipeline
-        from paper_2209_13027_amd.binding import (Context, OPT_CONV_ARITH, CONV_BF16X3, OPT_GRAM_ARITH, GRAM_BF16X3,
-                                                  GRAM_LAG_FP32)
+        from paper_2209_13027_amd.binding import (Context, OPT_CONV_ARITH, CONV_BF16X3, CONV_FP32, OPT_GRAM_ARITH,
+                                                  GRAM_BF16X3, GRAM_LAG_FP32)
         self.wl = wl = WORKLOADS[name]
         lag = split == "lag"
         self.split = split = split is True
         self.v1, self.v2, self.cls = make_views(wl)
         self.ctx = ctx = Context(0)
+        # the plain run and the lag run convolve with the fp32 matrix instructions (the fused last stage, which
+        # always does, is then bit-identical); the split run with three-piece bf16 operands
+        ctx.set_option(OPT_CONV_ARITH, CONV_FP32)
         if split:
             # three-piece bf16 operands in the Gram and in the convolution: the same checks, the same bars
             ctx.set_option(OPT_GRAM_ARITH, GRAM_BF16X3)

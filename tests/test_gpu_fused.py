@@ -21,6 +21,10 @@ def ctx():
         pytest.skip("no GPU")
     from paper_2209_13027_amd.binding import Context
     c = Context(0)
+    # the fused kernel contracts with the fp32 matrix instructions: its bit-exact reference is the unfused path in
+    # the same arithmetic
+    from paper_2209_13027_amd.binding import OPT_CONV_ARITH, CONV_FP32
+    c.set_option(OPT_CONV_ARITH, CONV_FP32)
     yield c
     c.close()
 

@@ -82,11 +82,18 @@ def test_hash_histogram_empty(ctx):
     (3, 32, 32, 5, 4), (2, 112, 92, 7, 8), (2, 128, 128, 5, 8), (1, 256, 256, 9, 8),
     (3, 19, 70, 3, 5), (2, 5, 7, 9, 3), (1, 1, 1, 3, 2), (2, 33, 130, 7, 11),
 ])
-def test_apply_stage(ctx, oracle, n, h, w, k, L):
+@pytest.mark.parametrize("arith", ["auto", "fp32"])
+def test_apply_stage(ctx, oracle, n, h, w, k, L, arith):
+    # auto: the default (three-piece bf16 operands from k = 5 on); fp32: the fp32 matrix instructions for every k
+    from paper_2209_13027_amd.binding import OPT_CONV_ARITH, CONV_AUTO, CONV_FP32
+    ctx.set_option(OPT_CONV_ARITH, CONV_FP32 if arith == "fp32" else CONV_AUTO)
     rng = np.random.default_rng(200 + k + h)
     V, _ = rand_views(rng, n, h, w)
     F = rng.standard_normal((L, k, k)).astype(np.float32)
-    got = ctx.apply_stage(dev(V), dev(F)).cpu().numpy()
+    try:
+        got = ctx.apply_stage(dev(V), dev(F)).cpu().numpy()
+    finally:
+        ctx.set_option(OPT_CONV_ARITH, CONV_AUTO)
     want = oracle.conv(V, F)
     scale = np.abs(F).sum(axis=(1, 2)).max() * np.abs(V).max()
     assert np.abs(got - want).max() <= 2e-6 * scale
