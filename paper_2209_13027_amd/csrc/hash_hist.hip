@@ -2,13 +2,23 @@
 // per-block code histogram (Section II-C).  Integer work only; HBM-bound: every map pixel is
 // read (ideally once) and every uint16 count is written once.
 //
-// One workgroup owns RB consecutive block rows of one map and a chunk of block columns.  Its
-// LDS holds their histograms as packed 16-bit counters (two bins per 32-bit word, which is
+// LDS holds block histograms as packed 16-bit counters (two bins per 32-bit word, which is
 // also the memory layout of the output, so the counts leave LDS as a plain vector copy).
-// Every pixel of the rows the block rows cover is hashed once per workgroup (L2 coalesced
-// plane reads, strict "> 0") and added with an LDS atomic to each block that contains it.
-// A count never exceeds the block area (<= 65535, checked on the host), so the two halves
-// of a word cannot overflow into each other.
+// A pixel is hashed (L2 coalesced plane reads, strict "> 0") and added with an LDS atomic to
+// each block that contains it.  A count never exceeds the block area (<= 65535, checked on
+// the host), so the two halves of a word cannot overflow into each other.
+//
+// Two kernels.  hash_hist_kernel (any geometry): one workgroup owns RB consecutive block rows
+// of one map and a chunk of block columns; with overlapping blocks the pixel rows that two
+// groups of block rows share are read by both.  hash_hist_sweep_kernel (wide maps whose rows
+// are readable as aligned float4, a ring of block rows fits in LDS): one workgroup sweeps a
+// whole map top to bottom in phases of a few block strides; only the block rows that overlap
+// the rows swept so far and are not yet complete are live, in a ring of LDS slots, and a
+// block row is written out and its slot cleared as soon as the sweep has passed its last
+// pixel row, so every pixel is read exactly once.  Measured: the LDS atomics bound neither
+// kernel (with them removed the time stays the same); on maps of 256 columns the single read
+// wins (4.4 -> 4.95 TB/s of algorithmic bytes), on maps of up to 128 columns the first kernel's
+// many small independent workgroups do (5.5 against 5.0 TB/s), so the width selects.
 //
 // The same kernel also writes the information-quality form of the output (Eq. 10):
 // o = -log p(t), p(t) = (count + 1) / (block area + bins), as fp32 or fp16.  The values for
@@ -21,6 +31,7 @@ namespace ddcca {
 
 constexpr int HIST_THREADS = 256;
 constexpr int HIST_LDS_BYTES = 32 * 1024;   // histogram bytes per workgroup (occupancy 4-5 per CU)
+constexpr int SWEEP_LDS_BYTES = 40 * 1024;  // the same for the ring of the sweep kernel
 
 struct HistParams {
     const float *maps;
@@ -29,6 +40,8 @@ struct HistParams {
     int lut_n;
     double log_total;
     int h, w, bh, bw, sy, sx, nby, nbx;
+    int ring;           // sweep kernel: block rows held in LDS
+    int phase_rows;     // sweep kernel: pixel rows per phase (a multiple of the block stride)
     int rb;             // block rows per workgroup
     int cols;           // block columns per workgroup
     int row_groups;     // ceil(nby / rb)
@@ -50,6 +63,63 @@ __device__ __forceinline__ void hist_add(unsigned int *lds_hist, const HistParam
     for (int i = ilo; i <= ihi; ++i)
         for (int j = jlo; j <= jhi; ++j)
             atomicAdd(&lds_hist[((i - i0) * ncol + (j - j0)) * WORDS + word], inc);
+}
+
+// Whether block rows of this output can leave as aligned 16-byte vectors.
+template <int OUT>
+__device__ __forceinline__ bool out_vec_ok(const void *out_map, int64_t map_elems, int64_t group_stride)
+{
+    constexpr int ESZ = (int)sizeof(typename HistOut<OUT>::type);
+    return ((((uintptr_t)out_map) | (uintptr_t)(map_elems * ESZ) | (uintptr_t)(group_stride * ESZ)) & 15) == 0;
+}
+
+// Write nrow block rows of ncol packed histograms each (src: LDS, rows ncol*WORDS words apart) to dst (rows
+// dst_row_stride elements apart) in the output type; CLEAR: zero the LDS words afterwards.
+template <int L2, int OUT, bool CLEAR>
+__device__ __forceinline__ void copy_out_rows(unsigned int *src_rows, int nrow, int ncol,
+                                              typename HistOut<OUT>::type *dst, int64_t dst_row_stride, bool vec_ok,
+                                              const float *lds_lut, const HistParams &p)
+{
+    typedef typename HistOut<OUT>::type OutT;
+    constexpr int BINS = 1 << L2;
+    constexpr int WORDS = BINS > 1 ? BINS / 2 : 1;
+    constexpr int ESZ = (int)sizeof(OutT);
+    constexpr int VW = 8 / ESZ;                                      // packed words per 16-byte store: 4, 2 or 1
+    if (BINS >= 2 * VW && vec_ok) {
+        const int row_vec = ncol * WORDS / VW;                       // 16-byte vectors per block row
+        for (int e = threadIdx.x; e < nrow * row_vec; e += HIST_THREADS) {
+            const int ir = e / row_vec, v = e - ir * row_vec;
+            unsigned *src = src_rows + (ir * ncol * WORDS) + VW * v;
+            OutT *d = dst + ir * dst_row_stride + 2 * VW * v;
+            if (OUT == DDCCA_FEAT_COUNT_U16) {
+                *reinterpret_cast<uint4 *>(d) = *reinterpret_cast<const uint4 *>(src);
+            } else {
+                alignas(16) OutT vals[2 * VW];
+#pragma unroll
+                for (int q = 0; q < VW; ++q) {
+                    const unsigned wv = src[q];
+                    vals[2 * q] = hist_convert<OUT>(wv & 0xffffu, lds_lut, p.lut_n, p.log_total);
+                    vals[2 * q + 1] = hist_convert<OUT>(wv >> 16, lds_lut, p.lut_n, p.log_total);
+                }
+                *reinterpret_cast<uint4 *>(d) = *reinterpret_cast<const uint4 *>(vals);
+            }
+            if (CLEAR) {
+#pragma unroll
+                for (int q = 0; q < VW; ++q) src[q] = 0u;
+            }
+        }
+    } else {
+        for (int e = threadIdx.x; e < nrow * ncol * BINS; e += HIST_THREADS) {
+            const int ir = e / (ncol * BINS), rest = e - ir * ncol * BINS;
+            const unsigned wv = src_rows[ir * ncol * WORDS + (rest >> 1)];
+            const unsigned c = (BINS > 1 ? (wv >> (16 * (rest & 1))) : wv) & 0xffffu;
+            dst[ir * dst_row_stride + rest] = hist_convert<OUT>(c, lds_lut, p.lut_n, p.log_total);
+        }
+        if (CLEAR) {
+            __syncthreads();                                         // two bins share a word: clear after all reads
+            for (int e = threadIdx.x; e < nrow * ncol * WORDS; e += HIST_THREADS) src_rows[e] = 0u;
+        }
+    }
 }
 
 __global__ void iq_lut_kernel(double total, int n, float *lut)
@@ -138,35 +208,79 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p, i
     // copy out: block row i of the chunk is ncol*BINS contiguous elements in the output
     const int64_t A = (int64_t)p.nby * p.nbx;
     OutT *out_map = reinterpret_cast<OutT *>(p.hist) + (n / p.group) * p.group_stride + (n % p.group) * A * BINS;
-    constexpr int ESZ = (int)sizeof(OutT);
-    constexpr int VW = 8 / ESZ;                                      // packed words per 16-byte store: 4, 2 or 1
-    if (BINS >= 2 * VW && ((((uintptr_t)out_map) | (uintptr_t)(A * BINS * ESZ) | (uintptr_t)(p.group_stride * ESZ)) & 15) == 0) {
-        const int row_vec = ncol * WORDS / VW;                       // 16-byte vectors per block row of the chunk
-        for (int e = threadIdx.x; e < nrow * row_vec; e += HIST_THREADS) {
-            const int ir = e / row_vec, v = e - ir * row_vec;
-            const unsigned *src = lds_hist + (ir * ncol * WORDS) + VW * v;
-            OutT *dst = out_map + ((int64_t)(i0 + ir) * p.nbx + j0) * BINS + 2 * VW * v;
-            if (OUT == DDCCA_FEAT_COUNT_U16) {
-                *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
-            } else {
-                alignas(16) OutT vals[2 * VW];
+    copy_out_rows<L2, OUT, false>(lds_hist, nrow, ncol, out_map + ((int64_t)i0 * p.nbx + j0) * BINS,
+                                  (int64_t)p.nbx * BINS, out_vec_ok<OUT>(out_map, A * BINS, p.group_stride), lds_lut, p);
+}
+
+template <int L2, int OUT>
+__global__ __launch_bounds__(HIST_THREADS) void hash_hist_sweep_kernel(HistParams p, int lds_hist_words)
+{
+    extern __shared__ unsigned int lds_hist[];
+    typedef typename HistOut<OUT>::type OutT;
+    constexpr int BINS = 1 << L2;
+    constexpr int WORDS = BINS > 1 ? BINS / 2 : 1;
+    float *lds_lut = reinterpret_cast<float *>(lds_hist + lds_hist_words);
+    if (OUT != DDCCA_FEAT_COUNT_U16)
+        for (int e = threadIdx.x; e < p.lut_n; e += HIST_THREADS) lds_lut[e] = p.lut[e];
+    const int64_t n = blockIdx.x;
+    const int row_words = p.nbx * WORDS;                 // one block row of histograms
+    for (int e = threadIdx.x; e < p.ring * row_words; e += HIST_THREADS) lds_hist[e] = 0u;
+    __syncthreads();
+
+    const int64_t P = (int64_t)p.h * p.w;
+    const float *base = p.maps + n * L2 * P;
+    const int64_t A = (int64_t)p.nby * p.nbx;
+    OutT *out_map = reinterpret_cast<OutT *>(p.hist) + (n / p.group) * p.group_stride + (n % p.group) * A * BINS;
+    const bool vec_out = out_vec_ok<OUT>(out_map, A * BINS, p.group_stride);
+    const int y_all = (p.nby - 1) * p.sy + p.bh;         // rows below belong to no block
+    const int x_hi = (p.nbx - 1) * p.sx + p.bw;          // columns to the right belong to no block
+    const int q_hi = (x_hi + 3) >> 2;
+    const int wide = x_hi > 128 ? 1 : 0;
+    const int TCOLS = wide ? 64 : 32, TROWS = HIST_THREADS / TCOLS;
+    const int tcol = threadIdx.x & (TCOLS - 1), trow = threadIdx.x / TCOLS;
+    int next_flush = 0;                                  // first block row not yet written out
+    for (int y0 = 0; y0 < y_all; y0 += p.phase_rows) {
+        const int y1 = min(y0 + p.phase_rows, y_all);
+        for (int y = y0 + trow; y < y1; y += TROWS) {
+            int ilo, ihi;
+            block_range(y, p.bh, p.sy, p.magic_sy, 0, p.nby, ilo, ihi);
+            const int slot_lo = ilo % p.ring;
+            const float *row = base + (int64_t)y * p.w;
+            for (int xq = tcol; xq < q_hi; xq += TCOLS) {
+                const float *src = row + 4 * xq;
+                unsigned code[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-                for (int q = 0; q < VW; ++q) {
-                    const unsigned wv = src[q];
-                    vals[2 * q] = hist_convert<OUT>(wv & 0xffffu, lds_lut, p.lut_n, p.log_total);
-                    vals[2 * q + 1] = hist_convert<OUT>(wv >> 16, lds_lut, p.lut_n, p.log_total);
+                for (int l = 0; l < L2; ++l) {
+                    const float4 v = *reinterpret_cast<const float4 *>(src + l * P);
+                    code[0] |= (v.x > 0.0f ? 1u : 0u) << l;
+                    code[1] |= (v.y > 0.0f ? 1u : 0u) << l;
+                    code[2] |= (v.z > 0.0f ? 1u : 0u) << l;
+                    code[3] |= (v.w > 0.0f ? 1u : 0u) << l;
                 }
-                *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(vals);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int x = 4 * xq + k;
+                    if (x >= x_hi) break;
+                    int jlo, jhi;
+                    block_range(x, p.bw, p.sx, p.magic_sx, 0, p.nbx, jlo, jhi);
+                    const unsigned inc = 1u << (16 * (code[k] & 1));
+                    const unsigned word = code[k] >> 1;
+                    int slot = slot_lo;
+                    for (int i = ilo; i <= ihi; ++i) {
+                        for (int j = jlo; j <= jhi; ++j) atomicAdd(&lds_hist[slot * row_words + j * WORDS + word], inc);
+                        slot = slot + 1 == p.ring ? 0 : slot + 1;
+                    }
+                }
             }
         }
-    } else {
-        for (int e = threadIdx.x; e < nrow * ncol * BINS; e += HIST_THREADS) {
-            const int ir = e / (ncol * BINS), rest = e - ir * ncol * BINS;
-            const unsigned wv = lds_hist[ir * ncol * WORDS + (rest >> 1)];
-            OutT *dst = out_map + ((int64_t)(i0 + ir) * p.nbx + j0) * BINS;
-            const unsigned c = (BINS > 1 ? (wv >> (16 * (rest & 1))) : wv) & 0xffffu;
-            dst[rest] = hist_convert<OUT>(c, lds_lut, p.lut_n, p.log_total);
-        }
+        __syncthreads();
+        // block rows whose last pixel row lies inside the rows swept so far are complete: write them, clear their slots
+        const int i_end = y1 < p.bh ? 0 : min(p.nby, fast_div(y1 - p.bh, p.sy, p.magic_sy) + 1);
+        for (int i = next_flush; i < i_end; ++i)
+            copy_out_rows<L2, OUT, true>(lds_hist + (i % p.ring) * row_words, 1, p.nbx, out_map + (int64_t)i * p.nbx * BINS,
+                                         (int64_t)p.nbx * BINS, vec_out, lds_lut, p);
+        next_flush = max(next_flush, i_end);
+        __syncthreads();
     }
 }
 
@@ -176,6 +290,34 @@ static void hist_launch(ddcca_ctx *ctx, HistParams p, int64_t n)
     constexpr int BINS = 1 << L2;
     constexpr int HIST_BYTES = (BINS > 1 ? BINS / 2 : 1) * 4;         // packed histogram of one block
     constexpr int ESZ = (int)sizeof(typename HistOut<OUT>::type);
+    // sweep kernel: aligned float4 rows and a ring of block rows within the LDS budget.  A phase covers m block
+    // strides (enough rows for about two 4-pixel groups per thread); during it the block rows from the oldest
+    // incomplete one to the newest one touched are live: ceil(bh / sy) + m - 1 of them.
+    if (p.vec4 && (p.nbx - 1) * p.sx + p.bw > 128) {
+        const int row_bytes = p.nbx * HIST_BYTES;
+        const int live = (p.bh + p.sy - 1) / p.sy;
+        const int quads_per_stride = (((p.nbx - 1) * p.sx + p.bw + 3) / 4) * p.sy;
+        int m = std::max(1, (2 * HIST_THREADS + quads_per_stride - 1) / quads_per_stride);
+        m = std::min(m, std::max(1, SWEEP_LDS_BYTES / row_bytes - live + 1));
+        m = std::min(m, p.nby);
+        const int ring = live + m - 1;
+        if ((int64_t)ring * row_bytes <= SWEEP_LDS_BYTES) {
+            p.ring = ring;
+            p.phase_rows = m * p.sy;
+            const int hist_words = ring * (row_bytes / 4);
+            const size_t lds = (size_t)hist_words * 4 + (OUT != DDCCA_FEAT_COUNT_U16 ? (size_t)p.lut_n * 4 : 0);
+            const int64_t maps_per_launch = std::max<int64_t>(p.group, ((int64_t)1 << 30) / p.group * p.group);
+            for (int64_t n0 = 0; n0 < n; n0 += maps_per_launch) {
+                const int64_t nb = std::min(maps_per_launch, n - n0);
+                HistParams q = p;
+                q.maps = p.maps + n0 * L2 * (int64_t)p.h * p.w;
+                q.hist = reinterpret_cast<char *>(p.hist) + (n0 / p.group) * p.group_stride * ESZ;
+                hipLaunchKernelGGL((hash_hist_sweep_kernel<L2, OUT>), dim3((unsigned)nb), dim3(HIST_THREADS), lds,
+                                   ctx->stream, q, hist_words);
+            }
+            return;
+        }
+    }
     const int max_blocks = std::max(1, HIST_LDS_BYTES / HIST_BYTES);
     p.cols = std::min(p.nbx, max_blocks);
     p.col_chunks = (p.nbx + p.cols - 1) / p.cols;

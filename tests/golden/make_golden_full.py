@@ -98,7 +98,7 @@ def run(name: str, ridge: float = 1e-4) -> None:
             keep1.append(y1)
             keep2.append(y2)
         if time.time() - t_last > 60:
-            note(f"stage 2: {s + b} of {M} images")
+            print(f"[{name} {time.time() - t0:7.0f}s] stage 2: {s + b} of {M} images", flush=True)
             t_last = time.time()
     cell_cls = np.repeat(np.arange(wl.n_classes, dtype=np.int32), L1)
     cell_grp = np.tile(np.arange(L1, dtype=np.int32), wl.n_classes)
