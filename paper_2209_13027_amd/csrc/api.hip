@@ -106,7 +106,7 @@ static void free_buffer(Buffer &b)
 static int accumulate_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps)
 {
     if (ctx->lag_active)
-        return launch_lag_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, false, (double *)ctx->lag_slots.ptr,
+        return launch_lag_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, (double *)ctx->lag_slots.ptr,
                                max_lag_slots(ctx), &ctx->lag_valid, (double *)ctx->lag_col_slots.ptr,
                                max_lag_col_slots(ctx), &ctx->lag_col_valid);
     return launch_patch_gram(ctx, v1, v2, n_maps, ctx->h, ctx->w, ctx->k, false, (double *)ctx->slots.ptr,
@@ -114,7 +114,7 @@ static int accumulate_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int
 }
 
 // lag statistics in the two slot sets -> stacked Gram
-static int lag_finish(ddcca_ctx *ctx, int valid, int col_valid, double *stacked_out, bool cross)
+static int lag_finish(ddcca_ctx *ctx, int valid, int col_valid, double *stacked_out)
 {
     const int k = ctx->k;
     int rc;
@@ -125,7 +125,7 @@ static int lag_finish(ddcca_ctx *ctx, int valid, int col_valid, double *stacked_
                                   (int)lag_col_slot_doubles(k), (double *)ctx->lag_C.ptr)))
         return rc;
     return launch_lag_to_stacked(ctx, (const double *)ctx->lag_R.ptr, (const double *)ctx->lag_C.ptr, stacked_out, k,
-                                 ctx->h, ctx->w, cross);
+                                 ctx->h, ctx->w);
 }
 
 // Gram of the cross-view block of n_img image pairs into stacked_out (fresh slots).  Always the dense kernel, also
@@ -159,7 +159,7 @@ static int corr_finish(ddcca_ctx *ctx)
     if ((rc = ensure(ctx, ctx->mats, 5 * (size_t)D * D * sizeof(double)))) return rc;
     double *st = (double *)ctx->stacked.ptr;
     if (ctx->lag_active) {
-        if ((rc = lag_finish(ctx, ctx->lag_valid, ctx->lag_col_valid, st, false))) return rc;
+        if ((rc = lag_finish(ctx, ctx->lag_valid, ctx->lag_col_valid, st))) return rc;
     } else if ((rc = launch_gram_reduce(ctx, (const double *)ctx->slots.ptr, ctx->slots_valid, k, st))) {
         return rc;
     }

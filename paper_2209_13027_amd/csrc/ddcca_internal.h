@@ -117,14 +117,13 @@ int max_lag_slots(ddcca_ctx *ctx);
 int max_lag_col_slots(ddcca_ctx *ctx);
 size_t lag_slot_doubles(int k);       // lag correlations: all rows + the r top and r bottom rows, per pair type
 size_t lag_col_slot_doubles(int k);   // border columns and corners
-// adds the lag statistics of n_maps map pairs to the two slot sets (cross_only: the (1,2) pair alone)
+// adds the lag statistics of n_maps map pairs to the two slot sets
 int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w, int k,
-                    bool cross_only, double *slots, int max_slots, int *slots_valid, double *col_slots,
-                    int max_col_slots, int *col_slots_valid);
+                    double *slots, int max_slots, int *slots_valid, double *col_slots, int max_col_slots,
+                    int *col_slots_valid);
 // stacked <- Gram of y = x - x_centre over the patches of the image, from the reduced statistics R (rows) and C
 // (columns), in the layout of the dense kernel's reduced slots
-int launch_lag_to_stacked(ddcca_ctx *ctx, const double *R, const double *C, double *stacked, int k, int h, int w,
-                          bool cross_only);
+int launch_lag_to_stacked(ddcca_ctx *ctx, const double *R, const double *C, double *stacked, int k, int h, int w);
 int launch_export(ddcca_ctx *ctx, const double *stacked_main, const double *stacked_cls,
                   const double *stacked_tot, int k, double n_patches, double *mats);
 int launch_label_check(ddcca_ctx *ctx, const int32_t *cls, int64_t n_img, int n_cls, int *flag);

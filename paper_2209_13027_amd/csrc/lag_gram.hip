@@ -74,14 +74,12 @@ struct LagParams {
 // One workgroup walks a contiguous range of (map, tile) items.  A tile is TH image rows x tw columns with a halo
 // of K = k-1 on every side (zeros outside the image), both views.  Wavefront w owns the row groups w, w+4, ... of
 // a tile; tiles start at multiples of 4 RG rows, so row group gi of the IMAGE always belongs to wavefront gi % 4.
-// CROSS: only the pair types that mix the views.
-template <int KS, bool CROSS>
+template <int KS>
 __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
 {
     using G = LagGeom<KS>;
     constexpr int K = G::K, RR = G::RR, NTY = G::NTY, RG = G::RG, TH = G::TH, NTG = G::NTG, NBG = G::NBG;
-    constexpr bool SAME = !CROSS;                  // types 0, 1 wanted
-    constexpr int NMF = SAME ? 4 : 2;              // matrix instructions per step
+    constexpr int NMF = 4;                         // matrix instructions per step
     extern __shared__ float lds[];
     typedef __attribute__((address_space(3))) float lds_float;
     typedef __attribute__((address_space(3))) char lds_char;
@@ -188,7 +186,6 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
             auto border = [&](double (&acc)[NTY][4]) {
 #pragma unroll
                 for (int t2 = 0; t2 < NTY; ++t2) {
-                    if (t2 < 2 && !SAME) continue;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         float x = c[t2][v];
@@ -201,7 +198,6 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
             if (is_bot) border(accb);
 #pragma unroll
             for (int t2 = 0; t2 < NTY; ++t2) {
-                if (t2 < 2 && !SAME) continue;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) accd[t2][v] += (double)c[t2][v];
                 c[t2] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -209,10 +205,8 @@ __global__ __launch_bounds__(LAG_THREADS) void lag_gram_kernel(LagParams p)
         };
         // one step: a1 x b1 -> (1,1), a2 x b2 -> (2,2), a1 x b2 -> (1,2), a2 x b1 -> (2,1)
         auto step = [&](float a1, float b2, float a2, float b1) {
-            if (SAME) {
-                c[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, c[0], 0, 0, 0);
-                c[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b2, c[1], 0, 0, 0);
-            }
+            c[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, c[0], 0, 0, 0);
+            c[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b2, c[1], 0, 0, 0);
             c[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b2, c[2], 0, 0, 0);
             c[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2, b1, c[3], 0, 0, 0);
         };
@@ -344,7 +338,6 @@ struct LagColParams {
     const float *v1, *v2;
     int h, w;
     int64_t n_maps;
-    int cross;                             // only the pair types that mix the views: (1,2) [and (2,1) at k = 9]
     double *slots;                         // [gridDim.x][NTY][2][r][256 + 2r*NL*NL]
     int slots_valid;
 };
@@ -366,8 +359,7 @@ __global__ __launch_bounds__(lagc_threads<KS>(), lagc_waves<KS>()) void lag_cols
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: what depends on it stays on the scalar unit
     const int m = min(lane & 15, NL - 1), kk = lane >> 4;
     const int cb0 = side == 0 ? -K : p.w - RR - K;                 // image column of staged column 0
-    const int ntype = p.cross ? NTY - 2 : NTY;                     // pair types wanted: all, or those from (1,2) on
-    const int t0 = p.cross ? 2 : 0;
+    constexpr int ntype = NTY, t0 = 0;                             // every pair type
     const int nchain = RR * ntype;
     const int64_t per = p.n_maps / gridDim.x, extra = p.n_maps % gridDim.x;
     const int64_t first = blockIdx.x * per + min((int64_t)blockIdx.x, extra);
@@ -579,7 +571,7 @@ __global__ __launch_bounds__(256) void lag_special_kernel(LagSpecialParams p)
 struct LagStats {
     const double *R;                       // [SETS][4][256] (+ 8 at k = 9): reduced lag_gram_kernel slots
     const double *C;                       // [4][2][r][256 + 2r*NL*NL]: reduced lag_cols_kernel slots
-    int ks, h, w, cross;
+    int ks, h, w;
 };
 
 // the pair type with the two views exchanged
@@ -663,7 +655,7 @@ __device__ double lag_entry(const LagStats &st, int type, int a, int b)
 // S_x[(d,a)][(d',b)] over the patch centres inside the image; the (2,1) pair is the (1,2) pair with the taps swapped
 __device__ __forceinline__ double lag_raw(const LagStats &st, int d, int a, int d2, int b)
 {
-    if (d == d2) return st.cross ? 0.0 : lag_entry(st, d, a, b);
+    if (d == d2) return lag_entry(st, d, a, b);
     return d == 0 ? lag_entry(st, 2, a, b) : lag_entry(st, 2, b, a);
 }
 
@@ -712,20 +704,18 @@ size_t lag_col_slot_doubles(int k)
 }
 
 template <int KS>
-static void lag_launch(ddcca_ctx *ctx, const LagParams &p, int grid, size_t lds, bool cross, const LagColParams &c,
-                       dim3 cgrid)
+static void lag_launch(ddcca_ctx *ctx, const LagParams &p, int grid, size_t lds, const LagColParams &c, dim3 cgrid)
 {
     static_assert(LagGeom<KS>::SLOT == (1 + LagGeom<KS>::NTG + LagGeom<KS>::NBG) * 1024 + (LagGeom<KS>::WIDE ? 8 : 0), "slot layout");
-    if (cross) hipLaunchKernelGGL((lag_gram_kernel<KS, true>), dim3(grid), dim3(LAG_THREADS), lds, ctx->stream, p);
-    else hipLaunchKernelGGL((lag_gram_kernel<KS, false>), dim3(grid), dim3(LAG_THREADS), lds, ctx->stream, p);
+    hipLaunchKernelGGL(lag_gram_kernel<KS>, dim3(grid), dim3(LAG_THREADS), lds, ctx->stream, p);
     hipLaunchKernelGGL(lag_cols_kernel<KS>, cgrid, dim3(lagc_threads<KS>()), 0, ctx->stream, c);
 }
 
 int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w, int k,
-                    bool cross_only, double *slots, int max_slots, int *slots_valid, double *col_slots,
-                    int max_col_slots, int *col_slots_valid)
+                    double *slots, int max_slots, int *slots_valid, double *col_slots, int max_col_slots,
+                    int *col_slots_valid)
 {
-    ProfScope prof(ctx, cross_only ? DDCCA_K_GRAM_CROSS : DDCCA_K_GRAM);
+    ProfScope prof(ctx, DDCCA_K_GRAM);
     if (!lag_supported(k)) return fail(ctx, DDCCA_EINVAL, "the lag-structured Gram needs k in {3, 5, 7, 9}");
     if (n_maps < 1 || h < 1 || w < 1) return fail(ctx, DDCCA_EINVAL, "lag-structured Gram: empty input");
     LagParams p;
@@ -749,24 +739,19 @@ int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_
     if (p.tw > LAG_TW_MAX || lds > 64 * 1024) return fail(ctx, DDCCA_EINVAL, "lag-structured Gram: tile too large");
     p.slots = slots;
     p.slots_valid = *slots_valid;
-    // (the sum images of the class-conditioned matrices are few: one workgroup per CU keeps their slot
-    // reduction, which reads every slot written, short)
-    if (cross_only) max_slots = std::min(max_slots, ctx->n_cu);
-    if (cross_only) max_col_slots = std::min(max_col_slots, std::max(1, ctx->n_cu / 2));
     const int grid = (int)std::min<int64_t>(max_slots, std::max<int64_t>(p.n_items, 1));
     // the border columns and corners of the same maps
     LagColParams c;
     c.v1 = v1; c.v2 = v2; c.h = h; c.w = w; c.n_maps = n_maps;
-    c.cross = cross_only ? 1 : 0;
     c.slots = col_slots;
     c.slots_valid = *col_slots_valid;
     const int cgrid = (int)std::min<int64_t>(max_col_slots, std::max<int64_t>(n_maps, 1));
     const dim3 cg(cgrid, 2);
     switch (k) {
-        case 3: lag_launch<3>(ctx, p, grid, lds, cross_only, c, cg); break;
-        case 5: lag_launch<5>(ctx, p, grid, lds, cross_only, c, cg); break;
-        case 7: lag_launch<7>(ctx, p, grid, lds, cross_only, c, cg); break;
-        case 9: lag_launch<9>(ctx, p, grid, lds, cross_only, c, cg); break;
+        case 3: lag_launch<3>(ctx, p, grid, lds, c, cg); break;
+        case 5: lag_launch<5>(ctx, p, grid, lds, c, cg); break;
+        case 7: lag_launch<7>(ctx, p, grid, lds, c, cg); break;
+        case 9: lag_launch<9>(ctx, p, grid, lds, c, cg); break;
         default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
     }
     if (lag_wide(k)) {
@@ -784,13 +769,12 @@ int launch_lag_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_
     return DDCCA_OK;
 }
 
-int launch_lag_to_stacked(ddcca_ctx *ctx, const double *R, const double *C, double *stacked, int k, int h, int w,
-                          bool cross_only)
+int launch_lag_to_stacked(ddcca_ctx *ctx, const double *R, const double *C, double *stacked, int k, int h, int w)
 {
     ProfScope prof(ctx, DDCCA_K_REDUCE);
     const int E = gram_tiles(k) * 256;
     LagStats st;
-    st.R = R; st.C = C; st.ks = k; st.h = h; st.w = w; st.cross = cross_only ? 1 : 0;
+    st.R = R; st.C = C; st.ks = k; st.h = h; st.w = w;
     hipLaunchKernelGGL(lag_to_stacked_kernel, dim3((E + 255) / 256), dim3(256), 0, ctx->stream, st, stacked);
     DDCCA_HIP(ctx, hipGetLastError());
     return DDCCA_OK;

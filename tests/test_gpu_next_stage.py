@@ -166,3 +166,33 @@ def test_end_to_end_with_streamed_learning(ctx, oracle, name, mpc, batch):
     assert got.shape == ref["hist"].shape
     l1 = np.abs(got.astype(np.int64) - ref["hist"]).sum() / ref["hist"].sum()
     assert l1 <= 1e-3, l1
+
+
+@pytest.mark.parametrize("m,h,w,k,L1,L2,n_cls", [
+    (3, 41, 4, 3, 1, 8, 2),     # an image as wide as one step of the matrix instruction; all D - 1 pairs of the stage
+    (4, 30, 3, 3, 2, 8, 2),     # narrower than one step; as wide as the patch
+    (4, 5, 37, 5, 2, 24, 2),    # the same lying down, k = 5, all D - 1 pairs
+])
+def test_streamed_route_on_narrow_images_with_every_pair(ctx, oracle, m, h, w, k, L1, L2, n_cls):
+    """Images narrower than (or as narrow as) one K-step of the matrix instruction and L = D - 1, the largest filter
+    count a stage has: on such an image most patches lie on the border, C_dd has small eigenvalues next to the
+    ridge, and the last pairs are the most sensitive ones of the stage.  Both second-stage routes (streamed from the
+    inputs, materialised maps) against the oracle at the bars of the path: rho to 1e-4 of the leading correlation
+    (the two routes differ from each other by a relative 1e-5 in the LAST correlation of such a case, which is its
+    conditioning and not a defect), filter cosines where the correlations are separated."""
+    v1, v2, cls = rand_problem(27000 + h + w, m, h, w, n_cls)
+    d1, d2, dc = dev(v1), dev(v2), dev(cls)
+    ref = oracle.learn_two_stage(v1, v2, cls, n_cls, k, L1, L2)
+    for streamed in (True, False):
+        model = pipeline.fit(ctx, d1, d2, dc, n_cls, k, L1, L2, streamed=streamed)
+        ctx.status()
+        for s, L in ((0, L1), (1, L2)):
+            r = ref["stage%d" % (s + 1)]
+            rho = model["rho"][s].cpu().numpy()
+            assert np.all(np.isfinite(rho))
+            assert np.abs(rho - r["rho"]).max() <= 1e-4 * r["rho"][0], (streamed, s, rho, r["rho"])
+            ok = r["gap"] > 1e-3
+            for d in range(2):
+                cos = cosines(model["filters"][2 * s + d].cpu().numpy(), r["W%d" % (d + 1)])
+                if ok.any():
+                    assert cos[ok].min() >= 0.9999, (streamed, s, d, cos, r["gap"])
