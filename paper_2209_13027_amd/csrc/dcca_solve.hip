@@ -15,7 +15,7 @@ namespace ddcca {
 constexpr int SOLVE_THREADS = 1024;
 constexpr int SOLVE_MAX_SWEEPS = 40;
 constexpr double SOLVE_TOL = 1e-15;      // rotate while |g_p . g_q| > tol * |g_p| |g_q|
-constexpr double SOLVE_QUAD = 1e-8;      // a sweep whose largest cosine was below this is the last one
+constexpr double SOLVE_QUAD = 1e-5;      // a sweep whose largest cosine was below this is the last one
 
 struct SolveParams {
     const double *C11, *C22, *Cw, *CT;
