@@ -94,7 +94,8 @@ def measure(name, args, K, W, detail):
     import torch
     from paper_2209_13027_amd import pipeline
     from paper_2209_13027_amd.binding import (Context, OPT_CONV_ARITH, CONV_BF16X3, CONV_FP32, CONV_AUTO,
-                                              OPT_GRAM_ARITH, GRAM_FP32, GRAM_BF16X3, GRAM_LAG_FP32)
+                                              OPT_GRAM_ARITH, GRAM_FP32, GRAM_BF16X3, GRAM_LAG_FP32,
+                                              OPT_NEXT_STAGE_MAPS, MAPS_RECOMPUTED, MAPS_STREAMED)
     from paper_2209_13027_amd.workloads import WORKLOADS, make_views
 
     wl = WORKLOADS[name]
@@ -188,6 +189,28 @@ def measure(name, args, K, W, detail):
         phases["extract"] = timed(lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block,
                                                            wl.stride, batch, out=feat, dtype=feat_dtype,
                                                            fused=args.fused), K2)
+        if args.gram != "lag":
+            # the same learning with the first stage's maps recomputed inside the second stage's Gram kernel
+            # (no maps in memory; the Gram pays for the convolution), for comparison
+            ctx.set_option(OPT_NEXT_STAGE_MAPS, MAPS_RECOMPUTED)
+            run = lambda: pipeline.fit(ctx, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2)
+            run()
+            ctx.profile_reset()
+            ctx.profile_select(["gram", "conv"])
+            ctx.profile_enable(True)
+            phases["learn_maps_recomputed"] = timed(run, K2)
+            ctx.profile_enable(False)
+            pr = ctx.profile_read()
+            phases["learn_maps_recomputed"]["gram_ms"] = pr["gram"]["ms"] / K2
+            phases["learn_maps_recomputed"]["conv_ms"] = pr["conv"]["ms"] / K2
+            ctx.set_option(OPT_NEXT_STAGE_MAPS, MAPS_STREAMED)
+            ctx.profile_reset()
+            ctx.profile_enable(True)
+            timed(run, K2)
+            ctx.profile_enable(False)
+            pr = ctx.profile_read()
+            phases["learn"]["gram_ms"] = pr["gram"]["ms"] / K2
+            phases["learn"]["conv_ms"] = pr["conv"]["ms"] / K2
         if not args.fused:
             # the same extraction with the second stage fused into the output layer, for comparison
             run = lambda: pipeline.extract(ctx, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride,

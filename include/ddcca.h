@@ -213,6 +213,19 @@ int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v
  *                     pairs, reads a lag with a component +8 as the exchanged pair at the
  *                     negated lag, and sums the one remaining tap pair (opposite patch
  *                     corners) directly.
+ * DDCCA_OPT_NEXT_STAGE_MAPS selects where ddcca_learn_next_stage_filters gets the maps of the
+ * previous stage from (Section II-B on Section II-A):
+ *   DDCCA_MAPS_STREAMED   (default) convolved batch by batch into a scratch buffer and read
+ *                     back by the Gram accumulation;
+ *   DDCCA_MAPS_RECOMPUTED the Gram kernel holds the INPUT tile (with the halo of both stages) in
+ *                     LDS and forms each map tile from it as it needs it (fp32 fused
+ *                     multiply-adds in tap order): the maps never exist in memory.  Same
+ *                     matrices up to the rounding order of the convolution (same bars).  Used
+ *                     when k_prev == k and the Gram arithmetic is not DDCCA_GRAM_LAG_FP32;
+ *                     otherwise the call proceeds as with DDCCA_MAPS_STREAMED.  The Gram is
+ *                     bound by the matrix unit, where the recomputation is paid in full,
+ *                     while the convolution it replaces is bound by memory: this mode trades
+ *                     time for memory traffic and scratch space.
  * Returns DDCCA_EINVAL for an unknown option or value, DDCCA_ESTATE when the Gram
  * arithmetic is changed between ddcca_corr_begin and the export / solve of that
  * accumulation. */
@@ -224,6 +237,9 @@ int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v
 #define DDCCA_GRAM_FP32      0
 #define DDCCA_GRAM_BF16X3    1
 #define DDCCA_GRAM_LAG_FP32  2
+#define DDCCA_OPT_NEXT_STAGE_MAPS 3
+#define DDCCA_MAPS_STREAMED   0
+#define DDCCA_MAPS_RECOMPUTED 1
 int ddcca_set_option(ddcca_ctx *ctx, int option, int value);
 
 /* Learn the filters of the stage that follows a given stage (Section II-B: the second stage

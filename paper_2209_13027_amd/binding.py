@@ -29,7 +29,8 @@ EXPORTS = [
     "ddcca_profile_enable", "ddcca_profile_read", "ddcca_profile_reset",
 ]
 FEAT_COUNT_U16, FEAT_IQ_F32, FEAT_IQ_F16 = 0, 1, 2
-OPT_CONV_ARITH, OPT_GRAM_ARITH = 1, 2
+OPT_CONV_ARITH, OPT_GRAM_ARITH, OPT_NEXT_STAGE_MAPS = 1, 2, 3
+MAPS_STREAMED, MAPS_RECOMPUTED = 0, 1
 CONV_FP32, CONV_BF16X3, CONV_AUTO = 0, 1, 2
 GRAM_FP32, GRAM_BF16X3, GRAM_LAG_FP32 = 0, 1, 2
 FEAT_TYPES = {torch.uint16: FEAT_COUNT_U16, torch.float32: FEAT_IQ_F32, torch.float16: FEAT_IQ_F16}

@@ -429,6 +429,14 @@ int ddcca_learn_next_stage_filters(ddcca_ctx *ctx, const float *v1, const float 
                        cimg + (size_t)(n_cell + G) * P)))
         return rc;
     ctx->class_img_ready = true;
+    if (ctx->next_stage_maps == DDCCA_MAPS_RECOMPUTED && !ctx->lag_active && k_prev == k) {
+        // the maps never exist: the Gram kernel produces each tile of them from the input tile it holds
+        if ((rc = launch_patch_gram_recomputed(ctx, v1, v2, n_img * G_in, h, w, k, Wp1, Wp2, L_prev,
+                                               (double *)ctx->slots.ptr, max_gram_slots(ctx, k), &ctx->slots_valid)))
+            return rc;
+        ctx->n_maps += n_img * G;
+        return ddcca_solve_filters(ctx, L, ridge, W1, W2, rho);
+    }
     // the maps themselves, one batch of samples at a time
     const size_t per_img = (size_t)G * P * sizeof(float);
     int64_t nb = batch_images;
@@ -462,6 +470,11 @@ int ddcca_set_option(ddcca_ctx *ctx, int option, int value)
             if (ctx->corr_active && !ctx->corr_exported)
                 return fail(ctx, DDCCA_ESTATE, "cannot change the Gram arithmetic during an accumulation");
             ctx->gram_arith = value;
+            return DDCCA_OK;
+        case DDCCA_OPT_NEXT_STAGE_MAPS:
+            if (value != DDCCA_MAPS_STREAMED && value != DDCCA_MAPS_RECOMPUTED)
+                return fail(ctx, DDCCA_EINVAL, "unknown next-stage map mode");
+            ctx->next_stage_maps = value;
             return DDCCA_OK;
         default: return fail(ctx, DDCCA_EINVAL, "unknown option");
     }

@@ -62,6 +62,7 @@ struct ddcca_ctx {
 
     int conv_arith = DDCCA_CONV_AUTO;       // DDCCA_OPT_CONV_ARITH
     int gram_arith = DDCCA_GRAM_FP32;       // DDCCA_OPT_GRAM_ARITH
+    int next_stage_maps = DDCCA_MAPS_STREAMED;   // DDCCA_OPT_NEXT_STAGE_MAPS
 
     // ---- profiling
     bool prof = false;
@@ -106,6 +107,10 @@ inline int gram_tiles(int k) { int nb = gram_blocks(k); return nb * (nb + 1) / 2
 // then undefined and must not be read).
 int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t n_maps, int h, int w,
                       int k, bool cross_only, double *slots, int max_slots, int *slots_valid);
+// the same over the maps W_l * input (previous stage, same patch size), recomputed tile by tile inside the kernel
+int launch_patch_gram_recomputed(ddcca_ctx *ctx, const float *in1, const float *in2, int64_t n_inputs, int h, int w,
+                                 int k, const float *Wp1, const float *Wp2, int L_prev, double *slots, int max_slots,
+                                 int *slots_valid);
 int max_gram_slots(ddcca_ctx *ctx, int k);
 int launch_gram_reduce(ddcca_ctx *ctx, const double *slots, int n_slots, int k, double *stacked);
 // the same fixed-order sum for slots of E doubles each

@@ -24,6 +24,13 @@
 // per lane) are made in registers right after the centre subtraction, so tiles, slots, flushes and the
 // export are those of the fp32 kernel.  The bf16 matrix instructions run beside the vector ALU, which the
 // fp32 ones do not, so the splitting work hides behind the matrix work of the other resident wavefront.
+//
+// Maps recomputed in the tile staging (Section II-B on Section II-A, DDCCA_MAPS_RECOMPUTED): when the maps
+// are the previous stage's convolution of given inputs, a workgroup can hold the INPUT tile (halo of both
+// stages) in LDS and produce the tile of each of the L_prev maps from it right into the pixel buffer the
+// contraction reads, so the maps never exist in HBM.  Items are then (input map, tile, filter) with the
+// filter innermost: the input tile is loaded once per L_prev items.  The convolution runs on the vector
+// ALU (8 outputs of a row per thread and pass, the filter taps as scalar operands).
 #include "conv_split.h"
 
 namespace ddcca {
@@ -31,6 +38,7 @@ namespace ddcca {
 constexpr int GRAM_THREADS = 256;          // 4 wavefronts
 constexpr int GRAM_TH = 16;                // patch rows per tile
 constexpr int GRAM_TW_MAX = 128;           // patch columns per tile (multiple of 4)
+constexpr size_t LDS_BYTES_PER_CU = 160 * 1024;
 constexpr int GRAM_KU = 2;                 // k-steps whose operand reads and centre subtractions are grouped
 
 struct GramParams {
@@ -44,6 +52,11 @@ struct GramParams {
     int flush_items;                       // items between fp64 flushes
     double *slots;                         // [n_slots][NT*256]
     int slots_valid;                       // slots below this hold earlier partial sums
+    // maps recomputed in the staging (FUSE kernels): v1, v2 are the INPUTS [n_inputs][h][w] and
+    // n_items = n_inputs * tiles * Lp
+    const float *Wp1, *Wp2;                // [Lp][KS][KS] filters of the previous stage per view
+    int Lp;
+    int raw_off, raw_pitch, raw_view_stride;   // LDS floats: input tiles after the DC cells
 };
 
 // Compile-time geometry.  TSPLIT wavefronts share one group of patch rows and split the
@@ -363,9 +376,128 @@ __device__ __forceinline__ void gram_tile_store(const GramParams &p, float *buf,
     }
 }
 
-template <int KS, int TSPLIT, bool CROSS, int WAVES_PER_EU, bool SPLIT>
+// ---- maps recomputed from an input tile ------------------------------------------------------------------
+template <int KS>
+struct GramRaw {
+    static constexpr int R = (KS - 1) / 2;
+    static constexpr int PH = GRAM_TH + 2 * R;             // map rows of a tile with its halo
+    static constexpr int RH = PH + 2 * R;                  // input rows under them
+    static constexpr int RUN = 8;                          // outputs of a row per thread and pass
+    static constexpr int SEG = (RUN + 2 * R + 3) & ~3;     // input columns under a run, whole float4s
+    static constexpr int runs_x(int pw) { return (pw + RUN - 1) / RUN; }
+    static constexpr int pitch(int pw) { return RUN * (runs_x(pw) - 1) + SEG; }
+    static constexpr int NE = (RH * pitch(GRAM_TW_MAX + 2 * R) + GRAM_THREADS - 1) / GRAM_THREADS;
+};
+
+// The input tile under (input map n, tile t) of both views into LDS; outside the image: 0 (Eq. 6 pads with
+// zeros).  Element (y, x) is image pixel (ty*TH - 2R + y, tx*tw - 2R + x).
+template <int KS>
+__device__ __forceinline__ void gram_raw_load(const GramParams &p, int64_t nt, int tiles, float *raw)
+{
+    using S = GramRaw<KS>;
+    const int64_t n = nt / tiles;
+    const int t = (int)(nt - n * tiles);
+    const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
+    const int gy0 = ty * GRAM_TH - 2 * S::R, gx0 = tx * p.tw - 2 * S::R;
+    const int64_t P = (int64_t)p.h * p.w;
+    const float *s1 = p.v1 + n * P, *s2 = p.v2 + n * P;
+    const int total = S::RH * p.raw_pitch;
+    float a[S::NE], b[S::NE];
+#pragma unroll
+    for (int i = 0; i < S::NE; ++i) {
+        const int e = threadIdx.x + GRAM_THREADS * i;
+        const int y = e / p.raw_pitch, x = e - y * p.raw_pitch;
+        const int gy = gy0 + y, gx = gx0 + x;
+        a[i] = 0.f;
+        b[i] = 0.f;
+        if (e < total && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w) {
+            const int64_t o = (int64_t)gy * p.w + gx;
+            a[i] = s1[o];
+            b[i] = s2[o];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < S::NE; ++i) {
+        const int e = threadIdx.x + GRAM_THREADS * i;
+        if (e < total) {
+            raw[e] = a[i];
+            raw[p.raw_view_stride + e] = b[i];
+        }
+    }
+}
+
+// Map l of the input tile into a pixel buffer: element (y, x) of the map tile is map pixel
+// (ty*TH - R + y, tx*tw - R + x) = sum_{dy,dx} W[l][dy][dx] * input(y + dy, x + dx) in tile coordinates
+// (Eq. 6), and 0 outside the image (the next stage pads the MAP with zeros).  Wavefronts 0, 1 take view 1,
+// wavefronts 2, 3 view 2, so that the taps are scalar operands.  Stored shifted by the DC estimates (c1, c2);
+// wavefronts 0 and 2 leave the mean of their own share as the estimate for the next tile.
+template <int KS>
+__device__ __forceinline__ void gram_tile_conv(const GramParams &p, const float *raw, float *buf, int l, int ty,
+                                               int tx, int pw, float c1, float c2, float *dc_next)
+{
+    using S = GramRaw<KS>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int view = __builtin_amdgcn_readfirstlane(wave >> 1);
+    const float *__restrict__ W = (view ? p.Wp2 : p.Wp1) + (size_t)l * KS * KS;
+    const float *rv = raw + view * p.raw_view_stride;
+    float *bv = buf + view * p.view_stride;
+    const float c = view ? c2 : c1;
+    const int nrx = S::runs_x(pw), nruns = S::PH * nrx;
+    const int gy0 = ty * GRAM_TH - S::R, gx0 = tx * p.tw - S::R;
+    float sum = 0.f, cnt = 0.f;
+    for (int run = threadIdx.x & 127; run < nruns; run += 128) {
+        const int y = run / nrx, x0 = (run - y * nrx) * S::RUN;
+        float acc[S::RUN];
+#pragma unroll
+        for (int j = 0; j < S::RUN; ++j) acc[j] = 0.f;
+        // (one filter row at a time: unrolled, all rows' input segments and taps would be in registers at once,
+        // next to the Gram accumulators that live across this phase)
+#pragma unroll 1
+        for (int dy = 0; dy < KS; ++dy) {
+            const float4 *rr = reinterpret_cast<const float4 *>(rv + (y + dy) * p.raw_pitch + x0);
+            float seg[S::SEG];
+#pragma unroll
+            for (int v = 0; v < S::SEG / 4; ++v) {
+                const float4 f = rr[v];
+                seg[4 * v] = f.x;
+                seg[4 * v + 1] = f.y;
+                seg[4 * v + 2] = f.z;
+                seg[4 * v + 3] = f.w;
+            }
+#pragma unroll
+            for (int dx = 0; dx < KS; ++dx) {
+                const float wv = W[dy * KS + dx];
+#pragma unroll
+                for (int j = 0; j < S::RUN; ++j) acc[j] = fmaf(wv, seg[j + dx], acc[j]);
+            }
+        }
+        const int gy = gy0 + y;
+        const bool yok = gy >= 0 && gy < p.h;
+#pragma unroll
+        for (int j = 0; j < S::RUN; ++j) {
+            const int x = x0 + j, gx = gx0 + x;
+            const float v = (yok && gx >= 0 && gx < p.w) ? acc[j] : 0.f;
+            if (x < pw) {
+                bv[y * p.pitch + x] = v - c;
+                sum += v;
+                cnt += 1.f;
+            }
+        }
+    }
+    if ((wave & 1) == 0) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            sum += __shfl_xor(sum, o);
+            cnt += __shfl_xor(cnt, o);
+        }
+        if (lane == 0) dc_next[view] = sum / cnt;          // (lane 0 holds at least one run: cnt > 0)
+    }
+}
+
+template <int KS, int TSPLIT, bool CROSS, int WAVES_PER_EU, bool SPLIT, bool FUSE>
 __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(GramParams p)
 {
+    static_assert(!(FUSE && CROSS), "maps are recomputed for the full Gram only");
     using G = GramGeom<KS, TSPLIT, CROSS>;
     using S = GramStage<KS>;
     constexpr int R = G::R, NB = G::NB, NT = G::NT;
@@ -408,8 +540,28 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
     int since_flush = 0;
     const int pw = p.tw + 2 * R;
 
+    float *raw = lds + p.raw_off;                          // FUSE: the input tiles of both views
+    // FUSE: an item is (input map n, tile t, filter l) = ((n * tiles + t) * Lp + l)
+    auto tile_of = [&](int64_t item, int &ty, int &tx) {
+        const int64_t nt = FUSE ? item / p.Lp : item;
+        const int t = (int)(nt % tiles);
+        ty = t / p.tiles_x;
+        tx = t - ty * p.tiles_x;
+    };
     float ra[S::NJY][S::NJX], rb[S::NJY][S::NJX];
-    if (count > 0) {
+    if (FUSE && count > 0) {
+        // first tile: once unshifted for its DC estimate, then again shifted by it
+        int ty, tx;
+        tile_of(first, ty, tx);
+        const int l = (int)(first % p.Lp);
+        gram_raw_load<KS>(p, first / p.Lp, tiles, raw);
+        __syncthreads();
+        gram_tile_conv<KS>(p, raw, lds, l, ty, tx, pw, 0.f, 0.f, dc + 2);
+        __syncthreads();
+        gram_tile_conv<KS>(p, raw, lds, l, ty, tx, pw, dc[2], dc[3], dc);
+        __syncthreads();
+    }
+    if (!FUSE && count > 0) {
         // first tile: its own DC estimate, then into buffer 0
         gram_tile_fetch<KS>(p, first, tiles, pw, ra, rb);
         float s1 = 0.f, s2 = 0.f;
@@ -444,11 +596,10 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
         const float *pix = lds + cur * p.buf_stride;
         const bool more = it + 1 < count;
         // the next tile travels from HBM to registers while this one is contracted
-        if (more) gram_tile_fetch<KS>(p, item + 1, tiles, pw, ra, rb);
+        if (!FUSE && more) gram_tile_fetch<KS>(p, item + 1, tiles, pw, ra, rb);
 
-        const int64_t m = item / tiles;
-        const int t = (int)(item - m * tiles);
-        const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
+        int ty, tx;
+        tile_of(item, ty, tx);
         const int rows = min(GRAM_TH, p.h - ty * GRAM_TH);
         const int cols = min(p.tw, p.w - tx * p.tw);
         if constexpr (SPLIT) {
@@ -465,7 +616,21 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
             rmw = true;
             since_flush = 0;
         }
-        if (more) {
+        if (FUSE && more) {
+            // (the input tile is read between barriers only, by gram_tile_conv: no wavefront is still in it)
+            const int64_t nx = item + 1;
+            const int l = (int)(nx % p.Lp);
+            if (l == 0) {
+                gram_raw_load<KS>(p, nx / p.Lp, tiles, raw);
+                __syncthreads();
+            }
+            int ny, nxx;
+            tile_of(nx, ny, nxx);
+            gram_tile_conv<KS>(p, raw, lds + (cur ^ 1) * p.buf_stride, l, ny, nxx, pw, dc[2 * cur], dc[2 * cur + 1],
+                               dc + 2 * (cur ^ 1));
+            __syncthreads();
+        }
+        if (!FUSE && more) {
             // DC shift of tile it+1 = estimate left by tile it (cells cur), new estimate into the other cells
             gram_tile_store<KS>(p, lds + (cur ^ 1) * p.buf_stride, pw, dc[2 * cur], dc[2 * cur + 1], ra, rb,
                                 dc + 2 * (cur ^ 1));
@@ -587,18 +752,97 @@ static GramShape gram_shape(int k)
 // one slot per resident workgroup
 int max_gram_slots(ddcca_ctx *ctx, int k) { return ctx->n_cu * gram_shape(k).waves_per_eu; }
 
-template <int KS, int TSPLIT, bool CROSS, int WPE, bool SPLIT>
+template <int KS, int TSPLIT, bool CROSS, int WPE, bool SPLIT, bool FUSE>
 static int gram_launch(ddcca_ctx *ctx, const GramParams &p, int grid, size_t lds)
 {
     static bool attr_set[MAX_DEVICES] = {};      // per device: the attribute is set on that device's code object
     if (!attr_set[ctx->device]) {
-        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)patch_gram_kernel<KS, TSPLIT, CROSS, WPE, SPLIT>,
+        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)patch_gram_kernel<KS, TSPLIT, CROSS, WPE, SPLIT, FUSE>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         attr_set[ctx->device] = true;
     }
-    hipLaunchKernelGGL((patch_gram_kernel<KS, TSPLIT, CROSS, WPE, SPLIT>), dim3(grid), dim3(GRAM_THREADS), lds,
+    hipLaunchKernelGGL((patch_gram_kernel<KS, TSPLIT, CROSS, WPE, SPLIT, FUSE>), dim3(grid), dim3(GRAM_THREADS), lds,
                        ctx->stream, p);
     DDCCA_HIP(ctx, hipGetLastError());
+    return DDCCA_OK;
+}
+
+// LDS layout of a launch with column tiles of at most tw_max patches; returns the bytes.
+static size_t gram_layout(GramParams &p, int k, int tw_max, bool split, bool fuse)
+{
+    const int w4 = (p.w + 3) & ~3;
+    // split wide images into equal column tiles of at most tw_max patches
+    const int ntx = (w4 + tw_max - 1) / tw_max;
+    p.tw = (((w4 + ntx - 1) / ntx) + 3) & ~3;
+    p.tiles_x = (p.w + p.tw - 1) / p.tw;
+    p.tiles_y = (p.h + GRAM_TH - 1) / GRAM_TH;
+    const int r = (k - 1) / 2;
+    // row pitch: >= tile width + halo, and congruent to k+3 mod 32 so that the window
+    // rows a lane group touches fall into distinct LDS banks
+    // (three-piece operands read whole groups of 32 patches: the pitch covers the rounded-up width)
+    int pitch = (split ? (p.tw + 31) / 32 * 32 : p.tw) + 2 * r;
+    while (pitch % 32 != (k + 3) % 32) ++pitch;
+    p.pitch = pitch;
+    p.view_stride = (GRAM_TH + 2 * r) * pitch + 16;      // +16: shift view 2 by half the banks
+    p.buf_stride = 2 * p.view_stride;
+    const int tsplit = gram_shape(k).tsplit;
+    const size_t tile_floats = (size_t)2 * p.buf_stride;
+    const size_t stage_floats = (size_t)((gram_tiles(k) + tsplit - 1) / tsplit) * 256;
+    p.dc_off = (int)std::max(tile_floats, stage_floats);
+    size_t floats = (size_t)p.dc_off + 4;
+    p.raw_off = p.raw_pitch = p.raw_view_stride = 0;
+    if (fuse) {
+        // input tile under the map tile: 8-column runs, the last one read as whole float4s
+        const int pw = p.tw + 2 * r, seg = (8 + 2 * r + 3) & ~3;
+        p.raw_off = (int)floats;                                     // (a multiple of 4 floats)
+        p.raw_pitch = 8 * ((pw + 7) / 8 - 1) + seg;
+        p.raw_view_stride = (GRAM_TH + 4 * r) * p.raw_pitch;
+        floats += (size_t)2 * p.raw_view_stride;
+    }
+    return floats * sizeof(float);
+}
+
+static int gram_run(ddcca_ctx *ctx, GramParams &p, int64_t n_maps, int k, bool cross_only, bool fuse, int max_slots,
+                    int *slots_valid)
+{
+    const bool split = ctx->gram_arith == DDCCA_GRAM_BF16X3;
+    const GramShape shape = gram_shape(k);
+    size_t lds = gram_layout(p, k, GRAM_TW_MAX, split, fuse);
+    // (with the input tiles next to the pixel buffers: narrower tiles until every resident workgroup fits)
+    for (int tw_max = GRAM_TW_MAX - 32; fuse && tw_max >= 32 && lds * shape.waves_per_eu > LDS_BYTES_PER_CU;
+         tw_max -= 32)
+        lds = gram_layout(p, k, tw_max, split, fuse);
+    p.n_items = n_maps * p.tiles_x * p.tiles_y;
+    const int npg = 4 / shape.tsplit;
+    // about 16k patches between fp64 flushes per wavefront
+    const int patches_per_group_item = (GRAM_TH / npg) * p.tw;
+    p.flush_items = std::max(1, 16384 / patches_per_group_item);
+    p.slots_valid = *slots_valid;
+    // one workgroup per resident position: what the register budget allows per SIMD, unless the tiles of that
+    // many workgroups do not fit a compute unit's LDS (k = 5 at the full tile width: three, not four) -- a grid
+    // larger than what is resident would run its surplus as a second, thinly occupied round
+    const int resident = std::min<int>(shape.waves_per_eu, (int)std::max<size_t>(1, LDS_BYTES_PER_CU / lds));
+    const int max_grid = std::min(max_slots, ctx->n_cu * resident);
+    const int grid = (int)std::min<int64_t>(max_grid, std::max<int64_t>(p.n_items, 1));
+    int rc;
+#define GRAM_PICK(KS, TS, WPE, SP)                                                                     \
+    (fuse ? gram_launch<KS, TS, false, WPE, SP, true>(ctx, p, grid, lds)                               \
+          : cross_only ? gram_launch<KS, TS, true, WPE, SP, false>(ctx, p, grid, lds)                  \
+                       : gram_launch<KS, TS, false, WPE, SP, false>(ctx, p, grid, lds))
+#define GRAM_CASE(KS, TS, WPE)                                                                         \
+    case KS: rc = split ? GRAM_PICK(KS, TS, WPE, true) : GRAM_PICK(KS, TS, WPE, false); break;
+    switch (k) {
+        GRAM_CASE(3, 1, 4)
+        GRAM_CASE(5, 1, 4)
+        GRAM_CASE(7, 1, 2)
+        GRAM_CASE(9, 2, 2)
+        default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
+    }
+#undef GRAM_CASE
+#undef GRAM_PICK
+    if (rc) return rc;
+    // slots below the old mark that this grid did not touch keep their data; new ones were initialised
+    *slots_valid = std::max(*slots_valid, grid);
     return DDCCA_OK;
 }
 
@@ -608,56 +852,21 @@ int launch_patch_gram(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t 
     ProfScope prof(ctx, cross_only ? DDCCA_K_GRAM_CROSS : DDCCA_K_GRAM);
     GramParams p;
     p.v1 = v1; p.v2 = v2; p.h = h; p.w = w;
-    const int w4 = (w + 3) & ~3;
-    // split wide images into equal column tiles of at most GRAM_TW_MAX patches
-    const int ntx = (w4 + GRAM_TW_MAX - 1) / GRAM_TW_MAX;
-    p.tw = (((w4 + ntx - 1) / ntx) + 3) & ~3;
-    p.tiles_x = (w + p.tw - 1) / p.tw;
-    p.tiles_y = (h + GRAM_TH - 1) / GRAM_TH;
-    p.n_items = n_maps * p.tiles_x * p.tiles_y;
-    const int r = (k - 1) / 2;
-    // row pitch: >= tile width + halo, and congruent to k+3 mod 32 so that the window
-    // rows a lane group touches fall into distinct LDS banks
-    const bool split = ctx->gram_arith == DDCCA_GRAM_BF16X3;
-    // (three-piece operands read whole groups of 32 patches: the pitch covers the rounded-up width)
-    int pitch = (split ? (p.tw + 31) / 32 * 32 : p.tw) + 2 * r;
-    while (pitch % 32 != (k + 3) % 32) ++pitch;
-    p.pitch = pitch;
-    p.view_stride = (GRAM_TH + 2 * r) * pitch + 16;      // +16: shift view 2 by half the banks
-    p.buf_stride = 2 * p.view_stride;
-    const GramShape shape = gram_shape(k);
-    const int npg = 4 / shape.tsplit;
-    const size_t tile_floats = (size_t)2 * p.buf_stride;
-    const size_t stage_floats = (size_t)((gram_tiles(k) + shape.tsplit - 1) / shape.tsplit) * 256;
-    p.dc_off = (int)std::max(tile_floats, stage_floats);
-    const size_t lds = (size_t)(p.dc_off + 4) * sizeof(float);
-    // about 16k patches between fp64 flushes per wavefront
-    const int patches_per_group_item = (GRAM_TH / npg) * p.tw;
-    p.flush_items = std::max(1, 16384 / patches_per_group_item);
+    p.Wp1 = p.Wp2 = nullptr; p.Lp = 0;
     p.slots = slots;
-    p.slots_valid = *slots_valid;
-    const int max_grid = max_slots;
-    const int grid = (int)std::min<int64_t>(max_grid, std::max<int64_t>(p.n_items, 1));
-    int rc;
-#define GRAM_CASE(KS, TS, WPE)                                                                   \
-    case KS:                                                                                     \
-        rc = split ? (cross_only ? gram_launch<KS, TS, true, WPE, true>(ctx, p, grid, lds)       \
-                                 : gram_launch<KS, TS, false, WPE, true>(ctx, p, grid, lds))     \
-                   : (cross_only ? gram_launch<KS, TS, true, WPE, false>(ctx, p, grid, lds)      \
-                                 : gram_launch<KS, TS, false, WPE, false>(ctx, p, grid, lds));   \
-        break;
-    switch (k) {
-        GRAM_CASE(3, 1, 4)
-        GRAM_CASE(5, 1, 4)
-        GRAM_CASE(7, 1, 2)
-        GRAM_CASE(9, 2, 2)
-        default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
-    }
-#undef GRAM_CASE
-    if (rc) return rc;
-    // slots below the old mark that this grid did not touch keep their data; new ones were initialised
-    *slots_valid = std::max(*slots_valid, grid);
-    return DDCCA_OK;
+    return gram_run(ctx, p, n_maps, k, cross_only, false, max_slots, slots_valid);
+}
+
+int launch_patch_gram_recomputed(ddcca_ctx *ctx, const float *in1, const float *in2, int64_t n_inputs, int h, int w,
+                                 int k, const float *Wp1, const float *Wp2, int L_prev, double *slots, int max_slots,
+                                 int *slots_valid)
+{
+    ProfScope prof(ctx, DDCCA_K_GRAM);
+    GramParams p;
+    p.v1 = in1; p.v2 = in2; p.h = h; p.w = w;
+    p.Wp1 = Wp1; p.Wp2 = Wp2; p.Lp = L_prev;
+    p.slots = slots;
+    return gram_run(ctx, p, n_inputs * L_prev, k, false, true, max_slots, slots_valid);
 }
 
 int launch_gram_reduce(ddcca_ctx *ctx, const double *slots, int n_slots, int k, double *stacked)

@@ -7,7 +7,7 @@ in the launch configuration bench.py times.
     accumulate over the same maps and the second-stage Gram -- the dominant kernel at its dominant launch shape,
     persistent grid, flush cadence and slot reduction over 10^8 .. 4*10^9 patches -- meets the oracle entry by
     entry; materialised (ddcca_apply_stage + accumulate) and streamed (ddcca_learn_next_stage_filters), in fp32,
-    three-piece bf16 and lag-structured arithmetic;
+    three-piece bf16 and lag-structured arithmetic, and with the maps recomputed inside the Gram kernel;
   * the GPU's own two-stage learning (its own stage-1 filters): canonical correlations and signed filter cosines
     against the oracle's (Eq. 2-5);
   * end to end: histograms of the stored sample of images from the full-size GPU run (GPU filters, GPU extraction)
@@ -77,8 +77,10 @@ def gold(request):
 
 def make_ctx(arith):
     from paper_2209_13027_amd.binding import (Context, OPT_CONV_ARITH, CONV_BF16X3, OPT_GRAM_ARITH, GRAM_BF16X3,
-                                              GRAM_LAG_FP32)
+                                              GRAM_LAG_FP32, OPT_NEXT_STAGE_MAPS, MAPS_RECOMPUTED)
     ctx = Context(0)
+    if arith == "recomputed":
+        ctx.set_option(OPT_NEXT_STAGE_MAPS, MAPS_RECOMPUTED)
     if arith == "bf16x3":
         ctx.set_option(OPT_GRAM_ARITH, GRAM_BF16X3)
         ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
@@ -109,10 +111,11 @@ def test_stage1_matrices_full_size(gold, arith):
         ctx.close()
 
 
-@pytest.mark.parametrize("arith", ["fp32", "bf16x3", "lag"])
+@pytest.mark.parametrize("arith", ["fp32", "bf16x3", "lag", "recomputed"])
 def test_stage2_matrices_full_size_streamed(gold, arith):
-    """ddcca_learn_next_stage_filters with the oracle's stage-1 filters: maps convolved batch by batch, class sum
-    images by linearity; the matrices it solved are exported afterwards."""
+    """ddcca_learn_next_stage_filters with the oracle's stage-1 filters: maps convolved batch by batch (or, with
+    `recomputed`, formed tile by tile inside the fp32 Gram kernel), class sum images by linearity; the matrices it
+    solved are exported afterwards."""
     wl = gold.wl
     ctx = make_ctx(arith)
     try:

@@ -196,3 +196,83 @@ def test_streamed_route_on_narrow_images_with_every_pair(ctx, oracle, m, h, w, k
                 cos = cosines(model["filters"][2 * s + d].cpu().numpy(), r["W%d" % (d + 1)])
                 if ok.any():
                     assert cos[ok].min() >= 0.9999, (streamed, s, d, cos, r["gap"])
+
+
+@pytest.mark.parametrize("arith", ["fp32", "bf16x3"])
+@pytest.mark.parametrize("n_img,G_in,h,w,k,L1,n_cls", [
+    (9, 1, 30, 44, 5, 4, 3),       # ragged tiles in both directions
+    (7, 1, 45, 70, 7, 8, 2),       # k = 7
+    (5, 1, 24, 40, 3, 3, 5),       # k = 3
+    (4, 1, 40, 36, 9, 8, 1),       # k = 9
+    (3, 1, 20, 300, 7, 5, 2),      # wider than one tile: three column tiles
+    (3, 1, 50, 150, 9, 8, 2),      # k = 9 over two column tiles, four row tiles
+    (6, 3, 28, 36, 5, 4, 2),       # inputs that are themselves maps (3 per sample)
+    (4, 1, 30, 3, 3, 2, 2),        # as wide as the patch
+    (2, 1, 3, 2, 5, 3, 1),         # smaller than the patch
+])
+def test_recomputed_maps_against_oracle_and_streamed(oracle, arith, n_img, G_in, h, w, k, L1, n_cls):
+    """DDCCA_MAPS_RECOMPUTED: the Gram kernel forms every tile of the previous stage's maps from the input tile it
+    holds (Section II-B on Section II-A); the matrices against the oracle's convolution (Eq. 6) and matrices of the
+    same inputs at the bars of the path, and against the streamed route of the same library."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2209_13027_amd.binding import (Context, OPT_GRAM_ARITH, GRAM_BF16X3, OPT_NEXT_STAGE_MAPS,
+                                              MAPS_RECOMPUTED, MAPS_STREAMED)
+    c = Context(0)
+    try:
+        if arith == "bf16x3":
+            c.set_option(OPT_GRAM_ARITH, GRAM_BF16X3)
+        v1, v2, cls = rand_problem(4100 + 7 * k + w, n_img * G_in, h, w, n_cls)
+        cls = cls[:n_img].copy()
+        d1, d2, dc = dev(v1), dev(v2), dev(cls)
+        rng = np.random.default_rng(k + h)
+        Wa = rng.standard_normal((2, L1, k, k)).astype(np.float32)
+        W1a, W2a = dev(Wa[0]), dev(Wa[1])
+        L2 = min(4, k * k - 1)
+        c.set_option(OPT_NEXT_STAGE_MAPS, MAPS_STREAMED)
+        c.learn_next_stage_filters(d1, d2, dc, G_in, h, w, n_cls, W1a, W2a, k, L2)
+        streamed = matrices_of_last_learning(c, k)
+        c.set_option(OPT_NEXT_STAGE_MAPS, MAPS_RECOMPUTED)
+        _, _, rho = c.learn_next_stage_filters(d1, d2, dc, G_in, h, w, n_cls, W1a, W2a, k, L2)
+        got = matrices_of_last_learning(c, k)
+        c.status()
+        y1 = oracle.conv(v1.astype(np.float64), Wa[0].astype(np.float64)).reshape(-1, h, w)
+        y2 = oracle.conv(v2.astype(np.float64), Wa[1].astype(np.float64)).reshape(-1, h, w)
+        G = G_in * L1
+        grp = np.tile(np.arange(G, dtype=np.int32), n_img)
+        want = oracle.stage_matrices(y1, y2, np.repeat(cls, G), grp, n_cls, G, k)
+        assert np.all(np.isfinite(rho.cpu().numpy()))
+        for name in ("C11", "C22", "C12", "Cw", "CT"):
+            assert rel_fro(got[name], want[name]) <= 1e-4, name
+            assert rel_fro(got[name], want[name]) <= 5e-6, (name, "looser than expected for fp32 maps and products")
+            assert rel_fro(got[name], streamed[name]) <= 5e-6, (name, "against the streamed route")
+    finally:
+        c.close()
+
+
+def test_recomputed_maps_end_to_end(oracle):
+    """Two-stage learning with the second stage's maps recomputed in the Gram kernel, then extraction, on small_face
+    (two images per class): filters and histograms against the oracle at the bars of the path."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2209_13027_amd.binding import Context, OPT_NEXT_STAGE_MAPS, MAPS_RECOMPUTED
+    wl = WORKLOADS["small_face"]
+    v1, v2, cls = make_views(wl, max_per_class=2)
+    d1, d2, dc = dev(v1), dev(v2), dev(cls)
+    c = Context(0)
+    try:
+        c.set_option(OPT_NEXT_STAGE_MAPS, MAPS_RECOMPUTED)
+        model = pipeline.fit(c, d1, d2, dc, wl.n_classes, wl.k, wl.L1, wl.L2, streamed=True)
+        feat = pipeline.extract(c, d1, d2, model["filters"], wl.k, wl.L1, wl.L2, wl.block, wl.stride)
+        c.status()
+    finally:
+        c.close()
+    ref = oracle.two_stage(v1, v2, cls, wl.n_classes, wl.k, wl.L1, wl.L2, wl.block)
+    refs = [ref["stage1"]["W1"], ref["stage1"]["W2"], ref["stage2"]["W1"], ref["stage2"]["W2"]]
+    gaps = [ref["stage1"]["gap"], ref["stage1"]["gap"], ref["stage2"]["gap"], ref["stage2"]["gap"]]
+    for W, R, gap in zip(model["filters"], refs, gaps):
+        assert cosines(W.cpu().numpy(), R)[gap > 1e-3].min() >= 0.9999
+    assert np.allclose(model["rho"][1].cpu().numpy(), ref["stage2"]["rho"], rtol=1e-4)
+    got = feat.cpu().numpy()
+    l1 = np.abs(got.astype(np.int64) - ref["hist"]).sum() / ref["hist"].sum()
+    assert l1 <= 1e-3, l1
