@@ -140,7 +140,7 @@ typedef struct ddcca_model {
     int k, L1, L2;
     int block_h, block_w, stride_y, stride_x;
     const float *W[2][2];     /* W[stage][view]: device, [L_stage][k][k] */
-    int64_t batch_images;     /* images per internal batch; 0 = library default */
+    int64_t batch_images;     /* images per internal batch; 0 = equal batches whose maps take at most 4 GiB per view */
 } ddcca_model;
 
 /* Both stages and the output layer for m new image pairs with a learned model:
@@ -248,7 +248,7 @@ int ddcca_set_option(ddcca_ctx *ctx, int option, int value);
  * ddcca_learn_stage_filters on the maps with G = G_in * L_prev.
  *   v1, v2 : DEVICE, [n_img][G_in][h][w] float, the INPUTS of the previous stage
  *   Wp1, Wp2 : DEVICE, [L_prev][k_prev][k_prev] float, the previous stage's filters per view
- *   batch_images : samples whose maps exist at a time (0 = as many as fit 4 GiB per view);
+ *   batch_images : samples whose maps exist at a time (0 = equal batches of at most 4 GiB per view);
  *                  it changes the result only through the order of the fp32 partial sums
  *                  inside a batch (relative 1e-6 or less)
  * Every batch is convolved into a scratch buffer of the context and accumulated at once.

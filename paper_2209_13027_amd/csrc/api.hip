@@ -384,6 +384,16 @@ int ddcca_learn_stage_filters(ddcca_ctx *ctx, const float *v1, const float *v2, 
     return ddcca_solve_filters(ctx, L, ridge, W1, W2, rho);
 }
 
+// The batch size that covers n items in the fewest batches of at most `most` items, all (nearly) equally large: a
+// short last batch would run its kernels on a fraction of the chip.
+static int64_t even_batch(int64_t n, int64_t most)
+{
+    if (n < 1) return 1;
+    most = std::max<int64_t>(1, std::min(most, n));
+    const int64_t batches = (n + most - 1) / most;
+    return (n + batches - 1) / batches;
+}
+
 static int run_conv(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L, float *out)
 {
     const bool split = ctx->conv_arith == DDCCA_CONV_BF16X3 || (ctx->conv_arith == DDCCA_CONV_AUTO && k >= 5);
@@ -442,6 +452,7 @@ int ddcca_learn_next_stage_filters(ddcca_ctx *ctx, const float *v1, const float 
     int64_t nb = batch_images;
     if (nb == 0) nb = std::max<int64_t>(1, (int64_t)(((size_t)4 << 30) / per_img));   // 4 GiB of maps per view
     nb = std::min(nb, n_img);
+    if (batch_images == 0) nb = even_batch(n_img, nb);
     if ((rc = ensure(ctx, ctx->maps1, (size_t)nb * per_img))) return rc;
     if ((rc = ensure(ctx, ctx->maps2, (size_t)nb * per_img))) return rc;
     float *m1 = (float *)ctx->maps1.ptr, *m2 = (float *)ctx->maps2.ptr;
@@ -571,7 +582,7 @@ static int extract_impl(ddcca_ctx *ctx, const float *v1, const float *v2, int64_
     int64_t batch = model->batch_images;
     if (batch == 0) {
         const double per_image = (double)L1 * (fused ? 1 : L2) * P * sizeof(float);
-        batch = (int64_t)std::max(1.0, 4.0 * 1073741824.0 / per_image);
+        batch = even_batch(m, (int64_t)std::max(1.0, 4.0 * 1073741824.0 / per_image));
     }
     batch = std::min(batch, m);
     if ((rc = ensure(ctx, ctx->maps1, (size_t)batch * L1 * P * sizeof(float)))) return rc;

@@ -153,6 +153,9 @@ def test_validation_of_the_widened_calls(binding):
     assert lib.ddcca_set_option(h, binding.OPT_CONV_ARITH, binding.CONV_AUTO) == binding.OK
     assert lib.ddcca_set_option(h, binding.OPT_CONV_ARITH, 3) == E
     assert lib.ddcca_set_option(h, binding.OPT_GRAM_ARITH, -1) == E
+    assert lib.ddcca_set_option(h, binding.OPT_NEXT_STAGE_MAPS, binding.MAPS_RECOMPUTED) == binding.OK
+    assert lib.ddcca_set_option(h, binding.OPT_NEXT_STAGE_MAPS, binding.MAPS_STREAMED) == binding.OK
+    assert lib.ddcca_set_option(h, binding.OPT_NEXT_STAGE_MAPS, 2) == E
     assert lib.ddcca_set_option(h, 99, 0) == E
     assert lib.ddcca_set_option(None, binding.OPT_CONV_ARITH, 0) == E
     # timing selection: any mask with a known kernel id; none is an error

@@ -276,3 +276,31 @@ def test_recomputed_maps_end_to_end(oracle):
     got = feat.cpu().numpy()
     l1 = np.abs(got.astype(np.int64) - ref["hist"]).sum() / ref["hist"].sum()
     assert l1 <= 1e-3, l1
+
+
+def test_recomputed_maps_option_falls_back_where_it_does_not_apply():
+    """k_prev != k, or the lag-structured Gram: the call proceeds as with streamed maps (bit for bit)."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2209_13027_amd.binding import (Context, DdccaError, OPT_GRAM_ARITH, GRAM_LAG_FP32, GRAM_FP32,
+                                              OPT_NEXT_STAGE_MAPS, MAPS_RECOMPUTED, MAPS_STREAMED)
+    c = Context(0)
+    try:
+        v1, v2, cls = rand_problem(515, 6, 26, 34, 2)
+        d1, d2, dc = dev(v1), dev(v2), dev(cls)
+        rng = np.random.default_rng(3)
+        for k_prev, k, arith in ((5, 3, GRAM_FP32), (5, 5, GRAM_LAG_FP32)):
+            Wa = rng.standard_normal((2, 4, k_prev, k_prev)).astype(np.float32)
+            c.set_option(OPT_GRAM_ARITH, arith)
+            out = []
+            for mode in (MAPS_STREAMED, MAPS_RECOMPUTED):
+                c.set_option(OPT_NEXT_STAGE_MAPS, mode)
+                c.learn_next_stage_filters(d1, d2, dc, 1, 26, 34, 2, dev(Wa[0]), dev(Wa[1]), k, 3)
+                out.append(matrices_of_last_learning(c, k))
+            for name in ("C11", "C22", "C12", "Cw", "CT"):
+                assert np.array_equal(out[0][name], out[1][name]), (k_prev, k, name)
+        with pytest.raises(DdccaError):
+            c.set_option(OPT_NEXT_STAGE_MAPS, 2)
+        c.status()
+    finally:
+        c.close()
