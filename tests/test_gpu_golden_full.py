@@ -153,15 +153,16 @@ def test_stage2_matrices_full_size_materialised(gold):
         torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("arith", ["fp32", "widened"])
+@pytest.mark.parametrize("arith", ["fp32", "bf16x3", "widened"])
 def test_two_stage_learning_and_features_full_size(gold, oracle, arith):
     """The whole path as bench.py runs it (pipeline.fit + pipeline.extract on the full workload), against the
-    oracle's filters and the oracle's histograms of the stored sample of images.  `widened`: lag-structured Gram,
-    three-piece bf16 convolution and the fused last stage together."""
+    oracle's filters and the oracle's histograms of the stored sample of images.  `bf16x3`: the dense Gram and the
+    convolution on three-piece bf16 operands; `widened`: lag-structured Gram, three-piece bf16 convolution and the
+    fused last stage together."""
     from paper_2209_13027_amd import pipeline
     from paper_2209_13027_amd.binding import OPT_CONV_ARITH, CONV_BF16X3
     wl, g = gold.wl, gold.g
-    ctx = make_ctx("lag" if arith == "widened" else "fp32")
+    ctx = make_ctx({"widened": "lag", "bf16x3": "bf16x3"}.get(arith, "fp32"))
     if arith == "widened":
         ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
     try:
