@@ -31,6 +31,8 @@
 // contraction reads, so the maps never exist in HBM.  Items are then (input map, tile, filter) with the
 // filter innermost: the input tile is loaded once per L_prev items.  The convolution runs on the vector
 // ALU (8 outputs of a row per thread and pass, the filter taps as scalar operands).
+#include <type_traits>
+
 #include "conv_split.h"
 
 namespace ddcca {
@@ -92,6 +94,8 @@ struct GramGeom {
         return n;
     }
     static constexpr int NACC = (used_tiles() + TSPLIT_ - 1) / TSPLIT_;   // accumulator tiles per wavefront
+    // groups of k-steps per loop iteration of the fp32 contraction (where the register budget has room for it)
+    static constexpr int GU = (KS == 7 || KS == 3) ? 8 : 1;
 };
 
 template <typename G, int ROLE>
@@ -136,16 +140,17 @@ __device__ __forceinline__ void gram_rows(const float *pix, int pitch, int rows,
                 for (int b = 0; b < NB; ++b)
                     z[u][b] = prow[pix_off[b] + 4 * u] - prow[cen_off[G::cen_index(b)] + 4 * u];
         }
-        for (int kg = 0; kg < groups; ++kg) {
+        // One group: the LDS reads of the group at column nx of pk (with GU > 1 the group after the last one reads
+        // 4 * KU columns past the row's last patch: inside the row pitch or the 16 floats that follow every view's
+        // tile, and never used), the MFMAs of the current one, the centre subtractions of the next.
+        auto group = [&](const float *pk, int nx) {
             float pa[KU][NB], pc[KU][G::NCEN];
-            // operands of the next group of steps (the last group reads its own columns again)
-            const int nx = 4 * KU * (kg + 1 < groups ? kg + 1 : kg);
 #pragma unroll
             for (int u = 0; u < KU; ++u) {
 #pragma unroll
-                for (int b = 0; b < NB; ++b) pa[u][b] = prow[pix_off[b] + nx + 4 * u];
+                for (int b = 0; b < NB; ++b) pa[u][b] = pk[pix_off[b] + nx + 4 * u];
 #pragma unroll
-                for (int v = 0; v < G::NCEN; ++v) pc[u][v] = prow[cen_off[v] + nx + 4 * u];
+                for (int v = 0; v < G::NCEN; ++v) pc[u][v] = pk[cen_off[v] + nx + 4 * u];
             }
             __builtin_amdgcn_sched_group_barrier(0x100, KU * (NB + G::NCEN), 0);     // LDS reads first
 #pragma unroll
@@ -155,6 +160,26 @@ __device__ __forceinline__ void gram_rows(const float *pix, int pitch, int rows,
             for (int u = 0; u < KU; ++u)
 #pragma unroll
                 for (int b = 0; b < NB; ++b) z[u][b] = pa[u][b] - pc[u][G::cen_index(b)];
+        };
+        // GU groups per iteration share one set of operand addresses (the later ones add an immediate offset)
+        constexpr int GU = G::GU;
+        if constexpr (GU == 1) {
+            // (the last group reads its own columns again)
+            for (int kg = 0; kg < groups; ++kg) group(prow, 4 * KU * (kg + 1 < groups ? kg + 1 : kg));
+        } else {
+            // runs of GU, GU/2, .. 1 groups, each run with one address update for all its groups
+            int kg = 0;
+            auto run = [&](auto n) {
+                constexpr int N = decltype(n)::value;
+                const float *pk = prow + 4 * KU * kg;
+#pragma unroll
+                for (int j = 0; j < N; ++j) group(pk, 4 * KU * (j + 1));
+                kg += N;
+            };
+            while (kg + GU <= groups) run(std::integral_constant<int, GU>{});
+            if constexpr (GU >= 8) if (kg + 4 <= groups) run(std::integral_constant<int, 4>{});
+            if constexpr (GU >= 4) if (kg + 2 <= groups) run(std::integral_constant<int, 2>{});
+            if (kg < groups) run(std::integral_constant<int, 1>{});
         }
         for (int kx = groups * KU; kx < full; ++kx) {
             float z0[NB];
