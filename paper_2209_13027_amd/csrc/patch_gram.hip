@@ -152,14 +152,17 @@ __device__ __forceinline__ void gram_rows(const float *pix, int pitch, int rows,
 #pragma unroll
                 for (int v = 0; v < G::NCEN; ++v) pc[u][v] = pk[cen_off[v] + nx + 4 * u];
             }
-            __builtin_amdgcn_sched_group_barrier(0x100, KU * (NB + G::NCEN), 0);     // LDS reads first
+            // three fenced phases: left to itself the scheduler moves the subtractions up to right behind the reads
+            // they use, where they wait for the LDS with one MFMA between
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < KU; ++u) gram_mfma_step<G, ROLE>(z[u], acc);
-            __builtin_amdgcn_sched_group_barrier(0x008, KU * G::NACC, 0);           // then every MFMA of the group
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < KU; ++u)
 #pragma unroll
                 for (int b = 0; b < NB; ++b) z[u][b] = pa[u][b] - pc[u][G::cen_index(b)];
+            __builtin_amdgcn_sched_barrier(0);
         };
         // GU groups per iteration share one set of operand addresses (the later ones add an immediate offset)
         constexpr int GU = G::GU;
