@@ -94,8 +94,8 @@ struct GramGeom {
         return n;
     }
     static constexpr int NACC = (used_tiles() + TSPLIT_ - 1) / TSPLIT_;   // accumulator tiles per wavefront
-    // groups of k-steps per loop iteration of the fp32 contraction (where the register budget has room for it)
-    static constexpr int GU = (KS == 7 || KS == 3) ? 8 : 1;
+    // groups of k-steps per run of the fp32 contraction's loop (one set of operand addresses per run)
+    static constexpr int GU = 8;
 };
 
 template <typename G, int ROLE>
@@ -771,7 +771,7 @@ static GramShape gram_shape(int k)
 {
     switch (k) {
         case 3: return {1, 4};
-        case 5: return {1, 4};
+        case 5: return {1, 3};
         case 7: return {1, 2};
         default: return {2, 2};
     }
@@ -861,7 +861,7 @@ static int gram_run(ddcca_ctx *ctx, GramParams &p, int64_t n_maps, int k, bool c
     case KS: rc = split ? GRAM_PICK(KS, TS, WPE, true) : GRAM_PICK(KS, TS, WPE, false); break;
     switch (k) {
         GRAM_CASE(3, 1, 4)
-        GRAM_CASE(5, 1, 4)
+        GRAM_CASE(5, 1, 3)
         GRAM_CASE(7, 1, 2)
         GRAM_CASE(9, 2, 2)
         default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
