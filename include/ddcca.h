@@ -170,25 +170,28 @@ int ddcca_extract_iq_features(ddcca_ctx *ctx, const float *v1, const float *v2, 
                               int w, const ddcca_model *model, int feat_type, void *feat);
 
 /* ---- fused last stage ------------------------------------------------------------------
- * Eq. 6 with the L2 filters W followed by the output layer (Eq. 7-12) in one kernel: the L2
- * maps of every input map are hashed and counted as they are computed and never written.
- * The result is bit-identical to ddcca_apply_stage with DDCCA_CONV_FP32 followed by
- * ddcca_hash_iq (the contraction runs in the same order).  in: [n][h][w]; W: [L2][k][k]; out as ddcca_hash_iq. */
+ * Eq. 6 with the L2 filters W followed by the output layer (Eq. 7-12) without the maps in
+ * memory: the L2 maps of every input map are hashed as they are computed and never written.
+ * The convolution runs in the arithmetic DDCCA_OPT_CONV_ARITH gives this patch size, in the
+ * same order as ddcca_apply_stage, so the result is that of ddcca_apply_stage followed by
+ * ddcca_hash_iq on the same context, bit for bit.  With the fp32 matrix instructions it is
+ * one kernel (convolution, hashing and histograms around a ring of block rows in LDS); with
+ * three-piece bf16 operands the convolution kernel writes the hash codes of its maps (one
+ * byte per pixel and 8 filters, context scratch) and a second kernel counts the histograms
+ * from those.  in: [n][h][w]; W: [L2][k][k]; out as ddcca_hash_iq. */
 int ddcca_apply_stage_hash(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W,
                            int k, int L2, int block_h, int block_w, int stride_y, int stride_x,
                            int feat_type, void *out);
 /* ddcca_extract_iq_features with the second stage and the output layer fused: the same
- * output, bit for bit when the convolution arithmetic is DDCCA_CONV_FP32 (otherwise up to
- * the sign of map values that round to one side of zero or the other); only the stage-1
- * maps of a batch are held in context scratch. */
+ * output, bit for bit; only the stage-1 maps of a batch (and, with three-piece operands,
+ * its hash codes) are held in context scratch. */
 int ddcca_extract_features_fused(ddcca_ctx *ctx, const float *v1, const float *v2, int64_t m, int h,
                                  int w, const ddcca_model *model, int feat_type, void *feat);
 
 /* ---- options ---------------------------------------------------------------------------
  * DDCCA_OPT_CONV_ARITH selects the arithmetic of the stage convolution (Eq. 6) in
  * ddcca_apply_stage, ddcca_learn_next_stage_filters and both stages of
- * ddcca_extract_features / ddcca_extract_iq_features (the fused last stage always uses the
- * fp32 instructions: it is bound by its vector work, not by the matrix unit):
+ * ddcca_extract_features / ddcca_extract_iq_features and their fused forms:
  *   DDCCA_CONV_FP32   fp32 products and sums on the fp32 matrix instructions;
  *   DDCCA_CONV_BF16X3 every fp32 operand split exactly into three bf16 pieces and the six
  *                     significant piece products summed in fp32 on the bf16 matrix pipeline:

@@ -208,7 +208,7 @@ void ddcca_destroy(ddcca_ctx *ctx)
         (void)hipSetDevice(ctx->device);
         (void)hipStreamSynchronize(ctx->stream);
         for (Buffer *b : {&ctx->lag_slots, &ctx->lag_col_slots, &ctx->lag_R, &ctx->lag_C, &ctx->prev_img, &ctx->slots, &ctx->class_sum, &ctx->class_img,
-                          &ctx->stacked, &ctx->seg, &ctx->mats, &ctx->solve_ws, &ctx->flags, &ctx->maps1, &ctx->maps2, &ctx->iq_lut})
+                          &ctx->stacked, &ctx->seg, &ctx->mats, &ctx->solve_ws, &ctx->flags, &ctx->maps1, &ctx->maps2, &ctx->codes, &ctx->iq_lut})
             free_buffer(*b);
         for (ProfSlot &s : ctx->prof_slot) {
             for (hipEvent_t e : s.start) (void)hipEventDestroy(e);
@@ -394,10 +394,34 @@ static int64_t even_batch(int64_t n, int64_t most)
     return (n + batches - 1) / batches;
 }
 
+// whether the stage convolution at this patch size runs on three-piece bf16 operands
+static bool conv_is_split(const ddcca_ctx *ctx, int k)
+{
+    return ctx->conv_arith == DDCCA_CONV_BF16X3 || (ctx->conv_arith == DDCCA_CONV_AUTO && k >= 5);
+}
+
 static int run_conv(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L, float *out)
 {
-    const bool split = ctx->conv_arith == DDCCA_CONV_BF16X3 || (ctx->conv_arith == DDCCA_CONV_AUTO && k >= 5);
-    return split ? launch_conv_split(ctx, in, n, h, w, W, k, L, out) : launch_conv(ctx, in, n, h, w, W, k, L, out);
+    return conv_is_split(ctx, k) ? launch_conv_split(ctx, in, n, h, w, W, k, L, out)
+                                 : launch_conv(ctx, in, n, h, w, W, k, L, out);
+}
+
+// The last stage fused with the output layer: no maps in memory.  In the arithmetic the convolution of this patch
+// size has (so that the result is that of run_conv + launch_hash_hist bit for bit): on three-piece operands the
+// convolution kernel itself hashes its maps and writes one byte per pixel and 8 filters, and the histograms are
+// counted from the code maps; on the fp32 matrix instructions, the ring kernel.
+static int run_conv_hash_hist(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L2,
+                              int bh, int bw, int sy, int sx, void *out, int feat_type, int64_t group,
+                              int64_t group_stride)
+{
+    if (conv_is_split(ctx, k)) {
+        int rc;
+        if ((rc = ensure(ctx, ctx->codes, (size_t)n * ((L2 + 7) / 8) * h * w))) return rc;
+        unsigned char *codes = (unsigned char *)ctx->codes.ptr;
+        if ((rc = launch_conv_split_codes(ctx, in, n, h, w, W, k, L2, codes))) return rc;
+        return launch_code_hist(ctx, codes, n, L2, h, w, bh, bw, sy, sx, out, feat_type, group, group_stride);
+    }
+    return launch_conv_hash_hist(ctx, in, n, h, w, W, k, L2, bh, bw, sy, sx, out, feat_type, group, group_stride);
 }
 
 int ddcca_learn_next_stage_filters(ddcca_ctx *ctx, const float *v1, const float *v2, const int32_t *cls, int64_t n_img,
@@ -596,9 +620,9 @@ static int extract_impl(ddcca_ctx *ctx, const float *v1, const float *v2, int64_
             if (!fused && (rc = run_conv(ctx, y, mb * L1, h, w, model->W[1][d], k, L2, z))) return rc;
             void *dst = reinterpret_cast<char *>(feat) + ((m0 * 2 + d) * L1) * A * bins * feat_elem_size(feat_type);
             if (fused)
-                rc = launch_conv_hash_hist(ctx, y, mb * L1, h, w, model->W[1][d], k, L2, model->block_h,
-                                           model->block_w, model->stride_y, model->stride_x, dst, feat_type, L1,
-                                           2 * L1 * A * bins);
+                rc = run_conv_hash_hist(ctx, y, mb * L1, h, w, model->W[1][d], k, L2, model->block_h,
+                                        model->block_w, model->stride_y, model->stride_x, dst, feat_type, L1,
+                                        2 * L1 * A * bins);
             else
                 rc = launch_hash_hist(ctx, z, mb * L1, L2, h, w, model->block_h, model->block_w, model->stride_y,
                                       model->stride_x, dst, feat_type, L1, 2 * L1 * A * bins);
@@ -632,8 +656,8 @@ int ddcca_apply_stage_hash(ddcca_ctx *ctx, const float *in, int64_t n, int h, in
     if (!in || !W || !out) return fail(ctx, DDCCA_EINVAL, "null data pointer");
     if ((rc = device_ready(ctx))) return rc;
     const int64_t A = (int64_t)((h - block_h) / stride_y + 1) * ((w - block_w) / stride_x + 1);
-    return launch_conv_hash_hist(ctx, in, n, h, w, W, k, L2, block_h, block_w, stride_y, stride_x, out, feat_type, 1,
-                                 A * ((int64_t)1 << L2));
+    return run_conv_hash_hist(ctx, in, n, h, w, W, k, L2, block_h, block_w, stride_y, stride_x, out, feat_type, 1,
+                              A * ((int64_t)1 << L2));
 }
 
 int ddcca_profile_enable(ddcca_ctx *ctx, int on)

@@ -83,6 +83,7 @@ struct ConvSplitParams {
     float *out;
     int h, w, L, tiles_x, tiles_y, th;
     long long n_items;          // images * tiles
+    unsigned char *codes;       // CODES kernels: [n][ceil(L/8)][h][w] hash code bytes instead of `out`
 };
 
 // A operand of lane (q, c) for output row u of a row group: row c of the instruction is filter g0 + c/2, shift
@@ -259,7 +260,11 @@ __device__ __forceinline__ void split_rows(const unsigned int *prow, const int (
     }
 }
 
-template <int KS, int NBX, int RU, int WAVES, bool VEC4>
+// CODES: the maps are not written.  The maps of an input are hashed on the spot (Eq. 7-9: bit g of the code =
+// [map g > 0]) and one byte per pixel and group of 8 filters leaves the kernel; the block histograms are counted
+// from the code maps by hash_hist_kernel<.., CODES>.  Same products and sums as the map-writing kernel, so the codes are those of its
+// maps bit for bit.
+template <int KS, int NBX, int RU, int WAVES, bool VEC4, bool CODES>
 __global__ __launch_bounds__(WAVES * 64) void conv_split_kernel(ConvSplitParams p)
 {
     typedef SplitConv<KS, NBX, RU> G;
@@ -302,6 +307,8 @@ __global__ __launch_bounds__(WAVES * 64) void conv_split_kernel(ConvSplitParams 
         int cur = 0;
         // uniform: every store of this pass is an aligned float2 (w even: pairs never straddle the edge)
         const bool fast = (w & 1) == 0 && (((uintptr_t)p.out) & 7) == 0 && g0 + 8 <= L;
+        // CODES: a lane's two codes (columns x, x+1) leave as one aligned 16-bit store
+        const bool code_pairs = (w & 1) == 0 && (((uintptr_t)p.codes) & 1) == 0;
         // lane (q,c) ends with planes g0+2q (acc[0..1]) and g0+2q+1 (acc[2..3]) at columns x, x+1
         const int ga = g0 + 2 * q;
         for (long long item = item0; item < item1; item += istep) {
@@ -324,6 +331,44 @@ __global__ __launch_bounds__(WAVES * 64) void conv_split_kernel(ConvSplitParams 
                 // and its surplus rows are not written)
                 floatx4 acc[RU][NBX];
                 split_rows<G, NBX, RU>(buf + r * G::PWORDS, toff, wa, acc);
+                if constexpr (CODES) {
+#pragma unroll
+                    for (int u = 0; u < RU; ++u) {
+                        // this lane's share of the codes of its column pair in every block: bits 2q, 2q+1 (its two
+                        // filters), low byte = column x, high byte = column x + 1; 16 bits per block
+                        unsigned int part[2] = {0u, 0u};
+#pragma unroll
+                        for (int b = 0; b < NBX; ++b) {
+                            unsigned int v = 0u;
+#pragma unroll
+                            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                                for (int j = 0; j < 2; ++j)
+                                    v |= (acc[u][b][2 * e + j] > 0.0f ? 1u : 0u) << (8 * j + 2 * q + e);
+                            part[b >> 1] |= v << (16 * (b & 1));
+                        }
+                        // OR over the four lane groups q (lanes c, c+16, c+32, c+48): every lane ends with all 8 bits
+#pragma unroll
+                        for (int i = 0; i < (NBX + 1) / 2; ++i) {
+                            part[i] |= (unsigned int)__shfl_xor((int)part[i], 16);
+                            part[i] |= (unsigned int)__shfl_xor((int)part[i], 32);
+                        }
+                        // lane group q writes block q: 64 lanes x 2 bytes = the 128 codes of the tile row
+                        const int x = tx * TW + q * CSPLIT_XB + 2 * c;
+                        if (r + u < rows && q < NBX && x < w) {
+                            const unsigned int two = (part[(q >> 1) & ((NBX + 1) / 2 - 1)] >> (16 * (q & 1))) & 0xffffu;
+                            unsigned char *d = p.codes + (n * ((L + 7) >> 3) + (g0 >> 3)) * P +
+                                               (int64_t)(ty * th + r + u) * w + x;
+                            if (code_pairs) {
+                                *reinterpret_cast<unsigned short *>(d) = (unsigned short)two;
+                            } else {
+                                d[0] = (unsigned char)(two & 0xffu);
+                                if (x + 1 < w) d[1] = (unsigned char)(two >> 8);
+                            }
+                        }
+                    }
+                    continue;
+                }
 #pragma unroll
                 for (int u = 0; u < RU; ++u) {
                     if (r + u >= rows) continue;
@@ -367,21 +412,21 @@ template <int KS> struct SplitShape { static constexpr int RU = 1, WAVES = 4; };
 template <> struct SplitShape<7> { static constexpr int RU = 2, WAVES = 4; };
 template <> struct SplitShape<3> { static constexpr int RU = 2, WAVES = 4; };
 
-template <int KS, int NBX, bool VEC4>
+template <int KS, int NBX, bool VEC4, bool CODES>
 static int conv_split_launch_vec(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int L,
-                                 float *out)
+                                 float *out, unsigned char *codes)
 {
     constexpr int RU = SplitShape<KS>::RU, WAVES = SplitShape<KS>::WAVES;
     typedef SplitConv<KS, NBX, RU> G;
     static_assert(2 * G::BUF * 4 * CSPLIT_WG_PER_CU <= 160 * 1024, "two workgroups per compute unit must fit in LDS");
     static bool attr_set[MAX_DEVICES] = {};      // per device: the attribute is set on that device's code object
     if (!attr_set[ctx->device]) {
-        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)conv_split_kernel<KS, NBX, RU, WAVES, VEC4>,
+        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)conv_split_kernel<KS, NBX, RU, WAVES, VEC4, CODES>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 2 * G::BUF * 4));
         attr_set[ctx->device] = true;
     }
     ConvSplitParams p;
-    p.in = in; p.W = W; p.out = out; p.h = h; p.w = w; p.L = L;
+    p.in = in; p.W = W; p.out = out; p.codes = codes; p.h = h; p.w = w; p.L = L;
     p.tiles_x = (w + G::TW - 1) / G::TW;
     // equal tile heights of at most CSPLIT_TH_MAX rows, a multiple of the rows one pass of the workgroup covers
     constexpr int PASS = RU * WAVES;
@@ -390,34 +435,35 @@ static int conv_split_launch_vec(ddcca_ctx *ctx, const float *in, int64_t n, int
     p.tiles_y = (h + p.th - 1) / p.th;
     p.n_items = (long long)n * p.tiles_x * p.tiles_y;
     const unsigned grid = (unsigned)std::min(p.n_items, (long long)CSPLIT_WG_PER_CU * ctx->n_cu);
-    hipLaunchKernelGGL((conv_split_kernel<KS, NBX, RU, WAVES, VEC4>), dim3(grid), dim3(WAVES * 64), 2 * G::BUF * 4,
+    hipLaunchKernelGGL((conv_split_kernel<KS, NBX, RU, WAVES, VEC4, CODES>), dim3(grid), dim3(WAVES * 64), 2 * G::BUF * 4,
                        ctx->stream, p);
     DDCCA_HIP(ctx, hipGetLastError());
     return DDCCA_OK;
 }
 
-template <int KS, int NBX>
+template <int KS, int NBX, bool CODES>
 static int conv_split_launch_nbx(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int L,
-                                 float *out)
+                                 float *out, unsigned char *codes)
 {
     // 16-byte loads when every image row starts on a 16-byte boundary
-    if ((w & 3) == 0 && (((uintptr_t)in) & 15) == 0) return conv_split_launch_vec<KS, NBX, true>(ctx, in, n, h, w, W, L, out);
-    return conv_split_launch_vec<KS, NBX, false>(ctx, in, n, h, w, W, L, out);
+    if ((w & 3) == 0 && (((uintptr_t)in) & 15) == 0)
+        return conv_split_launch_vec<KS, NBX, true, CODES>(ctx, in, n, h, w, W, L, out, codes);
+    return conv_split_launch_vec<KS, NBX, false, CODES>(ctx, in, n, h, w, W, L, out, codes);
 }
 
-template <int KS>
+template <int KS, bool CODES>
 static int conv_split_launch(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int L,
-                             float *out)
+                             float *out, unsigned char *codes)
 {
     // equal-width tiles of at most CSPLIT_MAX_NBX column blocks
     const int xblocks = (w + CSPLIT_XB - 1) / CSPLIT_XB;
     const int tiles_x = (xblocks + CSPLIT_MAX_NBX - 1) / CSPLIT_MAX_NBX;
     const int nbx = (xblocks + tiles_x - 1) / tiles_x;
     switch (nbx) {
-        case 1: return conv_split_launch_nbx<KS, 1>(ctx, in, n, h, w, W, L, out);
-        case 2: return conv_split_launch_nbx<KS, 2>(ctx, in, n, h, w, W, L, out);
-        case 3: return conv_split_launch_nbx<KS, 3>(ctx, in, n, h, w, W, L, out);
-        default: return conv_split_launch_nbx<KS, 4>(ctx, in, n, h, w, W, L, out);
+        case 1: return conv_split_launch_nbx<KS, 1, CODES>(ctx, in, n, h, w, W, L, out, codes);
+        case 2: return conv_split_launch_nbx<KS, 2, CODES>(ctx, in, n, h, w, W, L, out, codes);
+        case 3: return conv_split_launch_nbx<KS, 3, CODES>(ctx, in, n, h, w, W, L, out, codes);
+        default: return conv_split_launch_nbx<KS, 4, CODES>(ctx, in, n, h, w, W, L, out, codes);
     }
 }
 
@@ -426,10 +472,25 @@ int launch_conv_split(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, 
 {
     ProfScope prof(ctx, DDCCA_K_CONV);
     switch (k) {
-        case 3: return conv_split_launch<3>(ctx, in, n, h, w, W, L, out);
-        case 5: return conv_split_launch<5>(ctx, in, n, h, w, W, L, out);
-        case 7: return conv_split_launch<7>(ctx, in, n, h, w, W, L, out);
-        case 9: return conv_split_launch<9>(ctx, in, n, h, w, W, L, out);
+        case 3: return conv_split_launch<3, false>(ctx, in, n, h, w, W, L, out, nullptr);
+        case 5: return conv_split_launch<5, false>(ctx, in, n, h, w, W, L, out, nullptr);
+        case 7: return conv_split_launch<7, false>(ctx, in, n, h, w, W, L, out, nullptr);
+        case 9: return conv_split_launch<9, false>(ctx, in, n, h, w, W, L, out, nullptr);
+        default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
+    }
+}
+
+// The hash codes (Eq. 7-9) of the L maps this convolution would write: codes[n][ceil(L/8)][h][w], byte i of a pixel
+// = bits 8i .. 8i+7 of its code.
+int launch_conv_split_codes(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L,
+                            unsigned char *codes)
+{
+    ProfScope prof(ctx, DDCCA_K_CONV_HASH_HIST);
+    switch (k) {
+        case 3: return conv_split_launch<3, true>(ctx, in, n, h, w, W, L, nullptr, codes);
+        case 5: return conv_split_launch<5, true>(ctx, in, n, h, w, W, L, nullptr, codes);
+        case 7: return conv_split_launch<7, true>(ctx, in, n, h, w, W, L, nullptr, codes);
+        case 9: return conv_split_launch<9, true>(ctx, in, n, h, w, W, L, nullptr, codes);
         default: return fail(ctx, DDCCA_EINVAL, "unsupported k");
     }
 }

@@ -56,6 +56,7 @@ struct ddcca_ctx {
     ddcca::Buffer flags;                    // int[4]: [0] label error, [1] Cholesky pivot, [2] Jacobi sweeps exhausted
     bool static_solve_used = false;         // ddcca_dcca_solve_noalloc ran: its conditions sit in the static scratch
     ddcca::Buffer maps1, maps2;             // extract_features scratch
+    ddcca::Buffer codes;                    // hash codes of a batch, one byte per pixel (fused last stage)
     ddcca::Buffer iq_lut;                   // information-quality table of the output layer
     int64_t iq_lut_total = 0;               // block area + bins the table was built for (0 = none)
     int iq_lut_n = 0;
@@ -159,6 +160,12 @@ int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h
 int prepare_iq_table(ddcca_ctx *ctx, int out_type, int bh, int bw, int L2, const float **lut, int *lut_n,
                      double *log_total);
 // stage convolution of n input maps with the L2 filters W fused with hashing + block histograms: the
+// the fused last stage in two kernels when the convolution runs on three-piece operands: the convolution writes
+// the hash codes of its (at most 8) maps, one byte per pixel, and the histograms are counted from those
+int launch_conv_split_codes(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L,
+                            unsigned char *codes);
+int launch_code_hist(ddcca_ctx *ctx, const unsigned char *codes, int64_t n, int L2, int h, int w, int bh, int bw,
+                     int sy, int sx, void *out, int out_type, int64_t group, int64_t group_stride);
 // same output as launch_conv followed by launch_hash_hist, without the maps in between
 int launch_conv_hash_hist(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int k, int L2,
                           int bh, int bw, int sy, int sx, void *out, int out_type, int64_t group,

@@ -35,6 +35,7 @@ constexpr int SWEEP_LDS_BYTES = 40 * 1024;  // the same for the ring of the swee
 
 struct HistParams {
     const float *maps;
+    const unsigned char *codes;   // CODES kernels: [n][ceil(L2/8)][h][w] hash code bytes (the maps are not read)
     void *hist;         // uint16 counts, or fp32 / fp16 information quality
     const float *lut;   // information-quality table, lut[c] = log(total) - log(c + 1)
     int lut_n;
@@ -128,7 +129,9 @@ __global__ void iq_lut_kernel(double total, int n, float *lut)
     for (int c = threadIdx.x; c < n; c += blockDim.x) lut[c] = (float)(log_total - log((double)(c + 1)));
 }
 
-template <int L2, int OUT>
+// CODES: the input is the hash code itself, one byte plane per 8 filters (written by the convolution that would
+// have written the maps), instead of L2 planes of floats.
+template <int L2, int OUT, bool CODES = false>
 __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p, int lds_hist_words)
 {
     extern __shared__ unsigned int lds_hist[];
@@ -156,7 +159,9 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p, i
     __syncthreads();
 
     const int64_t P = (int64_t)p.h * p.w;
-    const float *base = p.maps + n * L2 * P;
+    const float *base = CODES ? nullptr : p.maps + n * L2 * P;
+    constexpr int CP = (L2 + 7) / 8;                                 // code byte planes
+    const unsigned char *cbase = CODES ? p.codes + n * CP * P : nullptr;
     const int y_lo = i0 * p.sy, y_hi = (i1 - 1) * p.sy + p.bh;       // rows [y_lo, y_hi)
     const int x_lo = j0 * p.sx, x_hi = (j1 - 1) * p.sx + p.bw;       // columns [x_lo, x_hi)
     // threads as TROWS rows x TCOLS columns of work items (no per-item index division); a
@@ -171,17 +176,29 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p, i
         for (int y = y_lo + trow; y < y_hi; y += TROWS) {
             int ilo, ihi;
             block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
-            const float *row = base + (int64_t)y * p.w;
+            const float *row = CODES ? nullptr : base + (int64_t)y * p.w;
             for (int xq = q_lo + tcol; xq < q_hi; xq += TCOLS) {
-                const float *src = row + 4 * xq;
                 unsigned c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+                if constexpr (CODES) {
 #pragma unroll
-                for (int l = 0; l < L2; ++l) {
-                    const float4 v = *reinterpret_cast<const float4 *>(src + l * P);
-                    c0 |= (v.x > 0.0f ? 1u : 0u) << l;
-                    c1 |= (v.y > 0.0f ? 1u : 0u) << l;
-                    c2 |= (v.z > 0.0f ? 1u : 0u) << l;
-                    c3 |= (v.w > 0.0f ? 1u : 0u) << l;
+                    for (int i = 0; i < CP; ++i) {
+                        const unsigned int v =
+                            *reinterpret_cast<const unsigned int *>(cbase + i * P + (int64_t)y * p.w + 4 * xq);
+                        c0 |= (v & 0xffu) << (8 * i);
+                        c1 |= ((v >> 8) & 0xffu) << (8 * i);
+                        c2 |= ((v >> 16) & 0xffu) << (8 * i);
+                        c3 |= (v >> 24) << (8 * i);
+                    }
+                } else {
+                    const float *src = row + 4 * xq;
+#pragma unroll
+                    for (int l = 0; l < L2; ++l) {
+                        const float4 v = *reinterpret_cast<const float4 *>(src + l * P);
+                        c0 |= (v.x > 0.0f ? 1u : 0u) << l;
+                        c1 |= (v.y > 0.0f ? 1u : 0u) << l;
+                        c2 |= (v.z > 0.0f ? 1u : 0u) << l;
+                        c3 |= (v.w > 0.0f ? 1u : 0u) << l;
+                    }
                 }
                 const int x = 4 * xq;
                 if (x >= x_lo && x < x_hi) hist_add<L2>(lds_hist, p, x, c0, ilo, ihi, i0, j0, j1, ncol);
@@ -194,11 +211,16 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p, i
         for (int y = y_lo + trow; y < y_hi; y += TROWS) {
             int ilo, ihi;
             block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
-            const float *row = base + (int64_t)y * p.w;
+            const float *row = CODES ? nullptr : base + (int64_t)y * p.w;
             for (int x = x_lo + tcol; x < x_hi; x += TCOLS) {
                 unsigned code = 0;
+                if constexpr (CODES) {
 #pragma unroll
-                for (int l = 0; l < L2; ++l) code |= (row[l * P + x] > 0.0f ? 1u : 0u) << l;
+                    for (int i = 0; i < CP; ++i) code |= (unsigned)cbase[i * P + (int64_t)y * p.w + x] << (8 * i);
+                } else {
+#pragma unroll
+                    for (int l = 0; l < L2; ++l) code |= (row[l * P + x] > 0.0f ? 1u : 0u) << l;
+                }
                 hist_add<L2>(lds_hist, p, x, code, ilo, ihi, i0, j0, j1, ncol);
             }
         }
@@ -284,7 +306,7 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_sweep_kernel(HistParam
     }
 }
 
-template <int L2, int OUT>
+template <int L2, int OUT, bool CODES = false>
 static void hist_launch(ddcca_ctx *ctx, HistParams p, int64_t n)
 {
     constexpr int BINS = 1 << L2;
@@ -293,7 +315,7 @@ static void hist_launch(ddcca_ctx *ctx, HistParams p, int64_t n)
     // sweep kernel: aligned float4 rows and a ring of block rows within the LDS budget.  A phase covers m block
     // strides (enough rows for about two 4-pixel groups per thread); during it the block rows from the oldest
     // incomplete one to the newest one touched are live: ceil(bh / sy) + m - 1 of them.
-    if (p.vec4 && (p.nbx - 1) * p.sx + p.bw > 128) {
+    if (!CODES && p.vec4 && (p.nbx - 1) * p.sx + p.bw > 128) {
         const int row_bytes = p.nbx * HIST_BYTES;
         const int live = (p.bh + p.sy - 1) / p.sy;
         const int quads_per_stride = (((p.nbx - 1) * p.sx + p.bw + 3) / 4) * p.sy;
@@ -331,9 +353,10 @@ static void hist_launch(ddcca_ctx *ctx, HistParams p, int64_t n)
     for (int64_t n0 = 0; n0 < n; n0 += maps_per_launch) {
         const int64_t nb = std::min(maps_per_launch, n - n0);
         HistParams q = p;
-        q.maps = p.maps + n0 * L2 * (int64_t)p.h * p.w;
+        if (CODES) q.codes = p.codes + n0 * ((L2 + 7) / 8) * (int64_t)p.h * p.w;
+        else q.maps = p.maps + n0 * L2 * (int64_t)p.h * p.w;
         q.hist = reinterpret_cast<char *>(p.hist) + (n0 / p.group) * p.group_stride * ESZ;
-        hipLaunchKernelGGL((hash_hist_kernel<L2, OUT>), dim3((unsigned)(nb * per_map)), dim3(HIST_THREADS), lds,
+        hipLaunchKernelGGL((hash_hist_kernel<L2, OUT, CODES>), dim3((unsigned)(nb * per_map)), dim3(HIST_THREADS), lds,
                            ctx->stream, q, hist_words);
     }
 }
@@ -341,6 +364,15 @@ static void hist_launch(ddcca_ctx *ctx, HistParams p, int64_t n)
 template <int OUT>
 static int hist_dispatch(ddcca_ctx *ctx, const HistParams &p, int64_t n, int L2)
 {
+    if (p.codes) {
+        switch (L2) {
+#define CASE(v) case v: hist_launch<v, OUT, true>(ctx, p, n); break;
+            CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12)
+#undef CASE
+            default: return fail(ctx, DDCCA_EINVAL, "L2 out of range");
+        }
+        return DDCCA_OK;
+    }
     switch (L2) {
 #define CASE(v) case v: hist_launch<v, OUT>(ctx, p, n); break;
         CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9) CASE(10) CASE(11) CASE(12)
@@ -375,22 +407,25 @@ int prepare_iq_table(ddcca_ctx *ctx, int out_type, int bh, int bw, int L2, const
     return DDCCA_OK;
 }
 
-int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int bh, int bw, int sy,
-                     int sx, void *out, int out_type, int64_t group, int64_t group_stride)
+static int hist_run(ddcca_ctx *ctx, const float *maps, const unsigned char *codes, int64_t n, int L2, int h, int w,
+                    int bh, int bw, int sy, int sx, void *out, int out_type, int64_t group, int64_t group_stride,
+                    int kernel_id)
 {
     HistParams p;
-    p.maps = maps; p.hist = out;
+    p.maps = maps; p.codes = codes; p.hist = out;
     p.h = h; p.w = w; p.bh = bh; p.bw = bw; p.sy = sy; p.sx = sx;
     p.nby = (h - bh) / sy + 1;
     p.nbx = (w - bw) / sx + 1;
     p.group = group; p.group_stride = group_stride;
-    p.vec4 = ((w & 3) == 0 && (((uintptr_t)maps) & 15) == 0) ? 1 : 0;
+    // rows readable as aligned groups of four pixels: 16 bytes of floats, or 4 bytes of codes
+    p.vec4 = codes ? (((w & 3) == 0 && (((uintptr_t)codes) & 3) == 0) ? 1 : 0)
+                   : (((w & 3) == 0 && (((uintptr_t)maps) & 15) == 0) ? 1 : 0);
     const bool small = h < 65536 && w < 65536;
     p.magic_sy = small ? (unsigned)((((uint64_t)1 << 32) + sy - 1) / sy) : 0u;
     p.magic_sx = small ? (unsigned)((((uint64_t)1 << 32) + sx - 1) / sx) : 0u;
     int rc;
     if ((rc = prepare_iq_table(ctx, out_type, bh, bw, L2, &p.lut, &p.lut_n, &p.log_total))) return rc;
-    ProfScope prof(ctx, DDCCA_K_HASH_HIST);
+    ProfScope prof(ctx, kernel_id);
     switch (out_type) {
         case DDCCA_FEAT_COUNT_U16: rc = hist_dispatch<DDCCA_FEAT_COUNT_U16>(ctx, p, n, L2); break;
         case DDCCA_FEAT_IQ_F32: rc = hist_dispatch<DDCCA_FEAT_IQ_F32>(ctx, p, n, L2); break;
@@ -400,6 +435,22 @@ int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h
     if (rc) return rc;
     DDCCA_HIP(ctx, hipGetLastError());
     return DDCCA_OK;
+}
+
+int launch_hash_hist(ddcca_ctx *ctx, const float *maps, int64_t n, int L2, int h, int w, int bh, int bw, int sy,
+                     int sx, void *out, int out_type, int64_t group, int64_t group_stride)
+{
+    return hist_run(ctx, maps, nullptr, n, L2, h, w, bh, bw, sy, sx, out, out_type, group, group_stride,
+                    DDCCA_K_HASH_HIST);
+}
+
+// The same histograms from code maps (one byte per pixel and 8 filters, launch_conv_split_codes): the second half of the fused
+// last stage when the convolution runs on three-piece operands.
+int launch_code_hist(ddcca_ctx *ctx, const unsigned char *codes, int64_t n, int L2, int h, int w, int bh, int bw,
+                     int sy, int sx, void *out, int out_type, int64_t group, int64_t group_stride)
+{
+    return hist_run(ctx, nullptr, codes, n, L2, h, w, bh, bw, sy, sx, out, out_type, group, group_stride,
+                    DDCCA_K_CONV_HASH_HIST);
 }
 
 }  // namespace ddcca

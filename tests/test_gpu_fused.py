@@ -1,4 +1,4 @@
-"""GPU tests of the fused last stage (stage convolution + hashing + block histograms in one kernel).
+"""GPU tests of the fused last stage (stage convolution + hashing + block histograms without the maps in memory).
 
 Against the oracle: conv (Eq. 6) -> hash (Eq. 7-9) -> block histogram, relative L1 of the counts <= 1e-3 (the
 end-to-end histogram bar: a map value within fp32 rounding of zero may hash differently in fp32 and fp64).
@@ -15,16 +15,17 @@ from paper_2209_13027_amd.workloads import WORKLOADS, make_views  # noqa: E402
 from paper_2209_13027_amd import pipeline  # noqa: E402
 
 
-@pytest.fixture(scope="module")
-def ctx():
+@pytest.fixture(scope="module", params=["fp32", "bf16x3"])
+def ctx(request):
+    """The fused last stage runs in the arithmetic the stage convolution has, so that its bit-exact reference is the
+    unfused path of the same context: with the fp32 matrix instructions one kernel (convolution, hashing and
+    histograms around a ring of block rows); with three-piece bf16 operands the convolution kernel writes the hash
+    codes of its maps (one byte per pixel and 8 filters) and the histograms are counted from those."""
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    from paper_2209_13027_amd.binding import Context
+    from paper_2209_13027_amd.binding import Context, OPT_CONV_ARITH, CONV_FP32, CONV_BF16X3
     c = Context(0)
-    # the fused kernel contracts with the fp32 matrix instructions: its bit-exact reference is the unfused path in
-    # the same arithmetic
-    from paper_2209_13027_amd.binding import OPT_CONV_ARITH, CONV_FP32
-    c.set_option(OPT_CONV_ARITH, CONV_FP32)
+    c.set_option(OPT_CONV_ARITH, CONV_FP32 if request.param == "fp32" else CONV_BF16X3)
     yield c
     c.close()
 
