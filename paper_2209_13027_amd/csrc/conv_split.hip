@@ -309,6 +309,13 @@ __global__ __launch_bounds__(WAVES * 64) void conv_split_kernel(ConvSplitParams 
         const bool fast = (w & 1) == 0 && (((uintptr_t)p.out) & 7) == 0 && g0 + 8 <= L;
         // CODES: a lane's two codes (columns x, x+1) leave as one aligned 16-bit store
         const bool code_pairs = (w & 1) == 0 && (((uintptr_t)p.codes) & 1) == 0;
+        // CODES: where the sign of accumulator entry 2e + j of an even / odd column block goes in the lane's packed
+        // word: bit 2q + e (the filter) of byte j (the column) of the block's 16 bits
+        unsigned int code_bit[2][4];
+#pragma unroll
+        for (int ob = 0; ob < 2; ++ob)
+#pragma unroll
+            for (int ej = 0; ej < 4; ++ej) code_bit[ob][ej] = 1u << (16 * ob + 8 * (ej & 1) + 2 * q + (ej >> 1));
         // lane (q,c) ends with planes g0+2q (acc[0..1]) and g0+2q+1 (acc[2..3]) at columns x, x+1
         const int ga = g0 + 2 * q;
         for (long long item = item0; item < item1; item += istep) {
@@ -341,11 +348,8 @@ __global__ __launch_bounds__(WAVES * 64) void conv_split_kernel(ConvSplitParams 
                         for (int b = 0; b < NBX; ++b) {
                             unsigned int v = 0u;
 #pragma unroll
-                            for (int e = 0; e < 2; ++e)
-#pragma unroll
-                                for (int j = 0; j < 2; ++j)
-                                    v |= (acc[u][b][2 * e + j] > 0.0f ? 1u : 0u) << (8 * j + 2 * q + e);
-                            part[b >> 1] |= v << (16 * (b & 1));
+                            for (int ej = 0; ej < 4; ++ej) v |= acc[u][b][ej] > 0.0f ? code_bit[b & 1][ej] : 0u;
+                            part[b >> 1] |= v;
                         }
                         // OR over the four lane groups q (lanes c, c+16, c+32, c+48): every lane ends with all 8 bits
 #pragma unroll

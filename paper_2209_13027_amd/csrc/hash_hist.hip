@@ -170,7 +170,41 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p, i
     const int wide = (x_hi - x_lo) > 128 ? 1 : 0;
     const int TCOLS = wide ? 64 : 32, TROWS = HIST_THREADS / TCOLS;
     const int tcol = threadIdx.x & (TCOLS - 1), trow = threadIdx.x / TCOLS;
-    if (p.vec4) {
+    if (CODES && p.vec4) {
+        // Code maps: no load latency to hide the bookkeeping behind, so the loops are turned inside out: a thread
+        // keeps its group of four columns, whose block columns are found once, and walks down the rows.
+        const int q_lo = x_lo >> 2, q_hi = (x_hi + 3) >> 2;
+        for (int xq = q_lo + tcol; xq < q_hi; xq += TCOLS) {
+            int jlo[4], jhi[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int x = 4 * xq + k;
+                block_range(x, p.bw, p.sx, p.magic_sx, j0, j1, jlo[k], jhi[k]);
+                if (x < x_lo || x >= x_hi) jhi[k] = jlo[k] - 1;          // not a column of this workgroup: no block
+            }
+            for (int y = y_lo + trow; y < y_hi; y += TROWS) {
+                int ilo, ihi;
+                block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
+                unsigned c[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int i = 0; i < CP; ++i) {
+                    const unsigned int v =
+                        *reinterpret_cast<const unsigned int *>(cbase + i * P + (int64_t)y * p.w + 4 * xq);
+                    c[0] |= (v & 0xffu) << (8 * i);
+                    c[1] |= ((v >> 8) & 0xffu) << (8 * i);
+                    c[2] |= ((v >> 16) & 0xffu) << (8 * i);
+                    c[3] |= (v >> 24) << (8 * i);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const unsigned inc = 1u << (16 * (c[k] & 1));
+                    unsigned int *cell = lds_hist + (c[k] >> 1) - j0 * WORDS;
+                    for (int i = ilo; i <= ihi; ++i)
+                        for (int j = jlo[k]; j <= jhi[k]; ++j) atomicAdd(cell + ((i - i0) * ncol + j) * WORDS, inc);
+                }
+            }
+        }
+    } else if (p.vec4) {
         // aligned quads of 4 pixels; the quad range covers [x_lo, x_hi) and is clipped per pixel
         const int q_lo = x_lo >> 2, q_hi = (x_hi + 3) >> 2;
         for (int y = y_lo + trow; y < y_hi; y += TROWS) {
@@ -179,26 +213,14 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p, i
             const float *row = CODES ? nullptr : base + (int64_t)y * p.w;
             for (int xq = q_lo + tcol; xq < q_hi; xq += TCOLS) {
                 unsigned c0 = 0, c1 = 0, c2 = 0, c3 = 0;
-                if constexpr (CODES) {
+                const float *src = row + 4 * xq;
 #pragma unroll
-                    for (int i = 0; i < CP; ++i) {
-                        const unsigned int v =
-                            *reinterpret_cast<const unsigned int *>(cbase + i * P + (int64_t)y * p.w + 4 * xq);
-                        c0 |= (v & 0xffu) << (8 * i);
-                        c1 |= ((v >> 8) & 0xffu) << (8 * i);
-                        c2 |= ((v >> 16) & 0xffu) << (8 * i);
-                        c3 |= (v >> 24) << (8 * i);
-                    }
-                } else {
-                    const float *src = row + 4 * xq;
-#pragma unroll
-                    for (int l = 0; l < L2; ++l) {
-                        const float4 v = *reinterpret_cast<const float4 *>(src + l * P);
-                        c0 |= (v.x > 0.0f ? 1u : 0u) << l;
-                        c1 |= (v.y > 0.0f ? 1u : 0u) << l;
-                        c2 |= (v.z > 0.0f ? 1u : 0u) << l;
-                        c3 |= (v.w > 0.0f ? 1u : 0u) << l;
-                    }
+                for (int l = 0; l < L2; ++l) {
+                    const float4 v = *reinterpret_cast<const float4 *>(src + l * P);
+                    c0 |= (v.x > 0.0f ? 1u : 0u) << l;
+                    c1 |= (v.y > 0.0f ? 1u : 0u) << l;
+                    c2 |= (v.z > 0.0f ? 1u : 0u) << l;
+                    c3 |= (v.w > 0.0f ? 1u : 0u) << l;
                 }
                 const int x = 4 * xq;
                 if (x >= x_lo && x < x_hi) hist_add<L2>(lds_hist, p, x, c0, ilo, ihi, i0, j0, j1, ncol);
