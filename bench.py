@@ -53,10 +53,11 @@ def algorithmic_work(wl, M, feat_bytes=2):
     }
 
 
-def measured_traffic(workload, kernel_prefix, must_contain=""):
-    """HBM bytes per launch (read + write) of the kernels whose name starts with `kernel_prefix`, from the
+def measured_traffic(workload, kernel_regex):
+    """HBM bytes per launch (read + write) of the kernels whose name matches `kernel_regex`, from the
     rocprofv3 --pmc passes summarised in profiles/traffic.json (FETCH_SIZE / WRITE_SIZE scaled by a plain
     copy of known size); None when no profile of this workload is committed."""
+    import re
     path = os.path.join(ROOT, "profiles", "traffic.json")
     if not os.path.exists(path):
         return None
@@ -66,7 +67,7 @@ def measured_traffic(workload, kernel_prefix, must_contain=""):
         return None
     tot_bytes, tot_launches = 0.0, 0
     for name, v in data.items():
-        if name.startswith(kernel_prefix) and must_contain in name and "read_mib_per_launch" in v:
+        if re.match(kernel_regex, name) and "read_mib_per_launch" in v:
             tot_bytes += v["launches"] * (v["read_mib_per_launch"] + v["write_mib_per_launch"]) * 1048576.0
             tot_launches += v["launches"]
     return tot_bytes / tot_launches if tot_launches else None
@@ -333,7 +334,9 @@ def measure(name, args, K, W, detail):
         kernels["conv_hash_hist"] = {"ms_per_step": fused_ms, "tflops": per(fused_flops, fused_ms) / 1e12,
                                      "frac_mfma_fp32": per(fused_flops, fused_ms) / 1e12 / PEAK_MFMA_FP32_TFLOPS,
                                      "gbs": per(fused_bytes, fused_ms) / 1e9}
-    traffic = measured_traffic(wl.name, "patch_gram_kernel", ", false,") if args.gram == "fp32" else None
+    # (the all-tiles, fp32, maps-from-memory instantiation: patch_gram_kernel<k, tsplit, false, waves, false, false>)
+    traffic = (measured_traffic(wl.name, r"patch_gram_kernel<\d+, \d+, false, \d+, false, false>")
+               if args.gram == "fp32" else None)
     # the peak the dominant kernel is held against: the fp32 matrix instructions; with three-piece bf16 operands one
     # fp32 product costs six bf16 products, so the ceiling for fp32-equivalent flop is a sixth of the bf16 peak
     gram_peak, gram_note = PEAK_MFMA_FP32_TFLOPS, None
