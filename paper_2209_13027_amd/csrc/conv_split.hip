@@ -438,7 +438,17 @@ static int conv_split_launch_vec(ddcca_ctx *ctx, const float *in, int64_t n, int
     p.th = std::min(CSPLIT_TH_MAX, ((h + nty - 1) / nty + PASS - 1) / PASS * PASS);
     p.tiles_y = (h + p.th - 1) / p.th;
     p.n_items = (long long)n * p.tiles_x * p.tiles_y;
-    const unsigned grid = (unsigned)std::min(p.n_items, (long long)CSPLIT_WG_PER_CU * ctx->n_cu);
+    unsigned grid = (unsigned)std::min(p.n_items, (long long)CSPLIT_WG_PER_CU * ctx->n_cu);
+    // Workgroup b takes items b, b + grid, ...: with a grid that shares a factor with the tiles of an image, a
+    // workgroup would meet only some of an image's tiles over and over -- and when the last tile row or column is
+    // smaller than the others, always the small ones or never (112 rows in tiles of 32: a quarter of the
+    // workgroups idle half of the time).  A grid coprime to the tile count deals every kind of tile to every
+    // workgroup.
+    const int tiles = p.tiles_x * p.tiles_y;
+    if ((h % p.th != 0 || w % G::TW != 0) && p.n_items > grid) {
+        auto gcd = [](unsigned a, unsigned b) { while (b) { const unsigned t = a % b; a = b; b = t; } return a; };
+        while (grid > 1 && gcd(grid, (unsigned)tiles) != 1) --grid;
+    }
     hipLaunchKernelGGL((conv_split_kernel<KS, NBX, RU, WAVES, VEC4, CODES>), dim3(grid), dim3(WAVES * 64), 2 * G::BUF * 4,
                        ctx->stream, p);
     DDCCA_HIP(ctx, hipGetLastError());
