@@ -217,6 +217,26 @@ def test_dcca_solve_max_filters(ctx, oracle):
     assert np.abs(filter_cosines(W1.cpu().numpy(), sol["W1"]))[ok].min() >= 0.9999
 
 
+def test_dcca_solve_largest_patch_with_every_pair(ctx, oracle):
+    """k = 9 with all D - 1 = 80 pairs: the largest problem the solve takes (more pairs than the 64 lane groups that
+    write them out in one pass)."""
+    rng = np.random.default_rng(19)
+    V1, V2 = rand_views(rng, 8, 24, 24)
+    cls = np.array([0, 1, 2, 3, 0, 1, 2, 3], np.int32)
+    mats = oracle.stage_matrices(V1, V2, cls, np.zeros(8, np.int32), 4, 1, 9)
+    L = 80
+    sol = oracle.dcca_solve(mats["C11"], mats["C22"], mats["Ctilde"], L)
+    W1, W2, rho = ctx.dcca_solve(dev(mats["C11"]), dev(mats["C22"]), dev(mats["Cw"]), dev(mats["CT"]), 9, L)
+    ctx.status()
+    rho, W1, W2 = rho.cpu().numpy(), W1.cpu().numpy(), W2.cpu().numpy()
+    assert np.all(np.isfinite(W1)) and np.all(np.isfinite(W2))
+    assert np.abs(rho - sol["rho"]).max() <= 1e-8 * sol["rho"][0]
+    ok = sol["gap"] > 1e-3
+    assert ok.sum() >= 20
+    assert filter_cosines(W1, sol["W1"])[ok].min() >= 0.9999
+    assert filter_cosines(W2, sol["W2"])[ok].min() >= 0.9999
+
+
 def test_bad_label_poisons_the_filters(ctx):
     """A label outside [0, n_cls) leaves its sample out of C_w / C_T: the solve of such an accumulation writes
     NaN instead of filters of inconsistent matrices, and ddcca_status reports and clears the condition."""
