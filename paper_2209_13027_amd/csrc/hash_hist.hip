@@ -32,6 +32,7 @@ namespace ddcca {
 constexpr int HIST_THREADS = 256;
 constexpr int HIST_LDS_BYTES = 32 * 1024;   // histogram bytes per workgroup (occupancy 4-5 per CU)
 constexpr int SWEEP_LDS_BYTES = 40 * 1024;  // the same for the ring of the sweep kernel
+constexpr int CODE_ROWS = 8;                // code-map rows a thread has in flight
 
 struct HistParams {
     const float *maps;
@@ -182,25 +183,39 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p, i
                 block_range(x, p.bw, p.sx, p.magic_sx, j0, j1, jlo[k], jhi[k]);
                 if (x < x_lo || x >= x_hi) jhi[k] = jlo[k] - 1;          // not a column of this workgroup: no block
             }
-            for (int y = y_lo + trow; y < y_hi; y += TROWS) {
-                int ilo, ihi;
-                block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
-                unsigned c[4] = {0u, 0u, 0u, 0u};
+            // the code words of the thread's next CODE_ROWS rows are all requested before the first is used: one
+            // small load per row and thread, waited for one by one, would leave the workgroup idle for a memory
+            // round trip per row
+            for (int yb = y_lo + trow; yb < y_hi; yb += CODE_ROWS * TROWS) {
+                unsigned int v[CODE_ROWS][CP];
 #pragma unroll
-                for (int i = 0; i < CP; ++i) {
-                    const unsigned int v =
-                        *reinterpret_cast<const unsigned int *>(cbase + i * P + (int64_t)y * p.w + 4 * xq);
-                    c[0] |= (v & 0xffu) << (8 * i);
-                    c[1] |= ((v >> 8) & 0xffu) << (8 * i);
-                    c[2] |= ((v >> 16) & 0xffu) << (8 * i);
-                    c[3] |= (v >> 24) << (8 * i);
+                for (int r = 0; r < CODE_ROWS; ++r) {
+                    const int y = min(yb + r * TROWS, y_hi - 1);                 // (a row past the end: reloaded, unused)
+#pragma unroll
+                    for (int i = 0; i < CP; ++i)
+                        v[r][i] = *reinterpret_cast<const unsigned int *>(cbase + i * P + (int64_t)y * p.w + 4 * xq);
                 }
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const unsigned inc = 1u << (16 * (c[k] & 1));
-                    unsigned int *cell = lds_hist + (c[k] >> 1) - j0 * WORDS;
-                    for (int i = ilo; i <= ihi; ++i)
-                        for (int j = jlo[k]; j <= jhi[k]; ++j) atomicAdd(cell + ((i - i0) * ncol + j) * WORDS, inc);
+                for (int r = 0; r < CODE_ROWS; ++r) {
+                    const int y = yb + r * TROWS;
+                    if (y >= y_hi) break;
+                    int ilo, ihi;
+                    block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
+                    unsigned c[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                    for (int i = 0; i < CP; ++i) {
+                        c[0] |= (v[r][i] & 0xffu) << (8 * i);
+                        c[1] |= ((v[r][i] >> 8) & 0xffu) << (8 * i);
+                        c[2] |= ((v[r][i] >> 16) & 0xffu) << (8 * i);
+                        c[3] |= (v[r][i] >> 24) << (8 * i);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const unsigned inc = 1u << (16 * (c[k] & 1));
+                        unsigned int *cell = lds_hist + (c[k] >> 1) - j0 * WORDS;
+                        for (int i = ilo; i <= ihi; ++i)
+                            for (int j = jlo[k]; j <= jhi[k]; ++j) atomicAdd(cell + ((i - i0) * ncol + j) * WORDS, inc);
+                    }
                 }
             }
         }
