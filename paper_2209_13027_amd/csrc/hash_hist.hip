@@ -10,15 +10,17 @@
 //
 // Two kernels.  hash_hist_kernel (any geometry): one workgroup owns RB consecutive block rows
 // of one map and a chunk of block columns; with overlapping blocks the pixel rows that two
-// groups of block rows share are read by both.  hash_hist_sweep_kernel (wide maps whose rows
-// are readable as aligned float4, a ring of block rows fits in LDS): one workgroup sweeps a
-// whole map top to bottom in phases of a few block strides; only the block rows that overlap
-// the rows swept so far and are not yet complete are live, in a ring of LDS slots, and a
-// block row is written out and its slot cleared as soon as the sweep has passed its last
-// pixel row, so every pixel is read exactly once.  Measured: the LDS atomics bound neither
-// kernel (with them removed the time stays the same); on maps of 256 columns the single read
-// wins (4.4 -> 4.95 TB/s of algorithmic bytes), on maps of up to 128 columns the first kernel's
-// many small independent workgroups do (5.5 against 5.0 TB/s), so the width selects.
+// groups of block rows share are read by both -- neighbouring groups walk their rows in
+// opposite directions, so that they want the shared rows at the same time and the second
+// read is served by the L2 of the XCD they share.  hash_hist_sweep_kernel (maps wider than 256
+// columns whose rows are readable as aligned float4, a ring of block rows fits in LDS): one
+// workgroup sweeps a whole map top to bottom in phases of a few block strides; only the block
+// rows that overlap the rows swept so far and are not yet complete are live, in a ring of LDS
+// slots, and a block row is written out and its slot cleared as soon as the sweep has passed
+// its last pixel row, so every pixel is read exactly once.  Measured: the LDS atomics bound
+// neither kernel (with them removed the time stays the same); the sweep kernels level off at
+// 5.0 TB/s whatever their schedule, the first kernel's many small independent workgroups reach
+// 5.6 TB/s of algorithmic bytes on maps of 128 columns and 5.07 on 256 (sweep: 4.95).
 //
 // The same kernel also writes the information-quality form of the output (Eq. 10):
 // o = -log p(t), p(t) = (count + 1) / (block area + bins), as fp32 or fp16.  The values for
@@ -222,7 +224,13 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p, i
     } else if (p.vec4) {
         // aligned quads of 4 pixels; the quad range covers [x_lo, x_hi) and is clipped per pixel
         const int q_lo = x_lo >> 2, q_hi = (x_hi + 3) >> 2;
-        for (int y = y_lo + trow; y < y_hi; y += TROWS) {
+        // Neighbouring groups of block rows share the pixel rows where their blocks overlap, and they run side by
+        // side on one XCD.  Even groups walk their rows bottom-up and odd ones top-down, so that a group and its
+        // lower neighbour want the shared rows at the same time (both at the start, or both at the end) and the
+        // second request finds them in that XCD's L2.
+        const bool upward = (rg & 1) == 0 && p.row_groups > 1;
+        for (int r = trow; r < y_hi - y_lo; r += TROWS) {
+            const int y = upward ? y_hi - 1 - r : y_lo + r;
             int ilo, ihi;
             block_range(y, p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
             const float *row = CODES ? nullptr : base + (int64_t)y * p.w;
@@ -352,7 +360,7 @@ static void hist_launch(ddcca_ctx *ctx, HistParams p, int64_t n)
     // sweep kernel: aligned float4 rows and a ring of block rows within the LDS budget.  A phase covers m block
     // strides (enough rows for about two 4-pixel groups per thread); during it the block rows from the oldest
     // incomplete one to the newest one touched are live: ceil(bh / sy) + m - 1 of them.
-    if (!CODES && p.vec4 && (p.nbx - 1) * p.sx + p.bw > 128) {
+    if (!CODES && p.vec4 && (p.nbx - 1) * p.sx + p.bw > 256) {
         const int row_bytes = p.nbx * HIST_BYTES;
         const int live = (p.bh + p.sy - 1) / p.sy;
         const int quads_per_stride = (((p.nbx - 1) * p.sx + p.bw + 3) / 4) * p.sy;
