@@ -134,7 +134,9 @@ __global__ void iq_lut_kernel(double total, int n, float *lut)
 
 // CODES: the input is the hash code itself, one byte plane per 8 filters (written by the convolution that would
 // have written the maps), instead of L2 planes of floats.
-template <int L2, int OUT, bool CODES = false>
+// PIPE: a thread's next row is requested before its current one is counted (twice the registers for the planes in
+// flight: chosen by the launcher when a thread has rows enough for it to pay).
+template <int L2, int OUT, bool CODES = false, bool PIPE = false>
 __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p, int lds_hist_words)
 {
     extern __shared__ unsigned int lds_hist[];
@@ -229,6 +231,49 @@ __global__ __launch_bounds__(HIST_THREADS) void hash_hist_kernel(HistParams p, i
         // lower neighbour want the shared rows at the same time (both at the start, or both at the end) and the
         // second request finds them in that XCD's L2.
         const bool upward = (rg & 1) == 0 && p.row_groups > 1;
+        if (PIPE && q_hi - q_lo <= TCOLS) {
+            // one group of four columns per thread (the usual case): the planes of the thread's next row are
+            // requested before the pixels of the current one are counted
+            const int xq = q_lo + tcol, nrows = y_hi - y_lo;
+            auto row_of = [&](int r) { return upward ? y_hi - 1 - r : y_lo + r; };
+            auto request = [&](int r, float4 (&v)[L2]) {
+                const float *src = base + (int64_t)row_of(r) * p.w + 4 * xq;
+#pragma unroll
+                for (int l = 0; l < L2; ++l) v[l] = *reinterpret_cast<const float4 *>(src + l * P);
+            };
+            auto count = [&](int r, const float4 (&v)[L2]) {
+                int ilo, ihi;
+                block_range(row_of(r), p.bh, p.sy, p.magic_sy, i0, i1, ilo, ihi);
+                unsigned c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+#pragma unroll
+                for (int l = 0; l < L2; ++l) {
+                    c0 |= (v[l].x > 0.0f ? 1u : 0u) << l;
+                    c1 |= (v[l].y > 0.0f ? 1u : 0u) << l;
+                    c2 |= (v[l].z > 0.0f ? 1u : 0u) << l;
+                    c3 |= (v[l].w > 0.0f ? 1u : 0u) << l;
+                }
+                const int x = 4 * xq;
+                if (x >= x_lo && x < x_hi) hist_add<L2>(lds_hist, p, x, c0, ilo, ihi, i0, j0, j1, ncol);
+                if (x + 1 >= x_lo && x + 1 < x_hi) hist_add<L2>(lds_hist, p, x + 1, c1, ilo, ihi, i0, j0, j1, ncol);
+                if (x + 2 >= x_lo && x + 2 < x_hi) hist_add<L2>(lds_hist, p, x + 2, c2, ilo, ihi, i0, j0, j1, ncol);
+                if (x + 3 >= x_lo && x + 3 < x_hi) hist_add<L2>(lds_hist, p, x + 3, c3, ilo, ihi, i0, j0, j1, ncol);
+            };
+            if (!CODES && xq < q_hi && trow < nrows) {
+                float4 va[L2], vb[L2];
+                int r = trow;
+                request(r, va);
+                while (true) {
+                    const int r2 = r + TROWS;
+                    if (r2 < nrows) request(r2, vb);
+                    count(r, va);
+                    if (r2 >= nrows) break;
+                    r = r2 + TROWS;
+                    if (r < nrows) request(r, va);
+                    count(r2, vb);
+                    if (r >= nrows) break;
+                }
+            }
+        } else
         for (int r = trow; r < y_hi - y_lo; r += TROWS) {
             const int y = upward ? y_hi - 1 - r : y_lo + r;
             int ilo, ihi;
@@ -394,6 +439,12 @@ static void hist_launch(ddcca_ctx *ctx, HistParams p, int64_t n)
     const int hist_words = p.rb * p.cols * (HIST_BYTES / 4);
     const size_t lds = (size_t)hist_words * 4 + (OUT != DDCCA_FEAT_COUNT_U16 ? (size_t)p.lut_n * 4 : 0);
     const int64_t per_map = (int64_t)p.row_groups * p.col_chunks;
+    // the pipelined form when a thread has one group of four columns and at least three rows of a row group
+    const int span = (p.cols - 1) * p.sx + p.bw, group_rows = (p.rb - 1) * p.sy + p.bh;
+    const int tcols = span > 128 ? 64 : 32;
+    // (groups of four columns a chunk spans: its first column is a multiple of cols * sx)
+    const int quads = (span + 3) / 4 + ((p.col_chunks > 1 && (p.cols * p.sx) % 4 != 0) ? 1 : 0);
+    const bool pipe = !CODES && p.vec4 && quads <= tcols && group_rows >= 3 * (HIST_THREADS / tcols);
     const int64_t maps_per_launch = std::max<int64_t>(p.group, (((int64_t)1 << 30) / per_map) / p.group * p.group);
     for (int64_t n0 = 0; n0 < n; n0 += maps_per_launch) {
         const int64_t nb = std::min(maps_per_launch, n - n0);
@@ -401,8 +452,12 @@ static void hist_launch(ddcca_ctx *ctx, HistParams p, int64_t n)
         if (CODES) q.codes = p.codes + n0 * ((L2 + 7) / 8) * (int64_t)p.h * p.w;
         else q.maps = p.maps + n0 * L2 * (int64_t)p.h * p.w;
         q.hist = reinterpret_cast<char *>(p.hist) + (n0 / p.group) * p.group_stride * ESZ;
-        hipLaunchKernelGGL((hash_hist_kernel<L2, OUT, CODES>), dim3((unsigned)(nb * per_map)), dim3(HIST_THREADS), lds,
-                           ctx->stream, q, hist_words);
+        if (pipe)
+            hipLaunchKernelGGL((hash_hist_kernel<L2, OUT, false, true>), dim3((unsigned)(nb * per_map)),
+                               dim3(HIST_THREADS), lds, ctx->stream, q, hist_words);
+        else
+            hipLaunchKernelGGL((hash_hist_kernel<L2, OUT, CODES>), dim3((unsigned)(nb * per_map)), dim3(HIST_THREADS),
+                               lds, ctx->stream, q, hist_words);
     }
 }
 
