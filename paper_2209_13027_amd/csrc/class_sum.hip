@@ -50,15 +50,35 @@ __global__ __launch_bounds__(256) void class_sum_kernel(const float *__restrict_
         const int lab = idx < n_img ? cls[idx] : -1;
         unsigned long long mask = __ballot(lab == c);
         while (mask) {
+            if (vec && p0 + 3 < P) {
+                // up to four members at a time: their loads are all requested before the first is added (the
+                // additions stay in ascending sample order)
+                float4 x[4], y[4];
+                int cnt = 0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (mask) {
+                        const int j = __ffsll((long long)mask) - 1;
+                        mask &= mask - 1;
+                        const int64_t o = ((base + j) * G + g) * P + p0;
+                        x[u] = *reinterpret_cast<const float4 *>(v1 + o);
+                        y[u] = *reinterpret_cast<const float4 *>(v2 + o);
+                        cnt = u + 1;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (u < cnt) {
+                        a1[0] += x[u].x; a1[1] += x[u].y; a1[2] += x[u].z; a1[3] += x[u].w;
+                        a2[0] += y[u].x; a2[1] += y[u].y; a2[2] += y[u].z; a2[3] += y[u].w;
+                    }
+                }
+                continue;
+            }
             const int j = __ffsll((long long)mask) - 1;
             mask &= mask - 1;
             const int64_t o = ((base + j) * G + g) * P + p0;
-            if (vec && p0 + 3 < P) {
-                const float4 x = *reinterpret_cast<const float4 *>(v1 + o);
-                const float4 y = *reinterpret_cast<const float4 *>(v2 + o);
-                a1[0] += x.x; a1[1] += x.y; a1[2] += x.z; a1[3] += x.w;
-                a2[0] += y.x; a2[1] += y.y; a2[2] += y.z; a2[3] += y.w;
-            } else {
+            {
                 for (int e = 0; e < 4; ++e)
                     if (p0 + e < P) {
                         a1[e] += v1[o + e];
