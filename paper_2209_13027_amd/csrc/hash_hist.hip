@@ -32,7 +32,7 @@
 namespace ddcca {
 
 constexpr int HIST_THREADS = 256;
-constexpr int HIST_LDS_BYTES = 32 * 1024;   // histogram bytes per workgroup (occupancy 4-5 per CU)
+constexpr int HIST_LDS_BYTES = 40 * 1024;   // histogram bytes per workgroup (4 per CU; 15 block rows of 15 x 256 bins: 3 equal groups)
 constexpr int SWEEP_LDS_BYTES = 40 * 1024;  // the same for the ring of the sweep kernel
 constexpr int CODE_ROWS = 8;                // code-map rows a thread has in flight
 
