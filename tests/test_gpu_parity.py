@@ -48,6 +48,8 @@ def rand_views(rng, n, h, w):
     (3, 1, 17, 23, 5, 3),            # one bit, ragged everything
     (2, 12, 40, 36, 9, 5),           # maximum code width
     (2, 3, 9, 300, (9, 11), (1, 7)),  # single block row, rectangular block, wide map
+    (2, 8, 72, 288, 16, 8),          # wider than 256 columns: one workgroup sweeps a map, two block rows live
+    (1, 4, 96, 320, (12, 16), (5, 8)),  # the same with 17 block rows through a ring of four, two strides a phase
     (1, 5, 8, 8, 8, 8),              # one block = whole map
 ])
 def test_hash_histogram_bit_exact(ctx, oracle, n, L2, h, w, block, stride):
