@@ -177,3 +177,93 @@ def test_apply_stage_hash_random_geometry(lib, ctx, oracle, case, arith):
     doubtful = int((np.abs(maps) <= 2e-6 * scale).any(axis=1).sum())
     cover = -(-block[0] // stride[0]) * -(-block[1] // stride[1])
     assert np.abs(g - want).sum() <= 2 * cover * doubtful, (doubtful, cover)
+
+
+# ------------------------------------------------------------------ extraction with given filters (Eq. 6-9, 11-12)
+@pytest.mark.parametrize("arith", ["auto", "fp32"])
+@pytest.mark.parametrize("case", range(10))
+def test_extract_features_random_geometry(lib, ctx, oracle, case, arith):
+    """Two convolution stages, hashing and block histograms of both views with random filters.  The stage-2 maps of
+    the GPU (two ddcca_apply_stage calls) meet the oracle's within the error bound of two fp32 stages; the
+    histograms of every extraction route (one batch, ragged batches, fused last stage) equal the oracle's hashing and
+    counting of exactly those maps, so that both sides take every sign decision on the same numbers."""
+    rng = np.random.default_rng(55000 + case)
+    k = int(rng.choice([3, 5, 7, 9]))
+    L1, L2 = int(rng.integers(1, 5)), int(rng.integers(1, 9))
+    h0, w0 = 1 + int(rng.integers(0, 50)), 1 + int(rng.integers(0, 90))
+    block, stride = draw_block(rng, h0, w0)
+    h, w = max(h0, block[0]), max(w0, block[1])
+    m = int(rng.integers(1, 6))
+    batch = int(rng.integers(1, m + 1))
+    say("extract_features", arith, dict(m=m, h=h, w=w, k=k, L1=L1, L2=L2, block=block, stride=stride, batch=batch))
+    V = rng.standard_normal((2, m, h, w)).astype(np.float32)
+    F = [rng.standard_normal((L, k, k)).astype(np.float32) for L in (L1, L1, L2, L2)]
+    dV, dF = [dev(V[0]), dev(V[1])], [dev(f) for f in F]
+    ctx.set_option(lib.OPT_CONV_ARITH, lib.CONV_FP32 if arith == "fp32" else lib.CONV_AUTO)
+    try:
+        Z = [ctx.apply_stage(ctx.apply_stage(dV[d], dF[d]).reshape(m * L1, h, w), dF[2 + d]).cpu().numpy()
+             for d in range(2)]
+        whole = ctx.extract_features(dV[0], dV[1], dF, k, L1, L2, block, stride)
+        batched = ctx.extract_features(dV[0], dV[1], dF, k, L1, L2, block, stride, batch_images=batch)
+        fused = ctx.extract_features(dV[0], dV[1], dF, k, L1, L2, block, stride, batch_images=batch, fused=True)
+        ctx.status()
+    finally:
+        ctx.set_option(lib.OPT_CONV_ARITH, lib.CONV_AUTO)
+    ref = oracle.extract_features(V[0], V[1], F, k, L1, L2, block, stride, keep_maps=True)
+    for d in range(2):
+        l1 = [np.abs(F[s * 2 + d]).sum(axis=(1, 2)).max() for s in range(2)]
+        assert np.abs(Z[d] - ref["Z"][d]).max() <= 4e-6 * l1[0] * l1[1] * np.abs(V[d]).max(), d
+    want = np.stack([oracle.block_hist(oracle.hash_maps(Z[d]), block, stride, 1 << L2)
+                     .reshape(m, L1, *ref["hist"].shape[3:]) for d in range(2)], axis=1)
+    assert want.shape == ref["hist"].shape == tuple(whole.shape)
+    for name, got in (("whole", whole), ("batched", batched), ("fused", fused)):
+        assert np.array_equal(got.cpu().numpy().astype(np.int64), want), name
+
+
+# ------------------------------------------------------------------ learning both stages (Sections II-A, II-B)
+def cosines(got, want):
+    g = got.reshape(got.shape[0], -1).astype(np.float64)
+    r = want.reshape(want.shape[0], -1)
+    return np.einsum("ga,ga->g", g, r) / (np.linalg.norm(g, axis=1) * np.linalg.norm(r, axis=1))
+
+
+@pytest.mark.parametrize("route", ["streamed", "materialised", "recomputed"])
+@pytest.mark.parametrize("case", range(8))
+def test_two_stage_learning_random_geometry(lib, oracle, case, route):
+    """Filters and correlations of both stages against the oracle on random small problems, by each of the three
+    routes the second stage has (maps streamed through scratch memory, kept in memory, recomputed in the Gram
+    kernel): rho to 1e-4 of the leading correlation, signed filter cosines where the correlations are separated."""
+    from paper_2209_13027_amd import pipeline
+    rng = np.random.default_rng(56000 + case)
+    k = int(rng.choice([3, 5, 7, 9]))
+    L1, L2 = int(rng.integers(1, 4)), int(rng.integers(1, 7))
+    n_cls = int(rng.integers(1, 4))
+    m = int(rng.integers(max(3, n_cls), 11))
+    h, w = 16 + int(rng.integers(0, 32)), 16 + int(rng.integers(0, 80))
+    batch = int(rng.integers(0, m + 1))
+    say("two-stage learning", route, dict(m=m, h=h, w=w, k=k, L1=L1, L2=L2, n_cls=n_cls, batch=batch))
+    cls = (np.arange(m) % n_cls).astype(np.int32)
+    base = rng.standard_normal((n_cls, h, w))
+    v1 = (base[cls] + 0.7 * rng.standard_normal((m, h, w))).astype(np.float32)
+    v2 = (0.5 * base[cls] ** 2 + 0.7 * rng.standard_normal((m, h, w))).astype(np.float32)
+    ref = oracle.learn_two_stage(v1, v2, cls, n_cls, k, L1, L2)
+    c = lib.Context(0)
+    try:
+        if route == "recomputed":
+            c.set_option(lib.OPT_NEXT_STAGE_MAPS, lib.MAPS_RECOMPUTED)
+        model = pipeline.fit(c, dev(v1), dev(v2), dev(cls), n_cls, k, L1, L2, streamed=route != "materialised",
+                             batch_images=batch)
+        c.status()
+        filters = [f.cpu().numpy() for f in model["filters"]]
+        rhos = [r.cpu().numpy() for r in model["rho"]]
+    finally:
+        c.close()
+    for s in range(2):
+        r = ref["stage%d" % (s + 1)]
+        assert np.all(np.isfinite(rhos[s]))
+        assert np.abs(rhos[s] - r["rho"]).max() <= 1e-4 * r["rho"][0], (s, rhos[s], r["rho"])
+        ok = r["gap"] > 1e-3
+        for d in range(2):
+            if ok.any():
+                cos = cosines(filters[2 * s + d], r["W%d" % (d + 1)])
+                assert cos[ok].min() >= 0.9999, (s, d, cos, r["gap"])
