@@ -334,8 +334,8 @@ def measure(name, args, K, W, detail):
         kernels["conv_hash_hist"] = {"ms_per_step": fused_ms, "tflops": per(fused_flops, fused_ms) / 1e12,
                                      "frac_mfma_fp32": per(fused_flops, fused_ms) / 1e12 / PEAK_MFMA_FP32_TFLOPS,
                                      "gbs": per(fused_bytes, fused_ms) / 1e9}
-    # (the all-tiles, fp32, maps-from-memory instantiation: patch_gram_kernel<k, tsplit, false, waves, false, false>)
-    traffic = (measured_traffic(wl.name, r"patch_gram_kernel<\d+, \d+, false, \d+, false, false>")
+    # (the all-tiles, fp32, maps-from-memory instantiation: patch_gram_kernel<k, tsplit, false, waves, false, false, *>, either tile staging)
+    traffic = (measured_traffic(wl.name, r"patch_gram_kernel<\d+, \d+, false, \d+, false, false, (true|false)>")
                if args.gram == "fp32" else None)
     # the peak the dominant kernel is held against: the fp32 matrix instructions; with three-piece bf16 operands one
     # fp32 product costs six bf16 products, so the ceiling for fp32-equivalent flop is a sixth of the bf16 peak

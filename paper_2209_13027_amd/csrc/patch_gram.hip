@@ -334,15 +334,12 @@ struct GramStage {
 // Issue the global loads of one tile (both views) into registers; elements outside the image
 // (zero padding) or outside the tile read as 0.
 template <int KS>
-__device__ __forceinline__ void gram_tile_fetch(const GramParams &p, int64_t item, int tiles, int pw,
+__device__ __forceinline__ void gram_tile_fetch(const GramParams &p, int64_t m, int ty, int tx, int pw,
                                                 float (&ra)[GramStage<KS>::NJY][GramStage<KS>::NJX],
                                                 float (&rb)[GramStage<KS>::NJY][GramStage<KS>::NJX])
 {
     using S = GramStage<KS>;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t m = item / tiles;
-    const int t = (int)(item - m * tiles);
-    const int ty = t / p.tiles_x, tx = t - ty * p.tiles_x;
     const int gy0 = ty * GRAM_TH - S::R + wave, gx0 = tx * p.tw - S::R + lane;
     const int64_t P = (int64_t)p.h * p.w;
     const float *s1 = p.v1 + m * P, *s2 = p.v2 + m * P;
@@ -402,6 +399,118 @@ __device__ __forceinline__ void gram_tile_store(const GramParams &p, float *buf,
             dc_next[1] = s2 * inv;
         }
     }
+}
+
+// Tile staging by aligned chunks of four pixels, for images whose rows start on 16-byte boundaries (w a multiple
+// of 4, aligned views): a fifth of the load and LDS-write instructions of the element-wise staging above, which
+// matters because the vector instructions of the staging run while the matrix pipeline of their SIMD waits.  Same
+// LDS layout.  Chunk e of a tile is row e / NCX, tile columns X0 + 4*(e % NCX) .. + 3; X0 <= 0 is such that the
+// chunk's image column is a multiple of 4 (tile widths are multiples of 4), so a chunk lies wholly inside the
+// image or outside.  Thread t carries chunks t, t + 256, ...
+template <int KS>
+struct GramStageV {
+    static constexpr int R = (KS - 1) / 2;
+    static constexpr int PH = GRAM_TH + 2 * R;
+    static constexpr int X0 = -((4 - R % 4) % 4);
+    static constexpr int NCX = (GRAM_TW_MAX + 2 * R - X0 + 3) / 4;
+    static constexpr int NV = (PH * NCX + GRAM_THREADS - 1) / GRAM_THREADS;
+    __device__ static void chunk(int j, int &yy, int &xx)
+    {
+        const int e = threadIdx.x + GRAM_THREADS * j;
+        yy = e / NCX;
+        xx = X0 + 4 * (e - yy * NCX);
+    }
+};
+
+template <int KS>
+__device__ __forceinline__ void gram_tile_fetch_v(const GramParams &p, int64_t m, int ty, int tx, int pw,
+                                                  float4 (&va)[GramStageV<KS>::NV], float4 (&vb)[GramStageV<KS>::NV])
+{
+    using S = GramStageV<KS>;
+    const int gy0 = ty * GRAM_TH - S::R, gx0 = tx * p.tw - S::R;
+    const int64_t P = (int64_t)p.h * p.w;
+    const float *s1 = p.v1 + m * P, *s2 = p.v2 + m * P;
+#pragma unroll
+    for (int j = 0; j < S::NV; ++j) {
+        int yy, xx;
+        S::chunk(j, yy, xx);
+        const int gy = gy0 + yy, gx = gx0 + xx;
+        float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+        // (one condition, not a chain: one masked region per chunk instead of nested branches)
+        const bool ok = (yy < S::PH) & (xx < pw) & (gy >= 0) & (gy < p.h) & (gx >= 0) & (gx < p.w);
+        if (ok) {
+            const int64_t o = (int64_t)gy * p.w + gx;
+            a = *reinterpret_cast<const float4 *>(s1 + o);
+            b = *reinterpret_cast<const float4 *>(s2 + o);
+        }
+        va[j] = a;
+        vb[j] = b;
+    }
+}
+
+// The DC estimate of a fetched tile: the mean over the second chunk of every lane of the last wavefront (256 pixels
+// of rows in the middle of the tile; the last wavefront carries the fewest chunks).  Called by that wavefront.
+template <int KS>
+__device__ __forceinline__ void gram_tile_mean_v(int pw, const float4 (&va)[GramStageV<KS>::NV],
+                                                 const float4 (&vb)[GramStageV<KS>::NV], float *dc_out)
+{
+    using S = GramStageV<KS>;
+    static_assert(S::NV >= 2 && 2 * GRAM_THREADS <= S::PH * S::NCX, "every lane has a second chunk inside the tile");
+    int yy, xx;
+    S::chunk(1, yy, xx);
+    const float a[4] = {va[1].x, va[1].y, va[1].z, va[1].w}, b[4] = {vb[1].x, vb[1].y, vb[1].z, vb[1].w};
+    float s1 = 0.f, s2 = 0.f, cnt = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (xx + i >= 0 && xx + i < pw) {
+            s1 += a[i];
+            s2 += b[i];
+            cnt += 1.f;
+        }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        s1 += __shfl_xor(s1, o);
+        s2 += __shfl_xor(s2, o);
+        cnt += __shfl_xor(cnt, o);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        dc_out[0] = s1 / cnt;
+        dc_out[1] = s2 / cnt;
+    }
+}
+
+// The LDS rows of a tile staged by chunks begin XS = -X0 columns before tile column 0, so that every chunk is stored
+// whole at a multiple of four columns (the readers start XS columns in; the row pitch covers the last chunk).  The
+// pitch is a multiple of 4 floats for k = 5 and 9 and even for k = 3 and 7.
+template <int KS>
+__device__ __forceinline__ void gram_chunk_store(float *dst, float4 v)
+{
+    if constexpr (KS == 5 || KS == 9) {
+        *reinterpret_cast<float4 *>(dst) = v;
+    } else {
+        *reinterpret_cast<float2 *>(dst) = make_float2(v.x, v.y);
+        *reinterpret_cast<float2 *>(dst + 2) = make_float2(v.z, v.w);
+    }
+}
+
+template <int KS>
+__device__ __forceinline__ void gram_tile_store_v(const GramParams &p, float *buf, int pw, float c1, float c2,
+                                                  const float4 (&va)[GramStageV<KS>::NV],
+                                                  const float4 (&vb)[GramStageV<KS>::NV], float *dc_next)
+{
+    using S = GramStageV<KS>;
+#pragma unroll
+    for (int j = 0; j < S::NV; ++j) {
+        int yy, xx;
+        S::chunk(j, yy, xx);
+        if ((yy < S::PH) & (xx < pw)) {
+            float *dst = buf + yy * p.pitch + (xx - S::X0);
+            gram_chunk_store<KS>(dst, make_float4(va[j].x - c1, va[j].y - c1, va[j].z - c1, va[j].w - c1));
+            gram_chunk_store<KS>(dst + p.view_stride,
+                                 make_float4(vb[j].x - c2, vb[j].y - c2, vb[j].z - c2, vb[j].w - c2));
+        }
+    }
+    if (threadIdx.x >= GRAM_THREADS - 64) gram_tile_mean_v<KS>(pw, va, vb, dc_next);
 }
 
 // ---- maps recomputed from an input tile ------------------------------------------------------------------
@@ -522,10 +631,11 @@ __device__ __forceinline__ void gram_tile_conv(const GramParams &p, const float 
     }
 }
 
-template <int KS, int TSPLIT, bool CROSS, int WAVES_PER_EU, bool SPLIT, bool FUSE>
+template <int KS, int TSPLIT, bool CROSS, int WAVES_PER_EU, bool SPLIT, bool FUSE, bool VEC>
 __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(GramParams p)
 {
     static_assert(!(FUSE && CROSS), "maps are recomputed for the full Gram only");
+    static_assert(!(FUSE && VEC), "the staging by chunks is for maps read from memory");
     using G = GramGeom<KS, TSPLIT, CROSS>;
     using S = GramStage<KS>;
     constexpr int R = G::R, NB = G::NB, NT = G::NT;
@@ -576,7 +686,20 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
         ty = t / p.tiles_x;
         tx = t - ty * p.tiles_x;
     };
-    float ra[S::NJY][S::NJX], rb[S::NJY][S::NJX];
+    // maps from memory: the workgroup's items are consecutive tiles, so the position (map, tile row, tile column)
+    // of the current tile and of the one in flight is stepped, not divided out of the item number per tile
+    int64_t m_cur = 0, m_nxt = 0;
+    int ty_cur = 0, tx_cur = 0, ty_nxt = 0, tx_nxt = 0;
+    if constexpr (!FUSE) {
+        m_cur = first / tiles;
+        const int t = (int)(first - m_cur * tiles);
+        ty_cur = t / p.tiles_x;
+        tx_cur = t - ty_cur * p.tiles_x;
+    }
+    // the tile in flight: by elements, or by aligned chunks of four (VEC)
+    using SV = GramStageV<KS>;
+    float ra[VEC ? 1 : S::NJY][VEC ? 1 : S::NJX], rb[VEC ? 1 : S::NJY][VEC ? 1 : S::NJX];
+    float4 va[VEC ? SV::NV : 1], vb[VEC ? SV::NV : 1];
     if (FUSE && count > 0) {
         // first tile: once unshifted for its DC estimate, then again shifted by it
         int ty, tx;
@@ -589,9 +712,19 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
         gram_tile_conv<KS>(p, raw, lds, l, ty, tx, pw, dc[2], dc[3], dc);
         __syncthreads();
     }
-    if (!FUSE && count > 0) {
+    if constexpr (VEC) {
+        if (count > 0) {
+            // first tile: its own DC estimate, then into buffer 0
+            gram_tile_fetch_v<KS>(p, m_cur, ty_cur, tx_cur, pw, va, vb);
+            if (wave == GRAM_THREADS / 64 - 1) gram_tile_mean_v<KS>(pw, va, vb, dc + 2);
+            __syncthreads();
+            gram_tile_store_v<KS>(p, lds, pw, dc[2], dc[3], va, vb, dc);
+            __syncthreads();
+        }
+    }
+    if constexpr (!FUSE && !VEC) if (count > 0) {
         // first tile: its own DC estimate, then into buffer 0
-        gram_tile_fetch<KS>(p, first, tiles, pw, ra, rb);
+        gram_tile_fetch<KS>(p, m_cur, ty_cur, tx_cur, pw, ra, rb);
         float s1 = 0.f, s2 = 0.f;
         if (wave == 0) {
 #pragma unroll
@@ -621,13 +754,24 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
     for (int64_t it = 0; it < count; ++it) {
         const int64_t item = first + it;
         const int cur = (int)(it & 1);
-        const float *pix = lds + cur * p.buf_stride;
+        const float *pix = lds + cur * p.buf_stride + (VEC ? -SV::X0 : 0);
         const bool more = it + 1 < count;
         // the next tile travels from HBM to registers while this one is contracted
-        if (!FUSE && more) gram_tile_fetch<KS>(p, item + 1, tiles, pw, ra, rb);
+        if constexpr (!FUSE) {
+            m_nxt = m_cur; ty_nxt = ty_cur; tx_nxt = tx_cur + 1;
+            if (tx_nxt == p.tiles_x) {
+                tx_nxt = 0;
+                if (++ty_nxt == p.tiles_y) { ty_nxt = 0; ++m_nxt; }
+            }
+        }
+        if constexpr (VEC) {
+            if (more) gram_tile_fetch_v<KS>(p, m_nxt, ty_nxt, tx_nxt, pw, va, vb);
+        } else if (!FUSE && more) {
+            gram_tile_fetch<KS>(p, m_nxt, ty_nxt, tx_nxt, pw, ra, rb);
+        }
 
-        int ty, tx;
-        tile_of(item, ty, tx);
+        int ty = ty_cur, tx = tx_cur;
+        if constexpr (FUSE) tile_of(item, ty, tx);
         const int rows = min(GRAM_TH, p.h - ty * GRAM_TH);
         const int cols = min(p.tw, p.w - tx * p.tw);
         if constexpr (SPLIT) {
@@ -660,10 +804,15 @@ __global__ __launch_bounds__(GRAM_THREADS, WAVES_PER_EU) void patch_gram_kernel(
         }
         if (!FUSE && more) {
             // DC shift of tile it+1 = estimate left by tile it (cells cur), new estimate into the other cells
-            gram_tile_store<KS>(p, lds + (cur ^ 1) * p.buf_stride, pw, dc[2 * cur], dc[2 * cur + 1], ra, rb,
-                                dc + 2 * (cur ^ 1));
+            if constexpr (VEC)
+                gram_tile_store_v<KS>(p, lds + (cur ^ 1) * p.buf_stride, pw, dc[2 * cur], dc[2 * cur + 1], va, vb,
+                                      dc + 2 * (cur ^ 1));
+            else
+                gram_tile_store<KS>(p, lds + (cur ^ 1) * p.buf_stride, pw, dc[2 * cur], dc[2 * cur + 1], ra, rb,
+                                    dc + 2 * (cur ^ 1));
             __syncthreads();
         }
+        m_cur = m_nxt; ty_cur = ty_nxt; tx_cur = tx_nxt;
     }
 }
 
@@ -780,23 +929,23 @@ static GramShape gram_shape(int k)
 // one slot per resident workgroup
 int max_gram_slots(ddcca_ctx *ctx, int k) { return ctx->n_cu * gram_shape(k).waves_per_eu; }
 
-template <int KS, int TSPLIT, bool CROSS, int WPE, bool SPLIT, bool FUSE>
+template <int KS, int TSPLIT, bool CROSS, int WPE, bool SPLIT, bool FUSE, bool VEC>
 static int gram_launch(ddcca_ctx *ctx, const GramParams &p, int grid, size_t lds)
 {
     static bool attr_set[MAX_DEVICES] = {};      // per device: the attribute is set on that device's code object
     if (!attr_set[ctx->device]) {
-        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)patch_gram_kernel<KS, TSPLIT, CROSS, WPE, SPLIT, FUSE>,
+        DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)patch_gram_kernel<KS, TSPLIT, CROSS, WPE, SPLIT, FUSE, VEC>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         attr_set[ctx->device] = true;
     }
-    hipLaunchKernelGGL((patch_gram_kernel<KS, TSPLIT, CROSS, WPE, SPLIT, FUSE>), dim3(grid), dim3(GRAM_THREADS), lds,
+    hipLaunchKernelGGL((patch_gram_kernel<KS, TSPLIT, CROSS, WPE, SPLIT, FUSE, VEC>), dim3(grid), dim3(GRAM_THREADS), lds,
                        ctx->stream, p);
     DDCCA_HIP(ctx, hipGetLastError());
     return DDCCA_OK;
 }
 
 // LDS layout of a launch with column tiles of at most tw_max patches; returns the bytes.
-static size_t gram_layout(GramParams &p, int k, int tw_max, bool split, bool fuse)
+static size_t gram_layout(GramParams &p, int k, int tw_max, bool split, bool fuse, bool vec)
 {
     const int w4 = (p.w + 3) & ~3;
     // split wide images into equal column tiles of at most tw_max patches
@@ -809,6 +958,8 @@ static size_t gram_layout(GramParams &p, int k, int tw_max, bool split, bool fus
     // rows a lane group touches fall into distinct LDS banks
     // (three-piece operands read whole groups of 32 patches: the pitch covers the rounded-up width)
     int pitch = (split ? (p.tw + 31) / 32 * 32 : p.tw) + 2 * r;
+    // (tiles staged by chunks of four: the rows begin (4 - r % 4) % 4 columns early and end with a whole chunk)
+    if (vec) pitch = std::max(pitch, (p.tw + 2 * r + (4 - r % 4) % 4 + 3) & ~3);
     while (pitch % 32 != (k + 3) % 32) ++pitch;
     p.pitch = pitch;
     p.view_stride = (GRAM_TH + 2 * r) * pitch + 16;      // +16: shift view 2 by half the banks
@@ -835,11 +986,13 @@ static int gram_run(ddcca_ctx *ctx, GramParams &p, int64_t n_maps, int k, bool c
 {
     const bool split = ctx->gram_arith == DDCCA_GRAM_BF16X3;
     const GramShape shape = gram_shape(k);
-    size_t lds = gram_layout(p, k, GRAM_TW_MAX, split, fuse);
+    // image rows on 16-byte boundaries: the tiles travel as aligned chunks of four pixels
+    const bool vec = !fuse && (p.w & 3) == 0 && (((uintptr_t)p.v1 | (uintptr_t)p.v2) & 15) == 0;
+    size_t lds = gram_layout(p, k, GRAM_TW_MAX, split, fuse, vec);
     // (with the input tiles next to the pixel buffers: narrower tiles until every resident workgroup fits)
     for (int tw_max = GRAM_TW_MAX - 32; fuse && tw_max >= 32 && lds * shape.waves_per_eu > LDS_BYTES_PER_CU;
          tw_max -= 32)
-        lds = gram_layout(p, k, tw_max, split, fuse);
+        lds = gram_layout(p, k, tw_max, split, fuse, vec);
     p.n_items = n_maps * p.tiles_x * p.tiles_y;
     const int npg = 4 / shape.tsplit;
     // about 16k patches between fp64 flushes per wavefront
@@ -853,10 +1006,12 @@ static int gram_run(ddcca_ctx *ctx, GramParams &p, int64_t n_maps, int k, bool c
     const int max_grid = std::min(max_slots, ctx->n_cu * resident);
     const int grid = (int)std::min<int64_t>(max_grid, std::max<int64_t>(p.n_items, 1));
     int rc;
+#define GRAM_VEC(KS, TS, CR, WPE, SP)                                                                  \
+    (vec ? gram_launch<KS, TS, CR, WPE, SP, false, true>(ctx, p, grid, lds)                            \
+         : gram_launch<KS, TS, CR, WPE, SP, false, false>(ctx, p, grid, lds))
 #define GRAM_PICK(KS, TS, WPE, SP)                                                                     \
-    (fuse ? gram_launch<KS, TS, false, WPE, SP, true>(ctx, p, grid, lds)                               \
-          : cross_only ? gram_launch<KS, TS, true, WPE, SP, false>(ctx, p, grid, lds)                  \
-                       : gram_launch<KS, TS, false, WPE, SP, false>(ctx, p, grid, lds))
+    (fuse ? gram_launch<KS, TS, false, WPE, SP, true, false>(ctx, p, grid, lds)                        \
+          : cross_only ? GRAM_VEC(KS, TS, true, WPE, SP) : GRAM_VEC(KS, TS, false, WPE, SP))
 #define GRAM_CASE(KS, TS, WPE)                                                                         \
     case KS: rc = split ? GRAM_PICK(KS, TS, WPE, true) : GRAM_PICK(KS, TS, WPE, false); break;
     switch (k) {
@@ -868,6 +1023,7 @@ static int gram_run(ddcca_ctx *ctx, GramParams &p, int64_t n_maps, int k, bool c
     }
 #undef GRAM_CASE
 #undef GRAM_PICK
+#undef GRAM_VEC
     if (rc) return rc;
     // slots below the old mark that this grid did not touch keep their data; new ones were initialised
     *slots_valid = std::max(*slots_valid, grid);
