@@ -411,10 +411,13 @@ __global__ __launch_bounds__(WAVES * 64) void conv_split_kernel(ConvSplitParams 
     }
 }
 
-// Output rows that share their pixel operands, and wavefronts per workgroup, per patch size.
-template <int KS> struct SplitShape { static constexpr int RU = 1, WAVES = 4; };
-template <> struct SplitShape<7> { static constexpr int RU = 2, WAVES = 4; };
-template <> struct SplitShape<3> { static constexpr int RU = 2, WAVES = 4; };
+// Output rows that share their pixel operands, wavefronts per workgroup and tile rows of maps that take several
+// tiles, per patch size.  (Tile rows, measured on 128 x 128 maps in one process: k = 5 writes 5.4-5.9 TB/s in tiles
+// of 16 rows against 5.0-5.1 in tiles of 32 and 3.6 in tiles of 4; k = 7 and 9 lose 3 % from 32 to 16 rows.)
+template <int KS> struct SplitShape { static constexpr int RU = 1, WAVES = 4, TH = CSPLIT_TH_MAX; };
+template <> struct SplitShape<7> { static constexpr int RU = 2, WAVES = 4, TH = CSPLIT_TH_MAX; };
+template <> struct SplitShape<5> { static constexpr int RU = 1, WAVES = 4, TH = 16; };
+template <> struct SplitShape<3> { static constexpr int RU = 2, WAVES = 4, TH = CSPLIT_TH_MAX; };
 
 template <int KS, int NBX, bool VEC4, bool CODES>
 static int conv_split_launch_vec(ddcca_ctx *ctx, const float *in, int64_t n, int h, int w, const float *W, int L,
@@ -432,10 +435,12 @@ static int conv_split_launch_vec(ddcca_ctx *ctx, const float *in, int64_t n, int
     ConvSplitParams p;
     p.in = in; p.W = W; p.out = out; p.codes = codes; p.h = h; p.w = w; p.L = L;
     p.tiles_x = (w + G::TW - 1) / G::TW;
-    // equal tile heights of at most CSPLIT_TH_MAX rows, a multiple of the rows one pass of the workgroup covers
+    // a map of at most CSPLIT_TH_MAX rows is one tile row; a higher one goes in equal tile heights of at most
+    // SplitShape::TH rows; a multiple of the rows one pass of the workgroup covers either way
     constexpr int PASS = RU * WAVES;
-    const int nty = (h + CSPLIT_TH_MAX - 1) / CSPLIT_TH_MAX;
-    p.th = std::min(CSPLIT_TH_MAX, ((h + nty - 1) / nty + PASS - 1) / PASS * PASS);
+    const int cap = h <= CSPLIT_TH_MAX ? CSPLIT_TH_MAX : SplitShape<KS>::TH;
+    const int nty = (h + cap - 1) / cap;
+    p.th = std::min(cap, ((h + nty - 1) / nty + PASS - 1) / PASS * PASS);
     p.tiles_y = (h + p.th - 1) / p.th;
     p.n_items = (long long)n * p.tiles_x * p.tiles_y;
     unsigned grid = (unsigned)std::min(p.n_items, (long long)CSPLIT_WG_PER_CU * ctx->n_cu);
