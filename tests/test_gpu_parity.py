@@ -158,6 +158,35 @@ def test_corr_batch_split_invariance(ctx):
             assert rel_fro(got[name], ref[name]) <= 1e-6, (name, cuts)
 
 
+@pytest.mark.parametrize("k,G,h,w", [(5, 1, 40, 132), (7, 2, 33, 96), (9, 1, 20, 260), (3, 3, 18, 8)])
+def test_corr_tile_staging_paths_agree(ctx, oracle, k, G, h, w):
+    """Tiles of images whose rows start on 16-byte boundaries are staged as aligned chunks of four pixels, all others
+    element by element.  The same images once in an aligned buffer and once in one that starts 4 bytes later: both
+    routes against the oracle, and against each other (they differ in the tile's DC estimate only, which the
+    algebra removes: rounding-level differences)."""
+    rng = np.random.default_rng(4300 + k)
+    n_img, n_cls = 5, 2
+    V1, V2 = rand_views(rng, n_img * G, h, w)
+    cls = rng.integers(0, n_cls, size=n_img).astype(np.int32)
+    want = oracle_matrices(oracle, V1, V2, cls, n_cls, G, k)
+    got = []
+    for shift in (0, 1):
+        bufs = []
+        for V in (V1, V2):
+            flat = torch.zeros(V.size + 4, dtype=torch.float32, device="cuda")
+            flat[shift:shift + V.size] = torch.from_numpy(V.ravel()).cuda()
+            bufs.append(flat[shift:shift + V.size].view(V.shape))
+            assert bufs[-1].data_ptr() % 16 == 4 * shift
+        ctx.corr_begin(k, n_cls, G, h, w)
+        ctx.corr_accumulate(bufs[0], bufs[1], dev(cls))
+        got.append({name: m.cpu().numpy() for name, m in ctx.corr_export(k).items()})
+        ctx.status()
+    for name in ("C11", "C22", "C12", "Cw", "CT"):
+        for g in got:
+            assert rel_fro(g[name], want[name]) <= 2e-6, name
+        assert rel_fro(got[0][name], got[1][name]) <= 2e-6, name
+
+
 def test_corr_reproducible(ctx):
     rng = np.random.default_rng(43)
     V1, V2 = rand_views(rng, 40, 32, 32)
