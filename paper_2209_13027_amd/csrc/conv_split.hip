@@ -52,7 +52,8 @@ struct SplitConv {
     static constexpr int PO = SHX & 1;
     // words per plane row: at least COLS/2, and congruent to RES modulo MOD (the bank rule above)
     static constexpr int MOD = KS == 3 ? 16 : 32;
-    static constexpr int RES = KS == 3 ? 8 : KS == 9 ? 17 : 16;
+    static constexpr int RES = KS == 3 ? 8 : 16;
+    static constexpr bool PAIRED_READS = KS >= 7;
     static constexpr int MINP = COLS / 2;
     static constexpr int PWORDS = MINP + (RES - MINP % MOD + MOD) % MOD;
     static constexpr int PLANE = PH_MAX * PWORDS;  // words per plane
@@ -61,14 +62,23 @@ struct SplitConv {
     // The pair in slot i of group q of instruction t: input row j (relative to the first output row's first tap
     // row) and pair dxp, i.e. tap columns 2*dxp and 2*dxp + 1.  Row-major over the pairs, except k = 5 with one
     // output row (three pairs per tap row): there group q holds row q and the fourth slots of groups 0..2 hold the
-    // pairs of row 4, so that partner groups again read words one plane row apart.
-    __device__ static bool slot(int t, int q, int i, int &j, int &dxp)
+    // pairs of row 4, so that partner groups again read words one plane row apart; and k = 9 with one output row
+    // (five pairs per tap row): the first two instructions take pairs 0..3 of one tap row per group (rows 0..7),
+    // the third takes pairs 0..3 of row 8 and the fifth pairs of the nine rows, three per group.  Where the four
+    // words of a group lie at offsets from its first word that are the same in every group (a tap row: 0, 1, 2,
+    // 3), one address register and two-word read instructions serve them (SlotDeltas below).
+    __host__ __device__ static constexpr bool slot(int t, int q, int i, int &j, int &dxp)
     {
         if (KS == 5 && RU == 1) {
-            if (t > 0) return false;
+            if (t > 0) { j = 0; dxp = 0; return false; }
             if (i < 3) { j = q; dxp = i; return true; }
             j = 4; dxp = q;
             return q < 3;
+        }
+        if (KS == 9 && RU == 1) {
+            if (t < 2 || q == 0) { j = 4 * t + q; dxp = i; return true; }
+            j = 3 * (q - 1) + (i < 3 ? i : 2); dxp = 4;
+            return i < 3;
         }
         const int pair = 4 * (4 * t + q) + i;
         j = pair / RP;
@@ -204,14 +214,52 @@ struct PixelOperand {
     SplitOperand h, m, l;
 };
 
+// Per instruction and slot: whether the slot's word lies at the same offset from the group's first word in every
+// group, and that offset.  An LDS read instruction costs the LDS about 4.4 clocks per wavefront whether it returns
+// one word or two (measured: one-word reads 58 B per clock and compute unit, two-word reads 96, 16-byte reads 143),
+// and at k >= 7 these reads, not their bytes, are what the contraction waits for; a slot with a uniform offset is
+// read from the first slot's address register plus a constant, which lets the compiler pair it with its neighbour.
+// A group none of whose slots holds a pair mirrors another group's addresses (split_offsets) and fits any offset; a
+// group that holds some pairs but not this one makes the slot non-uniform (its own address is used).
 template <class G>
-__device__ __forceinline__ void read_operand(PixelOperand &o, const unsigned int *src, const int (&off)[4])
+struct SlotDeltas {
+    int delta[G::STEPS][4];
+    bool uniform[G::STEPS][4];
+    constexpr SlotDeltas() : delta{}, uniform{}
+    {
+        for (int t = 0; t < G::STEPS; ++t)
+            for (int i = 0; i < 4; ++i) {
+                bool ok = true, have = false;
+                int d = 0;
+                for (int q = 0; q < 4; ++q) {
+                    int j0 = 0, x0 = 0, j = 0, x = 0;
+                    bool any = false;
+                    for (int e = 0; e < 4; ++e) any = any || G::slot(t, q, e, j, x);
+                    if (!any) continue;
+                    const bool v0 = G::slot(t, q, 0, j0, x0), v = G::slot(t, q, i, j, x);
+                    if (!v0 || !v) { ok = false; break; }
+                    const int dd = (j - j0) * G::PWORDS + (x - x0);
+                    if (have && dd != d) { ok = false; break; }
+                    d = dd;
+                    have = true;
+                }
+                uniform[t][i] = ok && have;
+                delta[t][i] = d;
+            }
+    }
+};
+
+template <class G>
+__device__ __forceinline__ void read_operand(PixelOperand &o, const unsigned int *src, const int (&off)[4], int t)
 {
+    constexpr SlotDeltas<G> tab{};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        o.h.w[i] = src[off[i]];
-        o.m.w[i] = src[G::PLANE + off[i]];
-        o.l.w[i] = src[2 * G::PLANE + off[i]];
+        // (k = 3 and 5 are bound by their stores and measured 0-2 % slower with paired reads: left as they were)
+        const int w = G::PAIRED_READS && tab.uniform[t][i] ? off[0] + tab.delta[t][i] : off[i];
+        o.h.w[i] = src[w];
+        o.m.w[i] = src[G::PLANE + w];
+        o.l.w[i] = src[2 * G::PLANE + w];
     }
 }
 
@@ -232,14 +280,14 @@ __device__ __forceinline__ void split_rows(const unsigned int *prow, const int (
     constexpr int NB = NBX / CB, N = G::STEPS * NB;
     PixelOperand op[2][CB];
 #pragma unroll
-    for (int k = 0; k < CB; ++k) read_operand<G>(op[0][k], prow + k * 16, toff[0]);
+    for (int k = 0; k < CB; ++k) read_operand<G>(op[0][k], prow + k * 16, toff[0], 0);
 #pragma unroll
     for (int idx = 0; idx < N; ++idx) {
         const int t = idx / NB, b0 = (idx - t * NB) * CB;
         if (idx + 1 < N) {
             const int t2 = (idx + 1) / NB, b2 = (idx + 1 - t2 * NB) * CB;
 #pragma unroll
-            for (int k = 0; k < CB; ++k) read_operand<G>(op[(idx + 1) & 1][k], prow + (b2 + k) * 16, toff[t2]);
+            for (int k = 0; k < CB; ++k) read_operand<G>(op[(idx + 1) & 1][k], prow + (b2 + k) * 16, toff[t2], t2);
         }
         // the reads above are issued before the products below (the scheduler would otherwise sink them to their
         // use and expose the LDS latency to the matrix pipeline)
