@@ -19,6 +19,7 @@
 namespace ddcca {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 constexpr int CONV_THREADS = 256;
 constexpr int CONV_TH = 32;        // tile rows per workgroup
@@ -95,6 +96,8 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_mfma_kernel(const float *__
         if (g0 > 0) load_weights(g0);             // the first group was fetched before the barrier
         // uniform per workgroup: every store of this pass is an aligned float2 (w even: pairs never straddle the edge)
         const bool fast = (w & 1) == 0 && (((uintptr_t)out) & 7) == 0 && g0 + 8 <= L;
+        // uniform: rows of a multiple of 32 pixels on a 128-byte aligned base (rows that split cache lines lose by the hint)
+        const bool streaming = (w & 31) == 0 && (((uintptr_t)out) & 127) == 0;
         const int nfull = min(NBX, (w - tx * TW) / CONV_XB);   // column blocks of this tile fully inside the image
         // lane (q,c) ends with planes g0+2q (acc[0..1]) and g0+2q+1 (acc[2..3]) at columns x, x+1
         const int ga = g0 + 2 * q;
@@ -112,7 +115,16 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_mfma_kernel(const float *__
             }
             const int gy = ty * CONV_TH + r;
             float *dst = out + (n * L + ga) * P + (int64_t)gy * w + gx_lane;
-            if (fast) {
+            if (fast && streaming) {
+                // the same stores with the non-temporal hint: the 128-byte segments are whole, aligned cache lines
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+#pragma unroll
+                    for (int b = 0; b < NBX; ++b)
+                        if (b < nfull || gx_lane + b * CONV_XB < w)
+                            __builtin_nontemporal_store(floatx2{acc[b][2 * e], acc[b][2 * e + 1]},
+                                                        reinterpret_cast<floatx2 *>(dst + e * P + b * CONV_XB));
+            } else if (fast) {
                 // 8-byte aligned rows, all 8 planes exist: column blocks fully inside the image are
                 // stored unconditionally, the ragged one (if any) per pixel pair
 #pragma unroll
