@@ -316,6 +316,17 @@ def measure(name, args, K, W, detail):
         "hash_hist": {"ms_per_step": hist_ms, "gbs": per(work["hist_bytes"], hist_ms) / 1e9,
                       "frac_hbm": per(work["hist_bytes"], hist_ms) / 1e9 / PEAK_HBM_GBS},
     }
+    # measured HBM bytes per launch (committed counter summary) beside the algorithmic ones, for the two memory-bound
+    # kernels of the default path: a ratio well above 1 would mean re-reads
+    if fused_ms == 0 and prof["conv"]["launches"] > 0 and prof["hash_hist"]["launches"] > 0:
+        conv_rx = (r"conv_split_kernel<\d+, \d+, \d+, \d+, (true|false), false>" if conv_is_split
+                   else r"conv_mfma_kernel<")
+        for key, rx, algo in (("conv", conv_rx, work["conv_bytes"]),
+                              ("hash_hist", r"hash_hist_kernel<\d+, \d+, false, (true|false)>", work["hist_bytes"])):
+            t = measured_traffic(wl.name, rx)
+            kernels[key]["algorithmic_bytes_per_launch"] = algo * K2 / prof[key]["launches"]
+            kernels[key]["traffic_bytes_per_launch"] = t
+            kernels[key]["traffic_source"] = "profiles/traffic.json (committed, not re-measured)" if t else None
     if "extract_conv_other" in phases:
         # extraction only: stage 1 once per view plus stage 2
         xbytes = 2 * M * P * (4 + 4 * L1v) + 2 * M * L1v * P * (4 + 4 * wl.L2)
