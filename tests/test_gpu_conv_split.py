@@ -89,3 +89,35 @@ def test_end_to_end_tiny_bf16x3(ctx, oracle):
             F = ref["stage%d" % (s + 1)]["F%d" % (d + 1)].reshape(-1, wl.k * wl.k)
             cos = np.sum(W * F, axis=1) / (np.linalg.norm(W, axis=1) * np.linalg.norm(F, axis=1))
             assert cos.min() >= 0.9999
+
+
+@pytest.mark.parametrize("arith", ["bf16x3", "fp32"])
+@pytest.mark.parametrize("n,h,w,k,L", [(3, 40, 64, 7, 8), (2, 33, 160, 9, 8), (2, 48, 96, 5, 8), (2, 20, 128, 3, 8)])
+def test_apply_stage_both_store_routes(ctx, oracle, arith, n, h, w, k, L):
+    """Rows of a multiple of 32 pixels: on a 128-byte aligned output the maps leave with the non-temporal hint, on an
+    output that starts 32 bytes later with ordinary stores.  Both are the oracle's maps, and bit for bit each other's."""
+    from paper_2209_13027_amd.binding import CONV_FP32
+    rng = np.random.default_rng(7100 + w + k)
+    V = rng.standard_normal((n, h, w)).astype(np.float32)
+    F = rng.standard_normal((L, k, k)).astype(np.float32)
+    ctx.set_option(OPT_CONV_ARITH, CONV_FP32 if arith == "fp32" else CONV_BF16X3)
+    try:
+        x, f = dev(V), dev(F)
+        count = n * L * h * w
+        buf_a = torch.full((count + 64,), float("nan"), dtype=torch.float32, device="cuda")
+        buf_b = torch.full((count + 64,), float("nan"), dtype=torch.float32, device="cuda")
+        assert buf_a.data_ptr() % 128 == 0 and buf_b.data_ptr() % 128 == 0
+        out_a = buf_a[:count].view(n, L, h, w)
+        out_b = buf_b[8:8 + count].view(n, L, h, w)                       # 32 bytes on: 8-byte stores, no hint
+        ctx.apply_stage(x, f, out=out_a)
+        ctx.apply_stage(x, f, out=out_b)
+        ctx.status()
+        a, b = out_a.cpu().numpy(), out_b.cpu().numpy()
+    finally:
+        ctx.set_option(OPT_CONV_ARITH, CONV_BF16X3)
+    want = oracle.conv(V, F)
+    scale = np.abs(F).sum(axis=(1, 2)).max() * np.abs(V).max()
+    assert np.abs(a - want).max() <= 2e-6 * scale
+    assert np.array_equal(a, b)
+    # nothing written past either output
+    assert torch.isnan(buf_a[count:]).all() and torch.isnan(buf_b[:8]).all() and torch.isnan(buf_b[8 + count:]).all()

@@ -63,6 +63,29 @@ def test_hash_histogram_bit_exact(ctx, oracle, n, L2, h, w, block, stride):
     assert np.array_equal(got.astype(np.int64), want)
 
 
+@pytest.mark.parametrize("L2,h,w,block,stride", [(8, 48, 64, 16, 8), (6, 40, 96, 8, 4), (8, 70, 288, 16, 8)])
+def test_hash_histogram_both_store_routes(ctx, oracle, L2, h, w, block, stride):
+    """Histograms whose block rows are whole 128-byte lines leave with the non-temporal hint when the output is
+    128-byte aligned, with ordinary 16-byte stores when it starts 16 bytes later: both are the oracle's counts."""
+    rng = np.random.default_rng(880 + L2 + w)
+    n = 3
+    Z = rng.standard_normal((n, L2, h, w)).astype(np.float32)
+    want = oracle.block_hist(oracle.hash_maps(Z), block, stride, 1 << L2)
+    count = int(np.prod(want.shape))
+    z = dev(Z)
+    outs = []
+    for shift in (0, 8):
+        buf = torch.full((count + 64,), 0xFFFF, dtype=torch.int32, device="cuda").to(torch.uint16)
+        assert buf.data_ptr() % 128 == 0
+        out = buf[shift:shift + count].view(want.shape)
+        ctx.hash_histogram(z, block, stride, out=out)
+        ctx.status()
+        outs.append(out.cpu().numpy().astype(np.int64))
+        whole = buf.cpu().numpy()
+        assert (whole[:shift] == 0xFFFF).all() and (whole[shift + count:] == 0xFFFF).all()   # nothing written outside
+    assert np.array_equal(outs[0], want) and np.array_equal(outs[1], want)
+
+
 def test_hash_histogram_smooth_maps(ctx, oracle):
     # smooth maps: long runs of equal codes (the common case on real maps)
     rng = np.random.default_rng(7)
