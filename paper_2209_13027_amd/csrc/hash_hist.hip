@@ -32,7 +32,15 @@
 namespace ddcca {
 
 constexpr int HIST_THREADS = 256;
-constexpr int HIST_LDS_BYTES = 40 * 1024;   // histogram bytes per workgroup (4 per CU; 15 block rows of 15 x 256 bins: 3 equal groups)
+// LDS per workgroup of the row-group kernel, histograms plus the information-quality table: 40 KB (four workgroups
+// per compute unit; 15 block rows of 15 x 256 bins: three groups of 5), and 60 KB for maps wider than 128 columns read
+// as floats (two groups of 8 and 7, two workgroups per compute unit).  Measured, 60 against 40 KB: 256-column maps 5.21
+// -> 5.43 TB/s (7.0 -> 6.5 ms per step of the 256 x 256 workload), 128-column maps 5.94 -> 5.98, 112 x 92 maps with 7 x 7
+// blocks 5.9 -> 4.5 (slower), and the kernel that counts from code maps, bound by its own instructions, 17 % slower;
+// 52 KB (groups of 6, 6 and 3) is slower than either, so the block rows are dealt evenly over the fewest groups the
+// budget allows.
+constexpr int HIST_LDS_BYTES = 40 * 1024;
+constexpr int HIST_LDS_BYTES_WIDE = 60 * 1024;
 constexpr int SWEEP_LDS_BYTES = 40 * 1024;  // the same for the ring of the sweep kernel
 constexpr int CODE_ROWS = 8;                // code-map rows a thread has in flight
 
@@ -444,11 +452,16 @@ static void hist_launch(ddcca_ctx *ctx, HistParams p, int64_t n)
             return;
         }
     }
-    const int max_blocks = std::max(1, HIST_LDS_BYTES / HIST_BYTES);
+    const int lut_bytes = OUT != DDCCA_FEAT_COUNT_U16 ? p.lut_n * 4 : 0;
+    const bool wide = !CODES && p.w > 128;
+    const int max_blocks = std::max(1, ((wide ? HIST_LDS_BYTES_WIDE : HIST_LDS_BYTES) - lut_bytes) / HIST_BYTES);
     p.cols = std::min(p.nbx, max_blocks);
     p.col_chunks = (p.nbx + p.cols - 1) / p.cols;
-    // several block rows per workgroup cut the re-reading of the rows that overlapping blocks share
-    p.rb = std::max(1, std::min(p.nby, max_blocks / p.cols));
+    // several block rows per workgroup cut the re-reading of the rows that overlapping blocks share; the fewest row
+    // groups the budget allows, equally high
+    const int rb_max = std::max(1, std::min(p.nby, max_blocks / p.cols));
+    p.row_groups = (p.nby + rb_max - 1) / rb_max;
+    p.rb = (p.nby + p.row_groups - 1) / p.row_groups;
     p.row_groups = (p.nby + p.rb - 1) / p.rb;
     const int hist_words = p.rb * p.cols * (HIST_BYTES / 4);
     const size_t lds = (size_t)hist_words * 4 + (OUT != DDCCA_FEAT_COUNT_U16 ? (size_t)p.lut_n * 4 : 0);
