@@ -24,7 +24,13 @@ namespace ddcca {
 constexpr int CSPLIT_XB = 32;           // pixels per column block (16 columns x 2 shifts)
 constexpr int CSPLIT_MAX_NBX = 4;       // column blocks per tile
 constexpr int CSPLIT_TH_MAX = 32;       // tile rows
-constexpr int CSPLIT_WG_PER_CU = 2;
+// Most rows of a tile and workgroups per compute unit, per patch size.  k = 9 contracts long enough per tile for its
+// matrix pipeline to be idle a third of the time with two wavefronts per SIMD (one splits its next tile or waits at
+// the tile barrier, the other has the SIMD to itself); with tiles of 16 rows two buffers take 46 KB, the kernel
+// compiled for three wavefronts per SIMD keeps 160 registers without spilling, and three workgroups share a compute
+// unit: 256 x 256 maps 1.19 -> 1.16 ms per launch of 2 048, the convolutions of that workload 12.3 -> 11.7 ms per step.
+template <int KS> constexpr int CSPLIT_TH1 = KS == 9 ? 16 : CSPLIT_TH_MAX;
+template <int KS> constexpr int CSPLIT_WG_PER_CU = KS == 9 ? 3 : 2;
 
 // RU consecutive output rows share the pixel operands: the taps of output row y+u are the input rows
 // y+u .. y+u+k-1, so RU rows together read the k+RU-1 input rows y .. y+k+RU-2; one set of operand registers
@@ -43,7 +49,7 @@ struct SplitConv {
     static constexpr int KG = (PAIRS + 3) / 4;     // groups of four pairs
     static constexpr int STEPS = (KG + 3) / 4;     // matrix instructions per piece product and output row
     static constexpr int TW = NBX * CSPLIT_XB;
-    static constexpr int PH_MAX = CSPLIT_TH_MAX + 2 * R;
+    static constexpr int PH_MAX = CSPLIT_TH1<KS> + 2 * R;
     static constexpr int COLS = (TW + KW + 6) / 4 * 4;   // staged pixels per tile row (row start a multiple of 4)
     static constexpr int V4 = COLS / 4;
     // staged columns start at the multiple of 4 at or below the first halo column tx*TW - R (TW is a multiple of
@@ -313,7 +319,7 @@ __device__ __forceinline__ void split_rows(const unsigned int *prow, const int (
 // from the code maps by hash_hist_kernel<.., CODES>.  Same products and sums as the map-writing kernel, so the codes are those of its
 // maps bit for bit.
 template <int KS, int NBX, int RU, int WAVES, bool VEC4, bool CODES>
-__global__ __launch_bounds__(WAVES * 64) void conv_split_kernel(ConvSplitParams p)
+__global__ __launch_bounds__(WAVES * 64, CSPLIT_WG_PER_CU<KS> == 3 ? 3 : 1) void conv_split_kernel(ConvSplitParams p)
 {
     typedef SplitConv<KS, NBX, RU> G;
     constexpr int R = G::R, TW = G::TW, STEPS = G::STEPS, THREADS = WAVES * 64;
@@ -478,8 +484,9 @@ __global__ __launch_bounds__(WAVES * 64) void conv_split_kernel(ConvSplitParams 
 
 // Output rows that share their pixel operands, wavefronts per workgroup and tile rows of maps that take several
 // tiles, per patch size.  (Tile rows, measured on 128 x 128 maps in one process: k = 5 writes 5.4-5.9 TB/s in tiles
-// of 16 rows against 5.0-5.1 in tiles of 32 and 3.6 in tiles of 4; k = 7 and 9 lose 3 % from 32 to 16 rows.)
-template <int KS> struct SplitShape { static constexpr int RU = 1, WAVES = 4, TH = CSPLIT_TH_MAX; };
+// of 16 rows against 5.0-5.1 in tiles of 32 and 3.6 in tiles of 4; k = 7 and 9 lose 3 % from 32 to 16 rows at two
+// workgroups per compute unit -- k = 9 takes 16 rows for its three, CSPLIT_TH1 above.)
+template <int KS> struct SplitShape { static constexpr int RU = 1, WAVES = 4, TH = CSPLIT_TH1<KS>; };
 template <> struct SplitShape<7> { static constexpr int RU = 2, WAVES = 4, TH = CSPLIT_TH_MAX; };
 template <> struct SplitShape<5> { static constexpr int RU = 1, WAVES = 4, TH = 16; };
 template <> struct SplitShape<3> { static constexpr int RU = 2, WAVES = 4, TH = CSPLIT_TH_MAX; };
@@ -490,7 +497,7 @@ static int conv_split_launch_vec(ddcca_ctx *ctx, const float *in, int64_t n, int
 {
     constexpr int RU = SplitShape<KS>::RU, WAVES = SplitShape<KS>::WAVES;
     typedef SplitConv<KS, NBX, RU> G;
-    static_assert(2 * G::BUF * 4 * CSPLIT_WG_PER_CU <= 160 * 1024, "two workgroups per compute unit must fit in LDS");
+    static_assert(2 * G::BUF * 4 * CSPLIT_WG_PER_CU<KS> <= 160 * 1024, "the workgroups of a compute unit must fit in LDS");
     static bool attr_set[MAX_DEVICES] = {};      // per device: the attribute is set on that device's code object
     if (!attr_set[ctx->device]) {
         DDCCA_HIP(ctx, hipFuncSetAttribute((const void *)conv_split_kernel<KS, NBX, RU, WAVES, VEC4, CODES>,
@@ -500,15 +507,15 @@ static int conv_split_launch_vec(ddcca_ctx *ctx, const float *in, int64_t n, int
     ConvSplitParams p;
     p.in = in; p.W = W; p.out = out; p.codes = codes; p.h = h; p.w = w; p.L = L;
     p.tiles_x = (w + G::TW - 1) / G::TW;
-    // a map of at most CSPLIT_TH_MAX rows is one tile row; a higher one goes in equal tile heights of at most
+    // a map of at most CSPLIT_TH1 rows is one tile row; a higher one goes in equal tile heights of at most
     // SplitShape::TH rows; a multiple of the rows one pass of the workgroup covers either way
     constexpr int PASS = RU * WAVES;
-    const int cap = h <= CSPLIT_TH_MAX ? CSPLIT_TH_MAX : SplitShape<KS>::TH;
+    const int cap = h <= CSPLIT_TH1<KS> ? CSPLIT_TH1<KS> : SplitShape<KS>::TH;
     const int nty = (h + cap - 1) / cap;
     p.th = std::min(cap, ((h + nty - 1) / nty + PASS - 1) / PASS * PASS);
     p.tiles_y = (h + p.th - 1) / p.th;
     p.n_items = (long long)n * p.tiles_x * p.tiles_y;
-    unsigned grid = (unsigned)std::min(p.n_items, (long long)CSPLIT_WG_PER_CU * ctx->n_cu);
+    unsigned grid = (unsigned)std::min(p.n_items, (long long)CSPLIT_WG_PER_CU<KS> * ctx->n_cu);
     // Workgroup b takes items b, b + grid, ...: with a grid that shares a factor with the tiles of an image, a
     // workgroup would meet only some of an image's tiles over and over -- and when the last tile row or column is
     // smaller than the others, always the small ones or never (112 rows in tiles of 32: a quarter of the
